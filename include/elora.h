@@ -1,0 +1,202 @@
+/*
+ * elora.h -- C ABI of libelora: the batched multi-adapter LoRA linear layer
+ * ("batch LoRA inference", Sec. 3.4 and Sec. 4.3 of the EdgeLoRA paper) for
+ * one AMD MI355X (gfx950).
+ *
+ *     y_t = W x_t + s * B_i (A_i x_t)          i = adapter of row t
+ *
+ * for every row t of a batch in which each request carries its own adapter
+ * index into a pool of resident adapters (closing equation of Sec. 3.4;
+ * shapes W [d_out, d_in], A_i [r_i, d_in], B_i [d_out, r_i] from Sec. 2.1).
+ * The adapters live in a pre-allocated pool of fixed-size blocks, one block
+ * per adapter, so that no memory is allocated while serving (Sec. 3.3 and
+ * Sec. 4.2, "pre-allocated memory pool").
+ *
+ * General conventions
+ *   - Plain C types only.  `elora_stream_t` is a hipStream_t passed as void*.
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers are ordinary process memory.  Every device buffer (x, W, y,
+ *     pool storage, workspace) is allocated, owned and freed by the caller;
+ *     the library never allocates or frees device memory.
+ *   - All tensors are dense row-major.  bf16 is the 16-bit brain float; fp16
+ *     is IEEE binary16.
+ *   - Every function returns an elora_status_t (0 = success) unless it returns
+ *     a size.  Nothing aborts, throws or prints.  On failure no work has been
+ *     enqueued by that call and out-parameters are untouched.
+ *   - All device work is enqueued on the caller's stream and the call returns
+ *     without waiting.  Calls that use the same pool must be ordered by the
+ *     caller (same stream, or events).
+ */
+#ifndef ELORA_H
+#define ELORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *elora_stream_t; /* hipStream_t; NULL = the default stream */
+
+typedef struct elora_pool elora_pool_t; /* opaque host object; holds metadata only */
+
+typedef enum {
+    ELORA_OK = 0,
+    ELORA_E_NULL = 1,       /* a required pointer is NULL */
+    ELORA_E_ALIGN = 2,      /* a device pointer is not 16-byte aligned (pool storage: 256) */
+    ELORA_E_DTYPE = 3,      /* unknown dtype / weight format, or a combination that is not supported */
+    ELORA_E_SHAPE = 4,      /* non-positive or inconsistent dimension (e.g. desc vs pool d_in/d_out) */
+    ELORA_E_RANK = 5,       /* rank < 1 or rank > the pool's max_rank */
+    ELORA_E_SLOT = 6,       /* slot < 0 or slot >= capacity */
+    ELORA_E_NOT_LOADED = 7, /* the slot holds no adapter */
+    ELORA_E_STORAGE = 8,    /* pool storage or workspace smaller than required */
+    ELORA_E_SEGMENTS = 9,   /* routing tables: both or neither of adapter_idx / seg_offsets given, or n_segments < 0 */
+    ELORA_E_HIP = 10        /* a HIP runtime call failed (no device, bad launch, ...) */
+} elora_status_t;
+
+typedef enum { ELORA_F32 = 0, ELORA_BF16 = 1 } elora_dtype_t; /* element type of x, y, A, B (and W if ELORA_W_SAME) */
+
+typedef enum {
+    ELORA_W_SAME = 0,    /* W [d_out, d_in] has the dtype of x */
+    ELORA_W_INT4_G32 = 1 /* W is 4-bit, symmetric, groups of 32 along d_in (the block format the paper's
+                            settings name "Q4_0", Sec. 5 "Model"; byte order is this library's own):
+                            uint8 [d_out, d_in/2], byte b of a row = code(k=2b) | code(k=2b+1) << 4,
+                            w = scale * (code - 8), scales fp16 [d_out, d_in/32].  Needs dtype bf16,
+                            d_in % 32 == 0. */
+} elora_wfmt_t;
+
+/* Kernel family a call is dispatched to (reported by elora_linear_plan). */
+typedef enum {
+    ELORA_PATH_GENERIC = 0, /* plain-ALU tiled kernels: any dtype / shape */
+    ELORA_PATH_DECODE = 1,  /* few rows: HBM-streaming split-K MFMA contraction + reduce/expand epilogue kernel */
+    ELORA_PATH_GEMM = 2     /* many rows: LDS-tiled bf16 MFMA GEMM with the expand as a K-extension */
+} elora_path_t;
+
+const char *elora_status_string(int status);
+int elora_version(void);
+
+/* ------------------------------------------------------------------ pool ---
+ * The resident adapter pool of Sec. 3.3 / 4.2: `capacity` blocks of equal size,
+ * each able to hold one adapter of rank <= max_rank for ONE linear layer
+ * (d_in, d_out).  Block i ("slot" i) is what adapter index i in a batch refers to.
+ */
+
+/* Bytes of device memory a pool needs; 0 if an argument is invalid. */
+size_t elora_pool_storage_bytes(int d_in, int d_out, int max_rank, int capacity, int dtype);
+
+/*
+ * Create the host object for a pool that lives in caller-owned device memory
+ * `dev_storage` (256-byte aligned, >= elora_pool_storage_bytes()).  Touches no
+ * device memory: the pool's device-side slot table is cleared by the first
+ * stream-carrying call on this pool (load / evict / linear), on that call's
+ * stream.  *out receives the handle.
+ * Errors: E_NULL, E_ALIGN, E_DTYPE, E_SHAPE, E_RANK (max_rank < 1 or > 256), E_STORAGE.
+ */
+int elora_pool_create(int d_in, int d_out, int max_rank, int capacity, int dtype,
+                      void *dev_storage, size_t storage_bytes, elora_pool_t **out);
+
+/* Free the host object.  The device storage stays with the caller; pending work must have finished. */
+int elora_pool_destroy(elora_pool_t *pool);
+
+/*
+ * Place an adapter in block `slot` (Sec. 3.3: a new adapter is assigned to a
+ * free block of the pool): A [rank, d_in], B [d_out, rank], both row-major in
+ * the pool's dtype, scale = alpha / rank.  Copies are asynchronous on `stream`;
+ * `src_on_device` says whether A and B are device (1) or host (0) pointers.
+ * Host sources must stay valid until the stream has passed the copy.
+ * Reloading an occupied slot replaces its content.  Linear calls enqueued
+ * later on the same stream see the new adapter.
+ * Errors: E_NULL, E_SLOT, E_RANK, E_HIP.
+ */
+int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale,
+                            const void *A, const void *B, int src_on_device, elora_stream_t stream);
+
+/* Mark `slot` empty (its block returns to the pool, Sec. 4.2).  Rows that still refer to it are
+ * treated like rows with an invalid index.  Errors: E_NULL, E_SLOT, E_NOT_LOADED, E_HIP. */
+int elora_pool_evict(elora_pool_t *pool, int slot, elora_stream_t stream);
+
+/* Host-side view of a slot: *rank = 0 if empty.  Errors: E_NULL, E_SLOT. */
+int elora_pool_slot_info(const elora_pool_t *pool, int slot, int *rank, float *scale);
+
+/*
+ * Rows whose adapter index was out of range (not -1, not in [0, capacity)) or
+ * named an empty slot are computed as base-model-only rows and counted in a
+ * sticky device-side record.  This call SYNCHRONISES `stream`, copies the
+ * record to the host, and (if `clear`) resets it.  *n_bad_rows = how many
+ * such rows since the last clear, *first_bad_row = the smallest such row
+ * index (-1 if none).  Errors: E_NULL, E_HIP.
+ */
+int elora_pool_poll_error(elora_pool_t *pool, int clear, int *n_bad_rows, int *first_bad_row,
+                          elora_stream_t stream);
+
+/* ---------------------------------------------------------------- linear --- */
+
+typedef struct {
+    /* shapes */
+    int n_tokens;          /* T >= 0 rows in the batch (0: nothing is done) */
+    int d_in;              /* K */
+    int d_out;             /* N */
+    int dtype;             /* elora_dtype_t of x, y (and of the pool) */
+    int wfmt;              /* elora_wfmt_t */
+    /* tensors (device) */
+    const void *x;         /* [n_tokens, d_in] */
+    const void *W;         /* [d_out, d_in] (or packed 4-bit [d_out, d_in/2]) */
+    const void *w_scales;  /* fp16 [d_out, d_in/32] for ELORA_W_INT4_G32, else NULL */
+    void *y;               /* [n_tokens, d_out], overwritten */
+    /* adapters */
+    const elora_pool_t *pool;   /* NULL: base model only (y = W x), routing tables are ignored */
+    /* routing (device int32): exactly one of the two forms when pool != NULL */
+    const int32_t *adapter_idx; /* [n_tokens] slot per row, -1 = no adapter for this row (decode form) */
+    const int32_t *seg_offsets; /* [n_segments + 1] rows seg_offsets[s] .. seg_offsets[s+1]-1 use        */
+    const int32_t *seg_adapter; /* [n_segments]     slot seg_adapter[s] (-1 = none); offsets start at 0, */
+    int n_segments;             /*                  are non-decreasing and end at n_tokens (prefill form) */
+    const float *scales;        /* NULL: each adapter's own scale; else device fp32, one per row (decode
+                                   form) or one per segment (prefill form), replacing it */
+    /* scratch (device) */
+    void *workspace;            /* >= elora_workspace_bytes(n_tokens, d_in, d_out, max_rank), 256-byte aligned */
+    size_t workspace_bytes;
+} elora_linear_desc_t;
+
+/* Device scratch one call may use, for up to n_tokens_max rows.  0 if an argument is invalid. */
+size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank);
+
+typedef struct {
+    int path;        /* elora_path_t */
+    int n_launches;  /* kernels one call enqueues */
+    int split_k;     /* K-splits of the streaming contraction (decode path), else 1 */
+    int tile_rows;   /* W rows (decode) or output rows (gemm) per workgroup, 0 for the generic path */
+    int tile_cols;   /* output columns per workgroup (gemm), else 0 */
+    int grid;        /* workgroups of the dominant kernel */
+} elora_plan_t;
+
+/*
+ * Validate a descriptor exactly as elora_batched_lora_linear does (everything
+ * that can be checked on the host without touching the device) and report
+ * which kernels the call would run.  Touches no device memory.
+ * Errors: E_NULL, E_ALIGN, E_DTYPE, E_SHAPE, E_SEGMENTS, E_STORAGE.
+ */
+int elora_linear_plan(const elora_linear_desc_t *desc, elora_plan_t *plan);
+
+/*
+ * The batched multi-adapter LoRA linear layer of Sec. 3.4: the base product
+ * W x is shared by the whole batch; every row adds s * B_i (A_i x) with the
+ * adapter its request names; results land at the rows' own positions in y.
+ * Accumulation is fp32; y is rounded once (bf16: round-to-nearest-even).
+ * Rows with adapter -1 get y = W x.  Invalid indices: see elora_pool_poll_error.
+ * The segment table itself is trusted to be well-formed (it is device data).
+ * Errors: those of elora_linear_plan, plus E_HIP.
+ */
+int elora_batched_lora_linear(const elora_linear_desc_t *desc, elora_stream_t stream);
+
+/*
+ * Test hook: when `path` is a valid elora_path_t, later calls use that kernel
+ * family if the descriptor is eligible for it (otherwise the generic one);
+ * -1 restores automatic selection.  Process-wide, not thread-safe.
+ */
+int elora_force_path(int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELORA_H */

@@ -1,0 +1,261 @@
+"""ctypes binding of libelora.so -- argument marshalling only.
+
+Function names and argument order follow include/elora.h.  Tensors are passed
+as torch tensors on the GPU (PyTorch is used for device memory and streams
+only); every step of the layer runs inside the library's HIP kernels.  There
+is no fallback: importing this module without a built libelora.so raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libelora.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2507_01438_amd.build` "
+        "(there is no non-HIP fallback for the batched LoRA linear layer)")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+# ---- enums (include/elora.h) -------------------------------------------------
+ELORA_OK = 0
+(ELORA_E_NULL, ELORA_E_ALIGN, ELORA_E_DTYPE, ELORA_E_SHAPE, ELORA_E_RANK, ELORA_E_SLOT,
+ ELORA_E_NOT_LOADED, ELORA_E_STORAGE, ELORA_E_SEGMENTS, ELORA_E_HIP) = range(1, 11)
+ELORA_F32, ELORA_BF16 = 0, 1
+ELORA_W_SAME, ELORA_W_INT4_G32 = 0, 1
+ELORA_PATH_GENERIC, ELORA_PATH_DECODE, ELORA_PATH_GEMM = 0, 1, 2
+
+EXPORTED = [
+    "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
+    "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_evict", "elora_pool_slot_info",
+    "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
+    "elora_force_path",
+]
+
+
+class elora_linear_desc_t(ctypes.Structure):
+    _fields_ = [
+        ("n_tokens", ctypes.c_int), ("d_in", ctypes.c_int), ("d_out", ctypes.c_int),
+        ("dtype", ctypes.c_int), ("wfmt", ctypes.c_int),
+        ("x", ctypes.c_void_p), ("W", ctypes.c_void_p), ("w_scales", ctypes.c_void_p), ("y", ctypes.c_void_p),
+        ("pool", ctypes.c_void_p),
+        ("adapter_idx", ctypes.c_void_p), ("seg_offsets", ctypes.c_void_p), ("seg_adapter", ctypes.c_void_p),
+        ("n_segments", ctypes.c_int),
+        ("scales", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+class elora_plan_t(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int), ("n_launches", ctypes.c_int), ("split_k", ctypes.c_int),
+                ("tile_rows", ctypes.c_int), ("tile_cols", ctypes.c_int), ("grid", ctypes.c_int)]
+
+
+lib.elora_status_string.restype = ctypes.c_char_p
+lib.elora_status_string.argtypes = [ctypes.c_int]
+lib.elora_version.restype = ctypes.c_int
+lib.elora_pool_storage_bytes.restype = ctypes.c_size_t
+lib.elora_pool_storage_bytes.argtypes = [ctypes.c_int] * 5
+lib.elora_pool_create.restype = ctypes.c_int
+lib.elora_pool_create.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_void_p)]
+lib.elora_pool_destroy.restype = ctypes.c_int
+lib.elora_pool_destroy.argtypes = [ctypes.c_void_p]
+lib.elora_pool_load_adapter.restype = ctypes.c_int
+lib.elora_pool_load_adapter.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float,
+                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+lib.elora_pool_evict.restype = ctypes.c_int
+lib.elora_pool_evict.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+lib.elora_pool_slot_info.restype = ctypes.c_int
+lib.elora_pool_slot_info.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
+lib.elora_pool_poll_error.restype = ctypes.c_int
+lib.elora_pool_poll_error.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int),
+                                      ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
+lib.elora_workspace_bytes.restype = ctypes.c_size_t
+lib.elora_workspace_bytes.argtypes = [ctypes.c_int] * 4
+lib.elora_linear_plan.restype = ctypes.c_int
+lib.elora_linear_plan.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.POINTER(elora_plan_t)]
+lib.elora_batched_lora_linear.restype = ctypes.c_int
+lib.elora_batched_lora_linear.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_void_p]
+lib.elora_force_path.restype = ctypes.c_int
+lib.elora_force_path.argtypes = [ctypes.c_int]
+
+
+class EloraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {elora_status_string(status)} (status {status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != ELORA_OK:
+        raise EloraError(status, where)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device/host address of a tensor, an int address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+# ---- same-name wrappers ---------------------------------------------------------
+
+def elora_status_string(status: int) -> str:
+    return lib.elora_status_string(int(status)).decode()
+
+
+def elora_version() -> int:
+    return int(lib.elora_version())
+
+
+def elora_pool_storage_bytes(d_in: int, d_out: int, max_rank: int, capacity: int, dtype: int) -> int:
+    return int(lib.elora_pool_storage_bytes(d_in, d_out, max_rank, capacity, dtype))
+
+
+def elora_pool_create(d_in, d_out, max_rank, capacity, dtype, dev_storage, storage_bytes) -> int:
+    """Returns the opaque pool handle (an address)."""
+    out = ctypes.c_void_p()
+    _check(lib.elora_pool_create(d_in, d_out, max_rank, capacity, dtype, _ptr(dev_storage), storage_bytes,
+                                 ctypes.byref(out)), "elora_pool_create")
+    return out.value
+
+
+def elora_pool_destroy(pool: int) -> None:
+    _check(lib.elora_pool_destroy(pool), "elora_pool_destroy")
+
+
+def elora_pool_load_adapter(pool, slot, rank, scale, A, B, src_on_device, stream=None) -> None:
+    _check(lib.elora_pool_load_adapter(pool, slot, rank, scale, _ptr(A), _ptr(B), int(src_on_device),
+                                       _stream(stream)), "elora_pool_load_adapter")
+
+
+def elora_pool_evict(pool, slot, stream=None) -> None:
+    _check(lib.elora_pool_evict(pool, slot, _stream(stream)), "elora_pool_evict")
+
+
+def elora_pool_slot_info(pool, slot):
+    r, s = ctypes.c_int(), ctypes.c_float()
+    _check(lib.elora_pool_slot_info(pool, slot, ctypes.byref(r), ctypes.byref(s)), "elora_pool_slot_info")
+    return r.value, s.value
+
+
+def elora_pool_poll_error(pool, clear: bool = True, stream=None):
+    """(n_bad_rows, first_bad_row); synchronises the stream."""
+    n, f = ctypes.c_int(), ctypes.c_int()
+    _check(lib.elora_pool_poll_error(pool, int(clear), ctypes.byref(n), ctypes.byref(f), _stream(stream)),
+           "elora_pool_poll_error")
+    return n.value, f.value
+
+
+def elora_workspace_bytes(n_tokens_max: int, d_in: int, d_out: int, max_rank: int) -> int:
+    return int(lib.elora_workspace_bytes(n_tokens_max, d_in, d_out, max_rank))
+
+
+def make_desc(*, n_tokens, d_in, d_out, dtype, x, W, y, workspace, workspace_bytes, wfmt=ELORA_W_SAME,
+              w_scales=None, pool=None, adapter_idx=None, seg_offsets=None, seg_adapter=None, n_segments=0,
+              scales=None) -> elora_linear_desc_t:
+    d = elora_linear_desc_t()
+    d.n_tokens, d.d_in, d.d_out, d.dtype, d.wfmt = n_tokens, d_in, d_out, dtype, wfmt
+    d.x, d.W, d.w_scales, d.y = _ptr(x), _ptr(W), _ptr(w_scales), _ptr(y)
+    d.pool = pool
+    d.adapter_idx, d.seg_offsets, d.seg_adapter = _ptr(adapter_idx), _ptr(seg_offsets), _ptr(seg_adapter)
+    d.n_segments = n_segments
+    d.scales = _ptr(scales)
+    d.workspace, d.workspace_bytes = _ptr(workspace), workspace_bytes
+    return d
+
+
+def elora_linear_plan(desc: elora_linear_desc_t) -> elora_plan_t:
+    plan = elora_plan_t()
+    _check(lib.elora_linear_plan(ctypes.byref(desc), ctypes.byref(plan)), "elora_linear_plan")
+    return plan
+
+
+def elora_batched_lora_linear(desc: elora_linear_desc_t, stream=None) -> None:
+    _check(lib.elora_batched_lora_linear(ctypes.byref(desc), _stream(stream)), "elora_batched_lora_linear")
+
+
+def elora_force_path(path: int) -> None:
+    _check(lib.elora_force_path(path), "elora_force_path")
+
+
+# ---- small holders that keep device memory alive (no arithmetic) ----------------------
+
+_TORCH_DTYPE = {ELORA_F32: torch.float32, ELORA_BF16: torch.bfloat16}
+
+
+class AdapterPool:
+    """Device storage (a torch byte tensor) plus the library's pool handle."""
+
+    def __init__(self, d_in, d_out, max_rank, capacity, dtype, device="cuda:0"):
+        self.d_in, self.d_out, self.max_rank, self.capacity, self.dtype = d_in, d_out, max_rank, capacity, dtype
+        self.nbytes = elora_pool_storage_bytes(d_in, d_out, max_rank, capacity, dtype)
+        if self.nbytes == 0:
+            raise EloraError(ELORA_E_SHAPE, "elora_pool_storage_bytes")
+        self.storage = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
+        self.handle = elora_pool_create(d_in, d_out, max_rank, capacity, dtype, self.storage, self.nbytes)
+
+    def load(self, slot, A, B, scale, stream=None):
+        """A [rank, d_in], B [d_out, rank]: torch tensors (device or host, contiguous) of the pool's dtype."""
+        assert A.is_contiguous() and B.is_contiguous()
+        assert A.is_cuda == B.is_cuda
+        elora_pool_load_adapter(self.handle, slot, A.shape[0], float(scale), A, B, A.is_cuda, stream)
+
+    def evict(self, slot, stream=None):
+        elora_pool_evict(self.handle, slot, stream)
+
+    def poll_error(self, clear=True, stream=None):
+        return elora_pool_poll_error(self.handle, clear, stream)
+
+    def close(self):
+        if self.handle is not None:
+            elora_pool_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class LoraLinear:
+    """Pre-allocated workspace + descriptor assembly for repeated calls on one layer."""
+
+    def __init__(self, d_in, d_out, dtype, pool: Optional[AdapterPool], n_tokens_max, device="cuda:0"):
+        self.d_in, self.d_out, self.dtype, self.pool = d_in, d_out, dtype, pool
+        self.n_tokens_max = n_tokens_max
+        self.ws_bytes = elora_workspace_bytes(n_tokens_max, d_in, d_out, pool.max_rank if pool else 1)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+
+    def desc(self, x, W, y, *, adapter_idx=None, seg_offsets=None, seg_adapter=None, scales=None,
+             wfmt=ELORA_W_SAME, w_scales=None) -> elora_linear_desc_t:
+        n_tokens = x.shape[0]
+        assert n_tokens <= self.n_tokens_max
+        return make_desc(
+            n_tokens=n_tokens, d_in=self.d_in, d_out=self.d_out, dtype=self.dtype, wfmt=wfmt, x=x, W=W,
+            w_scales=w_scales, y=y, pool=self.pool.handle if self.pool else None, adapter_idx=adapter_idx,
+            seg_offsets=seg_offsets, seg_adapter=seg_adapter,
+            n_segments=0 if seg_adapter is None else int(seg_adapter.shape[0]), scales=scales,
+            workspace=self.workspace, workspace_bytes=self.ws_bytes)
+
+    def __call__(self, x, W, y, stream=None, **kw):
+        d = self.desc(x, W, y, **kw)
+        elora_batched_lora_linear(d, stream)
+        return y

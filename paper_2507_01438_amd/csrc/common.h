@@ -1,0 +1,184 @@
+// Shared declarations of libelora's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/elora.h"
+
+namespace elora {
+
+// ---- device-visible views (passed to kernels by value) ---------------------
+
+struct SlotMeta {  // one entry of the pool's device-side slot table
+    int rank;      // 0 while the slot is empty
+    float scale;   // alpha / rank
+    int loaded;    // 1 once A and B are in place
+    int pad;
+};
+
+struct PoolView {
+    const SlotMeta *meta;  // [capacity]
+    const char *slots;     // block 0; block i at slots + i * slot_bytes
+    int *err;              // [0] = rows with a bad index so far, [1] = smallest such row (INT_MAX if none)
+    size_t slot_bytes;     // A region [max_rank, d_in] then B region [d_out, rank] (row stride = rank)
+    size_t b_offset;       // byte offset of the B region inside a block
+    int capacity;
+    int max_rank;
+};
+
+struct RouteView {
+    const int32_t *adapter_idx;  // decode form, or nullptr
+    const int32_t *seg_offsets;  // prefill form
+    const int32_t *seg_adapter;
+    int n_segments;
+    const float *scales;  // per row (decode form) / per segment (prefill form), or nullptr
+};
+
+struct RowRoute {
+    int slot;     // validated pool slot, -1 = base model only
+    int rank;     // 0 if slot < 0
+    float scale;  // 0 if slot < 0
+};
+
+// Workspace sections (byte offsets from the 256-byte aligned base).
+struct WsLayout {
+    size_t row_slot;   // int32 [T]
+    size_t row_scale;  // float [T]
+    size_t v;          // float/bf16 shrink results (and their K-split partials)
+    size_t partial;    // float split-K partial sums of the streaming contraction
+    size_t total;
+};
+
+constexpr int kDecodeMaxTokens = 64;  // rows the streaming (decode) kernels take
+constexpr int kDecodeMaxSplit = 8;    // K-splits of the base contraction
+constexpr int kDecodeMaxVSplit = 16;  // K-splits of the shrink
+constexpr int kMaxRank = 256;
+
+WsLayout ws_layout(int n_tokens, int d_in, int d_out, int max_rank);
+
+// ---- host-side pool object --------------------------------------------------
+
+}  // namespace elora
+
+struct elora_pool {
+    int d_in, d_out, max_rank, capacity, dtype;
+    char *storage;
+    size_t storage_bytes;
+    size_t meta_offset, slots_offset, slot_bytes, b_offset;
+    bool device_cleared;
+    elora::SlotMeta *host_meta;  // mirror of the device slot table
+    elora::PoolView view() const;
+};
+
+namespace elora {
+
+// lazily clears the device slot table; enqueued on `stream`
+int pool_ensure_cleared(elora_pool *pool, hipStream_t stream);
+
+struct LinearArgs {
+    int T, K, N;
+    int dtype, wfmt;
+    const void *x, *W, *w_scales;
+    void *y;
+    bool has_pool;
+    PoolView pool;
+    RouteView route;
+    char *ws;
+    WsLayout wsl;
+};
+
+int launch_generic(const LinearArgs &a, hipStream_t stream);
+int launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
+int launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
+
+bool decode_eligible(const elora_linear_desc_t &d, int max_rank);
+void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
+bool gemm_eligible(const elora_linear_desc_t &d, int max_rank);
+void gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
+
+#define ELORA_HIP_TRY(expr)                  \
+    do {                                     \
+        if ((expr) != hipSuccess) {          \
+            (void)hipGetLastError();         \
+            return ELORA_E_HIP;              \
+        }                                    \
+    } while (0)
+
+// ---- device helpers ----------------------------------------------------------
+
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even; NaN stays NaN (quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float fp16_to_f32(uint16_t h)
+{
+    _Float16 v;
+    __builtin_memcpy(&v, &h, 2);
+    return (float)v;
+}
+
+template <typename E> __device__ __forceinline__ float load_elem(const E *p, size_t i);
+template <> __device__ __forceinline__ float load_elem<float>(const float *p, size_t i) { return p[i]; }
+template <> __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+
+template <typename E> __device__ __forceinline__ void store_elem(E *p, size_t i, float v);
+template <> __device__ __forceinline__ void store_elem<float>(float *p, size_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void store_elem<uint16_t>(uint16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// Which adapter row t uses (Sec. 3.4: every request of the batch names its own adapter).
+// Index -1 means none.  Any other index outside the pool, or naming an empty slot, is
+// turned into "none" and, if `record`, counted in the pool's sticky error record.
+__device__ __forceinline__ RowRoute resolve_row(int t, const RouteView &r, const PoolView &p, bool record)
+{
+    int idx;
+    int scale_at = t;
+    if (r.adapter_idx != nullptr) {
+        idx = r.adapter_idx[t];
+    } else {
+        // last segment s with seg_offsets[s] <= t (empty segments have equal offsets and are skipped over)
+        int lo = 0, hi = r.n_segments;  // invariant: seg_offsets[lo] <= t < seg_offsets[hi]
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (r.seg_offsets[mid] <= t) lo = mid; else hi = mid;
+        }
+        idx = (r.n_segments > 0 && r.seg_offsets[lo] <= t && t < r.seg_offsets[lo + 1]) ? r.seg_adapter[lo] : -1;
+        scale_at = lo;
+    }
+    RowRoute out{-1, 0, 0.0f};
+    if (idx == -1) return out;
+    bool ok = idx >= 0 && idx < p.capacity;
+    SlotMeta m{0, 0.0f, 0, 0};
+    if (ok) {
+        m = p.meta[idx];
+        ok = m.loaded == 1 && m.rank >= 1 && m.rank <= p.max_rank;
+    }
+    if (!ok) {
+        if (record) {
+            atomicAdd(&p.err[0], 1);
+            atomicMin(&p.err[1], t);
+        }
+        return out;
+    }
+    out.slot = idx;
+    out.rank = m.rank;
+    out.scale = (r.scales != nullptr) ? r.scales[scale_at] : m.scale;
+    return out;
+}
+
+__device__ __forceinline__ const char *slot_A(const PoolView &p, int slot) { return p.slots + (size_t)slot * p.slot_bytes; }
+__device__ __forceinline__ const char *slot_B(const PoolView &p, int slot) { return p.slots + (size_t)slot * p.slot_bytes + p.b_offset; }
+
+#endif  // __HIPCC__
+
+}  // namespace elora

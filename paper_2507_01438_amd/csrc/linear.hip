@@ -1,0 +1,181 @@
+// Host side of elora_batched_lora_linear: validation, workspace layout, kernel-family selection.
+#include "common.h"
+
+using namespace elora;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+int g_forced_path = -1;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+WsLayout elora::ws_layout(int T, int K, int N, int R)
+{
+    (void)K;
+    WsLayout l;
+    size_t t = (size_t)(T > 0 ? T : 1);
+    size_t td = t < (size_t)kDecodeMaxTokens ? t : (size_t)kDecodeMaxTokens;
+    size_t off = 0;
+    l.row_slot = off;
+    off += align_up(t * sizeof(int32_t));
+    l.row_scale = off;
+    off += align_up(t * sizeof(float));
+    l.v = off;
+    size_t v_full = t * (size_t)R * sizeof(float);
+    size_t v_split = td * (size_t)R * sizeof(float) * kDecodeMaxVSplit;
+    off += align_up(v_full > v_split ? v_full : v_split);
+    l.partial = off;
+    off += align_up(td * (size_t)N * sizeof(float) * kDecodeMaxSplit);
+    l.total = off;
+    return l;
+}
+
+static int validate(const elora_linear_desc_t *d, WsLayout *wsl_out)
+{
+    if (d == nullptr) return ELORA_E_NULL;
+    if (d->dtype != ELORA_F32 && d->dtype != ELORA_BF16) return ELORA_E_DTYPE;
+    if (d->wfmt != ELORA_W_SAME && d->wfmt != ELORA_W_INT4_G32) return ELORA_E_DTYPE;
+    if (d->wfmt == ELORA_W_INT4_G32 && d->dtype != ELORA_BF16) return ELORA_E_DTYPE;
+    if (d->n_tokens < 0 || d->d_in <= 0 || d->d_out <= 0) return ELORA_E_SHAPE;
+    if (d->wfmt == ELORA_W_INT4_G32 && (d->d_in % 32) != 0) return ELORA_E_SHAPE;
+    if (d->x == nullptr || d->W == nullptr || d->y == nullptr || d->workspace == nullptr) return ELORA_E_NULL;
+    if (d->wfmt == ELORA_W_INT4_G32 && d->w_scales == nullptr) return ELORA_E_NULL;
+    int max_rank = 1;
+    if (d->pool != nullptr) {
+        const elora_pool *p = d->pool;
+        if (p->dtype != d->dtype) return ELORA_E_DTYPE;
+        if (p->d_in != d->d_in || p->d_out != d->d_out) return ELORA_E_SHAPE;
+        bool decode_form = d->adapter_idx != nullptr;
+        bool prefill_form = d->seg_offsets != nullptr || d->seg_adapter != nullptr;
+        if (decode_form == prefill_form) return ELORA_E_SEGMENTS;
+        if (prefill_form && (d->seg_offsets == nullptr || d->seg_adapter == nullptr || d->n_segments < 0))
+            return ELORA_E_SEGMENTS;
+        max_rank = p->max_rank;
+    }
+    if (!aligned16(d->x) || !aligned16(d->W) || !aligned16(d->y)) return ELORA_E_ALIGN;
+    if (d->w_scales != nullptr && !aligned16(d->w_scales)) return ELORA_E_ALIGN;
+    if (reinterpret_cast<uintptr_t>(d->workspace) % kAlign) return ELORA_E_ALIGN;
+    WsLayout wsl = ws_layout(d->n_tokens, d->d_in, d->d_out, max_rank);
+    if (d->workspace_bytes < wsl.total) return ELORA_E_STORAGE;
+    if (wsl_out) *wsl_out = wsl;
+    return ELORA_OK;
+}
+
+static void make_plan(const elora_linear_desc_t *d, elora_plan_t *plan)
+{
+    int max_rank = d->pool ? d->pool->max_rank : 1;
+    bool dec = decode_eligible(*d, max_rank);
+    bool gem = gemm_eligible(*d, max_rank);
+    int path = ELORA_PATH_GENERIC;
+    if (g_forced_path >= 0) {
+        if (g_forced_path == ELORA_PATH_DECODE && dec) path = ELORA_PATH_DECODE;
+        if (g_forced_path == ELORA_PATH_GEMM && gem) path = ELORA_PATH_GEMM;
+    } else if (dec) {
+        path = ELORA_PATH_DECODE;
+    } else if (gem) {
+        path = ELORA_PATH_GEMM;
+    }
+    plan->path = path;
+    plan->split_k = 1;
+    plan->tile_rows = 0;
+    plan->tile_cols = 0;
+    if (path == ELORA_PATH_DECODE) {
+        decode_plan(*d, plan);
+    } else if (path == ELORA_PATH_GEMM) {
+        gemm_plan(*d, plan);
+    } else {
+        plan->n_launches = d->pool ? 3 : 1;
+        plan->grid = ((d->n_tokens + 63) / 64) * ((d->d_out + 63) / 64);
+    }
+}
+
+extern "C" {
+
+const char *elora_status_string(int status)
+{
+    switch (status) {
+    case ELORA_OK: return "ok";
+    case ELORA_E_NULL: return "required pointer is NULL";
+    case ELORA_E_ALIGN: return "device pointer is misaligned";
+    case ELORA_E_DTYPE: return "unsupported dtype or weight format";
+    case ELORA_E_SHAPE: return "invalid or inconsistent shape";
+    case ELORA_E_RANK: return "rank out of range";
+    case ELORA_E_SLOT: return "slot out of range";
+    case ELORA_E_NOT_LOADED: return "slot holds no adapter";
+    case ELORA_E_STORAGE: return "pool storage or workspace too small";
+    case ELORA_E_SEGMENTS: return "routing tables: give exactly one of adapter_idx / segment tables";
+    case ELORA_E_HIP: return "HIP runtime call failed";
+    default: return "unknown status";
+    }
+}
+
+int elora_version(void) { return 1; }
+
+size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank)
+{
+    if (n_tokens_max < 0 || d_in <= 0 || d_out <= 0 || max_rank < 1 || max_rank > kMaxRank) return 0;
+    return ws_layout(n_tokens_max, d_in, d_out, max_rank).total;
+}
+
+int elora_force_path(int path)
+{
+    if (path < -1 || path > ELORA_PATH_GEMM) return ELORA_E_DTYPE;
+    g_forced_path = path;
+    return ELORA_OK;
+}
+
+int elora_linear_plan(const elora_linear_desc_t *desc, elora_plan_t *plan)
+{
+    if (plan == nullptr) return ELORA_E_NULL;
+    int rc = validate(desc, nullptr);
+    if (rc != ELORA_OK) return rc;
+    make_plan(desc, plan);
+    return ELORA_OK;
+}
+
+int elora_batched_lora_linear(const elora_linear_desc_t *d, elora_stream_t stream_)
+{
+    WsLayout wsl;
+    int rc = validate(d, &wsl);
+    if (rc != ELORA_OK) return rc;
+    if (d->n_tokens == 0) return ELORA_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    elora_plan_t plan;
+    make_plan(d, &plan);
+
+    LinearArgs a;
+    a.T = d->n_tokens;
+    a.K = d->d_in;
+    a.N = d->d_out;
+    a.dtype = d->dtype;
+    a.wfmt = d->wfmt;
+    a.x = d->x;
+    a.W = d->W;
+    a.w_scales = d->w_scales;
+    a.y = d->y;
+    a.has_pool = d->pool != nullptr;
+    a.ws = static_cast<char *>(d->workspace);
+    a.wsl = wsl;
+    if (a.has_pool) {
+        // the pool handle is const in the descriptor; clearing its device table on first use is
+        // the one mutation a linear call may need
+        rc = pool_ensure_cleared(const_cast<elora_pool *>(d->pool), stream);
+        if (rc != ELORA_OK) return rc;
+        a.pool = d->pool->view();
+        a.route = RouteView{d->adapter_idx, d->seg_offsets, d->seg_adapter, d->n_segments, d->scales};
+    } else {
+        a.pool = PoolView{nullptr, nullptr, nullptr, 0, 0, 0, 1};
+        a.route = RouteView{nullptr, nullptr, nullptr, 0, nullptr};
+    }
+    switch (plan.path) {
+    case ELORA_PATH_DECODE: return launch_decode(a, plan, stream);
+    case ELORA_PATH_GEMM: return launch_gemm(a, plan, stream);
+    default: return launch_generic(a, stream);
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,203 @@
+// The resident adapter pool (Sec. 3.3 / 4.2 of the paper: fixed-size pre-allocated blocks, one
+// per adapter, assigned and released at run time without allocating memory).
+//
+// Device layout inside the caller's storage (all sections 256-byte aligned):
+//   [0, 256)            error record: int n_bad_rows, int first_bad_row
+//   [meta_offset, ..)   SlotMeta[capacity]
+//   [slots_offset, ..)  capacity blocks of slot_bytes:
+//                         A region: [rank, d_in] row-major at the block start (room for max_rank rows)
+//                         B region: [d_out, rank] row-major at b_offset, row stride = the adapter's
+//                                   own rank (packed, so a low-rank adapter in a max_rank block is
+//                                   read as one contiguous stream)
+#include <limits.h>
+#include <new>
+
+#include "common.h"
+
+using namespace elora;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+size_t elem_bytes(int dtype) { return dtype == ELORA_F32 ? 4 : 2; }
+
+bool pool_dims_ok(int d_in, int d_out, int max_rank, int capacity, int dtype)
+{
+    return d_in > 0 && d_out > 0 && capacity > 0 && max_rank >= 1 && max_rank <= kMaxRank &&
+           (dtype == ELORA_F32 || dtype == ELORA_BF16);
+}
+
+__global__ void pool_clear_kernel(int *err, SlotMeta *meta, int capacity)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) {
+        err[0] = 0;
+        err[1] = INT_MAX;
+    }
+    if (i < capacity) meta[i] = SlotMeta{0, 0.0f, 0, 0};
+}
+
+__global__ void pool_set_meta_kernel(SlotMeta *meta, int slot, int rank, float scale, int loaded)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) meta[slot] = SlotMeta{rank, scale, loaded, 0};
+}
+
+__global__ void pool_clear_err_kernel(int *err)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        err[0] = 0;
+        err[1] = INT_MAX;
+    }
+}
+
+}  // namespace
+
+PoolView elora_pool::view() const
+{
+    PoolView v;
+    v.meta = reinterpret_cast<const SlotMeta *>(storage + meta_offset);
+    v.slots = storage + slots_offset;
+    v.err = reinterpret_cast<int *>(storage);
+    v.slot_bytes = slot_bytes;
+    v.b_offset = b_offset;
+    v.capacity = capacity;
+    v.max_rank = max_rank;
+    return v;
+}
+
+int elora::pool_ensure_cleared(elora_pool *pool, hipStream_t stream)
+{
+    if (pool->device_cleared) return ELORA_OK;
+    int blocks = (pool->capacity + 255) / 256;
+    hipLaunchKernelGGL(pool_clear_kernel, dim3(blocks), dim3(256), 0, stream,
+                       reinterpret_cast<int *>(pool->storage),
+                       reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset), pool->capacity);
+    ELORA_HIP_TRY(hipGetLastError());
+    pool->device_cleared = true;
+    return ELORA_OK;
+}
+
+extern "C" {
+
+size_t elora_pool_storage_bytes(int d_in, int d_out, int max_rank, int capacity, int dtype)
+{
+    if (!pool_dims_ok(d_in, d_out, max_rank, capacity, dtype)) return 0;
+    size_t e = elem_bytes(dtype);
+    size_t a_bytes = align_up((size_t)max_rank * d_in * e);
+    size_t b_bytes = align_up((size_t)max_rank * d_out * e);
+    return kAlign + align_up(sizeof(SlotMeta) * (size_t)capacity) + (a_bytes + b_bytes) * (size_t)capacity;
+}
+
+int elora_pool_create(int d_in, int d_out, int max_rank, int capacity, int dtype, void *dev_storage,
+                      size_t storage_bytes, elora_pool_t **out)
+{
+    if (out == nullptr || dev_storage == nullptr) return ELORA_E_NULL;
+    if (dtype != ELORA_F32 && dtype != ELORA_BF16) return ELORA_E_DTYPE;
+    if (d_in <= 0 || d_out <= 0 || capacity <= 0) return ELORA_E_SHAPE;
+    if (max_rank < 1 || max_rank > kMaxRank) return ELORA_E_RANK;
+    if (reinterpret_cast<uintptr_t>(dev_storage) % kAlign) return ELORA_E_ALIGN;
+    size_t need = elora_pool_storage_bytes(d_in, d_out, max_rank, capacity, dtype);
+    if (storage_bytes < need) return ELORA_E_STORAGE;
+
+    elora_pool *p = new (std::nothrow) elora_pool;
+    if (p == nullptr) return ELORA_E_NULL;
+    p->host_meta = new (std::nothrow) SlotMeta[capacity];
+    if (p->host_meta == nullptr) {
+        delete p;
+        return ELORA_E_NULL;
+    }
+    for (int i = 0; i < capacity; ++i) p->host_meta[i] = SlotMeta{0, 0.0f, 0, 0};
+    size_t e = elem_bytes(dtype);
+    p->d_in = d_in;
+    p->d_out = d_out;
+    p->max_rank = max_rank;
+    p->capacity = capacity;
+    p->dtype = dtype;
+    p->storage = static_cast<char *>(dev_storage);
+    p->storage_bytes = storage_bytes;
+    p->meta_offset = kAlign;
+    p->slots_offset = kAlign + align_up(sizeof(SlotMeta) * (size_t)capacity);
+    p->b_offset = align_up((size_t)max_rank * d_in * e);
+    p->slot_bytes = p->b_offset + align_up((size_t)max_rank * d_out * e);
+    p->device_cleared = false;
+    *out = p;
+    return ELORA_OK;
+}
+
+int elora_pool_destroy(elora_pool_t *pool)
+{
+    if (pool == nullptr) return ELORA_E_NULL;
+    delete[] pool->host_meta;
+    delete pool;
+    return ELORA_OK;
+}
+
+int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale, const void *A, const void *B,
+                            int src_on_device, elora_stream_t stream_)
+{
+    if (pool == nullptr || A == nullptr || B == nullptr) return ELORA_E_NULL;
+    if (slot < 0 || slot >= pool->capacity) return ELORA_E_SLOT;
+    if (rank < 1 || rank > pool->max_rank) return ELORA_E_RANK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int rc = pool_ensure_cleared(pool, stream);
+    if (rc != ELORA_OK) return rc;
+    size_t e = elem_bytes(pool->dtype);
+    char *block = pool->storage + pool->slots_offset + (size_t)slot * pool->slot_bytes;
+    hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    SlotMeta *dmeta = reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset);
+    // the slot reads as empty while its content is being replaced
+    hipLaunchKernelGGL(pool_set_meta_kernel, dim3(1), dim3(64), 0, stream, dmeta, slot, 0, 0.0f, 0);
+    ELORA_HIP_TRY(hipGetLastError());
+    pool->host_meta[slot] = SlotMeta{0, 0.0f, 0, 0};
+    ELORA_HIP_TRY(hipMemcpyAsync(block, A, (size_t)rank * pool->d_in * e, kind, stream));
+    ELORA_HIP_TRY(hipMemcpyAsync(block + pool->b_offset, B, (size_t)rank * pool->d_out * e, kind, stream));
+    hipLaunchKernelGGL(pool_set_meta_kernel, dim3(1), dim3(64), 0, stream, dmeta, slot, rank, scale, 1);
+    ELORA_HIP_TRY(hipGetLastError());
+    pool->host_meta[slot] = SlotMeta{rank, scale, 1, 0};
+    return ELORA_OK;
+}
+
+int elora_pool_evict(elora_pool_t *pool, int slot, elora_stream_t stream_)
+{
+    if (pool == nullptr) return ELORA_E_NULL;
+    if (slot < 0 || slot >= pool->capacity) return ELORA_E_SLOT;
+    if (!pool->host_meta[slot].loaded) return ELORA_E_NOT_LOADED;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int rc = pool_ensure_cleared(pool, stream);
+    if (rc != ELORA_OK) return rc;
+    hipLaunchKernelGGL(pool_set_meta_kernel, dim3(1), dim3(64), 0, stream,
+                       reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset), slot, 0, 0.0f, 0);
+    ELORA_HIP_TRY(hipGetLastError());
+    pool->host_meta[slot] = SlotMeta{0, 0.0f, 0, 0};
+    return ELORA_OK;
+}
+
+int elora_pool_slot_info(const elora_pool_t *pool, int slot, int *rank, float *scale)
+{
+    if (pool == nullptr || rank == nullptr || scale == nullptr) return ELORA_E_NULL;
+    if (slot < 0 || slot >= pool->capacity) return ELORA_E_SLOT;
+    *rank = pool->host_meta[slot].loaded ? pool->host_meta[slot].rank : 0;
+    *scale = pool->host_meta[slot].loaded ? pool->host_meta[slot].scale : 0.0f;
+    return ELORA_OK;
+}
+
+int elora_pool_poll_error(elora_pool_t *pool, int clear, int *n_bad_rows, int *first_bad_row, elora_stream_t stream_)
+{
+    if (pool == nullptr || n_bad_rows == nullptr || first_bad_row == nullptr) return ELORA_E_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int rc = pool_ensure_cleared(pool, stream);
+    if (rc != ELORA_OK) return rc;
+    int rec[2] = {0, INT_MAX};
+    ELORA_HIP_TRY(hipStreamSynchronize(stream));
+    ELORA_HIP_TRY(hipMemcpy(rec, pool->storage, sizeof rec, hipMemcpyDeviceToHost));
+    if (clear && rec[0] != 0) {
+        hipLaunchKernelGGL(pool_clear_err_kernel, dim3(1), dim3(64), 0, stream, reinterpret_cast<int *>(pool->storage));
+        ELORA_HIP_TRY(hipGetLastError());
+    }
+    *n_bad_rows = rec[0];
+    *first_bad_row = rec[0] > 0 ? rec[1] : -1;
+    return ELORA_OK;
+}
+
+}  // extern "C"

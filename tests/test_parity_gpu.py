@@ -1,0 +1,208 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the fp64 oracle on the same seeded bytes.
+
+Tolerances (max |y - ref| / max |ref|): 1e-2 for bf16 inputs with fp32 accumulation, 1e-5 for fp32.
+Adapter routing is integer work and must be exact (routing probes)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2507_01438_amd import inputs as I  # noqa: E402
+from gpu_harness import DeviceCase, rel_err, to_dev, y_to_f64  # noqa: E402
+
+TOL = {I.F32: 1e-5, I.BF16: 1e-2}
+GENERIC, DECODE, GEMM = 0, 1, 2
+
+
+def _check(case, y, ref, tol=None):
+    e = rel_err(y, ref)
+    assert e <= (tol or TOL[case.w.dtype]), f"{case.w.name}/{case.proj.name}: rel err {e:.3e} (path {case.last_plan.path})"
+    return e
+
+
+def test_config1_fp32_full():
+    w = I.config1()
+    case = DeviceCase(w, w.projections[0])
+    y = case.run()
+    assert case.last_plan.path == GENERIC
+    _check(case, y, case.reference())
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
+
+
+@pytest.mark.parametrize("path", [DECODE, GENERIC])
+def test_config2_qproj_decode_full(path):
+    w = I.config2()
+    case = DeviceCase(w, w.projections[0])
+    y = case.run(force_path=path)
+    assert case.last_plan.path == path
+    ref = case.reference()
+    e = _check(case, y, ref)
+    print(f"config2 path {path}: rel err {e:.2e}")
+    # the adapter term must be visible in the comparison: dropping it has to break the tolerance
+    base_only = case.reference(row_adapter=np.full(w.T, -1, dtype=np.int32))
+    assert rel_err(base_only, ref) > 5 * TOL[w.dtype]
+    # same call twice: bit-identical (fixed summation order, no float atomics)
+    y2 = case.run(force_path=path)
+    assert np.array_equal(y, y2)
+    case.close()
+
+
+SMALL = [
+    # (T, K, N, pool, ranks, no_adapter_rows)
+    (1, 256, 16, 2, 4, ()),
+    (7, 512, 48, 3, (1, 3, 8), (2,)),
+    (16, 768, 80, 4, (16, 2, 5, 8), ()),
+    (17, 1024, 1040, 5, (8, 16, 32, 64, 7), (0, 16)),
+    (33, 2048, 272, 6, 16, (5,)),
+    (64, 4096, 144, 9, (8, 16, 32, 64), (63,)),
+    (50, 1280, 4096 + 64, 7, (12, 24, 40), ()),
+]
+
+
+@pytest.mark.parametrize("path", [DECODE, GENERIC])
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_decode_shapes(shape, path):
+    T, K, N, pool, ranks, none_rows = shape
+    rk = np.resize(np.asarray(ranks, dtype=np.int32), pool)
+    w = I.small_workload(100 + T, I.BF16, K, N, T, pool, rk, no_adapter_rows=none_rows)
+    case = DeviceCase(w, w.projections[0])
+    y = case.run(force_path=path)
+    assert case.last_plan.path == path
+    _check(case, y, case.reference())
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
+
+
+@pytest.mark.parametrize("dtype,K,N", [(I.F32, 100, 30), (I.BF16, 72, 19), (I.F32, 512, 130)])
+def test_odd_shapes_take_the_generic_kernels(dtype, K, N):
+    w = I.small_workload(7, dtype, K, N, 13, 4, (3, 5, 1, 8), no_adapter_rows=(4,), x_std=1.0)
+    case = DeviceCase(w, w.projections[0])
+    y = case.run()
+    assert case.last_plan.path == GENERIC
+    _check(case, y, case.reference())
+    case.close()
+
+
+@pytest.mark.parametrize("path", [DECODE, GENERIC])
+def test_segment_routing_with_empty_and_adapterless_segments(path):
+    lengths = [5, 0, 1, 20, 0, 0, 7, 3]
+    w = I.small_workload(21, I.BF16, 512, 256, sum(lengths), 5, (8, 16, 4, 32, 2), segments=lengths,
+                         no_adapter_rows=(3,))
+    case = DeviceCase(w, w.projections[0])
+    y = case.run(force_path=path)
+    assert case.last_plan.path == path
+    _check(case, y, case.reference())
+    # per-segment scale override
+    seg_scales = np.linspace(-1.0, 3.0, len(lengths)).astype(np.float32)
+    y = case.run(scales=to_dev(seg_scales), force_path=path)
+    row_scale = np.repeat(seg_scales, lengths).astype(np.float32)
+    _check(case, y, case.reference(row_scale=row_scale))
+    case.close()
+
+
+@pytest.mark.parametrize("path", [DECODE, GENERIC])
+def test_per_row_scale_override(path):
+    w = I.small_workload(22, I.BF16, 512, 128, 19, 4, 8)
+    case = DeviceCase(w, w.projections[0])
+    rs = np.linspace(-2.0, 2.0, w.T).astype(np.float32)
+    y = case.run(scales=to_dev(rs), force_path=path)
+    _check(case, y, case.reference(row_scale=rs))
+    case.close()
+
+
+@pytest.mark.parametrize("path", [DECODE, GENERIC])
+def test_routing_probes_are_bit_exact(path):
+    """W = 0, x_t = e_0, A_i[0,0] = 1, B_i[0,0] = i mod 256, B_i[1,0] = i div 256, scale 1:
+    y[t,0] + 256 y[t,1] spells the adapter index that was applied to row t."""
+    from paper_2507_01438_amd import binding as B
+    P, K, N, T = 600, 256, 16, 64
+    rng = np.random.default_rng(3)
+    pool = B.AdapterPool(K, N, 4, P, B.ELORA_BF16)
+    for i in range(P):
+        A = np.zeros((1, K), np.float32); A[0, 0] = 1
+        Bm = np.zeros((N, 1), np.float32); Bm[0, 0] = i % 256; Bm[1, 0] = i // 256
+        pool.load(i, torch.from_numpy(I.f32_to_bf16_bits(A).view(np.int16)),
+                  torch.from_numpy(I.f32_to_bf16_bits(Bm).view(np.int16)), 1.0)
+    x = np.zeros((T, K), np.float32); x[:, 0] = 1
+    idx = rng.integers(0, P, size=T).astype(np.int32)
+    idx[5] = -1
+    lin = B.LoraLinear(K, N, B.ELORA_BF16, pool, T)
+    y = torch.zeros((T, N), dtype=torch.int16, device="cuda:0")
+    xd, Wd, idxd = to_dev(I.f32_to_bf16_bits(x)), to_dev(np.zeros((N, K), np.uint16)), to_dev(idx)
+    B.elora_force_path(path)
+    try:
+        lin(xd, Wd, y, adapter_idx=idxd)
+    finally:
+        B.elora_force_path(-1)
+    torch.cuda.synchronize()
+    yh = y_to_f64(y, I.BF16)
+    spelled = (yh[:, 0] + 256 * yh[:, 1]).astype(np.int64)
+    want = np.where(idx >= 0, idx, 0)
+    assert np.array_equal(spelled, want)
+    assert np.all(yh[:, 2:] == 0)
+    pool.close()
+
+
+@pytest.mark.parametrize("path", [DECODE, GENERIC])
+def test_bad_and_evicted_indices_fall_back_to_base_and_are_reported(path):
+    w = I.small_workload(31, I.BF16, 512, 64, 12, 4, 8)
+    w.adapter_idx = np.array([0, 1, 2, 3, 99, 1, -5, 2, 2, 0, 3, 1], dtype=np.int32)
+    case = DeviceCase(w, w.projections[0])
+    case.pool.evict(3)
+    y = case.run(force_path=path)
+    cleaned = np.array([0, 1, 2, -1, -1, 1, -1, 2, 2, 0, -1, 1], dtype=np.int32)
+    _check(case, y, case.reference(row_adapter=cleaned))
+    assert case.pool.poll_error() == (4, 3)      # rows 3, 4, 6, 10; smallest is 3
+    assert case.pool.poll_error() == (0, -1)     # cleared
+    case.close()
+
+
+def test_empty_batch_and_base_only_calls():
+    from paper_2507_01438_amd import binding as B
+    w = I.small_workload(41, I.BF16, 512, 64, 9, 2, 8)
+    case = DeviceCase(w, w.projections[0])
+    d = case.desc()
+    d.n_tokens = 0
+    B.elora_batched_lora_linear(d)               # nothing to do, no error
+    lin = B.LoraLinear(512, 64, B.ELORA_BF16, None, 9)
+    y = torch.zeros((9, 64), dtype=torch.int16, device="cuda:0")
+    lin(case.x, case.W, y)
+    torch.cuda.synchronize()
+    ref = case.reference(row_adapter=np.full(9, -1, dtype=np.int32))
+    assert rel_err(y_to_f64(y, I.BF16), ref) <= 1e-2
+    case.close()
+
+
+def test_reloading_a_slot_replaces_the_adapter():
+    w = I.small_workload(51, I.BF16, 512, 64, 6, 3, (8, 4, 8))
+    w.adapter_idx = np.array([0, 1, 2, 1, 1, 0], dtype=np.int32)
+    case = DeviceCase(w, w.projections[0])
+    A, Bm, s = w.adapter(w.projections[0], 2)    # put slot 2's rank-8 adapter into slot 1 (was rank 4)
+    case.pool.load(1, torch.from_numpy(A.view(np.int16)), torch.from_numpy(Bm.view(np.int16)), 0.5)
+    case.adapters[1] = (A, Bm, 0.5)
+    y = case.run()
+    _check(case, y, case.reference())
+    assert case.B.elora_pool_slot_info(case.pool.handle, 1) == (8, 0.5)
+    case.close()
+
+
+@pytest.mark.parametrize("name", ["q", "k", "v", "o", "gate", "up", "down"])
+def test_config3_layer_decode_full_shapes(name):
+    """All seven projections at their real shapes, 64 rows, 256 adapters of mixed rank; the oracle
+    computes every row on a seeded sample of 256 columns plus the first and last 16 columns."""
+    w = I.config3()
+    proj = I.LLAMA8B[name]
+    used = w.distinct_adapters()
+    case = DeviceCase(w, proj, load_slots=used)
+    y = case.run()
+    assert case.last_plan.path == DECODE
+    rng = np.random.default_rng(9)
+    cols = np.unique(np.concatenate([rng.choice(proj.N, 256, replace=False), np.arange(16), np.arange(proj.N - 16, proj.N)]))
+    ref = case.reference(cols=cols)
+    e = rel_err(y[:, cols], ref)
+    print(f"config3 {name}: rel err {e:.2e}, split_k {case.last_plan.split_k}, grid {case.last_plan.grid}")
+    assert e <= 1e-2
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
