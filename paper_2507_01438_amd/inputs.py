@@ -298,8 +298,7 @@ def small_workload(seed: int, dtype: int, K: int, N: int, T: int, pool: int, ran
     segment routing, optional rows/segments with adapter -1 (base model only)."""
     rng = np.random.default_rng([seed, 0])
     ranks = np.asarray(ranks, dtype=np.int32)
-    if ranks.shape == ():
-        ranks = np.full(pool, int(ranks), dtype=np.int32)
+    ranks = np.resize(ranks, pool).astype(np.int32)  # a shorter list repeats
     w = Workload(f"small_{seed}", seed, dtype, wfmt, [Projection("p", K, N)], pool=pool,
                  max_rank=int(ranks.max()) if ranks.size else 1, ranks=ranks, scale=scale, x_std=x_std)
     if segments is None:
