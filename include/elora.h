@@ -161,6 +161,15 @@ typedef struct {
 /* Device scratch one call may use, for up to n_tokens_max rows.  0 if an argument is invalid. */
 size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank);
 
+/*
+ * A workspace must be initialised ONCE, before its first use in a linear call: its first 4 KiB hold
+ * counters that every call leaves at zero again, and this call zeroes them (one small fill kernel on
+ * `stream`).  Call it again only after a call that used the workspace was aborted (device reset).
+ * Two calls that may run at the same time (different streams) need different workspaces.
+ * Errors: E_NULL, E_ALIGN, E_STORAGE, E_HIP.
+ */
+int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t stream);
+
 typedef struct {
     int path;        /* elora_path_t */
     int n_launches;  /* kernels one call enqueues */
@@ -195,6 +204,31 @@ int elora_batched_lora_linear(const elora_linear_desc_t *desc, elora_stream_t st
  * -1 restores automatic selection.  Process-wide, not thread-safe.
  */
 int elora_force_path(int path);
+
+/*
+ * Test hook: upper bound on the polls of the decode kernel's one internal wait (a tile epilogue
+ * waiting for the shrink results).  A workgroup whose bound runs out computes the values it needs
+ * itself; 0 makes every epilogue take that route.  Default 4194304.  Errors: E_SHAPE (limit < 0).
+ */
+int elora_debug_spin_limit(int limit);
+
+/* ------------------------------------------------------------- profiling ---
+ * Kernel timing for benchmarks (the roofline figure of a run is quoted on the
+ * call's dominant kernel: the streaming contraction on the decode path, the
+ * MFMA GEMM on the gemm path, the tiled base kernel on the generic path).
+ *
+ * elora_profile_arm(n): the next n calls of elora_batched_lora_linear each
+ *   record one HIP event just before and one just after their dominant kernel,
+ *   on the call's stream.  Creates 2n events (host objects, no device memory);
+ *   a previous set is released.  n = 0 disarms.  Errors: E_SHAPE (n < 0 or
+ *   n > 65536), E_HIP.
+ * elora_profile_read(ms, n): waits for the recorded events and writes the
+ *   elapsed milliseconds of the first min(n, recorded) calls to the HOST array
+ *   ms; returns that count through *n_out.  Errors: E_NULL, E_HIP.
+ * Process-wide, not thread-safe; meant for benchmarks only.
+ */
+int elora_profile_arm(int n_calls);
+int elora_profile_read(float *ms, int n, int *n_out);
 
 #ifdef __cplusplus
 }

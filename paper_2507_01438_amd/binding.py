@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libelora.so")
+LIB_PATH = os.environ.get("ELORA_LIB", os.path.join(_HERE, "libelora.so"))  # override: an alternative build
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -35,7 +35,8 @@ EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
     "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
-    "elora_force_path",
+    "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
+    "elora_debug_spin_limit",
 ]
 
 
@@ -84,6 +85,16 @@ lib.elora_batched_lora_linear.restype = ctypes.c_int
 lib.elora_batched_lora_linear.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_void_p]
 lib.elora_force_path.restype = ctypes.c_int
 lib.elora_force_path.argtypes = [ctypes.c_int]
+
+
+lib.elora_workspace_init.restype = ctypes.c_int
+lib.elora_workspace_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+lib.elora_debug_spin_limit.restype = ctypes.c_int
+lib.elora_debug_spin_limit.argtypes = [ctypes.c_int]
+lib.elora_profile_arm.restype = ctypes.c_int
+lib.elora_profile_arm.argtypes = [ctypes.c_int]
+lib.elora_profile_read.restype = ctypes.c_int
+lib.elora_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
 
 
 class EloraError(RuntimeError):
@@ -195,6 +206,26 @@ def elora_force_path(path: int) -> None:
     _check(lib.elora_force_path(path), "elora_force_path")
 
 
+def elora_workspace_init(workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib.elora_workspace_init(_ptr(workspace), workspace_bytes, _stream(stream)), "elora_workspace_init")
+
+
+def elora_debug_spin_limit(limit: int) -> None:
+    _check(lib.elora_debug_spin_limit(int(limit)), "elora_debug_spin_limit")
+
+
+def elora_profile_arm(n_calls: int) -> None:
+    _check(lib.elora_profile_arm(int(n_calls)), "elora_profile_arm")
+
+
+def elora_profile_read(n: int):
+    """Elapsed milliseconds of the dominant kernel of each armed call that has run (list of floats)."""
+    buf = (ctypes.c_float * max(n, 1))()
+    got = ctypes.c_int()
+    _check(lib.elora_profile_read(buf, int(n), ctypes.byref(got)), "elora_profile_read")
+    return [float(buf[i]) for i in range(got.value)]
+
+
 # ---- small holders that keep device memory alive (no arithmetic) ----------------------
 
 _TORCH_DTYPE = {ELORA_F32: torch.float32, ELORA_BF16: torch.bfloat16}
@@ -243,6 +274,7 @@ class LoraLinear:
         self.n_tokens_max = n_tokens_max
         self.ws_bytes = elora_workspace_bytes(n_tokens_max, d_in, d_out, pool.max_rank if pool else 1)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        elora_workspace_init(self.workspace, self.ws_bytes)
 
     def desc(self, x, W, y, *, adapter_idx=None, seg_offsets=None, seg_adapter=None, scales=None,
              wfmt=ELORA_W_SAME, w_scales=None) -> elora_linear_desc_t:

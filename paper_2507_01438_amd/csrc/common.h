@@ -44,6 +44,7 @@ struct RowRoute {
 
 // Workspace sections (byte offsets from the 256-byte aligned base).
 struct WsLayout {
+    size_t sync;       // int [kSyncInts] counters of the decode kernel; zero between calls
     size_t row_slot;   // int32 [T]
     size_t row_scale;  // float [T]
     size_t v;          // float/bf16 shrink results (and their K-split partials)
@@ -55,6 +56,7 @@ constexpr int kDecodeMaxTokens = 64;  // rows the streaming (decode) kernels tak
 constexpr int kDecodeMaxSplit = 8;    // K-splits of the base contraction
 constexpr int kDecodeMaxVSplit = 16;  // K-splits of the shrink
 constexpr int kMaxRank = 256;
+constexpr int kSyncInts = 1024;       // ints in the workspace's counter area
 
 WsLayout ws_layout(int n_tokens, int d_in, int d_out, int max_rank);
 
@@ -93,10 +95,15 @@ int launch_generic(const LinearArgs &a, hipStream_t stream);
 int launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
 int launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
 
+void decode_set_spin_limit(int limit);
 bool decode_eligible(const elora_linear_desc_t &d, int max_rank);
 void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
 bool gemm_eligible(const elora_linear_desc_t &d, int max_rank);
 void gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
+
+// benchmark hook: bracket the dominant kernel of a call with events when armed
+void profile_mark_begin(hipStream_t stream);
+void profile_mark_end(hipStream_t stream);
 
 #define ELORA_HIP_TRY(expr)                  \
     do {                                     \

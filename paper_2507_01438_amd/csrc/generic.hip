@@ -133,10 +133,12 @@ int launch_typed(const LinearArgs &a, hipStream_t stream)
         ELORA_HIP_TRY(hipGetLastError());
     }
     dim3 grid((a.N + 63) / 64, (a.T + 63) / 64);
+    profile_mark_begin(stream);
     hipLaunchKernelGGL((base_generic_kernel<WFMT, E>), grid, dim3(256), 0, stream, a.T, a.K, a.N,
                        static_cast<const E *>(a.x), a.W, static_cast<const uint16_t *>(a.w_scales), a.pool, row_slot,
                        row_scale, V, R, static_cast<E *>(a.y));
     ELORA_HIP_TRY(hipGetLastError());
+    profile_mark_end(stream);
     return ELORA_OK;
 }
 

@@ -11,7 +11,35 @@ int g_forced_path = -1;
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// profiling hook state
+hipEvent_t *g_prof_events = nullptr;
+int g_prof_calls = 0;     // armed calls
+int g_prof_begun = 0;     // calls whose begin event was recorded
+int g_prof_ended = 0;
+
+void profile_release()
+{
+    if (g_prof_events) {
+        for (int i = 0; i < 2 * g_prof_calls; ++i) (void)hipEventDestroy(g_prof_events[i]);
+        delete[] g_prof_events;
+    }
+    g_prof_events = nullptr;
+    g_prof_calls = g_prof_begun = g_prof_ended = 0;
+}
+
 }  // namespace
+
+void elora::profile_mark_begin(hipStream_t stream)
+{
+    if (g_prof_events && g_prof_begun < g_prof_calls && g_prof_begun == g_prof_ended)
+        if (hipEventRecord(g_prof_events[2 * g_prof_begun], stream) == hipSuccess) ++g_prof_begun;
+}
+
+void elora::profile_mark_end(hipStream_t stream)
+{
+    if (g_prof_events && g_prof_ended < g_prof_begun)
+        if (hipEventRecord(g_prof_events[2 * g_prof_ended + 1], stream) == hipSuccess) ++g_prof_ended;
+}
 
 WsLayout elora::ws_layout(int T, int K, int N, int R)
 {
@@ -20,6 +48,8 @@ WsLayout elora::ws_layout(int T, int K, int N, int R)
     size_t t = (size_t)(T > 0 ? T : 1);
     size_t td = t < (size_t)kDecodeMaxTokens ? t : (size_t)kDecodeMaxTokens;
     size_t off = 0;
+    l.sync = off;
+    off += align_up(sizeof(int) * kSyncInts);
     l.row_slot = off;
     off += align_up(t * sizeof(int32_t));
     l.row_scale = off;
@@ -121,10 +151,67 @@ size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank
     return ws_layout(n_tokens_max, d_in, d_out, max_rank).total;
 }
 
+namespace {
+__global__ void ws_clear_kernel(int *sync, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) sync[i] = 0;
+}
+}  // namespace
+
+int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t stream)
+{
+    if (workspace == nullptr) return ELORA_E_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return ELORA_E_ALIGN;
+    if (workspace_bytes < align_up(sizeof(int) * kSyncInts)) return ELORA_E_STORAGE;
+    hipLaunchKernelGGL(ws_clear_kernel, dim3((kSyncInts + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<int *>(workspace), kSyncInts);
+    ELORA_HIP_TRY(hipGetLastError());
+    return ELORA_OK;
+}
+
+int elora_debug_spin_limit(int limit)
+{
+    if (limit < 0) return ELORA_E_SHAPE;
+    decode_set_spin_limit(limit);
+    return ELORA_OK;
+}
+
 int elora_force_path(int path)
 {
     if (path < -1 || path > ELORA_PATH_GEMM) return ELORA_E_DTYPE;
     g_forced_path = path;
+    return ELORA_OK;
+}
+
+int elora_profile_arm(int n_calls)
+{
+    if (n_calls < 0 || n_calls > 65536) return ELORA_E_SHAPE;
+    profile_release();
+    if (n_calls == 0) return ELORA_OK;
+    g_prof_events = new hipEvent_t[2 * n_calls];
+    for (int i = 0; i < 2 * n_calls; ++i) {
+        if (hipEventCreate(&g_prof_events[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof_events[j]);
+            delete[] g_prof_events;
+            g_prof_events = nullptr;
+            (void)hipGetLastError();
+            return ELORA_E_HIP;
+        }
+    }
+    g_prof_calls = n_calls;
+    return ELORA_OK;
+}
+
+int elora_profile_read(float *ms, int n, int *n_out)
+{
+    if (ms == nullptr || n_out == nullptr) return ELORA_E_NULL;
+    int have = g_prof_ended < n ? g_prof_ended : n;
+    for (int i = 0; i < have; ++i) {
+        ELORA_HIP_TRY(hipEventSynchronize(g_prof_events[2 * i + 1]));
+        ELORA_HIP_TRY(hipEventElapsedTime(&ms[i], g_prof_events[2 * i], g_prof_events[2 * i + 1]));
+    }
+    *n_out = have;
     return ELORA_OK;
 }
 

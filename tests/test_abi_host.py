@@ -118,7 +118,7 @@ def test_kernel_family_selection(B):
     n = B.elora_pool_storage_bytes(4096, 4096, 16, 64, B.ELORA_BF16)
     h = B.elora_pool_create(4096, 4096, 16, 64, B.ELORA_BF16, FAKE, n)
     p = B.elora_linear_plan(_desc(B, h))
-    assert p.path == B.ELORA_PATH_DECODE and p.n_launches == 2 and p.grid >= 256 and p.split_k >= 1
+    assert p.path == B.ELORA_PATH_DECODE and p.n_launches == 1 and p.grid >= 256 and p.split_k >= 1
     # fp32 and odd shapes go to the plain-ALU kernels
     p = B.elora_linear_plan(_desc(B, None, dtype=B.ELORA_F32, d_in=512, d_out=512, n_tokens=8))
     assert p.path == B.ELORA_PATH_GENERIC
@@ -133,3 +133,13 @@ def test_kernel_family_selection(B):
         B.elora_force_path(9)
     assert B.elora_workspace_bytes(32, 4096, 4096, 0) == 0
     B.elora_pool_destroy(h)
+
+
+def test_workspace_init_and_hooks_validate_arguments(B):
+    assert B.lib.elora_workspace_init(None, 1 << 20, 0) == B.ELORA_E_NULL
+    assert B.lib.elora_workspace_init(FAKE + 8, 1 << 20, 0) == B.ELORA_E_ALIGN
+    assert B.lib.elora_workspace_init(FAKE, 100, 0) == B.ELORA_E_STORAGE
+    assert B.lib.elora_debug_spin_limit(-1) == B.ELORA_E_SHAPE
+    assert B.lib.elora_debug_spin_limit(1 << 22) == B.ELORA_OK
+    assert B.lib.elora_profile_arm(-1) == B.ELORA_E_SHAPE
+    assert B.lib.elora_profile_arm(0) == B.ELORA_OK

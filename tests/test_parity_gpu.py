@@ -206,3 +206,41 @@ def test_config3_layer_decode_full_shapes(name):
     assert e <= 1e-2
     assert case.pool.poll_error() == (0, -1)
     case.close()
+
+
+def test_decode_epilogue_without_the_shrink_hand_off():
+    """With the internal wait's bound at 0 every tile epilogue recomputes A_i x_t itself; the
+    result must still match, and the counters must be left clean for the next (normal) call."""
+    w = I.small_workload(61, I.BF16, 1024, 528, 37, 6, (8, 16, 24, 3), no_adapter_rows=(1,))
+    case = DeviceCase(w, w.projections[0])
+    ref = case.reference()
+    case.B.elora_debug_spin_limit(0)
+    try:
+        y0 = case.run(force_path=DECODE)
+    finally:
+        case.B.elora_debug_spin_limit(1 << 22)
+    _check(case, y0, ref)
+    y1 = case.run(force_path=DECODE)
+    _check(case, y1, ref)
+    case.close()
+
+
+def test_decode_back_to_back_calls_share_one_workspace():
+    """Many calls in a row on one stream and one workspace: the counters a call leaves behind
+    must be exactly what the next call expects (checked on the last result and on a changed batch)."""
+    w = I.config2()
+    case = DeviceCase(w, w.projections[0])
+    d = case.desc()
+    for _ in range(50):
+        case.B.elora_batched_lora_linear(d)
+    torch.cuda.synchronize()
+    y = y_to_f64(case.y[: w.T], w.dtype)
+    ref = case.reference()
+    assert rel_err(y, ref) <= 1e-2
+    # smaller batch on the same workspace afterwards
+    w.adapter_idx = w.adapter_idx[:9].copy()
+    case.adapter_idx = to_dev(w.adapter_idx)
+    case.x_h = case.x_h[:9]
+    y9 = case.run()
+    assert rel_err(y9, case.reference()) <= 1e-2
+    case.close()
