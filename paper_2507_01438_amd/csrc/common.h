@@ -100,6 +100,7 @@ bool decode_eligible(const elora_linear_desc_t &d, int max_rank);
 void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
 bool gemm_eligible(const elora_linear_desc_t &d, int max_rank);
 void gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
+size_t gemm_v_bytes(int n_tokens, int max_rank);  // bf16 shrink results, rank padded to the GEMM's K block
 
 // benchmark hook: bracket the dominant kernel of a call with events when armed
 void profile_mark_begin(hipStream_t stream);

@@ -57,7 +57,9 @@ WsLayout elora::ws_layout(int T, int K, int N, int R)
     l.v = off;
     size_t v_full = t * (size_t)R * sizeof(float);
     size_t v_split = td * (size_t)R * sizeof(float) * kDecodeMaxVSplit;
-    off += align_up(v_full > v_split ? v_full : v_split);
+    size_t v_gemm = gemm_v_bytes((int)t, R);
+    size_t v_max = v_full > v_split ? v_full : v_split;
+    off += align_up(v_max > v_gemm ? v_max : v_gemm);
     l.partial = off;
     off += align_up(td * (size_t)N * sizeof(float) * kDecodeMaxSplit);
     l.total = off;

@@ -244,3 +244,119 @@ def test_decode_back_to_back_calls_share_one_workspace():
     y9 = case.run()
     assert rel_err(y9, case.reference()) <= 1e-2
     case.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# prefill / mixed path (LDS-tiled MFMA GEMM with the expand as K-extension)
+# ---------------------------------------------------------------------------------------------
+
+GEMM_SMALL = [
+    # (K, N, pool, ranks, segment lengths, adapter-less segments)
+    (64, 8, 2, (8,), [1], ()),
+    (320, 136, 3, (16, 8, 24), [40, 3, 17, 1, 1, 90], (2,)),
+    (1024, 264, 4, (32, 16, 64, 8), [300, 20, 0, 257, 15], ()),          # runs crossing 256-row tiles
+    (512, 520, 5, (5, 16, 3, 8, 12), [100, 64, 30, 16, 50], (1,)),        # odd ranks: per-row expand
+    (256, 2048 + 40, 6, (16,), [1] * 70 + [130] + [1] * 60, (5, 100)),    # decode-like rows around a prompt
+]
+
+
+@pytest.mark.parametrize("shape", GEMM_SMALL)
+def test_gemm_path_small_shapes(shape):
+    K, N, pool, ranks, lengths, none_segs = shape
+    w = I.small_workload(300 + K, I.BF16, K, N, sum(lengths), pool, ranks, segments=lengths, no_adapter_rows=none_segs)
+    case = DeviceCase(w, w.projections[0])
+    y = case.run(force_path=GEMM)
+    assert case.last_plan.path == GEMM
+    _check(case, y, case.reference())
+    assert case.pool.poll_error() == (0, -1)
+    y2 = case.run(force_path=GEMM)
+    assert np.array_equal(y, y2)
+    case.close()
+
+
+def test_gemm_path_with_per_row_indices_and_scales():
+    w = I.small_workload(77, I.BF16, 512, 328, 333, 7, (16, 8, 32), no_adapter_rows=(0, 100, 332))
+    w.adapter_idx[40:200] = 3          # a long run in the middle of scattered indices
+    case = DeviceCase(w, w.projections[0])
+    rs = np.linspace(0.5, 2.5, w.T).astype(np.float32)
+    y = case.run(scales=to_dev(rs), force_path=GEMM)
+    assert case.last_plan.path == GEMM
+    _check(case, y, case.reference(row_scale=rs))
+    case.close()
+
+
+def test_gemm_path_int4_small():
+    lengths = [70, 1, 1, 1, 200, 30]
+    w = I.small_workload(88, I.BF16, 384, 272, sum(lengths), 4, (16, 8), wfmt=I.W_INT4_G32, segments=lengths)
+    case = DeviceCase(w, w.projections[0])
+    y = case.run()
+    assert case.last_plan.path == GEMM
+    _check(case, y, case.reference())
+    case.close()
+
+
+def test_gemm_routing_probes_are_bit_exact():
+    from paper_2507_01438_amd import binding as B
+    P, K, N = 300, 64, 16
+    lengths = [1] * 40 + [33, 100, 17] + [1] * 25
+    T = sum(lengths)
+    rng = np.random.default_rng(4)
+    pool = B.AdapterPool(K, N, 8, P, B.ELORA_BF16)
+    for i in range(P):
+        A = np.zeros((8, K), np.float32); A[0, 0] = 1
+        Bm = np.zeros((N, 8), np.float32); Bm[0, 0] = i % 256; Bm[1, 0] = i // 256
+        pool.load(i, torch.from_numpy(I.f32_to_bf16_bits(A).view(np.int16)),
+                  torch.from_numpy(I.f32_to_bf16_bits(Bm).view(np.int16)), 1.0)
+    x = np.zeros((T, K), np.float32); x[:, 0] = 1
+    seg_adapter = rng.integers(0, P, size=len(lengths)).astype(np.int32)
+    lin = B.LoraLinear(K, N, B.ELORA_BF16, pool, T)
+    y = torch.zeros((T, N), dtype=torch.int16, device="cuda:0")
+    B.elora_force_path(GEMM)
+    try:
+        lin(to_dev(I.f32_to_bf16_bits(x)), to_dev(np.zeros((N, K), np.uint16)), y,
+            seg_offsets=to_dev(I.offsets_from_lengths(lengths)), seg_adapter=to_dev(seg_adapter))
+    finally:
+        B.elora_force_path(-1)
+    torch.cuda.synchronize()
+    yh = y_to_f64(y, I.BF16)
+    assert np.array_equal((yh[:, 0] + 256 * yh[:, 1]).astype(np.int64), np.repeat(seg_adapter, lengths))
+    pool.close()
+
+
+def _sampled_check(case, w, proj, n_cols=64, n_rows=32, seed=5):
+    """All rows on a seeded sample of columns, and all columns on the first/last row of every
+    segment plus a seeded sample of rows."""
+    y = case.run()
+    rng = np.random.default_rng(seed)
+    cols = np.sort(rng.choice(proj.N, n_cols, replace=False))
+    e1 = rel_err(y[:, cols], case.reference(cols=cols))
+    so = w.seg_offsets
+    edge = [int(so[s]) for s in range(len(so) - 1) if so[s + 1] > so[s]] + \
+           [int(so[s + 1] - 1) for s in range(len(so) - 1) if so[s + 1] > so[s]]
+    rows = np.unique(np.concatenate([np.array(edge, dtype=np.int64), rng.choice(w.T, n_rows, replace=False)]))
+    e2 = rel_err(y[rows], case.reference(rows=rows))
+    return max(e1, e2)
+
+
+@pytest.mark.parametrize("name", ["gate", "down"])
+def test_config4_prefill_segments_full_shapes(name):
+    w = I.config4()
+    proj = I.LLAMA8B[name]
+    case = DeviceCase(w, proj, load_slots=w.distinct_adapters())
+    e = _sampled_check(case, w, proj)
+    assert case.last_plan.path == GEMM
+    print(f"config4 {name}: T={w.T} rel err {e:.2e} grid {case.last_plan.grid}")
+    assert e <= 1e-2
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
+
+
+def test_config5_mixed_int4_full_shape():
+    w = I.config5()
+    proj = w.projections[0]
+    case = DeviceCase(w, proj, load_slots=w.distinct_adapters())
+    e = _sampled_check(case, w, proj, n_rows=48)
+    assert case.last_plan.path == GEMM
+    print(f"config5: T={w.T} rel err {e:.2e}")
+    assert e <= 1e-2
+    case.close()
