@@ -7,9 +7,10 @@
 //           one masked MFMA pass per run of equal adapters
 //   gemm    Y = X W^T (Sec. 3.4: the base product, shared by the whole batch) on 256 x 256 tiles with
 //           LDS-staged 64-wide K blocks and v_mfma_f32_32x32x16_bf16; the expand B_i v_t is appended to
-//           the K loop as extra K blocks (one per run of rows that share an adapter: A-operand = the
-//           run's rows of V, B-operand = B_i), or, for runs too short to be worth a K block, added
-//           per row in the epilogue with plain FMAs.  The epilogue rounds once to bf16 and stores each
+//           the K loop as extra K blocks: a run of rows that share an adapter takes rank (rounded up to
+//           8) of a block's 64 K columns, with the run's rows of V as A-operand (zero in all other rows)
+//           and B_i as B-operand in the same columns, so one block serves several short runs at once
+//           (decode rows of a mixed batch included).  The epilogue rounds once to bf16 and stores each
 //           row at its own position.
 #include "common.h"
 
@@ -132,11 +133,23 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int 
 // gemm
 // ------------------------------------------------------------------------------------------------
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kGemmThreads = 512;        // 8 waves: 2 along M x 4 along N, 128 x 64 outputs per wave
-constexpr int kLdsRow = BK + 8;          // bf16 elements per staged row (+16 bytes: conflict-free 16-byte reads)
-constexpr int kStageElems = (BM + BN) * kLdsRow;
-constexpr int kMinRunForMfma = 16;       // shorter runs of equal adapters are expanded per row in the epilogue
+constexpr int kGemmThreads = 256;        // 4 waves, one per SIMD: 2 along M x 2 along N, 128 x 128 outputs per wave
+constexpr int kStageElems = (BM + BN) * BK;            // one LDS stage: 256 rows of X and 256 rows of W, 64 KiB
+constexpr int kPieces = BM * (BK / 8) / kGemmThreads;  // 16-byte pieces per operand and thread (8)
+
+// A staged row is 8 chunks of 16 bytes.  Chunk c of tile row r lives in slot c ^ ((r >> 1) & 7) of that row,
+// which spreads the 16-byte fragment reads of 16 consecutive rows over all LDS banks without padding
+// (the direct global->LDS loads can only fill LDS contiguously, 1 KiB per wave and instruction).
+__device__ __forceinline__ int lds_pos(int r, int c) { return r * BK + ((c ^ ((r >> 1) & 7)) << 3); }
 constexpr int kMaxRuns = BM;
+constexpr int kXcds = 8, kSuperM = 4, kSuperN = 8;  // tile block per XCD (32 compute units each)
+
+int gemm_grid(int tiles_m, int tiles_n)
+{
+    int supers = ((tiles_m + kSuperM - 1) / kSuperM) * ((tiles_n + kSuperN - 1) / kSuperN);
+    supers = (supers + kXcds - 1) / kXcds * kXcds;
+    return supers * kSuperM * kSuperN;
+}
 
 struct GemmArgs {
     int T, K, N;
@@ -154,6 +167,25 @@ struct Run {
     int start, end, slot, rank;
 };
 
+// A piece of the expand: rank entries [j0, j0 + width) of run `run`, placed at K columns [kcol, kcol + width)
+// of an expand block (width and kcol are multiples of 8).
+struct Item {
+    uint16_t run, j0;
+    uint8_t kcol, width;
+    uint16_t pad;
+};
+constexpr int kMaxItems = kMaxRuns * (kMaxRank / BK);
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    bf16x2_t v = __builtin_convertvector(float2_t{lo, hi}, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, v);
+}
+
 template <int WFMT>
 __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, PoolView pool, int has_pool)
 {
@@ -163,30 +195,42 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     __shared__ unsigned long long s_mask[BM / 64];
     __shared__ Run s_runs[kMaxRuns];
     __shared__ int s_nruns;
-    __shared__ unsigned char s_valu_row[BM];  // 1: this row's expand is added in the epilogue
+    __shared__ Item s_items[kMaxItems];
+    __shared__ uint16_t s_blk_first[kMaxItems + 1];  // expand block b holds items [s_blk_first[b], s_blk_first[b + 1])
+    __shared__ int s_nblk;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = ga.T, K = ga.K, N = ga.N;
-    // consecutive workgroups walk down a column of row tiles so that they share the W tile in L2
-    const int tm = blockIdx.x % ga.tiles_m, tn = blockIdx.x / ga.tiles_m;
+    // Workgroup b runs on XCD b % 8 (round-robin dispatch) and every XCD has its own L2.  The 32
+    // workgroups that an XCD runs side by side are given one 4 x 8 block of tiles, so that they walk
+    // through K together and share the staged slabs of X (8 readers) and W (4 readers) in that L2.
+    const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
+    const int super = (seq / (kSuperM * kSuperN)) * kXcds + xcd, within = seq % (kSuperM * kSuperN);
+    const int supers_n = (ga.tiles_n + kSuperN - 1) / kSuperN;
+    const int tm = (super / supers_n) * kSuperM + within % kSuperM;
+    const int tn = (super % supers_n) * kSuperN + within / kSuperM;
+    if (tm >= ga.tiles_m || tn >= ga.tiles_n) return;  // padding of the tile grid to whole 4 x 8 blocks
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // ---- runs of equal adapters among the tile's rows ---------------------------------------------
-    if (tid == 0) s_nruns = 0;
-    if (tid < BM) {
+    // ---- runs of equal adapters among the tile's rows (one thread per row) ------------------------
+    static_assert(kGemmThreads == BM, "one thread per tile row");
+    if (tid == 0) {
+        s_nruns = 0;
+        s_nblk = 0;
+    }
+    {
         int slot = -1;
         if (has_pool && m0 + tid < T) slot = ga.row_slot[m0 + tid];
         s_slot[tid] = slot;
-        s_valu_row[tid] = 0;
     }
     __syncthreads();
-    if (tid < BM) {
+    {
         const bool is_start = tid == 0 || s_slot[tid] != s_slot[tid - 1];
         const unsigned long long mk = __ballot(is_start);
         if (lane == 0) s_mask[wave] = mk;
     }
     __syncthreads();
-    if (tid < BM && s_slot[tid] >= 0 && (tid == 0 || s_slot[tid] != s_slot[tid - 1])) {
+    if (s_slot[tid] >= 0 && (tid == 0 || s_slot[tid] != s_slot[tid - 1])) {
         int end = BM;
         for (int w = wave; w < BM / 64; ++w) {
             unsigned long long mk = s_mask[w];
@@ -201,169 +245,234 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     }
     __syncthreads();
     const int nruns = s_nruns;
-    // which runs go through the K-extension (MFMA), which are added per row in the epilogue
-    if (tid < nruns) {
-        const Run r = s_runs[tid];
-        const bool mfma = (r.end - r.start) >= kMinRunForMfma && (r.rank & 7) == 0;
-        if (!mfma) {
-            for (int q = r.start; q < r.end; ++q) s_valu_row[q] = 1;
-            s_runs[tid].rank = 0;  // no K blocks for this run
+    // pack the runs' rank columns into expand blocks of 64 K columns
+    if (tid == 0 && nruns > 0) {
+        int nitems = 0, nblk = 0, used = BK;
+        for (int ri = 0; ri < nruns; ++ri) {
+            const int rank = s_runs[ri].rank;
+            for (int j0 = 0; j0 < rank; j0 += BK) {
+                const int w = (min(BK, rank - j0) + 7) & ~7;
+                if (used + w > BK) {
+                    s_blk_first[nblk++] = (uint16_t)nitems;
+                    used = 0;
+                }
+                s_items[nitems++] = Item{(uint16_t)ri, (uint16_t)j0, (uint8_t)used, (uint8_t)w, 0};
+                used += w;
+            }
         }
+        s_blk_first[nblk] = (uint16_t)nitems;
+        s_nblk = nblk;
     }
     __syncthreads();
+    const int base_blocks = K / BK;
+    const int total_blocks = base_blocks + s_nblk;
 
-    // ---- main loop ---------------------------------------------------------------------------------
-    const int wm = wave >> 2, wn = wave & 3;  // wave's 128 x 64 block inside the tile
-    floatx16 acc[4][2];
+    // ---- main loop -----------------------------------------------------------------------------------
+    const int wm = wave >> 1, wn = wave & 1;  // wave's 128 x 128 block inside the tile
+    floatx16 acc[4][4];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
-    // staging: 256 rows x 8 pieces of 16 bytes for each operand, 4 + 4 pieces per thread
-    u32x4 ra[4], rb[4];
-    const int base_blocks = K / BK;
+    // Staging of the next K block.  Base blocks: X rows (and bf16 W rows) travel global -> LDS directly
+    // (global_load_lds_dwordx4: no registers, no LDS store instructions); 4-bit W rows are fetched as
+    // codes + scale and converted when they are parked in LDS.  Expand blocks (few) go through registers
+    // because rows outside the run have to be zeroed.  Rows past the end of X / W are clamped to the last
+    // row: what they produce is never stored.
+    u32x4 rr[kPieces];     // register staging (expand blocks)
+    uint32_t rq[kPieces];  // 4-bit W: packed codes of 8 weights
+    float rs[kPieces];     //          and their group scale
+    const int prow = tid >> 3, pchunk = tid & 7;  // register path: piece i = row prow + 32 i, chunk pchunk
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
 
-    // K blocks: [0, base_blocks) are the base product; then, per run, ceil(rank / BK) blocks of the expand
-    auto load_block = [&](int blk) {
+    // issue the loads of K block `blk` into stage `buf`
+    auto issue_block = [&](int blk, int buf) {
+        uint16_t *sa = stage0 + buf * kStageElems;
+        uint16_t *sb = sa + BM * BK;
         if (blk < base_blocks) {
             const int k0 = blk * BK;
+            // instruction q of a wave fills rows 8q .. 8q+7 of the stage: lane -> (row 8q + lane / 8, slot lane % 8)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int p = tid + i * kGemmThreads, r = p >> 3, c = p & 7;
-                ra[i] = (m0 + r < T) ? *reinterpret_cast<const u32x4 *>(ga.x + (size_t)(m0 + r) * K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+            for (int i = 0; i < 8; ++i) {
+                const int q = wave * 8 + i, row = 8 * q + (lane >> 3);
+                const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+                const int gr = min(m0 + row, T - 1);
+                __builtin_amdgcn_global_load_lds((gptr_t)(ga.x + (size_t)gr * K + k0 + chunk * 8), (lptr_t)(sa + q * 512), 16, 0, 0);
             }
             if (WFMT == ELORA_W_SAME) {
                 const uint16_t *W = static_cast<const uint16_t *>(ga.W);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int p = tid + i * kGemmThreads, r = p >> 3, c = p & 7;
-                    rb[i] = (n0 + r < N) ? *reinterpret_cast<const u32x4 *>(W + (size_t)(n0 + r) * K + k0 + c * 8) : u32x4{0, 0, 0, 0};
+                for (int i = 0; i < 8; ++i) {
+                    const int q = wave * 8 + i, row = 8 * q + (lane >> 3);
+                    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+                    const int gr = min(n0 + row, N - 1);
+                    __builtin_amdgcn_global_load_lds((gptr_t)(W + (size_t)gr * K + k0 + chunk * 8), (lptr_t)(sb + q * 512), 16, 0, 0);
                 }
             } else {
-                // 4-bit groups of 32: 8 consecutive weights = 4 bytes; w = scale * (code - 8)
+                // 4-bit groups of 32 along K: 8 consecutive weights = 4 bytes, one fp16 scale per group
                 const uint8_t *W = static_cast<const uint8_t *>(ga.W);
+                const int k = k0 + pchunk * 8;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int p = tid + i * kGemmThreads, r = p >> 3, c = p & 7;
-                    u32x4 out{0, 0, 0, 0};
-                    if (n0 + r < N) {
-                        const int k = k0 + c * 8;
-                        const uint32_t packed = *reinterpret_cast<const uint32_t *>(W + (size_t)(n0 + r) * (K >> 1) + (k >> 1));
-                        const float sc = fp16_to_f32(ga.w_scales[(size_t)(n0 + r) * (K >> 5) + (k >> 5)]);
+                for (int i = 0; i < kPieces; ++i) {
+                    const int r = min(n0 + prow + 32 * i, N - 1);
+                    rq[i] = *reinterpret_cast<const uint32_t *>(W + (size_t)r * (K >> 1) + (k >> 1));
+                    rs[i] = fp16_to_f32(ga.w_scales[(size_t)r * (K >> 5) + (k >> 5)]);
+                }
+            }
+        }
+    };
+    // make stage `buf` hold K block `blk` (everything that is not a direct load happens here)
+    auto commit_block = [&](int blk, int buf) {
+        uint16_t *sa = stage0 + buf * kStageElems;
+        uint16_t *sb = sa + BM * BK;
+        if (blk < base_blocks) {
+            if (WFMT != ELORA_W_SAME) {
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int lo = (packed >> (8 * q)) & 15, hi = (packed >> (8 * q + 4)) & 15;
-                            // scale * (code - 8) is exact in fp32 (fp16 scale times a 4-bit integer) and is
-                            // then rounded once to bf16
-                            out[q] = (uint32_t)f32_to_bf16(sc * (float)(lo - 8)) | ((uint32_t)f32_to_bf16(sc * (float)(hi - 8)) << 16);
-                        }
+                for (int i = 0; i < kPieces; ++i) {
+                    // w = scale * (code - 8): exact in fp32 (fp16 scale times a small integer), rounded once to bf16
+                    u32x4 out;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int lo = (rq[i] >> (8 * q)) & 15, hi = (rq[i] >> (8 * q + 4)) & 15;
+                        out[q] = pack_bf16x2(rs[i] * (float)(lo - 8), rs[i] * (float)(hi - 8));
                     }
-                    rb[i] = out;
+                    *reinterpret_cast<u32x4 *>(sb + lds_pos(prow + 32 * i, pchunk)) = out;
                 }
             }
             return;
         }
-        // expand blocks: find the run and the rank offset this block belongs to
-        int e = blk - base_blocks;
-        int ri = 0, j0 = 0;
-        for (; ri < nruns; ++ri) {
-            const int nb = (s_runs[ri].rank + BK - 1) / BK;
-            if (e < nb) {
-                j0 = e * BK;
-                break;
+        // expand block: K columns 8 * pchunk .. + 7 of this thread's pieces belong to exactly one item (or none)
+        const int e = blk - base_blocks;
+        const int kc = pchunk * 8;
+        int run_start = 0, run_end = 0, run_rank = 0, j = 0;
+        const uint16_t *Bm = nullptr;
+        for (int it = s_blk_first[e]; it < s_blk_first[e + 1]; ++it) {
+            const Item item = s_items[it];
+            if (kc >= item.kcol && kc < item.kcol + item.width) {
+                const Run run = s_runs[item.run];
+                run_start = run.start;
+                run_end = run.end;
+                run_rank = run.rank;
+                j = item.j0 + (kc - item.kcol);
+                Bm = reinterpret_cast<const uint16_t *>(slot_B(pool, run.slot));
             }
-            e -= nb;
         }
-        const Run run = s_runs[ri];
-        const uint16_t *Bm = reinterpret_cast<const uint16_t *>(slot_B(pool, run.slot));
+        // A-operand: the run's rows of V (zero beyond the rank up to Rpad); every other row contributes nothing
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int p = tid + i * kGemmThreads, r = p >> 3, c = p & 7;
-            const int j = j0 + c * 8;
-            // rows of V outside the run belong to other adapters: they contribute nothing here.
-            // V holds zeros beyond the row's rank up to Rpad.
-            ra[i] = (r >= run.start && r < run.end && j < ga.Rpad)
-                        ? *reinterpret_cast<const u32x4 *>(ga.V + (size_t)(m0 + r) * ga.Rpad + j)
-                        : u32x4{0, 0, 0, 0};
-            rb[i] = (n0 + r < N && j < run.rank) ? *reinterpret_cast<const u32x4 *>(Bm + (size_t)(n0 + r) * run.rank + j)
-                                                  : u32x4{0, 0, 0, 0};
+        for (int i = 0; i < kPieces; ++i) {
+            const int r = prow + 32 * i;
+            rr[i] = (r >= run_start && r < run_end) ? *reinterpret_cast<const u32x4 *>(ga.V + (size_t)(m0 + r) * ga.Rpad + j)
+                                                    : u32x4{0, 0, 0, 0};
         }
-    };
-    auto store_block = [&](int buf) {
-        uint16_t *sa = stage0 + buf * kStageElems;
-        uint16_t *sb = sa + BM * kLdsRow;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int p = tid + i * kGemmThreads, r = p >> 3, c = p & 7;
-            *reinterpret_cast<u32x4 *>(sa + r * kLdsRow + c * 8) = ra[i];
-            *reinterpret_cast<u32x4 *>(sb + r * kLdsRow + c * 8) = rb[i];
-        }
-    };
-    auto compute_block = [&](int buf) {
-        const uint16_t *sa = stage0 + buf * kStageElems + (wm * 128 + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
-        const uint16_t *sb = stage0 + buf * kStageElems + BM * kLdsRow + (wn * 64 + (lane & 31)) * kLdsRow + (lane >> 5) * 8;
+        for (int i = 0; i < kPieces; ++i) *reinterpret_cast<u32x4 *>(sa + lds_pos(prow + 32 * i, pchunk)) = rr[i];
+        // B-operand: B_i[n, j .. j + 7] (row stride = rank; zero at and beyond the rank)
+        const bool vec = Bm != nullptr && (run_rank & 7) == 0;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[4], fb[2];
+        for (int i = 0; i < kPieces; ++i) {
+            const int n = n0 + prow + 32 * i;
+            u32x4 v{0, 0, 0, 0};
+            if (Bm != nullptr && n < N) {
+                const uint16_t *src = Bm + (size_t)n * run_rank + j;
+                if (vec) {
+                    if (j < run_rank) v = *reinterpret_cast<const u32x4 *>(src);
+                } else {
 #pragma unroll
-            for (int a = 0; a < 4; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(sa + a * 32 * kLdsRow + ks * 16);
-#pragma unroll
-            for (int b = 0; b < 2; ++b) fb[b] = *reinterpret_cast<const bf16x8 *>(sb + b * 32 * kLdsRow + ks * 16);
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-        }
-    };
-
-    int total_blocks = base_blocks;
-    for (int ri = 0; ri < nruns; ++ri) total_blocks += (s_runs[ri].rank + BK - 1) / BK;
-
-    load_block(0);
-    store_block(0);
-    __syncthreads();
-    for (int blk = 0; blk < total_blocks; ++blk) {
-        const int buf = blk & 1;
-        const bool more = (blk + 1) < total_blocks;
-        if (more) load_block(blk + 1);
-        compute_block(buf);
-        if (more) store_block(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue -----------------------------------------------------------------------------------
-    // C layout of the 32x32 MFMA: lane holds column (lane % 32); value i sits in row (i / 4) * 8 + (lane / 32) * 4 + i % 4
-#pragma unroll
-    for (int a = 0; a < 4; ++a) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int rl = wm * 128 + a * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);  // row inside the tile
-            const int row = m0 + rl;
-            if (row >= T) continue;
-            float o[2] = {acc[a][0][i], acc[a][1][i]};
-            if (s_valu_row[rl]) {
-                const int slot = s_slot[rl];
-                const int rank = pool.meta[slot].rank;
-                const uint16_t *Bm = reinterpret_cast<const uint16_t *>(slot_B(pool, slot));
-                const uint16_t *v = ga.V + (size_t)row * ga.Rpad;
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const int col = n0 + wn * 64 + b * 32 + (lane & 31);
-                    if (col < N) {
-                        float d = 0.0f;
-                        for (int j = 0; j < rank; ++j) d = fmaf(bf16_to_f32(v[j]), bf16_to_f32(Bm[(size_t)col * rank + j]), d);
-                        o[b] += d;
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t lo = (j + 2 * q < run_rank) ? src[2 * q] : 0u;
+                        const uint32_t hi = (j + 2 * q + 1 < run_rank) ? src[2 * q + 1] : 0u;
+                        v[q] = lo | (hi << 16);
                     }
                 }
             }
+            rr[i] = v;
+        }
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const int col = n0 + wn * 64 + b * 32 + (lane & 31);
-                if (col < N) ga.y[(size_t)row * N + col] = f32_to_bf16(o[b]);
+        for (int i = 0; i < kPieces; ++i) *reinterpret_cast<u32x4 *>(sb + lds_pos(prow + 32 * i, pchunk)) = rr[i];
+    };
+    bf16x8 fr[2][8];  // fragments of one 16-wide K step: [0..3] rows of X, [4..7] rows of W; double-buffered
+    // fragment row = block base (multiple of 32) + lane % 32, so the swizzle term only depends on the lane
+    const int fsw = ((lane & 31) >> 1) & 7, fhalf = lane >> 5;
+    auto read_frags = [&](bf16x8 *dst, int buf, int ks) {
+        const int slot = ((ks * 2 + fhalf) ^ fsw) << 3;
+        const uint16_t *sa = stage0 + buf * kStageElems + (wm * 128 + (lane & 31)) * BK + slot;
+        const uint16_t *sb = stage0 + buf * kStageElems + BM * BK + (wn * 128 + (lane & 31)) * BK + slot;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) dst[a] = *reinterpret_cast<const bf16x8 *>(sa + a * 32 * BK);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) dst[4 + b] = *reinterpret_cast<const bf16x8 *>(sb + b * 32 * BK);
+    };
+    auto mfma_step = [&](const bf16x8 *f) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[a], f[4 + b], acc[a][b], 0, 0, 0);
+    };
+
+    issue_block(0, 0);
+    commit_block(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct loads have landed in LDS
+    __syncthreads();
+    read_frags(fr[0], 0, 0);
+    // One K block per iteration, four K steps of 16.  While the matrix cores work on step s the LDS
+    // reads of step s + 1 are already under way; the loads of the next block are issued at the top and
+    // land in the other stage on their own; the one barrier of the iteration sits before the last step,
+    // so that the matrix cores drain step 2 while the waves meet.
+    for (int blk = 0; blk < total_blocks; ++blk) {
+        const int buf = blk & 1;
+        const bool more = (blk + 1) < total_blocks;
+        if (more) issue_block(blk + 1, buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fr[1], buf, 1);
+        mfma_step(fr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fr[0], buf, 2);
+        mfma_step(fr[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fr[1], buf, 3);
+        mfma_step(fr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) {
+            commit_block(blk + 1, buf ^ 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            read_frags(fr[0], buf ^ 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(fr[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- epilogue -------------------------------------------------------------------------------------
+    // C layout of the 32x32 MFMA: lane holds column (lane % 32); value i sits in row (i / 4) * 8 + (lane / 32) * 4 + i % 4.
+    // Neighbouring lanes swap one value per row pair so that every lane stores two adjacent columns (4 bytes).
+    const bool odd = lane & 1;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int ip = 0; ip < 8; ++ip) {
+            float o[4][2];  // [b][row i0 / i1]
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) o[b][h] = acc[a][b][2 * ip + h];
+            const int i_mine = 2 * ip + (odd ? 1 : 0);
+            const int rl = wm * 128 + a * 32 + (i_mine >> 2) * 8 + (lane >> 5) * 4 + (i_mine & 3);
+            const int row = m0 + rl;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                // even lane keeps row i0 and gets the neighbour's i0 value; odd lane keeps row i1 and gets the neighbour's i1
+                const float send = odd ? o[b][0] : o[b][1];
+                const float recv = __shfl_xor(send, 1);
+                const float mine = odd ? o[b][1] : o[b][0];
+                const int col = n0 + wn * 128 + b * 32 + (lane & 30);  // even column of the pair
+                if (row < T && col < N)
+                    *reinterpret_cast<uint32_t *>(ga.y + (size_t)row * N + col) = odd ? pack_bf16x2(recv, mine) : pack_bf16x2(mine, recv);
             }
         }
     }
@@ -384,7 +493,7 @@ void elora::gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
     plan->n_launches = d.pool ? 3 : 2;
     plan->tile_rows = BM;
     plan->tile_cols = BN;
-    plan->grid = ((d.n_tokens + BM - 1) / BM) * ((d.d_out + BN - 1) / BN);
+    plan->grid = gemm_grid((d.n_tokens + BM - 1) / BM, (d.d_out + BN - 1) / BN);
 }
 
 size_t elora::gemm_v_bytes(int n_tokens, int max_rank) { return (size_t)n_tokens * round_up(max_rank, BK) * sizeof(uint16_t); }
@@ -419,7 +528,7 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
     ga.tiles_m = (a.T + BM - 1) / BM;
     ga.tiles_n = (a.N + BN - 1) / BN;
     const size_t lds = (size_t)2 * kStageElems * sizeof(uint16_t);
-    dim3 grid(ga.tiles_m * ga.tiles_n), block(kGemmThreads);
+    dim3 grid(gemm_grid(ga.tiles_m, ga.tiles_n)), block(kGemmThreads);
     profile_mark_begin(stream);
     if (a.wfmt == ELORA_W_SAME) {
         static bool attr_done = false;
