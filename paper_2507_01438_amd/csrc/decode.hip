@@ -99,45 +99,6 @@ __device__ __forceinline__ float2 load_shared_f32x2(const float *p)
     return float2{__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32))};
 }
 
-// One wave: v[t][j0], v[t][j0+1] = A_i[j0..j0+1, :] . x[t, :] over the whole of K (K % 256 == 0).
-__device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, const uint16_t *__restrict__ A1,
-                                            const uint16_t *__restrict__ xt, int K, int lane, float &r0, float &r1)
-{
-    float s0 = 0.0f, s1 = 0.0f;
-    const int pieces = K >> 3;  // 16-byte pieces per row
-    for (int pb = 0; pb < pieces; pb += 64 * 8) {
-        u32x4 xv[8], a0[8], a1[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int p = pb + i * 64 + lane;
-            const bool in = p < pieces;
-            const size_t off = (size_t)(in ? p : 0) * 8;
-            xv[i] = *reinterpret_cast<const u32x4 *>(xt + off);
-            a0[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(A0 + off));
-            a1[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(A1 + off));
-        }
-        __builtin_amdgcn_sched_barrier(0);  // keep all 24 loads in flight together: do not interleave the math
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if (pb + i * 64 + lane >= pieces) xv[i] = u32x4{0, 0, 0, 0};  // past the row: contributes nothing
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float xl = __uint_as_float(xv[i][q] << 16), xh = __uint_as_float(xv[i][q] & 0xffff0000u);
-                s0 = fmaf(__uint_as_float(a0[i][q] << 16), xl, s0);
-                s0 = fmaf(__uint_as_float(a0[i][q] & 0xffff0000u), xh, s0);
-                s1 = fmaf(__uint_as_float(a1[i][q] << 16), xl, s1);
-                s1 = fmaf(__uint_as_float(a1[i][q] & 0xffff0000u), xh, s1);
-            }
-        }
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        s0 += __shfl_xor(s0, off);
-        s1 += __shfl_xor(s1, off);
-    }
-    r0 = s0;
-    r1 = s1;
-}
-
 template <int TT>
 __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
                                                           const uint16_t *__restrict__ W, PoolView pool,

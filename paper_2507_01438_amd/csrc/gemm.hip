@@ -38,16 +38,22 @@ __global__ void gemm_route_kernel(int T, RouteView route, PoolView pool, int has
 }
 
 // ------------------------------------------------------------------------------------------------
-// shrink: 32-row tiles, 4 waves split K, one masked pass per run of equal adapters
+// shrink.  Workgroups [0, n_tiles): one 32-row tile each, 4 waves split K, one masked MFMA pass per run
+// of >= kShortRun equal adapters.  Workgroups [n_tiles, n_tiles + T): one row each; a row that sits in a
+// shorter run (a decode row of a mixed batch, or the few rows a run leaves in a neighbouring tile) is
+// computed there with plain FMAs, straight from its own adapter, and all other row workgroups exit at once.
+// Either way V[t, :] = bf16(s_t * A_i x_t), with zeros beyond the rank up to Rpad and in rows without adapter.
 // ------------------------------------------------------------------------------------------------
 constexpr int kShrinkRows = 32;
 constexpr int kShrinkThreads = 256;
 constexpr int kShrinkColsPerPass = 64;  // rank columns per pass (4 MFMA column blocks of 16)
+constexpr int kShortRun = 8;
+constexpr int kShrinkUnroll = 4;        // K steps of 32 whose loads are issued together
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
-__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int K, const uint16_t *__restrict__ x,
-                                                                     PoolView pool,
+__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int K, int n_tiles,
+                                                                     const uint16_t *__restrict__ x, PoolView pool,
                                                                      const int32_t *__restrict__ row_slot,
                                                                      const float *__restrict__ row_scale,
                                                                      uint16_t *__restrict__ V, int Rpad)
@@ -55,17 +61,57 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int 
     __shared__ int s_slot[kShrinkRows];
     __shared__ float s_red[4][kShrinkRows][kShrinkColsPerPass + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    if ((int)blockIdx.x >= n_tiles) {
+        // ---- one row of a short run ---------------------------------------------------------------
+        const int t = blockIdx.x - n_tiles;
+        const int r0 = t / kShrinkRows * kShrinkRows, r1 = min(r0 + kShrinkRows, T);
+        const int slot = row_slot[t];
+        int lo = t, hi = t + 1;  // the run's piece inside this tile
+        while (lo > r0 && row_slot[lo - 1] == slot) --lo;
+        while (hi < r1 && row_slot[hi] == slot) ++hi;
+        if (hi - lo >= kShortRun) return;
+        float *vrow = &s_red[0][0][0];  // Rpad <= 256 floats
+        int rank = 0;
+        if (slot >= 0) {
+            rank = pool.meta[slot].rank;
+            const uint16_t *A = reinterpret_cast<const uint16_t *>(slot_A(pool, slot));
+            for (int j0 = 2 * wave; j0 < rank; j0 += 2 * 4) {
+                const bool two = (j0 + 1) < rank;
+                float a0, a1;
+                shrink_pair(A + (size_t)j0 * K, two ? A + (size_t)(j0 + 1) * K : A + (size_t)j0 * K, x + (size_t)t * K, K, lane, a0, a1);
+                if (lane == 0) {
+                    vrow[j0] = a0;
+                    if (two) vrow[j0 + 1] = a1;
+                }
+            }
+        }
+        __syncthreads();
+        const float sc = slot >= 0 ? row_scale[t] : 0.0f;
+        for (int j = tid; j < Rpad; j += kShrinkThreads) V[(size_t)t * Rpad + j] = (j < rank) ? f32_to_bf16(sc * vrow[j]) : (uint16_t)0;
+        return;
+    }
+
+    // ---- 32-row tile ------------------------------------------------------------------------------
     const int r0 = blockIdx.x * kShrinkRows;
     if (tid < kShrinkRows) s_slot[tid] = (r0 + tid < T) ? row_slot[r0 + tid] : -1;
-    // rows without adapter and columns beyond the rank read as zero in the GEMM's K-extension
-    for (int e = tid; e < kShrinkRows * Rpad; e += kShrinkThreads) {
-        int r = e / Rpad;
-        if (r0 + r < T) V[(size_t)(r0 + r) * Rpad + (e - r * Rpad)] = 0;
+    __syncthreads();
+    // rows of long runs: zero now, the passes below fill in the rank columns (short-run rows belong to
+    // their own workgroups)
+    for (int r = 0; r < kShrinkRows && r0 + r < T;) {
+        int e = r + 1;
+        while (e < kShrinkRows && s_slot[e] == s_slot[r]) ++e;
+        if (e - r >= kShortRun)
+            for (int q = tid; q < (e - r) * Rpad; q += kShrinkThreads) {
+                const int rr = r + q / Rpad;
+                if (r0 + rr < T) V[(size_t)(r0 + rr) * Rpad + q % Rpad] = 0;
+            }
+        r = e;
     }
     __syncthreads();
 
     const int m = lane & 15, g = lane >> 4;
-    const int kq = K / 4;  // K % 64 == 0, so each wave's quarter is a multiple of 16; steps of 32 with a guard
+    const int kq = K / 4;  // K % 64 == 0: each wave's quarter of K is a multiple of 16
     const int kbeg = wave * kq, kend = kbeg + kq;
 
     int run_start = 0;
@@ -73,7 +119,7 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int 
         const int slot = s_slot[run_start];
         int run_end = run_start + 1;
         while (run_end < kShrinkRows && s_slot[run_end] == slot) ++run_end;
-        if (slot >= 0) {
+        if (slot >= 0 && run_end - run_start >= kShortRun) {
             const int rank = pool.meta[slot].rank;
             const uint16_t *A = reinterpret_cast<const uint16_t *>(slot_A(pool, slot));
             for (int j0 = 0; j0 < rank; j0 += kShrinkColsPerPass) {
@@ -83,27 +129,35 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int 
 #pragma unroll
                     for (int b = 0; b < 4; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
                 const int ncb = min(4, (rank - j0 + 15) / 16);  // 16-column blocks in this pass
-                for (int k = kbeg; k < kend; k += 32) {
-                    const int kk = k + g * 8;
-                    const bool kin = kk < kend;  // the last step of a quarter may be half empty
-                    bf16x8 xa[2], ab[4];
+                for (int k = kbeg; k < kend; k += 32 * kShrinkUnroll) {
+                    bf16x8 xa[kShrinkUnroll][2], ab[kShrinkUnroll][4];
 #pragma unroll
-                    for (int a = 0; a < 2; ++a) {
-                        const int row = r0 + a * 16 + m;
-                        u32x4 v = (kin && row < T) ? *reinterpret_cast<const u32x4 *>(x + (size_t)row * K + kk) : u32x4{0, 0, 0, 0};
-                        xa[a] = __builtin_bit_cast(bf16x8, v);
+                    for (int u = 0; u < kShrinkUnroll; ++u) {
+                        const int kk = k + u * 32 + g * 8;
+                        const bool kin = kk < kend;  // the tail of a quarter may be partly empty
+#pragma unroll
+                        for (int a = 0; a < 2; ++a) {
+                            const int row = min(r0 + a * 16 + m, T - 1);
+                            u32x4 v = *reinterpret_cast<const u32x4 *>(x + (size_t)row * K + (kin ? kk : kbeg));
+                            if (!kin) v = u32x4{0, 0, 0, 0};
+                            xa[u][a] = __builtin_bit_cast(bf16x8, v);
+                        }
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const int j = j0 + b * 16 + m;
+                            u32x4 v{0, 0, 0, 0};
+                            if (b < ncb) v = *reinterpret_cast<const u32x4 *>(A + (size_t)min(j, rank - 1) * K + (kin ? kk : kbeg));
+                            if (j >= rank) v = u32x4{0, 0, 0, 0};
+                            ab[u][b] = __builtin_bit_cast(bf16x8, v);
+                        }
                     }
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int j = j0 + b * 16 + m;
-                        u32x4 v = (kin && b < ncb && j < rank) ? *reinterpret_cast<const u32x4 *>(A + (size_t)j * K + kk) : u32x4{0, 0, 0, 0};
-                        ab[b] = __builtin_bit_cast(bf16x8, v);
-                    }
+                    for (int u = 0; u < kShrinkUnroll; ++u)
 #pragma unroll
-                    for (int a = 0; a < 2; ++a)
+                        for (int a = 0; a < 2; ++a)
 #pragma unroll
-                        for (int b = 0; b < 4; ++b)
-                            if (b < ncb) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab[b], xa[a], acc[a][b], 0, 0, 0);
+                            for (int b = 0; b < 4; ++b)
+                                if (b < ncb) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab[u][b], xa[u][a], acc[a][b], 0, 0, 0);
                 }
                 // MFMA rows = rank rows j (A-operand), columns = batch rows (B-operand):
                 // lane holds batch row (lane % 16), rank rows (lane / 16) * 4 + 0..3
@@ -144,12 +198,7 @@ __device__ __forceinline__ int lds_pos(int r, int c) { return r * BK + ((c ^ ((r
 constexpr int kMaxRuns = BM;
 constexpr int kXcds = 8, kSuperM = 4, kSuperN = 8;  // tile block per XCD (32 compute units each)
 
-int gemm_grid(int tiles_m, int tiles_n)
-{
-    int supers = ((tiles_m + kSuperM - 1) / kSuperM) * ((tiles_n + kSuperN - 1) / kSuperN);
-    supers = (supers + kXcds - 1) / kXcds * kXcds;
-    return supers * kSuperM * kSuperN;
-}
+int gemm_grid(int tiles_m, int tiles_n) { return (tiles_m * tiles_n + kXcds - 1) / kXcds * kXcds; }
 
 struct GemmArgs {
     int T, K, N;
@@ -201,15 +250,24 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = ga.T, K = ga.K, N = ga.N;
-    // Workgroup b runs on XCD b % 8 (round-robin dispatch) and every XCD has its own L2.  The 32
-    // workgroups that an XCD runs side by side are given one 4 x 8 block of tiles, so that they walk
-    // through K together and share the staged slabs of X (8 readers) and W (4 readers) in that L2.
+    // Workgroup b runs on XCD b % 8 (round-robin dispatch) and every XCD has its own L2.  The tiles are
+    // listed block by block (blocks of 4 x 8 tiles; the blocks column by column through the grid, the tiles
+    // column-major inside a block) and each XCD takes one contiguous eighth of that list.  So the 32
+    // workgroups it runs side by side sit in one or two blocks, walk through K together and share the staged
+    // slabs of X and W in its L2; every XCD gets the same number of tiles; and every XCD's share runs through
+    // all rows of the batch, so that rows with many expand blocks (decode rows of a mixed batch) are spread
+    // over all XCDs.
+    const int n_valid = ga.tiles_m * ga.tiles_n, per_xcd = (n_valid + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds, seq = blockIdx.x / kXcds;
-    const int super = (seq / (kSuperM * kSuperN)) * kXcds + xcd, within = seq % (kSuperM * kSuperN);
-    const int supers_n = (ga.tiles_n + kSuperN - 1) / kSuperN;
-    const int tm = (super / supers_n) * kSuperM + within % kSuperM;
-    const int tn = (super % supers_n) * kSuperN + within / kSuperM;
-    if (tm >= ga.tiles_m || tn >= ga.tiles_n) return;  // padding of the tile grid to whole 4 x 8 blocks
+    int pos = xcd * per_xcd + seq;
+    if (seq >= per_xcd || pos >= n_valid) return;
+    const int sc = pos / (ga.tiles_m * kSuperN);            // only the last column of blocks can be narrower than 8
+    const int sw = min(kSuperN, ga.tiles_n - sc * kSuperN);
+    pos -= sc * ga.tiles_m * kSuperN;
+    const int sr = pos / (kSuperM * sw);                    // only the last block of a column can be lower than 4
+    const int sh = min(kSuperM, ga.tiles_m - sr * kSuperM);
+    pos -= sr * kSuperM * sw;
+    const int tm = sr * kSuperM + pos % sh, tn = sc * kSuperN + pos / sh;
     const int m0 = tm * BM, n0 = tn * BN;
 
     // ---- runs of equal adapters among the tile's rows (one thread per row) ------------------------
@@ -283,8 +341,8 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     // because rows outside the run have to be zeroed.  Rows past the end of X / W are clamped to the last
     // row: what they produce is never stored.
     u32x4 rr[kPieces];     // register staging (expand blocks)
-    uint32_t rq[kPieces];  // 4-bit W: packed codes of 8 weights
-    float rs[kPieces];     //          and their group scale
+    uint32_t rq[2][kPieces];  // 4-bit W: packed codes of 8 weights and their group scale; set 0 = the block that is
+    float rs[2][kPieces];     // being parked in LDS during this iteration, set 1 = the block after it (in flight)
     const int prow = tid >> 3, pchunk = tid & 7;  // register path: piece i = row prow + 32 i, chunk pchunk
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
@@ -312,39 +370,45 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
                     const int gr = min(n0 + row, N - 1);
                     __builtin_amdgcn_global_load_lds((gptr_t)(W + (size_t)gr * K + k0 + chunk * 8), (lptr_t)(sb + q * 512), 16, 0, 0);
                 }
-            } else {
-                // 4-bit groups of 32 along K: 8 consecutive weights = 4 bytes, one fp16 scale per group
-                const uint8_t *W = static_cast<const uint8_t *>(ga.W);
-                const int k = k0 + pchunk * 8;
-#pragma unroll
-                for (int i = 0; i < kPieces; ++i) {
-                    const int r = min(n0 + prow + 32 * i, N - 1);
-                    rq[i] = *reinterpret_cast<const uint32_t *>(W + (size_t)r * (K >> 1) + (k >> 1));
-                    rs[i] = fp16_to_f32(ga.w_scales[(size_t)r * (K >> 5) + (k >> 5)]);
-                }
             }
+        }
+    };
+    // 4-bit W: fetch codes and scales of K block `blk` (groups of 32 along K: 8 consecutive weights = 4 bytes,
+    // one fp16 scale per group) into register set `set`
+    auto fetch_codes = [&](int blk, int set) {
+        if (WFMT == ELORA_W_SAME || blk >= base_blocks) return;
+        const uint8_t *W = static_cast<const uint8_t *>(ga.W);
+        const int k = blk * BK + pchunk * 8;
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) {
+            const int r = min(n0 + prow + 32 * i, N - 1);
+            rq[set][i] = *reinterpret_cast<const uint32_t *>(W + (size_t)r * (K >> 1) + (k >> 1));
+            rs[set][i] = fp16_to_f32(ga.w_scales[(size_t)r * (K >> 5) + (k >> 5)]);
+        }
+    };
+    // 4-bit W: convert pieces [i0, i1) of register set `set` to bf16 and park them in stage `buf`.
+    // w = scale * (code - 8) = fma(code, scale, -8 scale): exact in fp32 (fp16 scale times a small integer),
+    // then rounded once to bf16.
+    auto park_codes = [&](int blk, int buf, int set, int i0, int i1) {
+        if (WFMT == ELORA_W_SAME || blk >= base_blocks) return;
+        uint16_t *sb = stage0 + buf * kStageElems + BM * BK;
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) {
+            if (i < i0 || i >= i1) continue;
+            const float sc = rs[set][i], c8 = -8.0f * sc;
+            const uint32_t lo = rq[set][i] & 0x0f0f0f0fu, hi = (rq[set][i] >> 4) & 0x0f0f0f0fu;
+            u32x4 out;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                out[q] = pack_bf16x2(fmaf((float)((lo >> (8 * q)) & 0xffu), sc, c8), fmaf((float)((hi >> (8 * q)) & 0xffu), sc, c8));
+            *reinterpret_cast<u32x4 *>(sb + lds_pos(prow + 32 * i, pchunk)) = out;
         }
     };
     // make stage `buf` hold K block `blk` (everything that is not a direct load happens here)
     auto commit_block = [&](int blk, int buf) {
         uint16_t *sa = stage0 + buf * kStageElems;
         uint16_t *sb = sa + BM * BK;
-        if (blk < base_blocks) {
-            if (WFMT != ELORA_W_SAME) {
-#pragma unroll
-                for (int i = 0; i < kPieces; ++i) {
-                    // w = scale * (code - 8): exact in fp32 (fp16 scale times a small integer), rounded once to bf16
-                    u32x4 out;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int lo = (rq[i] >> (8 * q)) & 15, hi = (rq[i] >> (8 * q + 4)) & 15;
-                        out[q] = pack_bf16x2(rs[i] * (float)(lo - 8), rs[i] * (float)(hi - 8));
-                    }
-                    *reinterpret_cast<u32x4 *>(sb + lds_pos(prow + 32 * i, pchunk)) = out;
-                }
-            }
-            return;
-        }
+        if (blk < base_blocks) return;
         // expand block: K columns 8 * pchunk .. + 7 of this thread's pieces belong to exactly one item (or none)
         const int e = blk - base_blocks;
         const int kc = pchunk * 8;
@@ -415,33 +479,50 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     };
 
     issue_block(0, 0);
+    fetch_codes(0, 0);
+    park_codes(0, 0, 0, 0, kPieces);
+    fetch_codes(1, 0);
     commit_block(0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct loads have landed in LDS
     __syncthreads();
     read_frags(fr[0], 0, 0);
     // One K block per iteration, four K steps of 16.  While the matrix cores work on step s the LDS
     // reads of step s + 1 are already under way; the loads of the next block are issued at the top and
-    // land in the other stage on their own; the one barrier of the iteration sits before the last step,
-    // so that the matrix cores drain step 2 while the waves meet.
+    // land in the other stage on their own (4-bit W: its codes were fetched one iteration earlier and are
+    // converted and parked between the steps); the one barrier of the iteration sits before the last
+    // step, so that the matrix cores drain step 2 while the waves meet.
     for (int blk = 0; blk < total_blocks; ++blk) {
         const int buf = blk & 1;
         const bool more = (blk + 1) < total_blocks;
-        if (more) issue_block(blk + 1, buf ^ 1);
+        if (more) {
+            issue_block(blk + 1, buf ^ 1);
+            fetch_codes(blk + 2, 1);
+        }
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fr[1], buf, 1);
         mfma_step(fr[0]);
+        if (more) park_codes(blk + 1, buf ^ 1, 0, 0, 3);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fr[0], buf, 2);
         mfma_step(fr[1]);
+        if (more) park_codes(blk + 1, buf ^ 1, 0, 3, 6);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fr[1], buf, 3);
         mfma_step(fr[0]);
+        if (more) park_codes(blk + 1, buf ^ 1, 0, 6, kPieces);
         __builtin_amdgcn_sched_barrier(0);
         if (more) {
             commit_block(blk + 1, buf ^ 1);
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
             read_frags(fr[0], buf ^ 1, 0);
+            if (WFMT != ELORA_W_SAME) {
+#pragma unroll
+                for (int i = 0; i < kPieces; ++i) {
+                    rq[0][i] = rq[1][i];
+                    rs[0][i] = rs[1][i];
+                }
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(fr[1]);
@@ -510,8 +591,9 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
                        row_slot, row_scale);
     ELORA_HIP_TRY(hipGetLastError());
     if (a.has_pool) {
-        hipLaunchKernelGGL(sgmv_shrink_kernel, dim3((a.T + kShrinkRows - 1) / kShrinkRows), dim3(kShrinkThreads), 0, stream,
-                           a.T, a.K, static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
+        const int n_tiles = (a.T + kShrinkRows - 1) / kShrinkRows;
+        hipLaunchKernelGGL(sgmv_shrink_kernel, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
+                           static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
         ELORA_HIP_TRY(hipGetLastError());
     }
     GemmArgs ga;
