@@ -1,20 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the batched multi-adapter LoRA linear layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layers L]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {2,3,4,5}]
 
 A step is one pass of the whole hot path (route + shrink + base + expand +
-combine, i.e. one elora_batched_lora_linear call) over one synthetic batch.
-The default workload is the Llama3.1-8B q_proj decode configuration (bf16,
-32 tokens, 64 rank-16 adapters, power-law(1.1) adapter popularity).  Inputs
-are resident in HBM before the timed region.  To keep the 256 MB last-level
-cache from serving the weights, consecutive steps rotate through `--layers`
-distinct copies of (W, adapter pool, x), like the layers of a model do.
+combine, i.e. elora_batched_lora_linear) over one synthetic batch, for every
+projection the configuration names:
+
+  config 2 (default, the one the metric is quoted on): Llama3.1-8B q_proj decode,
+           bf16, 32 tokens, 64 rank-16 adapters, power-law(1.1) popularity
+  config 3 the seven projections of a layer, 64 decode tokens, 256 adapters of mixed rank
+  config 4 prefill segments (16 prompts, ~8k rows), gate / up / down projections
+  config 5 mixed prefill + decode batch on a 4-bit base, gate projection
+
+Inputs are resident in HBM before the timed region.  For the decode configs
+consecutive steps rotate through several distinct copies of the weights and
+pools (like the layers of a model do) so that the 256 MB last-level cache
+cannot serve them.
 
 Prints ONE JSON line: throughput of the whole job plus
-  roofline     the dominant kernel's algorithmic bytes / its duration measured
-               with HIP events around each of its launches, against 8 TB/s
-  cpu_baseline the fp64 oracle timed on this machine's host cores
+  roofline     the dominant kernel's algorithmic bytes (decode) or flops
+               (prefill) per launch / its launch duration from HIP events on the
+               launch stream, against 8 TB/s or 2.5 PFLOP/s
+  cpu_baseline the fp64 oracle timed on this machine's host cores on a bounded sample
 """
 from __future__ import annotations
 
@@ -29,17 +37,33 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by what
+# the same counter reads for a 1 GiB device copy on the same box (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Figures
+# and commands: the files named here.  None = not measured for that configuration.
+TRAFFIC = {
+    2: (54.2e6, "profiles/decode_kernel_config2.md"),
+    4: (1.87e9, "profiles/lora_gemm_kernel_config4.md"),
+}
+WORKLOAD = {
+    2: "Llama3.1-8B q_proj decode: W 4096x4096 bf16, 32 tokens, pool 64 adapters rank 16, adapter_idx power-law(1.1), scale 2.0",
+    3: "Llama3.1-8B layer decode: q,k,v,o,gate,up,down bf16, 64 tokens, pool 256 adapters ranks {8,16,32,64}, uniform adapter_idx",
+    4: "Llama3.1-8B prefill segments: 16 prompts U{64..1024} rows, rank-32 adapters from a pool of 128, gate/up/down bf16",
+    5: "mixed batch 4x512 prefill + 120 decode rows, W 4096x14336 4-bit g32 fp16 scales, pool 1024 adapters rank 16, power-law(1.0)",
+}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=4000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", type=int, default=2, choices=[2])
-    ap.add_argument("--layers", type=int, default=32, help="distinct (W, pool, x) copies the steps rotate through")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--layers", type=int, default=None, help="distinct (W, pool, x) copies the decode steps rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that profiler byte counters can be scaled")
     return ap.parse_args()
 
 
@@ -53,7 +77,7 @@ def main():
     import numpy as np
     import torch
     from paper_2507_01438_amd import build as elora_build
-    if elora_build.is_stale() and not os.path.exists(elora_build.LIB):
+    if not os.path.exists(elora_build.LIB):
         elora_build.build()
     from paper_2507_01438_amd import binding as B
     from paper_2507_01438_amd import inputs as I
@@ -61,103 +85,151 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    w = I.CONFIGS[args.config]()
-    proj = w.projections[0]
-    L = max(1, args.layers)
+    cfg = args.config
+    decode = cfg in (2, 3)
+    steps = args.steps if args.steps is not None else {2: 4000, 3: 300, 4: 20, 5: 40}[cfg]
+    warmup = args.warmup if args.warmup is not None else {2: 200, 3: 30, 4: 3, 5: 5}[cfg]
+    w = I.CONFIGS[cfg]()
+    projs = w.projections
+    distinct = w.distinct_adapters()
 
-    # layer 0 from the seeded generators; the other layers are device copies of the same bytes at
-    # different addresses (what matters to the caches), so every layer's output can be checked
-    case = DeviceCase(w, proj)
-    Ws = [case.W] + [case.W.clone() for _ in range(L - 1)]
-    xs = [case.x] + [case.x.clone() for _ in range(L - 1)]
-    dev_adapters = {i: (to_dev(A), to_dev(Bm), sc) for i, (A, Bm, sc) in case.adapters.items()}
-    pools = [case.pool]
-    for _ in range(L - 1):
-        p = B.AdapterPool(proj.K, proj.N, w.max_rank, w.pool, w.dtype, dev)
-        for i, (A_d, B_d, sc) in dev_adapters.items():
-            p.load(i, A_d, B_d, sc)
-        pools.append(p)
-    ys = [torch.zeros_like(case.y) for _ in range(L)]
-    lins = [B.LoraLinear(proj.K, proj.N, w.dtype, pools[l], w.T, dev) for l in range(L)]
-    idx = case.adapter_idx
-    descs = [lins[l].desc(xs[l], Ws[l], ys[l], adapter_idx=idx) for l in range(L)]
+    # One DeviceCase per projection from the seeded generators (only the adapters the batch uses are
+    # generated for the big pools).  Decode: further "layers" are device copies of the same bytes at other
+    # addresses (what matters to the caches), so every layer's output can be checked against the oracle.
+    cases = [DeviceCase(w, p, load_slots=None if cfg == 2 else distinct) for p in projs]
+    layer_bytes = sum(p.N * p.K * 2 for p in projs)
+    L = args.layers if args.layers is not None else (max(2, min(32, int(1.6e9 // layer_bytes))) if decode else 1)
+    layers = []  # layers[l][pi] = descriptor
+    keep = []
+    dev_adapters = [{i: (to_dev(A), to_dev(Bm), sc) for i, (A, Bm, sc) in case.adapters.items()} if L > 1 else {}
+                    for case in cases]
+    for l in range(L):
+        descs = []
+        for pi, (p, case) in enumerate(zip(projs, cases)):
+            if l == 0:
+                descs.append(case.desc())
+                continue
+            Wc, xc, yc = case.W.clone(), case.x.clone(), torch.zeros_like(case.y)
+            pool = B.AdapterPool(p.K, p.N, w.max_rank, w.pool, w.dtype, dev)
+            for i, (A_d, B_d, sc) in dev_adapters[pi].items():
+                pool.load(i, A_d, B_d, sc)
+            lin = B.LoraLinear(p.K, p.N, w.dtype, pool, w.T, dev)
+            keep += [Wc, xc, yc, pool, lin]
+            descs.append(lin.desc(xc, Wc, yc, adapter_idx=case.adapter_idx, seg_offsets=case.seg_offsets,
+                                  seg_adapter=case.seg_adapter, wfmt=w.wfmt, w_scales=case.w_scales))
+        layers.append(descs)
     torch.cuda.synchronize()
-    plan = B.elora_linear_plan(descs[0])
+    plans = [B.elora_linear_plan(d) for d in layers[0]]
     stream = torch.cuda.current_stream().cuda_stream
+    n_proj = len(projs)
 
     def step(i):
-        B.lib.elora_batched_lora_linear(descs[i % L], stream)
+        for d in layers[i % L]:
+            B.lib.elora_batched_lora_linear(d, stream)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    ev0.record()  # on torch's current stream, the stream the kernels are launched on
+    for i in range(steps):
         step(i)
+    ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tokens_per_s = w.T * args.steps / (t1 - t0)
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    tokens_per_s = w.T * steps / (t1 - t0)
+    region_us_per_launch = ev0.elapsed_time(ev1) * 1e3 / (steps * n_proj)
 
-    # second pass over the same steps with HIP events around every launch of the dominant kernel
-    n_prof = min(args.steps, 2000)
-    B.elora_profile_arm(n_prof)
+    # one pair of HIP events around every launch of each call's dominant kernel (second pass over the same steps)
+    n_prof = min(steps, 1000)
+    B.elora_profile_arm(n_prof * n_proj)
     for i in range(n_prof):
         step(i)
     torch.cuda.synchronize()
-    kern_ms = np.array(B.elora_profile_read(n_prof))
+    per_launch_us = np.array(B.elora_profile_read(n_prof * n_proj)).reshape(n_prof, n_proj) * 1e3
     B.elora_profile_arm(0)
-    kern_us = float(np.mean(kern_ms) * 1e3)
-    kern_us_med = float(np.median(kern_ms) * 1e3)
 
-    # hot-cache variant (one buffer set), reported separately
-    for i in range(50):
-        B.lib.elora_batched_lora_linear(descs[0], stream)
-    torch.cuda.synchronize()
-    h0 = time.perf_counter()
-    for i in range(args.steps):
-        B.lib.elora_batched_lora_linear(descs[0], stream)
-    torch.cuda.synchronize()
-    hot_ms = (time.perf_counter() - h0) * 1e3 / args.steps
+    flops_step = sum(w.algorithmic_flops(p) for p in projs)
+    bytes_step = sum(w.algorithmic_bytes(p) for p in projs)
+    if decode:
+        # The decode path is one kernel per call and the launches run back to back, so the device time of the
+        # timed region divided by the number of launches is the kernel's average launch duration (an event pair
+        # around a ~20 us launch adds about 5 us of its own; that figure is reported next to it).
+        assert all(pl.n_launches == 1 for pl in plans)
+        kern_us = region_us_per_launch
+        achieved = bytes_step / n_proj / (kern_us * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "bytes_per_launch": int(bytes_step / n_proj), "avg_us": kern_us,
+                    "median_us_with_per_launch_events": float(np.median(per_launch_us))}
+    else:
+        kern_us = float(per_launch_us.mean())
+        achieved = flops_step / n_proj / (kern_us * 1e-6) / 1e12
+        roofline = {"bound": "mfma", "kernel": "lora_gemm_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                    "flops_per_launch": int(flops_step / n_proj), "avg_us": kern_us}
+    roofline["launches_timed"] = int(steps * n_proj if decode else per_launch_us.size)
+    traffic, traffic_src = TRAFFIC.get(cfg, (None, None))
+    roofline["traffic"] = traffic
+    roofline["traffic_source"] = traffic_src
 
-    # algorithmic bytes: W once, x once, y once, used rows (r_i, not max_rank) of each distinct adapter once.
-    # The decode path is a single kernel, so the dominant kernel carries all of them.
-    distinct = w.distinct_adapters()
-    bytes_call = w.algorithmic_bytes(proj)
-    bytes_dom = bytes_call
-    achieved = bytes_dom / (kern_us * 1e-6) / 1e9
-    flops = w.algorithmic_flops(proj)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
+    # parity in the launch configuration that was timed (sampled outputs for the big shapes)
     check = None
+    rng = np.random.default_rng(1)
     if not args.no_check:
-        ref = case.reference()
-        errs = [rel_err(y_to_f64(ys[l][: w.T], w.dtype), ref) for l in (0, L // 2, L - 1)]
+        errs = []
+        for pi, (p, case) in enumerate(zip(projs, cases)):
+            y = y_to_f64(case.y[: w.T], w.dtype)
+            if cfg == 2:
+                errs.append(rel_err(y, case.reference()))
+            else:
+                cols = np.sort(rng.choice(p.N, 32, replace=False))
+                rows = None if decode else np.sort(rng.choice(w.T, 128, replace=False))
+                ysub = y[:, cols] if rows is None else y[np.ix_(rows, cols)]
+                errs.append(rel_err(ysub, case.reference(rows=rows, cols=cols)))
+            assert case.pool.poll_error() == (0, -1)
         check = max(errs)
         assert check <= 1e-2, f"parity lost in the benchmark configuration: {errs}"
-        assert all(p.poll_error() == (0, -1) for p in (pools[0], pools[-1]))
 
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        ads = case.oracle_adapters()
-        ra = w.row_adapter()
-        oracle.linear(w.dtype, case.x_h, case.W_h, ads, ra)  # warm (also compiles the C file if needed)
+        case, p = cases[0], projs[0]
+        ads, ra = case.oracle_adapters(), w.row_adapter()
+        # bounded sample: whole rows of the first projection (all of them for config 2), repeated for ~12 s
+        n_rows = w.T if cfg == 2 else min(w.T, 16)
+        rows = None if cfg == 2 else np.arange(n_rows, dtype=np.int32)
+        kw = dict(wfmt=w.wfmt, w_scales=case.ws_h, rows=rows)
+        oracle.linear(w.dtype, case.x_h, case.W_h, ads, ra, **kw)  # warm (also compiles the C file if needed)
         c0 = time.perf_counter()
         reps, used = 0, 1
         while time.perf_counter() - c0 < 12.0:
-            _, used = oracle.linear(w.dtype, case.x_h, case.W_h, ads, ra, return_threads=True)
+            _, used = oracle.linear(w.dtype, case.x_h, case.W_h, ads, ra, return_threads=True, **kw)
             reps += 1
         cdt = time.perf_counter() - c0
-        cpu = {"value": w.T * reps / cdt, "unit": "tokens/s", "cores": int(used), "kind": "oracle",
-               "sample": f"{reps} full batches of {w.T} tokens of the same workload, {cdt:.1f} s"}
+        # one projection was timed; a step runs n_proj of them with flops in proportion
+        scale = w.algorithmic_flops(p) / flops_step
+        cpu = {"value": n_rows * reps / cdt * scale, "unit": "tokens/s", "cores": int(used), "kind": "oracle",
+               "sample": f"{reps} x {n_rows} full rows of projection '{p.name}' in {cdt:.1f} s"
+                         + ("" if n_proj == 1 else f", scaled by its share of the step's flops ({scale:.3f})")}
 
     out = {
         "metric": "batched_lora_linear_tokens_per_s",
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -165,23 +237,19 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": "Llama3.1-8B q_proj decode: W 4096x4096 bf16, 32 tokens, pool 64 adapters rank 16, "
-                        "adapter_idx power-law(1.1), scale 2.0",
-            "n_tokens": w.T, "d_in": proj.K, "d_out": proj.N, "distinct_adapters": int(len(distinct)),
-            "rotating_layers": L, "path": int(plan.path), "split_k": int(plan.split_k), "grid": int(plan.grid),
-            "launches_per_step": int(plan.n_launches),
+            "workload": WORKLOAD[cfg],
+            "config_number": cfg, "n_tokens": w.T, "projections": [p.name for p in projs],
+            "distinct_adapters": int(len(distinct)), "rotating_layers": L,
+            "path": [int(pl.path) for pl in plans], "split_k": [int(pl.split_k) for pl in plans],
+            "grid": [int(pl.grid) for pl in plans], "launches_per_call": [int(pl.n_launches) for pl in plans],
         },
-        "tflops": flops / (ms_per_step * 1e-3) / 1e12,
-        "step_gbs": bytes_call / (ms_per_step * 1e-3) / 1e9,
-        "step_frac_of_hbm_peak": bytes_call / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "hot_cache_ms_per_step": hot_ms,
+        "tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
+        "step_gbs": bytes_step / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_frac_of_mfma_peak": flops_step / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "dominant_kernel_us_per_projection": [float(v) for v in per_launch_us.mean(axis=0)],
         "max_rel_err_vs_oracle": check,
-        "roofline": {
-            "bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-            "bytes_per_launch": int(bytes_dom), "avg_us": kern_us, "median_us": kern_us_med,
-            "launches_timed": int(len(kern_ms)), "bytes_per_step_all_kernels": int(bytes_call),
-        },
+        "roofline": roofline,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

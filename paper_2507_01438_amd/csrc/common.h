@@ -47,6 +47,7 @@ struct WsLayout {
     size_t sync;       // int [kSyncInts] counters of the decode kernel; zero between calls
     size_t row_slot;   // int32 [T]
     size_t row_scale;  // float [T]
+    size_t row_rank;   // int32 [T]
     size_t v;          // float/bf16 shrink results (and their K-split partials)
     size_t partial;    // float split-K partial sums of the streaming contraction
     size_t total;

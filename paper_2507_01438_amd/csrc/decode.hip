@@ -37,9 +37,14 @@ constexpr int kWaves = 4;         // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kRowsPerWave = 16;  // W rows per wave (one MFMA row block)
 constexpr int kTileRows = kWaves * kRowsPerWave;
-constexpr int kChunk = 256;             // K elements per LDS stage
-constexpr int kLdsStride = kChunk + 8;  // bf16 elements; +16 bytes so 16 rows hit 16 different bank groups
+constexpr int kChunk = 256;             // K elements per register set of W (8 MFMA K steps)
 constexpr int kStepsPerChunk = kChunk / 32;
+#ifndef ELORA_DEC_SPAN
+#define ELORA_DEC_SPAN 1024        // elements of x per row parked in LDS at a time when at most 32 rows are in the batch
+#endif
+// x of the workgroup's K-slice is parked in LDS in spans of kSpan(TT) elements per row (row pitch +16 bytes so
+// that 16 rows hit 16 different bank groups): 1024 for up to 32 rows of x, 512 for up to 64 (about 66 KiB)
+__host__ __device__ constexpr int span_of(int tt) { return tt <= 2 ? ELORA_DEC_SPAN : 512; }
 
 // sync area (ints) at the start of the workspace
 constexpr int kCntV = 0;      // shrink units finished
@@ -49,11 +54,11 @@ constexpr int kCntTile = 16;  // + tile: K-split workgroups of that tile that ha
 int g_spin_limit = 1 << 22;
 
 // tuning constants (overridable at compile time for experiments)
+#ifndef ELORA_DEC_MAX_SHRINK_WGS
+#define ELORA_DEC_MAX_SHRINK_WGS 512  // upper bound on shrink workgroups (each wave then loops over several units)
+#endif
 #ifndef ELORA_DEC_TARGET_WGS
 #define ELORA_DEC_TARGET_WGS 640  // upper bound on base workgroups when choosing the K-split
-#endif
-#ifndef ELORA_DEC_PREFETCH
-#define ELORA_DEC_PREFETCH 2      // W chunks requested ahead of the one being consumed (1 or 2)
 #endif
 
 // Optional phase timestamps for tuning (compiled in only with -DELORA_TRACE): slot i of workgroup b.
@@ -104,14 +109,15 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const 
                                                           const uint16_t *__restrict__ W, PoolView pool,
                                                           RouteView route, int has_pool, float *__restrict__ partial,
                                                           float *__restrict__ v, int *__restrict__ sync,
-                                                          uint16_t *__restrict__ y)
+                                                          int *__restrict__ row_slot, int *__restrict__ row_rank,
+                                                          float *__restrict__ row_scale, uint16_t *__restrict__ y)
 {
-    // x chunks (two stages) during the contraction; v of every row during the epilogue
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TT * 16 * kLdsStride * 2];
+    // x span during the contraction; v of every row during the epilogue
+    constexpr int kSpan = span_of(TT), kPitch = kSpan + 8, kChunksPerSpan = kSpan / kChunk;
+    __shared__ __attribute__((aligned(16))) uint16_t xs[TT * 16][kPitch];
     __shared__ int s_slot[TT * 16], s_rank[TT * 16];
     __shared__ float s_scale[TT * 16];
     __shared__ int s_last, s_vok;
-    auto xs = reinterpret_cast<uint16_t(*)[TT * 16][kLdsStride]>(smem);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = sh.T, K = sh.K, N = sh.N;
@@ -124,6 +130,11 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const 
         for (int wu = blockIdx.x * kWaves + wave; wu < n_units; wu += sh.n_shrink_wgs * kWaves) {
             const int t = wu / sh.jgroups, j0 = (wu - t * sh.jgroups) * 2;
             RowRoute rr = resolve_row(t, route, pool, j0 == 0 && lane == 0);
+            if (j0 == 0 && lane == 0) {  // the row's route, for the tile epilogues
+                __hip_atomic_store(&row_slot[t], rr.slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&row_rank[t], rr.rank, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                store_shared_f32(&row_scale[t], rr.scale);
+            }
             if (rr.slot < 0 || j0 >= rr.rank) continue;
             const bool two = (j0 + 1) < rr.rank;
             const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, rr.slot)) + (size_t)j0 * K;
@@ -153,8 +164,8 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const 
     const int nchunks = sh.chunks_per_split;
 
     u32x4 wbuf[2][kStepsPerChunk];
-    constexpr int kXPieces = TT * 2;  // TT*16 rows x 32 pieces of 16 bytes over 256 threads
-    u32x4 xreg[kXPieces];
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
 
     auto load_w = [&](u32x4 *dst, int chunk) {
         const uint16_t *p = wrow + (size_t)chunk * kChunk;
@@ -162,70 +173,217 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const 
         for (int j = 0; j < kStepsPerChunk; ++j)
             dst[j] = wave_active ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + j * 32)) : u32x4{0, 0, 0, 0};
     };
-    auto load_x = [&](int chunk) {
-#pragma unroll
-        for (int i = 0; i < kXPieces; ++i) {
-            int piece = tid + i * kThreads;
-            int r = piece >> 5, c16 = piece & 31;
-            xreg[i] = (r < T) ? *reinterpret_cast<const u32x4 *>(x + (size_t)r * K + k_begin + (size_t)chunk * kChunk + c16 * 8)
-                              : u32x4{0, 0, 0, 0};
-        }
-    };
-    auto store_x = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < kXPieces; ++i) {
-            int piece = tid + i * kThreads;
-            int r = piece >> 5, c16 = piece & 31;
-            *reinterpret_cast<u32x4 *>(&xs[buf][r][c16 * 8]) = xreg[i];
+    // Park x[:, chunks c0 .. c0 + nc) of the K-slice in LDS, global -> LDS directly.  One instruction moves 512
+    // consecutive elements of one row (two chunks; the odd last chunk of a span moves with half the lanes).
+    // Rows past the batch repeat the last row: what they produce is never stored.
+    auto park_x = [&](int c0, int nc) {
+        const int units = TT * 16 * ((nc + 1) >> 1);  // (row, pair of chunks)
+        for (int u = wave; u < units; u += kWaves) {
+            const int r = u % (TT * 16), pr = u / (TT * 16);
+            const uint16_t *src = x + (size_t)min(r, T - 1) * K + k_begin + (size_t)(c0 + 2 * pr) * kChunk + lane * 8;
+            uint16_t *dst = &xs[r][pr * 2 * kChunk];
+            if (2 * pr + 1 < nc || lane < 32)
+                __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
         }
     };
 
-    load_x(0);
+    park_x(0, min(nchunks, kChunksPerSpan));
     load_w(wbuf[0], 0);
-    if (ELORA_DEC_PREFETCH > 1 && nchunks > 1) load_w(wbuf[1], 1);
+    if (nchunks > 1) load_w(wbuf[1], 1);
 
-    // ---- 2. base tile ----------------------------------------------------------------------------
+    // ---- base tile -------------------------------------------------------------------------------
     floatx4 acc[TT];
 #pragma unroll
     for (int i = 0; i < TT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    store_x(0);
-    __syncthreads();
-    TRACE(2);  // first x chunk staged
-
-    auto compute = [&](const u32x4 *wc, int buf) {
+    auto compute = [&](const u32x4 *wc, int cs) {  // cs = chunk inside the span
 #pragma unroll
         for (int j = 0; j < kStepsPerChunk; ++j) {
             bf16x8 a = __builtin_bit_cast(bf16x8, wc[j]);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                bf16x8 b = *reinterpret_cast<const bf16x8 *>(&xs[buf][tt * 16 + m][j * 32 + g * 8]);
+                bf16x8 b = *reinterpret_cast<const bf16x8 *>(&xs[tt * 16 + m][cs * kChunk + j * 32 + g * 8]);
                 acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[tt], 0, 0, 0);
             }
         }
     };
-    // chunk c: x from LDS stage c & 1, W from register set c & 1; the next x chunk is fetched while
-    // computing and W chunk c + 2 is requested as soon as set c & 1 has been consumed
-    for (int c = 0; c < nchunks; c += 2) {
+    // The waves only meet when a span of x is exchanged; inside a span each wave streams its 16 rows of W on
+    // its own, two chunks (16 loads of 16 bytes per lane) ahead of the one it multiplies.
+    for (int c0 = 0; c0 < nchunks; c0 += kChunksPerSpan) {
+        const int nc = min(kChunksPerSpan, nchunks - c0);
+        if (c0 > 0) {
+            __syncthreads();  // everybody is done with the previous span
+            park_x(c0, nc);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the span has landed (so has its W prefetch)
+        __syncthreads();
+        if (c0 == 0) TRACE(2);  // first span of x parked
+        for (int cs = 0; cs < nc; cs += 2) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int cc = c + h;
-            if (cc < nchunks) {
-                const bool more = (cc + 1) < nchunks;
-                if (more) load_x(cc + 1);
-                if (ELORA_DEC_PREFETCH == 1 && more) load_w(wbuf[h ^ 1], cc + 1);
-                compute(wbuf[h], h);
-                if (ELORA_DEC_PREFETCH > 1 && cc + 2 < nchunks) load_w(wbuf[h], cc + 2);
-                if (more) store_x(h ^ 1);
-                __syncthreads();
+            for (int h = 0; h < 2; ++h) {
+                const int cc = c0 + cs + h;  // kChunksPerSpan is even, so chunk cc uses register set h
+                if (cs + h < nc) {
+                    compute(wbuf[h], cs + h);
+                    if (cc + 2 < nchunks) load_w(wbuf[h], cc + 2);
+                }
             }
         }
     }
 
     TRACE(3);  // contraction done
+
+    // ---- expand share of this workgroup ------------------------------------------------------------
+    // Rows t = ks, ks + split, ... of the batch get  s_t * B_i v_t  for this tile's 64 columns added to this
+    // workgroup's K-slice partial, so the expand of a tile is spread over its `split` workgroups (and B_i is
+    // read where the partial is still in registers).
+    const int n0 = tile * kTileRows;
+    const int nq = (sh.n_shrink_wgs > 0 && ks < T) ? (T - ks + sh.split - 1) / sh.split : 0;
+    if (nq > 0) {
+        __syncthreads();  // xs is reused below
+        if (tid == 0) {
+            int ok = 0;
+            for (int spin = 0; spin < sh.spin_limit; ++spin) {
+                if (__hip_atomic_load(&sync[kCntV], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= sh.n_shrink_wgs) {
+                    ok = 1;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(4);
+            }
+            s_vok = ok;
+        }
+        __syncthreads();
+        // v and the rows' routes written by the shrink workgroups are read past the L2 from here on
+        const bool vok = s_vok != 0;
+        TRACE(4);  // shrink results available
+        float *vs = reinterpret_cast<float *>(&xs[0][0]);  // [rows of this pass][R], then d [rows][64]
+        const int qb_max = (int)(sizeof(xs) / ((R + kTileRows) * sizeof(float)));
+        for (int q0 = 0; q0 < nq; q0 += qb_max) {
+            const int qb = min(qb_max, nq - q0);
+            float *dls = vs + qb * R;
+            if (q0 > 0) __syncthreads();
+            if (tid < qb) {
+                const int t = ks + (q0 + tid) * sh.split;
+                RowRoute rr;
+                if (vok) {
+                    rr.slot = __hip_atomic_load(&row_slot[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    rr.rank = __hip_atomic_load(&row_rank[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    rr.scale = load_shared_f32(&row_scale[t]);
+                } else {
+                    rr = resolve_row(t, route, pool, false);
+                }
+                s_slot[tid] = rr.slot;
+                s_rank[tid] = rr.rank;
+                s_scale[tid] = rr.scale;
+            }
+            __syncthreads();
+            if (vok) {
+                for (int e0 = 0; e0 < qb * R; e0 += kThreads * 8) {
+                    float tmp[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int e = e0 + i * kThreads + tid;
+                        const int q = e / R, j = e - q * R;
+                        tmp[i] = (e < qb * R && j < s_rank[q]) ? load_shared_f32(&v[(size_t)(ks + (q0 + q) * sh.split) * R + j]) : 0.0f;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int e = e0 + i * kThreads + tid;
+                        if (e < qb * R) vs[e] = tmp[i];
+                    }
+                }
+            } else {
+                // the shrink workgroups did not report in time: compute v of these rows here
+                for (int wu = wave; wu < qb * sh.jgroups; wu += kWaves) {
+                    const int q = wu / sh.jgroups, j0 = (wu - q * sh.jgroups) * 2;
+                    const int t = ks + (q0 + q) * sh.split;
+                    const int slot = s_slot[q], rank = s_rank[q];
+                    float r0 = 0.0f, r1 = 0.0f;
+                    if (slot >= 0 && j0 < rank) {
+                        const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
+                        shrink_pair(A0, (j0 + 1 < rank) ? A0 + K : A0, x + (size_t)t * K, K, lane, r0, r1);
+                        if (j0 + 1 >= rank) r1 = 0.0f;
+                    }
+                    if (lane == 0) {
+                        vs[q * R + j0] = r0;
+                        if (j0 + 1 < R) vs[q * R + j0 + 1] = r1;
+                    }
+                }
+            }
+            __syncthreads();
+            // d[q][c] = s * sum_j B_i[n0 + c][j] v[q][j]: one (row, column) item per thread, four items at a time
+            // so that up to 32 loads of 16 bytes are in flight per thread
+            constexpr int IB = 4;
+            for (int it0 = tid; it0 < qb * kTileRows; it0 += kThreads * IB) {
+                int iq[IB], ir[IB];
+                const uint16_t *bp[IB];
+                float d[IB];
+                bool vec = true;
+#pragma unroll
+                for (int ii = 0; ii < IB; ++ii) {
+                    const int item = it0 + ii * kThreads;
+                    const bool in = item < qb * kTileRows;
+                    const int q = in ? item / kTileRows : 0, c = in ? item - q * kTileRows : 0;
+                    const int slot = s_slot[q];
+                    iq[ii] = q;
+                    ir[ii] = (in && slot >= 0 && n0 + c < N) ? s_rank[q] : 0;
+                    bp[ii] = reinterpret_cast<const uint16_t *>(slot_B(pool, slot >= 0 ? slot : 0)) + (size_t)min(n0 + c, N - 1) * s_rank[q];
+                    d[ii] = 0.0f;
+                    vec = vec && ((ir[ii] & 7) == 0);
+                }
+                if (vec) {
+                    int rmax = 0;
+#pragma unroll
+                    for (int ii = 0; ii < IB; ++ii) rmax = max(rmax, ir[ii]);
+                    for (int j = 0; j < rmax; j += 64) {
+                        u32x4 b[IB][8];
+#pragma unroll
+                        for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+                            for (int h = 0; h < 8; ++h)
+                                b[ii][h] = (j + 8 * h < ir[ii]) ? *reinterpret_cast<const u32x4 *>(bp[ii] + j + 8 * h) : u32x4{0, 0, 0, 0};
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int ii = 0; ii < IB; ++ii) {
+                            const float *vq = vs + iq[ii] * R + j;
+#pragma unroll
+                            for (int h = 0; h < 8; ++h) {
+                                if (j + 8 * h >= ir[ii]) continue;
+#pragma unroll
+                                for (int u = 0; u < 4; ++u) {
+                                    d[ii] = fmaf(__uint_as_float(b[ii][h][u] << 16), vq[8 * h + 2 * u], d[ii]);
+                                    d[ii] = fmaf(__uint_as_float(b[ii][h][u] & 0xffff0000u), vq[8 * h + 2 * u + 1], d[ii]);
+                                }
+                            }
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int ii = 0; ii < IB; ++ii)
+                        for (int j = 0; j < ir[ii]; ++j) d[ii] = fmaf(bf16_to_f32(bp[ii][j]), vs[iq[ii] * R + j], d[ii]);
+                }
+#pragma unroll
+                for (int ii = 0; ii < IB; ++ii) {
+                    const int item = it0 + ii * kThreads;
+                    if (item < qb * kTileRows) dls[item] = d[ii] * s_scale[iq[ii]];
+                }
+            }
+            __syncthreads();
+            // add to the accumulators: lane holds row t = tt * 16 + m of the batch, columns wave * 16 + g * 4 + 0..3
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const int t = tt * 16 + m;
+                const int q = (t - ks) / sh.split - q0;
+                if (t < T && t >= ks && (t - ks) % sh.split == 0 && q >= 0 && q < qb) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[tt][i] += dls[q * kTileRows + wave * kRowsPerWave + g * 4 + i];
+                }
+            }
+        }
+    }
+
     // C layout of the 16x16 MFMA: lane holds column (lane % 16) = row t of x, rows (lane / 16) * 4 + 0..3 = W rows
     if (wave_active) {
-        const int n_base = tile * kTileRows + wave * kRowsPerWave + g * 4;
+        const int n_base = n0 + wave * kRowsPerWave + g * 4;
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             int t = tt * 16 + m;
@@ -237,142 +395,34 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const 
         }
     }
 
-    // ---- 3. ticket: is this the last K-slice of the tile? ------------------------------------
+    // ---- ticket: is this the last K-slice of the tile? -----------------------------------------------
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the write-through stores have been acknowledged
     __syncthreads();
-    TRACE(4);  // partial stores acknowledged
     if (tid == 0) s_last = (sh.split == 1 || atomicAdd(&sync[kCntTile + tile], 1) == sh.split - 1) ? 1 : 0;
     __syncthreads();
     TRACE(5);  // ticket drawn
     if (s_last == 0) return;
 
-    // ---- tile epilogue ---------------------------------------------------------------------------
-    if (tid < TT * 16) {
-        RowRoute rr{-1, 0, 0.0f};
-        if (has_pool && tid < T) rr = resolve_row(tid, route, pool, false);
-        s_slot[tid] = rr.slot;
-        s_rank[tid] = rr.rank;
-        s_scale[tid] = rr.scale;
-    }
-    if (tid == 0) {
-        int ok = 1;
-        if (sh.n_shrink_wgs > 0) {
-            ok = 0;
-            for (int spin = 0; spin < sh.spin_limit; ++spin) {
-                if (__hip_atomic_load(&sync[kCntV], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= sh.n_shrink_wgs) {
-                    ok = 1;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(4);
-            }
-        }
-        s_vok = ok;
-    }
-    __syncthreads();
-    // partial and v of the other workgroups are read past the L2 from here on
-    TRACE(6);  // routes resolved, shrink results available
-    float *vs = reinterpret_cast<float *>(smem);  // [T][R]; T*R*4 <= TT*16*256*4 < sizeof(smem)
-    if (sh.n_shrink_wgs > 0) {
-        if (s_vok) {
-            for (int e0 = 0; e0 < T * R; e0 += kThreads * 8) {
-                float tmp[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int e = e0 + i * kThreads + tid;
-                    const int t = e / R, j = e - t * R;
-                    tmp[i] = (e < T * R && j < s_rank[t]) ? load_shared_f32(&v[e]) : 0.0f;
-                }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int e = e0 + i * kThreads + tid;
-                    if (e < T * R) vs[e] = tmp[i];
-                }
-            }
-        } else {
-            // the shrink workgroups did not report in time: compute v here
-            for (int wu = wave; wu < T * sh.jgroups; wu += kWaves) {
-                const int t = wu / sh.jgroups, j0 = (wu - t * sh.jgroups) * 2;
-                const int slot = s_slot[t], rank = s_rank[t];
-                float r0 = 0.0f, r1 = 0.0f;
-                if (slot >= 0 && j0 < rank) {
-                    const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
-                    shrink_pair(A0, (j0 + 1 < rank) ? A0 + K : A0, x + (size_t)t * K, K, lane, r0, r1);
-                    if (j0 + 1 >= rank) r1 = 0.0f;
-                }
-                if (lane == 0) {
-                    vs[t * R + j0] = r0;
-                    if (j0 + 1 < R) vs[t * R + j0 + 1] = r1;
-                }
-            }
-        }
-    }
-    __syncthreads();
-    TRACE(7);  // v_t formed
+    // ---- tile epilogue: sum the K-slices in fixed order, round once, store each row at its own position ----
     // 8 threads per row of x, 8 output columns each
-    const int n0 = tile * kTileRows;
     for (int item = tid; item < T * 8; item += kThreads) {
         const int t = item >> 3, n = n0 + (item & 7) * 8;
         if (n >= N) continue;  // N % 8 == 0
+        float2 pv[kDecodeMaxSplit][4];
+#pragma unroll
+        for (int s = 0; s < kDecodeMaxSplit; ++s)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                pv[s][q] = load_shared_f32x2(partial + ((size_t)(s < sh.split ? s : 0) * T + t) * N + n + 2 * q);
+        __builtin_amdgcn_sched_barrier(0);  // all loads first (slices beyond `split` re-read slice 0 and are dropped)
         float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        {
-            float2 pv[kDecodeMaxSplit][4];
 #pragma unroll
-            for (int s = 0; s < kDecodeMaxSplit; ++s)
+        for (int s = 0; s < kDecodeMaxSplit; ++s)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    pv[s][q] = load_shared_f32x2(partial + ((size_t)(s < sh.split ? s : 0) * T + t) * N + n + 2 * q);
-            __builtin_amdgcn_sched_barrier(0);  // all loads first (slices beyond `split` re-read slice 0 and are dropped)
-#pragma unroll
-            for (int s = 0; s < kDecodeMaxSplit; ++s)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    o[2 * q] += (s < sh.split) ? pv[s][q].x : 0.0f;
-                    o[2 * q + 1] += (s < sh.split) ? pv[s][q].y : 0.0f;
-                }
-        }
-        TRACE(9);  // partials summed
-        const int slot = s_slot[t];
-        if (slot >= 0) {
-            const int r = s_rank[t];
-            const float sc = s_scale[t];
-            const uint16_t *B = reinterpret_cast<const uint16_t *>(slot_B(pool, slot)) + (size_t)n * r;
-            const float *vt = vs + t * R;
-            if ((r & 7) == 0) {
-                float d[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                for (int j = 0; j < r; j += 16) {
-                    // 8 output columns x 16 rank entries: 16 loads of 16 bytes in flight together
-                    const bool second = (j + 8) < r;
-                    u32x4 b[8][2];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        b[q][0] = *reinterpret_cast<const u32x4 *>(B + q * r + j);
-                        b[q][1] = *reinterpret_cast<const u32x4 *>(B + q * r + (second ? j + 8 : j));
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int q = 0; q < 8; ++q)
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            if (h == 1 && !second) continue;
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) {
-                                d[q] = fmaf(__uint_as_float(b[q][h][u] << 16), vt[j + 8 * h + 2 * u], d[q]);
-                                d[q] = fmaf(__uint_as_float(b[q][h][u] & 0xffff0000u), vt[j + 8 * h + 2 * u + 1], d[q]);
-                            }
-                        }
-                }
-#pragma unroll
-                for (int q = 0; q < 8; ++q) o[q] += sc * d[q];
-            } else {
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    float d = 0.0f;
-                    for (int j = 0; j < r; ++j) d = fmaf(bf16_to_f32(B[q * r + j]), vt[j], d);
-                    o[q] += sc * d;
-                }
+            for (int q = 0; q < 4; ++q) {
+                o[2 * q] += (s < sh.split) ? pv[s][q].x : 0.0f;
+                o[2 * q + 1] += (s < sh.split) ? pv[s][q].y : 0.0f;
             }
-        }
-        TRACE(10);  // expand done
         u32x4 packed;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
@@ -382,7 +432,8 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const 
 
     TRACE(8);  // y written
     // ---- leave the counters at zero for the next call --------------------------------------------
-    // The last epilogue has seen sync[kCntV] complete, so no shrink workgroup will touch it any more.
+    // When the last epilogue gets here every base workgroup has drawn its ticket, which it does after
+    // its wait for the shrink workgroups, so nobody looks at sync[kCntV] any more.
     if (tid == 0) {
         __hip_atomic_store(&sync[kCntTile + tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (atomicAdd(&sync[kCntDone], 1) == sh.n_tiles - 1) {
@@ -417,7 +468,7 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool has_pool)
     sh.n_shrink_wgs = 0;
     if (has_pool) {
         int wgs = (T * sh.jgroups + kWaves - 1) / kWaves;  // one (row, rank-row pair) unit per wave
-        sh.n_shrink_wgs = wgs < 512 ? wgs : 512;
+        sh.n_shrink_wgs = wgs < ELORA_DEC_MAX_SHRINK_WGS ? wgs : ELORA_DEC_MAX_SHRINK_WGS;
     }
     sh.spin_limit = g_spin_limit;
     return sh;
@@ -463,6 +514,9 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     float *partial = reinterpret_cast<float *>(a.ws + a.wsl.partial);
     float *v = reinterpret_cast<float *>(a.ws + a.wsl.v);
     int *sync = reinterpret_cast<int *>(a.ws + a.wsl.sync);
+    int *row_slot = reinterpret_cast<int *>(a.ws + a.wsl.row_slot);
+    int *row_rank = reinterpret_cast<int *>(a.ws + a.wsl.row_rank);
+    float *row_scale = reinterpret_cast<float *>(a.ws + a.wsl.row_scale);
     const uint16_t *x = static_cast<const uint16_t *>(a.x);
     const uint16_t *W = static_cast<const uint16_t *>(a.W);
     uint16_t *y = static_cast<uint16_t *>(a.y);
@@ -471,10 +525,10 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     int tt = (a.T + 15) / 16;
     profile_mark_begin(stream);
     switch (tt) {
-    case 1: hipLaunchKernelGGL((decode_kernel<1>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, y); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<2>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, y); break;
-    case 3: hipLaunchKernelGGL((decode_kernel<3>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, y); break;
-    default: hipLaunchKernelGGL((decode_kernel<4>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, y); break;
+    case 1: hipLaunchKernelGGL((decode_kernel<1>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<2>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
+    case 3: hipLaunchKernelGGL((decode_kernel<3>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
+    default: hipLaunchKernelGGL((decode_kernel<4>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
     }
     ELORA_HIP_TRY(hipGetLastError());
     profile_mark_end(stream);

@@ -54,6 +54,8 @@ WsLayout elora::ws_layout(int T, int K, int N, int R)
     off += align_up(t * sizeof(int32_t));
     l.row_scale = off;
     off += align_up(t * sizeof(float));
+    l.row_rank = off;
+    off += align_up(t * sizeof(int32_t));
     l.v = off;
     size_t v_full = t * (size_t)R * sizeof(float);
     size_t v_split = td * (size_t)R * sizeof(float) * kDecodeMaxVSplit;
