@@ -162,9 +162,11 @@ typedef struct {
 size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank);
 
 /*
- * A workspace must be initialised ONCE, before its first use in a linear call: its first 4 KiB hold
- * counters that every call leaves at zero again, and this call zeroes them (one small fill kernel on
- * `stream`).  Call it again only after a call that used the workspace was aborted (device reset).
+ * A workspace must be initialised ONCE, over its whole size, before its first use in a linear call.
+ * Its first 4 KiB hold counters (idle state: zero) and most of the rest are mailboxes through which the
+ * workgroups of a decode call hand each other partial results (idle state: all bits set).  This call
+ * writes the idle state (one fill kernel on `stream`), and every linear call leaves the workspace idle
+ * again.  Call it again only after a call that used the workspace was aborted (device reset).
  * Two calls that may run at the same time (different streams) need different workspaces.
  * Errors: E_NULL, E_ALIGN, E_STORAGE, E_HIP.
  */
@@ -173,7 +175,7 @@ int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t
 typedef struct {
     int path;        /* elora_path_t */
     int n_launches;  /* kernels one call enqueues */
-    int split_k;     /* K-splits of the streaming contraction (decode path), else 1 */
+    int split_k;     /* K-slices of the streaming contraction (decode path: 1, 2, 4 or 8), else 1 */
     int tile_rows;   /* W rows (decode) or output rows (gemm) per workgroup, 0 for the generic path */
     int tile_cols;   /* output columns per workgroup (gemm), else 0 */
     int grid;        /* workgroups of the dominant kernel */
@@ -206,9 +208,10 @@ int elora_batched_lora_linear(const elora_linear_desc_t *desc, elora_stream_t st
 int elora_force_path(int path);
 
 /*
- * Test hook: upper bound on the polls of the decode kernel's one internal wait (a tile epilogue
- * waiting for the shrink results).  A workgroup whose bound runs out computes the values it needs
- * itself; 0 makes every epilogue take that route.  Default 4194304.  Errors: E_SHAPE (limit < 0).
+ * Test hook: upper bound on the polls of each wait inside the decode kernel (a workgroup waiting for
+ * results of another one).  A workgroup whose bound runs out computes what it needs from the inputs
+ * by itself, and the call removes whatever was posted to it before it ends; 0 makes every waiter take
+ * that route at once.  Default 4194304.  Errors: E_SHAPE (limit < 0).
  */
 int elora_debug_spin_limit(int limit);
 

@@ -43,19 +43,21 @@ struct RowRoute {
 };
 
 // Workspace sections (byte offsets from the 256-byte aligned base).
+// The first three sections belong to the decode kernel, sit at offsets that do not depend on the batch, and
+// are in their idle state between calls (counters zero, mailboxes all-ones); nothing else writes there.
 struct WsLayout {
-    size_t sync;       // int [kSyncInts] counters of the decode kernel; zero between calls
+    size_t sync;       // int [kSyncInts] counters of the decode kernel
+    size_t vmail;      // float [kDecodeMaxTokens][kMaxRank] mailbox for the shrink results of the decode kernel
+    size_t mail;       // float mailboxes for the K-slice pieces of the decode kernel (decode_mail_bytes(d_out))
     size_t row_slot;   // int32 [T]
     size_t row_scale;  // float [T]
     size_t row_rank;   // int32 [T]
-    size_t v;          // float/bf16 shrink results (and their K-split partials)
-    size_t partial;    // float split-K partial sums of the streaming contraction
+    size_t v;          // float/bf16 shrink results of the generic and gemm kernels
     size_t total;
 };
 
 constexpr int kDecodeMaxTokens = 64;  // rows the streaming (decode) kernels take
 constexpr int kDecodeMaxSplit = 8;    // K-splits of the base contraction
-constexpr int kDecodeMaxVSplit = 16;  // K-splits of the shrink
 constexpr int kMaxRank = 256;
 constexpr int kSyncInts = 1024;       // ints in the workspace's counter area
 
@@ -99,6 +101,7 @@ int launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t strea
 void decode_set_spin_limit(int limit);
 bool decode_eligible(const elora_linear_desc_t &d, int max_rank);
 void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
+size_t decode_mail_bytes(int d_out);  // mailboxes of the decode kernel for d_out output columns
 bool gemm_eligible(const elora_linear_desc_t &d, int max_rank);
 void gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
 size_t gemm_v_bytes(int n_tokens, int max_rank);  // bf16 shrink results, rank padded to the GEMM's K block
@@ -145,15 +148,18 @@ template <typename E> __device__ __forceinline__ void store_elem(E *p, size_t i,
 template <> __device__ __forceinline__ void store_elem<float>(float *p, size_t i, float v) { p[i] = v; }
 template <> __device__ __forceinline__ void store_elem<uint16_t>(uint16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
 
-// Which adapter row t uses (Sec. 3.4: every request of the batch names its own adapter).
-// Index -1 means none.  Any other index outside the pool, or naming an empty slot, is
-// turned into "none" and, if `record`, counted in the pool's sticky error record.
-__device__ __forceinline__ RowRoute resolve_row(int t, const RouteView &r, const PoolView &p, bool record)
-{
+// Which adapter row t uses (Sec. 3.4: every request of the batch names its own adapter), in two steps so
+// that a caller can put other work between the dependent loads.
+// Step 1: the index the routing tables give for row t (-1 = none) and where its scale override sits.
+struct RouteIndex {
     int idx;
-    int scale_at = t;
+    int scale_at;
+};
+__device__ __forceinline__ RouteIndex route_index(int t, const RouteView &r)
+{
+    RouteIndex out{-1, t};
     if (r.adapter_idx != nullptr) {
-        idx = r.adapter_idx[t];
+        out.idx = r.adapter_idx[t];
     } else {
         // last segment s with seg_offsets[s] <= t (empty segments have equal offsets and are skipped over)
         int lo = 0, hi = r.n_segments;  // invariant: seg_offsets[lo] <= t < seg_offsets[hi]
@@ -161,17 +167,21 @@ __device__ __forceinline__ RowRoute resolve_row(int t, const RouteView &r, const
             int mid = (lo + hi) >> 1;
             if (r.seg_offsets[mid] <= t) lo = mid; else hi = mid;
         }
-        idx = (r.n_segments > 0 && r.seg_offsets[lo] <= t && t < r.seg_offsets[lo + 1]) ? r.seg_adapter[lo] : -1;
-        scale_at = lo;
+        out.idx = (r.n_segments > 0 && r.seg_offsets[lo] <= t && t < r.seg_offsets[lo + 1]) ? r.seg_adapter[lo] : -1;
+        out.scale_at = lo;
     }
+    return out;
+}
+// Step 2: validate against the slot's table entry `m` (read from p.meta[idx] by the caller when idx is inside the
+// pool, anything otherwise) and pick the scale (`scale_override` = r.scales[ri.scale_at], read by the caller when
+// r.scales is given and idx is not -1).  Index -1 means none.  Any other index outside the pool, or naming an
+// empty slot, is turned into "none" and, if `record`, counted in the pool's sticky error record.
+__device__ __forceinline__ RowRoute route_finish(int t, const RouteIndex &ri, const SlotMeta &m, float scale_override,
+                                                 const RouteView &r, const PoolView &p, bool record)
+{
     RowRoute out{-1, 0, 0.0f};
-    if (idx == -1) return out;
-    bool ok = idx >= 0 && idx < p.capacity;
-    SlotMeta m{0, 0.0f, 0, 0};
-    if (ok) {
-        m = p.meta[idx];
-        ok = m.loaded == 1 && m.rank >= 1 && m.rank <= p.max_rank;
-    }
+    if (ri.idx == -1) return out;
+    const bool ok = ri.idx >= 0 && ri.idx < p.capacity && m.loaded == 1 && m.rank >= 1 && m.rank <= p.max_rank;
     if (!ok) {
         if (record) {
             atomicAdd(&p.err[0], 1);
@@ -179,13 +189,22 @@ __device__ __forceinline__ RowRoute resolve_row(int t, const RouteView &r, const
         }
         return out;
     }
-    out.slot = idx;
+    out.slot = ri.idx;
     out.rank = m.rank;
-    out.scale = (r.scales != nullptr) ? r.scales[scale_at] : m.scale;
+    out.scale = (r.scales != nullptr) ? scale_override : m.scale;
     return out;
+}
+__device__ __forceinline__ RowRoute resolve_row(int t, const RouteView &r, const PoolView &p, bool record)
+{
+    const RouteIndex ri = route_index(t, r);
+    SlotMeta m{0, 0.0f, 0, 0};
+    if (ri.idx >= 0 && ri.idx < p.capacity) m = p.meta[ri.idx];
+    const float so = (r.scales != nullptr && ri.idx != -1) ? r.scales[ri.scale_at] : 0.0f;
+    return route_finish(t, ri, m, so, r, p, record);
 }
 
 typedef uint32_t elora_u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 elora_bf16x2 __attribute__((ext_vector_type(2)));
 
 // One wave: v[t][j0], v[t][j0+1] = A_i[j0..j0+1, :] . x[t, :] over the whole of K (K % 256 == 0).
 __device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, const uint16_t *__restrict__ A1,
@@ -210,11 +229,11 @@ __device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, con
             if (pb + i * 64 + lane >= pieces) xv[i] = elora_u32x4{0, 0, 0, 0};  // past the row: contributes nothing
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float xl = __uint_as_float(xv[i][q] << 16), xh = __uint_as_float(xv[i][q] & 0xffff0000u);
-                s0 = fmaf(__uint_as_float(a0[i][q] << 16), xl, s0);
-                s0 = fmaf(__uint_as_float(a0[i][q] & 0xffff0000u), xh, s0);
-                s1 = fmaf(__uint_as_float(a1[i][q] << 16), xl, s1);
-                s1 = fmaf(__uint_as_float(a1[i][q] & 0xffff0000u), xh, s1);
+                // two bf16 products and the running sum in one instruction (products exact, fp32 accumulation)
+                // (elements are copied to scalars first: a bit cast straight from a vector element picks element 0)
+                const uint32_t xw = xv[i][q], aw0 = a0[i][q], aw1 = a1[i][q];
+                s0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw0), __builtin_bit_cast(elora_bf16x2, xw), s0, false);
+                s1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw1), __builtin_bit_cast(elora_bf16x2, xw), s1, false);
             }
         }
     }

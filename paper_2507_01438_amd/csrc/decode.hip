@@ -1,26 +1,37 @@
 // Decode path (few rows, HBM-bound): bf16, up to 64 rows, ONE launch per call.
 //
-// The grid holds two kinds of workgroups:
+// Every workgroup is a (tile, ks) pair: 64 rows of W (= 64 output columns) and one K-slice.  It runs
+// three phases:
 //
-//   shrink workgroups (the first n_shrink_wgs): each wave takes (row t, two rank rows j) units and
-//       computes  v[t][j] = sum_k A_i[j,k] x[t,k]  over the whole of d_in with plain FMAs and one
-//       wavefront reduction (A_i x_t of the row's own adapter, Sec. 3.4).  When a workgroup has
-//       stored its results it adds one to sync[kCntV].
-//   base workgroups (tile, ks): 64 rows of W and one K-slice,
-//       partial[ks][t][n] = sum_{k in slice ks} W[n,k] x[t,k]   (Sec. 3.4: W x [x_0..x_n], shared by
-//       the whole batch).  Each wave streams 16 rows of W straight from global memory into the
-//       A-operand of v_mfma_f32_16x16x32_bf16 (row = lane % 16, 8 consecutive k per lane); the rows of
-//       x are the B-operand, read from an LDS copy of the current 256-wide K-chunk.  W loads are
-//       issued two chunks ahead.  The LAST of a tile's `split` workgroups to arrive (atomic ticket,
-//       nobody waits for a ticket) runs the tile epilogue: it sums the K-split partials in fixed
-//       order and writes  y[t,n] = bf16(base + s_i * sum_j B_i[n,j] v[t][j])  at the row's own
-//       position (Sec. 3.4: results are combined and land at their original locations).
+//   1. shrink share.  The (row t, two rank rows j) units of  v[t][j] = sum_k A_i[j,k] x[t,k]  (A_i x_t of
+//      the row's own adapter, Sec. 3.4) are dealt out over the workgroups, one unit per wave: plain FMAs over
+//      the whole of d_in and one wavefront reduction.  Results go into the v mailbox.
+//   2. base contraction.  partial[ks][t][n] = sum_{k in slice ks} W[n,k] x[t,k]  (Sec. 3.4: W x [x_0..x_n],
+//      shared by the whole batch).  Each wave streams 16 rows of W straight from global memory into the
+//      A-operand of v_mfma_f32_16x16x32_bf16 (row = lane % 16, 8 consecutive k per lane); the rows of x
+//      are the B-operand, read from a small LDS ring that direct-to-LDS loads keep filled.
+//   3. exchange and expand.  Workgroup ks OWNS 64 / split of the tile's columns.  Every workgroup posts the
+//      pieces of its partial to their owners' mailboxes; each owner takes v, forms
+//          d[t][n] = s_t * sum_j B_i[n,j] v[t][j]      for its own columns,
+//      adds the pieces in fixed order (slice 0, 1, ...) and d, rounds once and writes
+//          y[t,n] = bf16(W x_t + s_i B_i A_i x_t)   at the row's own position (Sec. 3.4: results are
+//      combined and land at their original locations).
 //
-// The only wait in the kernel is the epilogue's wait for the shrink workgroups (sync[kCntV]).  Those
-// come first in the grid and wait for nothing, and at most n_tiles workgroups can be waiting, so the
-// wait always ends; it is bounded all the same, and a workgroup whose bound runs out computes the
-// v[t][:] it needs by itself.  Counters live in the first bytes of the caller's workspace and are back
-// at zero when the kernel ends (so the call can be replayed from a HIP graph).
+// Mailboxes hold the bit pattern 0xFFFFFFFF ("empty") between calls.  A reader polls the data itself
+// until no word is empty, so a hand-over costs one store and one load, with no flags, counters or
+// fences on the way.  Piece mailboxes have one reader, who puts the empty pattern back; the v mailbox
+// is emptied by the last workgroup of the call to finish.  Arithmetic cannot produce the pattern: it is
+// a NaN whose low mantissa bits are set, while every NaN here descends from a bf16 (low 16 bits zero)
+// or is the default NaN.  All accesses to mailboxes are agent-scope, which on gfx950 go past the
+// per-XCD L2.
+//
+// Every wait is bounded.  A reader whose bound runs out computes what it needs from the inputs on its
+// own (v of the rows it is working on, or its columns of y from scratch) and, for pieces, raises the
+// call's dirty flag: the last workgroup to finish then empties all piece mailboxes, because pieces
+// posted to a reader that gave up are still lying there.  Nobody waits before its own shrink share is
+// posted, and owners only wait for the workgroups of their own tile, which sit next to each other in
+// the grid and on the same XCD.  Counters and flags are zero again when the kernel ends, so a call can
+// be replayed from a HIP graph.
 //
 // Summation order is fixed (no float atomics): results are bit-identical from run to run.
 #include "common.h"
@@ -33,270 +44,623 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef ELORA_DEC_SUB
+#define ELORA_DEC_SUB 128  // elements of K per sub-span (a base workgroup keeps two sub-spans in flight): 128 or 256
+#endif
+
 constexpr int kWaves = 4;         // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kRowsPerWave = 16;  // W rows per wave (one MFMA row block)
 constexpr int kTileRows = kWaves * kRowsPerWave;
-constexpr int kChunk = 256;             // K elements per register set of W (8 MFMA K steps)
-constexpr int kStepsPerChunk = kChunk / 32;
-#ifndef ELORA_DEC_SPAN
-#define ELORA_DEC_SPAN 1024        // elements of x per row parked in LDS at a time when at most 32 rows are in the batch
-#endif
-// x of the workgroup's K-slice is parked in LDS in spans of kSpan(TT) elements per row (row pitch +16 bytes so
-// that 16 rows hit 16 different bank groups): 1024 for up to 32 rows of x, 512 for up to 64 (about 66 KiB)
-__host__ __device__ constexpr int span_of(int tt) { return tt <= 2 ? ELORA_DEC_SPAN : 512; }
+constexpr int kGranules = kTileRows / 4;  // a granule = 4 adjacent columns = what one lane holds of one row of x
+constexpr int kChunk = 256;               // K elements per register set of W (8 MFMA K steps)
+constexpr int kPitch = ELORA_DEC_SUB == 128 ? 520 : 776;  // LDS elements per row of x: room for the x ring (3 sub-spans) and for the staging afterwards
+constexpr uint32_t kEmpty = 0xFFFFFFFFu;
+
+constexpr int kXcds = 8;                  // workgroup b runs on XCD b % 8
 
 // sync area (ints) at the start of the workspace
-constexpr int kCntV = 0;      // shrink units finished
-constexpr int kCntDone = 1;   // tile epilogues finished
-constexpr int kCntTile = 16;  // + tile: K-split workgroups of that tile that have arrived
+constexpr int kCntAll = 0;        // XCDs all of whose workgroups have finished
+constexpr int kCntXcd = 32;       // + 32 x (a cache line of its own): workgroups of XCD x that have finished, plus
+constexpr int kGaveUp = 1 << 16;  // this much for every owner on XCD x that gave up (its piece mailboxes may hold pieces nobody took)
 
 int g_spin_limit = 1 << 22;
 
 // tuning constants (overridable at compile time for experiments)
-#ifndef ELORA_DEC_MAX_SHRINK_WGS
-#define ELORA_DEC_MAX_SHRINK_WGS 512  // upper bound on shrink workgroups (each wave then loops over several units)
+#ifndef ELORA_DEC_AHEAD
+#define ELORA_DEC_AHEAD 2  // sub-spans a base workgroup keeps in flight: 1 or 2
 #endif
 #ifndef ELORA_DEC_TARGET_WGS
-#define ELORA_DEC_TARGET_WGS 640  // upper bound on base workgroups when choosing the K-split
+#define ELORA_DEC_TARGET_WGS 256  // base workgroups aimed at: one per compute unit (two fit)
 #endif
 
-// Optional phase timestamps for tuning (compiled in only with -DELORA_TRACE): slot i of workgroup b.
+// Optional phase timestamps for tuning (compiled in only with -DELORA_TRACE): slot i of workgroup b.  The stamps are
+// kept in registers and written out when the workgroup is done, so that taking them adds no memory operations.
 #ifdef ELORA_TRACE
 __device__ long long elora_trace_buf[4096 * 16];
-#define TRACE(i)                                                                                   \
-    do {                                                                                           \
-        if (threadIdx.x == 0 && blockIdx.x < 4096) elora_trace_buf[blockIdx.x * 16 + (i)] = wall_clock64(); \
+#define TRACE_DECL long long trace_t[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
+#define TRACE(i) trace_t[i] = wall_clock64()
+#define TRACE_DUMP                                                                                   \
+    do {                                                                                             \
+        if (threadIdx.x == 0 && blockIdx.x < 4096)                                                   \
+            for (int i_ = 0; i_ < 16; ++i_) elora_trace_buf[blockIdx.x * 16 + i_] = trace_t[i_];     \
     } while (0)
 #else
+#define TRACE_DECL do {} while (0)
 #define TRACE(i) do {} while (0)
+#define TRACE_DUMP do {} while (0)
 #endif
 
 struct DecodeShape {
     int T, K, N;
-    int split;  // K-slices of the base contraction
-    int chunks_per_split;
+    int split;      // K-slices of the base contraction = owners per tile: 1, 2, 4 or 8
+    int chunks;     // K / 256; slice ks covers chunks [ks * chunks / split, (ks + 1) * chunks / split)
     int n_tiles;
-    int n_shrink_wgs;  // leading workgroups that compute v = A_i x_t
-    int jgroups;       // pairs of rank rows per row of x: ceil(max_rank / 2)
+    int total;      // n_tiles * split (tile, ks) pairs
+    int grid;       // total rounded up to a multiple of 8 * split: workgroups launched (the surplus only shares in the shrink)
+    int n_pub;      // the first n_pub workgroups of the grid share the shrink units
+    int jgroups;    // pairs of rank rows per row of x: ceil(max_rank / 2)
+    int G;          // granules per owner: 16 / split
+    int lgG;        // log2 G
+    int lgRp;       // log2 of max_rank rounded up to a power of two
     int spin_limit;
+    int zero;       // 0
 };
 
-// Data that one workgroup writes and another reads inside the same launch (partial, v) goes
-// through agent-scope accesses, which on gfx950 write through / read past the per-XCD L2, so the
-// hand-over needs no cache-wide write-back or invalidate (those cost tens of microseconds here).
-__device__ __forceinline__ void store_shared_f32(float *p, float v)
+// ---- mailbox accesses (agent scope: past the per-XCD L2) -----------------------------------------
+__device__ __forceinline__ void mb_store_f32(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t mb_load_u32(const float *p)
 {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(reinterpret_cast<const uint32_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void store_shared_f32x2(float *p, float a, float b)
+// immediate of s_waitcnt for "at most n vector-memory operations outstanding" (other counters: no wait)
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | 0x0F70 | ((n >> 4) << 14); }
+
+// Piece mailboxes are written and read by workgroups of one tile, which share an XCD, so the XCD's L2 is where they
+// meet.  Stores are write-through all the way to memory (agent scope: nothing is left for the cache write-back at
+// the end of the kernel) and leave the line in the L2; reads are plain loads the first time (nothing of these lines
+// can be in the first-level cache yet) and atomic read-modify-writes (OR with zero) when they have to be repeated:
+// those always execute in the L2, so they can neither see a stale first-level line nor have to go out to memory.
+__device__ __forceinline__ void piece_store(float *p, float a, float b, float c, float d)
 {
-    uint64_t u = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
-    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint64_t *q = reinterpret_cast<uint64_t *>(p);
+    __hip_atomic_store(q, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, (uint64_t)__float_as_uint(c) | ((uint64_t)__float_as_uint(d) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float load_shared_f32(const float *p)
+__device__ __forceinline__ void piece_clear(float *p)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint64_t *q = reinterpret_cast<uint64_t *>(p);
+    __hip_atomic_store(q, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float2 load_shared_f32x2(const float *p)
+// `zero` is 0, but only the host knows (the compiler would turn an OR with a literal zero into a plain load)
+__device__ __forceinline__ u32x4 piece_load(const float *p, uint64_t zero)
 {
-    uint64_t u = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return float2{__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32))};
+    uint64_t *q = reinterpret_cast<uint64_t *>(const_cast<float *>(p));
+    const uint64_t lo = __hip_atomic_fetch_or(q, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const uint64_t hi = __hip_atomic_fetch_or(q + 1, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+}
+
+// piece (tile, owner, sender): [T][G][4] floats
+__device__ __forceinline__ size_t piece_floats(const DecodeShape &sh) { return (size_t)sh.T * sh.G * 4; }
+__device__ __forceinline__ float *piece_ptr(float *mail, const DecodeShape &sh, int tile, int owner, int sender)
+{
+    return mail + ((size_t)(tile * sh.split + owner) * sh.split + sender) * piece_floats(sh);
+}
+
+// Columns [nc0, nc0 + ncols) of y for all rows, from the inputs alone (after a wait ran out): slow, exact.
+__device__ void recompute_columns(const DecodeShape &sh, const uint16_t *__restrict__ x, const uint16_t *__restrict__ W,
+                                  const PoolView &pool, const RouteView &route, int has_pool, uint16_t *__restrict__ y,
+                                  int nc0, int ncols, int wave, int lane)
+{
+    const int T = sh.T, K = sh.K, N = sh.N;
+    for (int t = wave; t < T; t += kWaves) {
+        RowRoute rr{-1, 0, 0.0f};
+        if (has_pool) rr = resolve_row(t, route, pool, false);
+        const uint16_t *xt = x + (size_t)t * K;
+        float d = 0.0f;  // lane c: adapter term of column nc0 + c
+        if (rr.slot >= 0) {
+            const uint16_t *A = reinterpret_cast<const uint16_t *>(slot_A(pool, rr.slot));
+            const uint16_t *B = reinterpret_cast<const uint16_t *>(slot_B(pool, rr.slot));
+            for (int j0 = 0; j0 < rr.rank; j0 += 2) {
+                const bool two = (j0 + 1) < rr.rank;
+                float r0, r1;
+                shrink_pair(A + (size_t)j0 * K, A + (size_t)(two ? j0 + 1 : j0) * K, xt, K, lane, r0, r1);
+                if (lane < ncols && nc0 + lane < N) {
+                    const uint16_t *Bn = B + (size_t)(nc0 + lane) * rr.rank;
+                    d = fmaf(bf16_to_f32(Bn[j0]), r0, d);
+                    if (two) d = fmaf(bf16_to_f32(Bn[j0 + 1]), r1, d);
+                }
+            }
+        }
+        for (int c = 0; c < ncols && nc0 + c < N; ++c) {
+            const uint16_t *wn = W + (size_t)(nc0 + c) * K;
+            float s = 0.0f;
+            for (int k = lane * 8; k < K; k += 64 * 8) {
+                const u32x4 wv = *reinterpret_cast<const u32x4 *>(wn + k), xv = *reinterpret_cast<const u32x4 *>(xt + k);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    s = fmaf(__uint_as_float(wv[q] << 16), __uint_as_float(xv[q] << 16), s);
+                    s = fmaf(__uint_as_float(wv[q] & 0xffff0000u), __uint_as_float(xv[q] & 0xffff0000u), s);
+                }
+            }
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+            const float dc = __shfl(d, c);
+            if (lane == 0) y[(size_t)t * N + nc0 + c] = f32_to_bf16(s + rr.scale * dc);
+        }
+    }
 }
 
 template <int TT>
-__global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
-                                                          const uint16_t *__restrict__ W, PoolView pool,
-                                                          RouteView route, int has_pool, float *__restrict__ partial,
-                                                          float *__restrict__ v, int *__restrict__ sync,
-                                                          int *__restrict__ row_slot, int *__restrict__ row_rank,
-                                                          float *__restrict__ row_scale, uint16_t *__restrict__ y)
+__global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
+                                                                           const uint16_t *__restrict__ W, PoolView pool,
+                                                                           RouteView route, int has_pool, float *__restrict__ mail,
+                                                                           float *__restrict__ vmail, int *__restrict__ sync,
+                                                                           uint16_t *__restrict__ y)
 {
-    // x span during the contraction; v of every row during the epilogue
-    constexpr int kSpan = span_of(TT), kPitch = kSpan + 8, kChunksPerSpan = kSpan / kChunk;
-    __shared__ __attribute__((aligned(16))) uint16_t xs[TT * 16][kPitch];
-    __shared__ int s_slot[TT * 16], s_rank[TT * 16];
-    __shared__ float s_scale[TT * 16];
-    __shared__ int s_last, s_vok;
+    // x ring during the contraction; staging of pieces, v and d afterwards
+    __shared__ __attribute__((aligned(16))) uint16_t xs[TT * 16 * kPitch];
+    __shared__ int s_slot[kDecodeMaxTokens], s_rank[kDecodeMaxTokens];
+    __shared__ float s_scale[kDecodeMaxTokens];
+    __shared__ int s_flag, s_fail, s_vfail, s_odd;
+    __shared__ float s_red[2][kWaves][2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = sh.T, K = sh.K, N = sh.N;
     const int R = pool.max_rank;
+    float *const lds_f = reinterpret_cast<float *>(&xs[0]);
+    constexpr int kLdsFloats = TT * 16 * kPitch / 2;  // the area counted in floats
+    TRACE_DECL;
     TRACE(0);
-
-    // ---- shrink workgroups ---------------------------------------------------------------------
-    if ((int)blockIdx.x < sh.n_shrink_wgs) {
-        const int n_units = T * sh.jgroups;
-        for (int wu = blockIdx.x * kWaves + wave; wu < n_units; wu += sh.n_shrink_wgs * kWaves) {
-            const int t = wu / sh.jgroups, j0 = (wu - t * sh.jgroups) * 2;
-            RowRoute rr = resolve_row(t, route, pool, j0 == 0 && lane == 0);
-            if (j0 == 0 && lane == 0) {  // the row's route, for the tile epilogues
-                __hip_atomic_store(&row_slot[t], rr.slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&row_rank[t], rr.rank, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                store_shared_f32(&row_scale[t], rr.scale);
-            }
-            if (rr.slot < 0 || j0 >= rr.rank) continue;
-            const bool two = (j0 + 1) < rr.rank;
-            const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, rr.slot)) + (size_t)j0 * K;
-            const uint16_t *A1 = two ? A0 + K : A0;
-            float r0, r1;
-            shrink_pair(A0, A1, x + (size_t)t * K, K, lane, r0, r1);
-            if (lane == 0) {
-                store_shared_f32(&v[(size_t)t * R + j0], r0);
-                if (two) store_shared_f32(&v[(size_t)t * R + j0 + 1], r1);
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the write-through stores have been acknowledged
-        __syncthreads();
-        if (tid == 0) atomicAdd(&sync[kCntV], 1);
-        TRACE(1);
-        return;
+    if (tid == 0) {
+        s_fail = 0;
+        s_vfail = 0;
+        s_odd = 0;
     }
 
-    // ---- base workgroups: issue the first W and x loads before anything else -------------------
-    const int bid = blockIdx.x - sh.n_shrink_wgs;
-    const int tile = bid % sh.n_tiles, ks = bid / sh.n_tiles;
-    const int m = lane & 15, g = lane >> 4;
-    const int row = tile * kTileRows + wave * kRowsPerWave + m;                // W row this lane feeds
-    const bool wave_active = (tile * kTileRows + wave * kRowsPerWave) < N;     // N % 16 == 0: all 16 rows in or out
-    const int k_begin = ks * sh.chunks_per_split * kChunk;
-    const uint16_t *wrow = W + (size_t)(wave_active ? row : 0) * K + k_begin + g * 8;
-    const int nchunks = sh.chunks_per_split;
+    // Workgroup b runs on XCD b % 8.  The (tile, ks) pairs are numbered tile-major and every XCD takes a contiguous
+    // eighth of them (a multiple of `split`), so the workgroups that exchange pieces share an XCD: they start together.
+    const int per_xcd = sh.grid / kXcds;
+    const int pair = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
+    const bool idle = pair >= sh.total;  // surplus workgroup: only shares in the shrink
+    const int tile = idle ? 0 : pair / sh.split, ks = idle ? 0 : pair - tile * sh.split;
 
-    u32x4 wbuf[2][kStepsPerChunk];
-    typedef const __attribute__((address_space(1))) void *gptr_t;
-    typedef __attribute__((address_space(3))) void *lptr_t;
-
-    auto load_w = [&](u32x4 *dst, int chunk) {
-        const uint16_t *p = wrow + (size_t)chunk * kChunk;
-#pragma unroll
-        for (int j = 0; j < kStepsPerChunk; ++j)
-            dst[j] = wave_active ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + j * 32)) : u32x4{0, 0, 0, 0};
-    };
-    // Park x[:, chunks c0 .. c0 + nc) of the K-slice in LDS, global -> LDS directly.  One instruction moves 512
-    // consecutive elements of one row (two chunks; the odd last chunk of a span moves with half the lanes).
-    // Rows past the batch repeat the last row: what they produce is never stored.
-    auto park_x = [&](int c0, int nc) {
-        const int units = TT * 16 * ((nc + 1) >> 1);  // (row, pair of chunks)
-        for (int u = wave; u < units; u += kWaves) {
-            const int r = u % (TT * 16), pr = u / (TT * 16);
-            const uint16_t *src = x + (size_t)min(r, T - 1) * K + k_begin + (size_t)(c0 + 2 * pr) * kChunk + lane * 8;
-            uint16_t *dst = &xs[r][pr * 2 * kChunk];
-            if (2 * pr + 1 < nc || lane < 32)
-                __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
+    // Finishing is counted per XCD and then over the XCDs.  The last workgroup of an XCD empties, if some owner there
+    // gave up, the piece mailboxes of the XCD's tiles (through the same L2 the pieces went through); the last
+    // workgroup of the call empties the v mailbox (everybody has read what it needed).  Counters and flags go back
+    // to zero.  Everything this workgroup posted has been acknowledged before it counts itself.
+    auto finish_call = [&]() {
+        TRACE_DUMP;
+        const int xcd = blockIdx.x % kXcds;
+        if (tid == 0) {
+            int flag = 0;
+            // (counted in the XCD's own L2: every workgroup that touches this counter runs on this XCD)
+            const int before = __hip_atomic_fetch_add(&sync[kCntXcd + 32 * xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if ((before & (kGaveUp - 1)) == per_xcd - 1) {
+                __hip_atomic_store(&sync[kCntXcd + 32 * xcd], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (before >= kGaveUp) flag |= 2;
+                if (atomicAdd(&sync[kCntAll], 1) == kXcds - 1) {
+                    __hip_atomic_store(&sync[kCntAll], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    flag |= 1;
+                }
+            }
+            s_flag = flag;
+        }
+        __syncthreads();
+        if ((s_flag & 1) && has_pool)
+            for (int e = tid; e < T * R; e += kThreads) mb_store_f32(&vmail[e], __uint_as_float(kEmpty));
+        if (s_flag & 2) {
+            // pairs xcd * per_xcd .. + per_xcd - 1 (those below `total`): split pieces each
+            const int p0 = xcd * per_xcd, p1 = min(p0 + per_xcd, sh.total);
+            float *base = mail + (size_t)p0 * sh.split * piece_floats(sh);
+            const size_t n = p1 > p0 ? (size_t)(p1 - p0) * sh.split * piece_floats(sh) : 0;
+            for (size_t e = (size_t)tid * 4; e < n; e += (size_t)kThreads * 4) piece_clear(base + e);
         }
     };
 
-    park_x(0, min(nchunks, kChunksPerSpan));
-    load_w(wbuf[0], 0);
-    if (nchunks > 1) load_w(wbuf[1], 1);
+    // ---- set-up of the base contraction (its first loads go out in the middle of phase 1) ----------------------
+    const int m = lane & 15, g = lane >> 4;
+    const int n0 = tile * kTileRows;
+    const int row = n0 + wave * kRowsPerWave + m;                    // W row this lane feeds
+    const bool wave_active = !idle && (n0 + wave * kRowsPerWave) < N;  // N % 16 == 0: all 16 rows in or out
+    const int c_begin = (int)((long long)ks * sh.chunks / sh.split);
+    const int nchunks = (int)((long long)(ks + 1) * sh.chunks / sh.split) - c_begin;  // >= 1: split <= chunks
+    const int k_begin = c_begin * kChunk;
+    const uint16_t *wrow = W + (size_t)(wave_active ? row : 0) * K + k_begin + g * 8;
 
-    // ---- base tile -------------------------------------------------------------------------------
+    // The K-slice goes by in sub-spans of 128 elements (4 MFMA K steps).  Per sub-span every thread has 4 loads of
+    // W in flight (16 rows x 128 elements per wave, straight into registers) and every wave moves its share of
+    // the rows of x global -> LDS; kDepth sub-spans are on their way at any time, no more: requests a compute unit
+    // has queued beyond what the memory system is working on only delay whatever that unit asks for next (the
+    // helper workgroups live on latency), without adding bandwidth.
+    constexpr int kSub = ELORA_DEC_SUB, kSubSteps = kSub / 32;
+    constexpr int kAhead = ELORA_DEC_AHEAD;          // sub-spans in flight while one is being multiplied: 1 or 2
+    constexpr int kBufs = 3;                         // the sub-spans in flight and the one being multiplied
+    constexpr int kRowsPerInstr = 512 / kSub;        // a direct-to-LDS instruction moves 1 KiB: 4 rows of 128 or 2 rows of 256 elements
+    constexpr int kLanesPerRow = 64 / kRowsPerInstr;
+    constexpr int kXInstr = TT * 16 / kRowsPerInstr / kWaves;  // such instructions per wave and sub-span
+    constexpr int kOps = kXInstr + kSubSteps;                  // vector-memory operations per wave and sub-span
+    static_assert(kSub == 128 || kSub == 256, "sub-span");
+    static_assert(sizeof(xs) >= (size_t)kBufs * TT * 16 * kSub * 2, "x ring fits");
+    static_assert(kOps < 64, "vmcnt range");
+    u32x4 wset[2][kSubSteps];
+    typedef const __attribute__((address_space(1))) void *gptr_t;
+    typedef __attribute__((address_space(3))) void *lptr_t;
+    uint16_t *const xring = &xs[0];  // [kBufs][TT * 16 rows][kSub / 8 slots of 8 elements]; slot = chunk ^ (row % 16)
+    const int nsub = nchunks * (kChunk / kSub);  // >= 2 when kSub == 128; >= 1 otherwise
+
+    // x first, then W: when the wave's W loads of a sub-span are back, so is its share of x (in-order counter).
+    // Rows past the batch repeat the last row, and waves whose 16 rows of W lie past d_out load row 0: what they
+    // produce is never posted, but every wave issues the same number of operations.
+    auto issue = [&](int p, u32x4 *dst) {
+        uint16_t *buf = xring + (size_t)(p % kBufs) * (TT * 16 * kSub);
+#pragma unroll
+        for (int i = 0; i < kXInstr; ++i) {
+            const int r = (wave * kXInstr + i) * kRowsPerInstr + lane / kLanesPerRow;
+            const int chunk = (lane % kLanesPerRow) ^ (r & 15);
+            const uint16_t *src = x + (size_t)min(r, T - 1) * K + k_begin + (size_t)p * kSub + chunk * 8;
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(buf + (wave * kXInstr + i) * 512), 16, 0, 0);
+        }
+        const uint16_t *pw = wrow + (size_t)p * kSub;
+#pragma unroll
+        for (int j = 0; j < kSubSteps; ++j) dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + j * 32));
+    };
+
     floatx4 acc[TT];
 #pragma unroll
     for (int i = 0; i < TT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](const u32x4 *wc, int cs) {  // cs = chunk inside the span
+    // wait until at most `later` sub-spans are still on their way, meet the other waves (their shares of x for
+    // sub-span p are in LDS then, and everybody is done with sub-span p - 1), multiply
+    auto arrive = [&](bool one_later) {
+        if (one_later) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOps));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    auto multiply = [&](int p, const u32x4 *wc) {
+        // The LDS reads are written as assembly: the compiler holds every LDS read back until ALL direct-to-LDS
+        // loads in flight have landed (it cannot tell the ring's buffers apart), which would undo the prefetch.
+        const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)(xring + (size_t)(p % kBufs) * (TT * 16 * kSub)) + (uint32_t)m * (kSub * 2);
+        u32x4 b[kSubSteps][TT];
 #pragma unroll
-        for (int j = 0; j < kStepsPerChunk; ++j) {
-            bf16x8 a = __builtin_bit_cast(bf16x8, wc[j]);
+        for (int j = 0; j < kSubSteps; ++j)
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                bf16x8 b = *reinterpret_cast<const bf16x8 *>(&xs[tt * 16 + m][cs * kChunk + j * 32 + g * 8]);
-                acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[tt], 0, 0, 0);
+            for (int tt = 0; tt < TT; ++tt)
+                asm volatile("ds_read_b128 %0, %1" : "=v"(b[j][tt]) : "v"(base + (uint32_t)(tt * 16 * kSub * 2) + (uint32_t)(((j * 4 + g) ^ m) << 4)) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < kSubSteps; ++j)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) asm volatile("" : "+v"(b[j][tt]));  // nothing may use b before the wait above
+#pragma unroll
+        for (int j = 0; j < kSubSteps; ++j) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wc[j]);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[j][tt]), acc[tt], 0, 0, 0);
+        }
+    };
+    auto step = [&](int p, const u32x4 *wc, bool one_later) {
+        arrive(one_later);
+        multiply(p, wc);
+    };
+
+    // ---- phase 1: routes of all rows, and this workgroup's share of the shrink ---------------------------
+    // A unit = (row t, rank rows j0 and j0 + 1) is worked on by the whole workgroup: thread = 16-byte pieces tid,
+    // tid + 256, ... of the three rows involved (x_t and two rows of A_i), 1024 pieces (K = 4096 elements) a round.
+    constexpr int UL = 2;  // pieces per thread and round
+    const int pieces = K >> 3;
+    auto unit_load = [&](const uint16_t *A0, const uint16_t *A1, const uint16_t *xt, int pb, u32x4 *xv, u32x4 *a0, u32x4 *a1) {
+#pragma unroll
+        for (int i = 0; i < UL; ++i) {
+            const int pc = pb + i * kThreads + tid;
+            const size_t off = (size_t)(pc < pieces ? pc : 0) * 8;  // past the row: some piece of it, dropped below
+            xv[i] = *reinterpret_cast<const u32x4 *>(xt + off);
+            a0[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(A0 + off));
+            a1[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(A1 + off));
+        }
+    };
+    auto unit_dot = [&](int pb, const u32x4 *xv, const u32x4 *a0, const u32x4 *a1, float &s0, float &s1) {
+#pragma unroll
+        for (int i = 0; i < UL; ++i) {
+            const bool in = pb + i * kThreads + tid < pieces;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t xw = in ? xv[i][q] : 0u, aw0 = a0[i][q], aw1 = a1[i][q];
+                s0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw0), __builtin_bit_cast(elora_bf16x2, xw), s0, false);
+                s1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw1), __builtin_bit_cast(elora_bf16x2, xw), s1, false);
             }
         }
     };
-    // The waves only meet when a span of x is exchanged; inside a span each wave streams its 16 rows of W on
-    // its own, two chunks (16 loads of 16 bytes per lane) ahead of the one it multiplies.
-    for (int c0 = 0; c0 < nchunks; c0 += kChunksPerSpan) {
-        const int nc = min(kChunksPerSpan, nchunks - c0);
-        if (c0 > 0) {
-            __syncthreads();  // everybody is done with the previous span
-            park_x(c0, nc);
+    // the four waves' sums of one unit meet in LDS (two sets, used in turn: one barrier per unit); thread 0 posts v
+    auto unit_finish = [&](int n, int t, int j0, bool valid, bool two, float s0, float s1) {
+        for (int off = 32; off > 0; off >>= 1) {
+            s0 += __shfl_xor(s0, off);
+            s1 += __shfl_xor(s1, off);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the span has landed (so has its W prefetch)
-        __syncthreads();
-        if (c0 == 0) TRACE(2);  // first span of x parked
-        for (int cs = 0; cs < nc; cs += 2) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int cc = c0 + cs + h;  // kChunksPerSpan is even, so chunk cc uses register set h
-                if (cs + h < nc) {
-                    compute(wbuf[h], cs + h);
-                    if (cc + 2 < nchunks) load_w(wbuf[h], cc + 2);
+        if (lane == 0) {
+            s_red[n & 1][wave][0] = s0;
+            s_red[n & 1][wave][1] = s1;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (tid == 0 && valid) {
+            const float r0 = (s_red[n & 1][0][0] + s_red[n & 1][1][0]) + (s_red[n & 1][2][0] + s_red[n & 1][3][0]);
+            const float r1 = (s_red[n & 1][0][1] + s_red[n & 1][1][1]) + (s_red[n & 1][2][1] + s_red[n & 1][3][1]);
+            mb_store_f32(&vmail[(size_t)t * R + j0], r0);
+            if (two) mb_store_f32(&vmail[(size_t)t * R + j0 + 1], r1);
+        }
+    };
+    const int n_units = has_pool ? T * sh.jgroups : 0;
+    // units number n_first on of this workgroup (the routes are in LDS), each from its loads to its v in one go
+    auto units_from = [&](int n_first) {
+        if ((int)blockIdx.x >= sh.n_pub) return;
+        int n = n_first;
+        for (int u = blockIdx.x + sh.n_pub * n_first; u < n_units; u += sh.n_pub, ++n) {
+            const int t = u / sh.jgroups, j0 = (u - t * sh.jgroups) * 2;
+            const int slot = s_slot[t], rank = s_rank[t];
+            const bool valid = slot >= 0 && j0 < rank, two = (j0 + 1) < rank;
+            float s0 = 0.0f, s1 = 0.0f;
+            if (valid) {
+                const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
+                const uint16_t *A1 = two ? A0 + K : A0;
+                for (int pb = 0; pb < pieces; pb += UL * kThreads) {
+                    u32x4 xv[UL], a0[UL], a1[UL];
+                    unit_load(A0, A1, x + (size_t)t * K, pb, xv, a0, a1);
+                    unit_dot(pb, xv, a0, a1, s0, s1);
                 }
             }
+            unit_finish(n, t, j0, valid, two, s0, s1);
+        }
+    };
+    if (idle) {
+        if (has_pool) {
+            if (tid < T) {
+                const RowRoute rr = resolve_row(tid, route, pool, blockIdx.x == 0);
+                s_slot[tid] = rr.slot;
+                s_rank[tid] = rr.rank;
+            }
+            __syncthreads();
+            units_from(0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this workgroup's stores have been acknowledged
+        __syncthreads();
+        finish_call();
+        return;
+    }
+    // A route takes two dependent loads (index, then the slot's table entry) that have nothing to hide behind, so
+    // everything that can be asked for meanwhile is: the first round of the workgroup's first shrink unit (its A_i is
+    // known with the index; whether the rank reaches that far is checked afterwards) and the first sub-spans of W
+    // and x.  In-order return then delivers the routes first, the unit next and the stream right after.  (Straight-
+    // line code on purpose: the compiler then counts the loads in flight exactly.)
+    if (has_pool) {
+        const int tr = min(tid, T - 1);  // threads past the batch repeat its last row and keep nothing
+        const bool unit0 = (int)blockIdx.x < sh.n_pub && (int)blockIdx.x < n_units;
+        const int t0 = unit0 ? (int)blockIdx.x / sh.jgroups : 0, j00 = ((int)blockIdx.x - t0 * sh.jgroups) * 2;
+        const RouteIndex ri = route_index(tr, route);
+        const RouteIndex r0i = route_index(t0, route);
+        SlotMeta mt = pool.meta[(ri.idx >= 0 && ri.idx < pool.capacity) ? ri.idx : 0];
+        float so = (route.scales != nullptr && ri.idx != -1) ? route.scales[ri.scale_at] : 0.0f;
+        u32x4 uxv[UL], ua0[UL], ua1[UL];
+        __builtin_amdgcn_sched_barrier(0);
+        TRACE(11);  // index known, table entry asked for
+        if (unit0) {
+            const int slot0 = (r0i.idx >= 0 && r0i.idx < pool.capacity) ? r0i.idx : 0;  // any slot is memory that may be read
+            const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot0)) + (size_t)j00 * K;
+            unit_load(A0, (j00 + 1 < R) ? A0 + K : A0, x + (size_t)t0 * K, 0, uxv, ua0, ua1);
+            issue(0, wset[0]);
+            if (kAhead == 2 && (kSub == 128 || nsub > 1)) {
+                issue(1, wset[1]);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * UL + 2 * kOps));  // everything older: the table entry
+            } else {
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * UL + kOps));
+            }
+        } else {
+            issue(0, wset[0]);
+            if (kAhead == 2 && (kSub == 128 || nsub > 1)) {
+                issue(1, wset[1]);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
+            } else {
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOps));
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" : "+v"(mt.rank), "+v"(mt.scale), "+v"(mt.loaded), "+v"(so));  // not looked at before this point
+        TRACE(12);  // table entry here
+        const RowRoute rr = route_finish(tr, ri, mt, so, route, pool, blockIdx.x == 0 && tid < T);
+        if (tid < T) {
+            s_slot[tid] = rr.slot;
+            s_rank[tid] = rr.rank;
+            s_scale[tid] = rr.scale;
+            if (rr.rank & 7) s_odd = 1;  // rows of this B_i are not 16-byte aligned
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the routes are in LDS (a full fence would also wait for the stream)
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        TRACE(13);  // routes in LDS
+        if (unit0) {
+            const int slot = s_slot[t0], rank = s_rank[t0];
+            const bool valid = slot >= 0 && j00 < rank, two = (j00 + 1) < rank;
+            float s0 = 0.0f, s1 = 0.0f;
+            if (kAhead == 2 && (kSub == 128 || nsub > 1)) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));  // the unit's loads are back
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOps));
+            unit_dot(0, uxv, ua0, ua1, s0, s1);
+            if (valid) {
+                const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j00 * K;
+                const uint16_t *A1 = two ? A0 + K : A0;
+                for (int pb = UL * kThreads; pb < pieces; pb += UL * kThreads) {  // K above 4096: the other rounds
+                    u32x4 xv[UL], a0[UL], a1[UL];
+                    unit_load(A0, A1, x + (size_t)t0 * K, pb, xv, a0, a1);
+                    unit_dot(pb, xv, a0, a1, s0, s1);
+                }
+            }
+            unit_finish(0, t0, j00, valid, two, s0, s1);
+            units_from(1);
+        }
+        TRACE(1);
+    } else {
+        issue(0, wset[0]);
+        if (kAhead == 2 && (kSub == 128 || nsub > 1)) issue(1, wset[1]);
+    }
+
+    // ---- phase 2: base contraction -------------------------------------------------------------------------
+    // Two sub-spans in flight, no more: requests a compute unit has queued beyond what the memory system is
+    // working on only delay whatever that unit asks for next, without adding bandwidth.
+    if (kAhead == 1) {
+        // one sub-span on its way: the next one is asked for as soon as the waves have met, then the current one is multiplied
+        for (int p = 0; p < nsub; p += 2) {
+            arrive(false);
+            if (p == 0) TRACE(4);
+            if (p + 1 < nsub) issue(p + 1, wset[1]);
+            multiply(p, wset[0]);
+            if (p + 1 < nsub) {
+                arrive(false);
+                if (p + 2 < nsub) issue(p + 2, wset[0]);
+                multiply(p + 1, wset[1]);
+            }
+        }
+    } else if (nsub == 1) {  // only with 256-element sub-spans
+        step(0, wset[0], false);
+    } else {
+        int p = 0;
+        for (; p + 3 < nsub; p += 2) {
+            step(p, wset[0], true);
+            if (p == 0) TRACE(4);
+            issue(p + 2, wset[0]);
+            step(p + 1, wset[1], true);
+            issue(p + 3, wset[1]);
+        }
+        if (p + 2 < nsub) {  // three left
+            step(p, wset[0], true);
+            issue(p + 2, wset[0]);
+            step(p + 1, wset[1], true);
+            step(p + 2, wset[0], false);
+        } else {  // two left
+            step(p, wset[0], true);
+            step(p + 1, wset[1], false);
+        }
+    }
+    TRACE(5);  // contraction done
+
+    // ---- phase 3: post the pieces of this K-slice to their owners ---------------------------------------------
+    // C layout of the 16x16 MFMA: lane holds column (lane % 16) = row t of x, rows (lane / 16) * 4 + 0..3 = W rows,
+    // i.e. granule wave * 4 + g of the tile
+    if (wave_active) {
+        const int q16 = wave * 4 + g;
+        float *dst0 = piece_ptr(mail, sh, tile, q16 >> sh.lgG, ks) + (size_t)(q16 & (sh.G - 1)) * 4;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const int t = tt * 16 + m;
+            if (t < T) piece_store(dst0 + (size_t)t * sh.G * 4, acc[tt][0], acc[tt][1], acc[tt][2], acc[tt][3]);
         }
     }
 
-    TRACE(3);  // contraction done
+    // own columns: granules og0 .. og0 + G - 1 of the tile, columns nc0 .. nc0 + 4 G - 1 of y
+    const int og0 = ks * sh.G, nc0 = n0 + og0 * 4, ncols = sh.G * 4;
+    const int n_cells = T * sh.G;  // (row, granule) cells of the owned columns
 
-    // ---- expand share of this workgroup ------------------------------------------------------------
-    // Rows t = ks, ks + split, ... of the batch get  s_t * B_i v_t  for this tile's 64 columns added to this
-    // workgroup's K-slice partial, so the expand of a tile is spread over its `split` workgroups (and B_i is
-    // read where the partial is still in registers).
-    const int n0 = tile * kTileRows;
-    const int nq = (sh.n_shrink_wgs > 0 && ks < T) ? (T - ks + sh.split - 1) / sh.split : 0;
-    if (nq > 0) {
-        __syncthreads();  // xs is reused below
-        if (tid == 0) {
-            int ok = 0;
-            for (int spin = 0; spin < sh.spin_limit; ++spin) {
-                if (__hip_atomic_load(&sync[kCntV], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= sh.n_shrink_wgs) {
-                    ok = 1;
+    // What follows runs on four waves with nothing to overlap it, and a wave on its own issues an instruction only
+    // every 8 to 10 clocks: the number of instructions on this path is what the tail of the kernel costs.  The common
+    // case (every rank a multiple of 8, none above 64) therefore has a short path of its own.
+    const bool lean = !has_pool || (s_odd == 0 && R <= 64 && sh.lgRp >= 3);
+    if (lean) {
+        const int lgRp = sh.lgRp, Rp = 1 << lgRp;  // pitch of v in LDS: max_rank rounded up to a power of two, 8 .. 64
+        float *const vs = lds_f;                                     // [T][Rp]
+        float *const dsum = lds_f + (has_pool ? (T << lgRp) : 0);    // [T][ncols]
+        constexpr int VV = kDecodeMaxTokens * 64 / 4 / kThreads;     // 16-byte vectors of v per thread, at most
+        const int nch = has_pool ? R >> 3 : 0;                       // 16-byte pieces of a row of B_i at the largest rank
+        const int n_bit = has_pool ? T << (sh.lgG + 2) : 0;          // (row, own column) items
+        const size_t pstride = piece_floats(sh);
+        u32x4 vv[VV];
+        bool vneed[VV];
+        u32x4 b[2][8];
+        const float *vrow[2];
+        bool valid[2];
+        u32x4 pv[kDecodeMaxSplit];
+        // rows of B_i for two items (it0, it0 + 256); pieces of a row past its rank repeat its last piece (v is zero there)
+        auto b_issue = [&](int it0) {
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                const int item = it0 + ii * kThreads;
+                const int t = item < n_bit ? item >> (sh.lgG + 2) : 0, c = item & (ncols - 1);
+                const int slot = s_slot[t], rank = s_rank[t];
+                valid[ii] = item < n_bit && slot >= 0 && nc0 + c < N;
+                const uint16_t *bp = reinterpret_cast<const uint16_t *>(slot_B(pool, valid[ii] ? slot : 0)) +
+                                     (valid[ii] ? (size_t)(nc0 + c) * rank : 0);
+                const int last = valid[ii] ? rank - 8 : 0;
+#pragma unroll
+                for (int hh = 0; hh < 8; ++hh)
+                    if (hh < nch) b[ii][hh] = *reinterpret_cast<const u32x4 *>(bp + min(8 * hh, last));
+                vrow[ii] = vs + (t << lgRp);
+            }
+        };
+        // the pieces of one (row, granule) cell: plain loads
+        auto p_issue = [&](int cell) {
+            const float *src0 = piece_ptr(mail, sh, tile, ks, 0) + (size_t)cell * 4;
+#pragma unroll
+            for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
+                if (sd < sh.split) pv[sd] = *reinterpret_cast<const u32x4 *>(src0 + sd * pstride);
+        };
+        if (has_pool) {
+            // v: first through the L2 (the workgroups of an XCD all want the same values, and the L2 holds nothing
+            // from before this launch); what was not there yet is asked for again past the L2.  The rows of B_i for
+            // this thread's first items go out with it: they only need the routes.
+#pragma unroll
+            for (int i = 0; i < VV; ++i) {
+                const int vi = tid + i * kThreads;
+                const int t = vi >> (lgRp - 2), j = (vi & ((Rp >> 2) - 1)) * 4;
+                vneed[i] = t < T && j < s_rank[min(t, T - 1)];
+                vv[i] = u32x4{0, 0, 0, 0};
+                if (vneed[i]) vv[i] = *reinterpret_cast<const u32x4 *>(vmail + (size_t)t * R + j);
+            }
+            b_issue(tid);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();  // the x ring is reused below (no fence: the requests above stay in flight)
+        asm volatile("" ::: "memory");
+        TRACE(8);
+        if (has_pool) {
+            bool gave_up = sh.spin_limit == 0;
+            for (int spin = 0; !gave_up; ++spin) {
+                bool all = true;
+#pragma unroll
+                for (int i = 0; i < VV; ++i)
+                    all = all && !(vneed[i] && (vv[i][0] == kEmpty || vv[i][1] == kEmpty || vv[i][2] == kEmpty || vv[i][3] == kEmpty));
+                if (all) break;
+                if (spin >= sh.spin_limit) {
+                    gave_up = true;
                     break;
                 }
-                __builtin_amdgcn_s_sleep(4);
-            }
-            s_vok = ok;
-        }
-        __syncthreads();
-        // v and the rows' routes written by the shrink workgroups are read past the L2 from here on
-        const bool vok = s_vok != 0;
-        TRACE(4);  // shrink results available
-        float *vs = reinterpret_cast<float *>(&xs[0][0]);  // [rows of this pass][R], then d [rows][64]
-        const int qb_max = (int)(sizeof(xs) / ((R + kTileRows) * sizeof(float)));
-        for (int q0 = 0; q0 < nq; q0 += qb_max) {
-            const int qb = min(qb_max, nq - q0);
-            float *dls = vs + qb * R;
-            if (q0 > 0) __syncthreads();
-            if (tid < qb) {
-                const int t = ks + (q0 + tid) * sh.split;
-                RowRoute rr;
-                if (vok) {
-                    rr.slot = __hip_atomic_load(&row_slot[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    rr.rank = __hip_atomic_load(&row_rank[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    rr.scale = load_shared_f32(&row_scale[t]);
-                } else {
-                    rr = resolve_row(t, route, pool, false);
-                }
-                s_slot[tid] = rr.slot;
-                s_rank[tid] = rr.rank;
-                s_scale[tid] = rr.scale;
-            }
-            __syncthreads();
-            if (vok) {
-                for (int e0 = 0; e0 < qb * R; e0 += kThreads * 8) {
-                    float tmp[8];
+                __builtin_amdgcn_s_sleep(2);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int e = e0 + i * kThreads + tid;
-                        const int q = e / R, j = e - q * R;
-                        tmp[i] = (e < qb * R && j < s_rank[q]) ? load_shared_f32(&v[(size_t)(ks + (q0 + q) * sh.split) * R + j]) : 0.0f;
-                    }
+                for (int i = 0; i < VV; ++i) {
+                    const int vi = tid + i * kThreads;
+                    const float *src = vmail + (size_t)(vi >> (lgRp - 2)) * R + (vi & ((Rp >> 2) - 1)) * 4;
+                    if (vneed[i])
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int e = e0 + i * kThreads + tid;
-                        if (e < qb * R) vs[e] = tmp[i];
-                    }
+                        for (int u = 0; u < 4; ++u)
+                            if (vv[i][u] == kEmpty) vv[i][u] = mb_load_u32(src + u);
                 }
-            } else {
-                // the shrink workgroups did not report in time: compute v of these rows here
-                for (int wu = wave; wu < qb * sh.jgroups; wu += kWaves) {
-                    const int q = wu / sh.jgroups, j0 = (wu - q * sh.jgroups) * 2;
-                    const int t = ks + (q0 + q) * sh.split;
-                    const int slot = s_slot[q], rank = s_rank[q];
+            }
+#pragma unroll
+            for (int i = 0; i < VV; ++i) {
+                const int vi = tid + i * kThreads;
+                if (vi < (T << (lgRp - 2))) *reinterpret_cast<u32x4 *>(vs + (size_t)vi * 4) = vv[i];  // zeros at and above the rank
+            }
+            if (gave_up) s_vfail = 1;
+            TRACE(9);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (s_vfail) {
+                // the shrink results did not arrive in time: compute v here
+                for (int wu = wave; wu < T * sh.jgroups; wu += kWaves) {
+                    const int t = wu / sh.jgroups, j0 = (wu - t * sh.jgroups) * 2;
+                    const int slot = s_slot[t], rank = s_rank[t];
                     float r0 = 0.0f, r1 = 0.0f;
                     if (slot >= 0 && j0 < rank) {
                         const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
@@ -304,173 +668,404 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(DecodeShape sh, const 
                         if (j0 + 1 >= rank) r1 = 0.0f;
                     }
                     if (lane == 0) {
+                        vs[(t << lgRp) + j0] = r0;
+                        if (j0 + 1 < Rp) vs[(t << lgRp) + j0 + 1] = r1;
+                    }
+                }
+                __syncthreads();
+            }
+            TRACE(10);
+        }
+        // the pieces of this thread's first cell are asked for now: the other K-slices have had time to arrive, and the
+        // loads are under way while the adapter term is formed
+        if (tid < n_cells) p_issue(tid);
+        if (has_pool) {
+            // d[t][c] = s_t * sum_j B_i[nc0 + c][j] v[t][j]: one (row, own column) item per thread, two items at a time
+            for (int it0 = tid; it0 < n_bit; it0 += 2 * kThreads) {
+                if (it0 != tid) b_issue(it0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ii = 0; ii < 2; ++ii) {
+                    float d = 0.0f;
+#pragma unroll
+                    for (int hh = 0; hh < 8; ++hh) {
+                        if (hh < nch) {
+                            const floatx4 v0 = *reinterpret_cast<const floatx4 *>(vrow[ii] + 8 * hh);
+                            const floatx4 v1 = *reinterpret_cast<const floatx4 *>(vrow[ii] + 8 * hh + 4);
+                            d = fmaf(__uint_as_float(b[ii][hh][0] << 16), v0[0], d);
+                            d = fmaf(__uint_as_float(b[ii][hh][0] & 0xffff0000u), v0[1], d);
+                            d = fmaf(__uint_as_float(b[ii][hh][1] << 16), v0[2], d);
+                            d = fmaf(__uint_as_float(b[ii][hh][1] & 0xffff0000u), v0[3], d);
+                            d = fmaf(__uint_as_float(b[ii][hh][2] << 16), v1[0], d);
+                            d = fmaf(__uint_as_float(b[ii][hh][2] & 0xffff0000u), v1[1], d);
+                            d = fmaf(__uint_as_float(b[ii][hh][3] << 16), v1[2], d);
+                            d = fmaf(__uint_as_float(b[ii][hh][3] & 0xffff0000u), v1[3], d);
+                        }
+                    }
+                    const int item = it0 + ii * kThreads;
+                    if (item < n_bit) dsum[item] = valid[ii] ? d * s_scale[item >> (sh.lgG + 2)] : 0.0f;
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+        TRACE(2);  // adapter term formed
+        // every (row, granule) cell of the own columns: the piece of each K-slice (again through L2 atomics while one
+        // is missing), added in fixed order, plus d, rounded once, stored at the row's own position
+        for (int cell = tid; cell < n_cells; cell += kThreads) {
+            const int t = cell >> sh.lgG, qo = cell & (sh.G - 1);
+            const int n = nc0 + qo * 4;
+            if (cell != tid) p_issue(cell);
+            if (n >= N) continue;
+            float *src0 = piece_ptr(mail, sh, tile, ks, 0) + (size_t)cell * 4;
+            bool gave_up = sh.spin_limit == 0;
+            for (int spin = 0; !gave_up; ++spin) {
+                bool all = true;
+#pragma unroll
+                for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
+                    if (sd < sh.split) all = all && pv[sd][0] != kEmpty && pv[sd][1] != kEmpty && pv[sd][2] != kEmpty && pv[sd][3] != kEmpty;
+                if (all) break;
+                if (spin >= sh.spin_limit) {
+                    gave_up = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+                for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
+                    if (sd < sh.split && (pv[sd][0] == kEmpty || pv[sd][1] == kEmpty || pv[sd][2] == kEmpty || pv[sd][3] == kEmpty))
+                        pv[sd] = piece_load(src0 + sd * pstride, (uint64_t)(uint32_t)sh.zero);
+            }
+            if (gave_up) {
+                s_fail = 1;
+                continue;
+            }
+            floatx4 o = __builtin_bit_cast(floatx4, pv[0]);
+#pragma unroll
+            for (int sd = 1; sd < kDecodeMaxSplit; ++sd) {
+                if (sd < sh.split) {
+                    const floatx4 pc = __builtin_bit_cast(floatx4, pv[sd]);
+                    o[0] += pc[0];
+                    o[1] += pc[1];
+                    o[2] += pc[2];
+                    o[3] += pc[3];
+                }
+            }
+            if (has_pool) {
+                const floatx4 dd = *reinterpret_cast<const floatx4 *>(dsum + (size_t)cell * 4);
+                o[0] += dd[0];
+                o[1] += dd[1];
+                o[2] += dd[2];
+                o[3] += dd[3];
+            }
+            const uint64_t packed = (uint64_t)f32_to_bf16(o[0]) | ((uint64_t)f32_to_bf16(o[1]) << 16) |
+                                    ((uint64_t)f32_to_bf16(o[2]) << 32) | ((uint64_t)f32_to_bf16(o[3]) << 48);
+            *reinterpret_cast<uint64_t *>(y + (size_t)t * N + n) = packed;
+#pragma unroll
+            for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
+                if (sd < sh.split) piece_clear(src0 + sd * pstride);  // empty again for the next call
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        TRACE(6);
+        if (s_fail) {
+            // some piece did not arrive in time: this workgroup computes its columns from the inputs, and the pieces
+            // that are still on their way are removed when the call ends
+            if (tid == 0) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            recompute_columns(sh, x, W, pool, route, has_pool, y, nc0, ncols, wave, lane);
+        }
+    } else {
+    const int n_items = sh.split * n_cells;  // (sender, cell) = 16 T: at most four per thread
+    // LDS: [pieces: n_items x 4][d: n_cells x 4][v of a block of rows: qb x R]
+    float *const stage = lds_f, *const dsum = stage + (size_t)n_items * 4, *const vs = dsum + (size_t)n_cells * 4;
+    const int qb_max = (kLdsFloats - (n_items + n_cells) * 4) / (has_pool ? R : 1);  // rows of v that fit: at least 8
+
+    // Three hand-overs end here: the pieces of the other K-slices, v, and (plain loads) the rows of B_i.  All first
+    // requests go out together, before anything is waited for.
+    // (index spaces are laid out so that they come apart with shifts and divisions by constants: this part of the
+    // kernel runs on four waves per workgroup with nothing to overlap it)
+    constexpr int PB = TT, VB = 8, IB = 2;
+    u32x4 pval[PB];
+    bool pneed[PB];
+    const float *psrc[PB];
+    int pdst[PB];
+#pragma unroll
+    for (int u = 0; u < PB; ++u) {
+        // item = (sender, row of the 16 TT, granule): TT * 256 items, TT per thread
+        const int item = tid + u * kThreads;
+        const int qo = item & (sh.G - 1), rs = item >> sh.lgG;
+        const int sd = rs / (TT * 16), t = rs - sd * (TT * 16);
+        const int cell = t * sh.G + qo;
+        pneed[u] = t < T && nc0 + qo * 4 < N;
+        psrc[u] = piece_ptr(mail, sh, tile, ks, sd) + (size_t)(pneed[u] ? cell : 0) * 4;
+        pdst[u] = (sd * n_cells + cell) * 4;
+    }
+    auto p_load = [&]() {
+#pragma unroll
+        for (int u = 0; u < PB; ++u)
+            if (pneed[u]) pval[u] = piece_load(psrc[u], (uint64_t)(uint32_t)sh.zero);
+    };
+    // v: element e of the block of rows q0 .. q0 + qb - 1 is (row q0 + (e >> lgRp), rank column e & (Rp - 1))
+    const int Rp = 1 << sh.lgRp;
+    auto v_load = [&](int q0, int qb, int e0, uint32_t *val, bool *need) {
+#pragma unroll
+        for (int i = 0; i < VB; ++i) {
+            const int e = e0 + i * kThreads + tid;
+            const int q = e >> sh.lgRp, j = e & (Rp - 1);
+            need[i] = q < qb && j < s_rank[q0 + min(q, qb - 1)];
+            // first through the L2 (the workgroups of an XCD all want the same values; the L2 holds nothing from before
+            // this launch); a value that was not there yet is asked for again past the L2
+            val[i] = need[i] ? reinterpret_cast<const uint32_t *>(vmail)[(size_t)(q0 + q) * R + j] : 0u;
+        }
+    };
+    // B_i: item = (row q of the block, own column c); 16-byte pieces of the row, 8 at a time, from rank column j on
+    struct BItem {
+        const uint16_t *bp;  // row nc0 + c of B_i (or some valid address if the item has nothing to add)
+        int q, rank;         // rank 0: nothing to add
+        bool vec;            // rows of B_i are 16-byte aligned
+    };
+    auto b_item = [&](int q0, int qb, int item) {
+        BItem it;
+        const int q1 = item >> (sh.lgG + 2), c = item & (ncols - 1);
+        const bool in = q1 < qb;
+        const int q = in ? q1 : 0;
+        const int slot = s_slot[q0 + q], rank = s_rank[q0 + q];
+        const bool use = in && slot >= 0 && nc0 + c < N;
+        it.q = q;
+        it.rank = use ? rank : 0;
+        it.vec = (rank & 7) == 0;
+        it.bp = reinterpret_cast<const uint16_t *>(slot_B(pool, use ? slot : 0)) + (use ? (size_t)(nc0 + c) * rank : 0);
+        return it;
+    };
+    auto b_load = [&](const BItem &it, int j, u32x4 *b) {
+#pragma unroll
+        for (int hh = 0; hh < 8; ++hh) {
+            if (j + 8 * hh >= R) continue;  // nobody's rank reaches this far
+            const bool in = it.vec && j + 8 * hh < it.rank;
+            b[hh] = *reinterpret_cast<const u32x4 *>(in ? it.bp + j + 8 * hh : reinterpret_cast<const uint16_t *>(slot_B(pool, 0)));
+        }
+    };
+
+    uint32_t vval[VB];
+    bool vneed[VB];
+    BItem bit[IB];
+    u32x4 bpre[IB][8];
+    if (has_pool) {
+        const int qb = min(qb_max, T);
+        v_load(0, qb, 0, vval, vneed);
+#pragma unroll
+        for (int ii = 0; ii < IB; ++ii) {
+            bit[ii] = b_item(0, qb, tid + ii * kThreads);
+            b_load(bit[ii], 0, bpre[ii]);
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // the x ring is reused below (no fence: the requests above stay in flight)
+    asm volatile("" ::: "memory");
+    TRACE(8);
+
+    // ---- the adapter term of the own columns -------------------------------------------------------------------
+    if (has_pool) {
+        for (int q0 = 0; q0 < T; q0 += qb_max) {
+            const int qb = min(qb_max, T - q0);
+            if (q0 > 0) __syncthreads();
+            // v of these rows out of the mailbox (entries below the row's rank; the others count as zero)
+            bool gave_up = false;
+            for (int e0 = 0; e0 < (qb << sh.lgRp) && !gave_up; e0 += kThreads * VB) {
+                if (q0 > 0 || e0 > 0) v_load(q0, qb, e0, vval, vneed);
+                for (int spin = 0;; ++spin) {
+                    bool all = true;
+#pragma unroll
+                    for (int i = 0; i < VB; ++i) all = all && !(vneed[i] && vval[i] == kEmpty);
+                    if (all) break;
+                    if (spin >= sh.spin_limit) {
+                        gave_up = true;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+#pragma unroll
+                    for (int i = 0; i < VB; ++i) {
+                        const int e = e0 + i * kThreads + tid;
+                        if (vneed[i] && vval[i] == kEmpty) vval[i] = mb_load_u32(&vmail[(size_t)(q0 + (e >> sh.lgRp)) * R + (e & (Rp - 1))]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < VB; ++i) {
+                    const int e = e0 + i * kThreads + tid;
+                    const int q = e >> sh.lgRp, j = e & (Rp - 1);
+                    if (q < qb && j < R) vs[q * R + j] = vneed[i] ? __uint_as_float(vval[i]) : 0.0f;
+                }
+            }
+            if (gave_up || sh.spin_limit == 0) s_vfail = 1;
+            TRACE(9);
+            __syncthreads();
+            TRACE(10);
+            if (s_vfail) {
+                // the shrink results did not arrive in time: compute v of these rows here
+                for (int wu = wave; wu < qb * sh.jgroups; wu += kWaves) {
+                    const int q = wu / sh.jgroups, j0 = (wu - q * sh.jgroups) * 2;
+                    const int slot = s_slot[q0 + q], rank = s_rank[q0 + q];
+                    float r0 = 0.0f, r1 = 0.0f;
+                    if (slot >= 0 && j0 < rank) {
+                        const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
+                        shrink_pair(A0, (j0 + 1 < rank) ? A0 + K : A0, x + (size_t)(q0 + q) * K, K, lane, r0, r1);
+                        if (j0 + 1 >= rank) r1 = 0.0f;
+                    }
+                    if (lane == 0) {
                         vs[q * R + j0] = r0;
                         if (j0 + 1 < R) vs[q * R + j0 + 1] = r1;
                     }
                 }
+                __syncthreads();
             }
-            __syncthreads();
-            // d[q][c] = s * sum_j B_i[n0 + c][j] v[q][j]: one (row, column) item per thread, four items at a time
-            // so that up to 32 loads of 16 bytes are in flight per thread
-            constexpr int IB = 4;
-            for (int it0 = tid; it0 < qb * kTileRows; it0 += kThreads * IB) {
-                int iq[IB], ir[IB];
-                const uint16_t *bp[IB];
+            // d[t][c] = s_t * sum_j B_i[nc0 + c][j] v[t][j]: one (row, column) item per thread, two items at a time
+            for (int it0 = tid; it0 < qb * ncols; it0 += kThreads * IB) {
+                const bool first = q0 == 0 && it0 == tid;
                 float d[IB];
-                bool vec = true;
+                int rmax = 0;
 #pragma unroll
                 for (int ii = 0; ii < IB; ++ii) {
-                    const int item = it0 + ii * kThreads;
-                    const bool in = item < qb * kTileRows;
-                    const int q = in ? item / kTileRows : 0, c = in ? item - q * kTileRows : 0;
-                    const int slot = s_slot[q];
-                    iq[ii] = q;
-                    ir[ii] = (in && slot >= 0 && n0 + c < N) ? s_rank[q] : 0;
-                    bp[ii] = reinterpret_cast<const uint16_t *>(slot_B(pool, slot >= 0 ? slot : 0)) + (size_t)min(n0 + c, N - 1) * s_rank[q];
+                    if (!first) bit[ii] = b_item(q0, qb, it0 + ii * kThreads);
                     d[ii] = 0.0f;
-                    vec = vec && ((ir[ii] & 7) == 0);
+                    rmax = max(rmax, bit[ii].vec ? bit[ii].rank : 0);
                 }
-                if (vec) {
-                    int rmax = 0;
+                for (int j = 0; j < rmax; j += 64) {
+                    if (!first || j > 0) {
 #pragma unroll
-                    for (int ii = 0; ii < IB; ++ii) rmax = max(rmax, ir[ii]);
-                    for (int j = 0; j < rmax; j += 64) {
-                        u32x4 b[IB][8];
+                        for (int ii = 0; ii < IB; ++ii) b_load(bit[ii], j, bpre[ii]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int ii = 0; ii < IB; ++ii)
+                    for (int ii = 0; ii < IB; ++ii) {
+                        const float *vq = vs + bit[ii].q * R + j;
 #pragma unroll
-                            for (int h = 0; h < 8; ++h)
-                                b[ii][h] = (j + 8 * h < ir[ii]) ? *reinterpret_cast<const u32x4 *>(bp[ii] + j + 8 * h) : u32x4{0, 0, 0, 0};
-                        __builtin_amdgcn_sched_barrier(0);
+                        for (int hh = 0; hh < 8; ++hh) {
+                            if (!bit[ii].vec || j + 8 * hh >= bit[ii].rank) continue;
 #pragma unroll
-                        for (int ii = 0; ii < IB; ++ii) {
-                            const float *vq = vs + iq[ii] * R + j;
-#pragma unroll
-                            for (int h = 0; h < 8; ++h) {
-                                if (j + 8 * h >= ir[ii]) continue;
-#pragma unroll
-                                for (int u = 0; u < 4; ++u) {
-                                    d[ii] = fmaf(__uint_as_float(b[ii][h][u] << 16), vq[8 * h + 2 * u], d[ii]);
-                                    d[ii] = fmaf(__uint_as_float(b[ii][h][u] & 0xffff0000u), vq[8 * h + 2 * u + 1], d[ii]);
-                                }
+                            for (int u = 0; u < 4; ++u) {
+                                d[ii] = fmaf(__uint_as_float(bpre[ii][hh][u] << 16), vq[8 * hh + 2 * u], d[ii]);
+                                d[ii] = fmaf(__uint_as_float(bpre[ii][hh][u] & 0xffff0000u), vq[8 * hh + 2 * u + 1], d[ii]);
                             }
                         }
                     }
-                } else {
-#pragma unroll
-                    for (int ii = 0; ii < IB; ++ii)
-                        for (int j = 0; j < ir[ii]; ++j) d[ii] = fmaf(bf16_to_f32(bp[ii][j]), vs[iq[ii] * R + j], d[ii]);
                 }
 #pragma unroll
                 for (int ii = 0; ii < IB; ++ii) {
+                    if (!bit[ii].vec)  // rows of B_i not 16-byte aligned: element by element
+                        for (int j = 0; j < bit[ii].rank; ++j) d[ii] = fmaf(bf16_to_f32(bit[ii].bp[j]), vs[bit[ii].q * R + j], d[ii]);
                     const int item = it0 + ii * kThreads;
-                    if (item < qb * kTileRows) dls[item] = d[ii] * s_scale[iq[ii]];
-                }
-            }
-            __syncthreads();
-            // add to the accumulators: lane holds row t = tt * 16 + m of the batch, columns wave * 16 + g * 4 + 0..3
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                const int t = tt * 16 + m;
-                const int q = (t - ks) / sh.split - q0;
-                if (t < T && t >= ks && (t - ks) % sh.split == 0 && q >= 0 && q < qb) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[tt][i] += dls[q * kTileRows + wave * kRowsPerWave + g * 4 + i];
+                    if (item < qb * ncols) dsum[(size_t)q0 * ncols + item] = d[ii] * s_scale[q0 + bit[ii].q];
                 }
             }
         }
     }
+    TRACE(2);  // adapter term formed
 
-    // C layout of the 16x16 MFMA: lane holds column (lane % 16) = row t of x, rows (lane / 16) * 4 + 0..3 = W rows
-    if (wave_active) {
-        const int n_base = n0 + wave * kRowsPerWave + g * 4;
+    // ---- take the pieces of every (row, granule) cell --------------------------------------------------------------
+    {
+        bool gave_up = sh.spin_limit == 0;
+        for (int spin = 0; !gave_up; ++spin) {
+            p_load();
+            bool all = true;
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            int t = tt * 16 + m;
-            if (t < T) {
-                float *p = partial + ((size_t)ks * T + t) * N + n_base;
-                store_shared_f32x2(p, acc[tt][0], acc[tt][1]);
-                store_shared_f32x2(p + 2, acc[tt][2], acc[tt][3]);
+            for (int u = 0; u < PB; ++u) {
+                if (pneed[u] && pval[u][0] != kEmpty && pval[u][1] != kEmpty && pval[u][2] != kEmpty && pval[u][3] != kEmpty) {
+                    pneed[u] = false;
+                    *reinterpret_cast<u32x4 *>(stage + pdst[u]) = pval[u];
+                    piece_clear(const_cast<float *>(psrc[u]));  // empty again for the next call
+                }
+                all = all && !pneed[u];
             }
-        }
-    }
-
-    // ---- ticket: is this the last K-slice of the tile? -----------------------------------------------
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the write-through stores have been acknowledged
-    __syncthreads();
-    if (tid == 0) s_last = (sh.split == 1 || atomicAdd(&sync[kCntTile + tile], 1) == sh.split - 1) ? 1 : 0;
-    __syncthreads();
-    TRACE(5);  // ticket drawn
-    if (s_last == 0) return;
-
-    // ---- tile epilogue: sum the K-slices in fixed order, round once, store each row at its own position ----
-    // 8 threads per row of x, 8 output columns each
-    for (int item = tid; item < T * 8; item += kThreads) {
-        const int t = item >> 3, n = n0 + (item & 7) * 8;
-        if (n >= N) continue;  // N % 8 == 0
-        float2 pv[kDecodeMaxSplit][4];
-#pragma unroll
-        for (int s = 0; s < kDecodeMaxSplit; ++s)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                pv[s][q] = load_shared_f32x2(partial + ((size_t)(s < sh.split ? s : 0) * T + t) * N + n + 2 * q);
-        __builtin_amdgcn_sched_barrier(0);  // all loads first (slices beyond `split` re-read slice 0 and are dropped)
-        float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < kDecodeMaxSplit; ++s)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                o[2 * q] += (s < sh.split) ? pv[s][q].x : 0.0f;
-                o[2 * q + 1] += (s < sh.split) ? pv[s][q].y : 0.0f;
+            if (all) break;
+            if (spin >= sh.spin_limit) {
+                gave_up = true;
+                break;
             }
-        u32x4 packed;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            packed[q] = (uint32_t)f32_to_bf16(o[2 * q]) | ((uint32_t)f32_to_bf16(o[2 * q + 1]) << 16);
-        *reinterpret_cast<u32x4 *>(y + (size_t)t * N + n) = packed;
-    }
-
-    TRACE(8);  // y written
-    // ---- leave the counters at zero for the next call --------------------------------------------
-    // When the last epilogue gets here every base workgroup has drawn its ticket, which it does after
-    // its wait for the shrink workgroups, so nobody looks at sync[kCntV] any more.
-    if (tid == 0) {
-        __hip_atomic_store(&sync[kCntTile + tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (atomicAdd(&sync[kCntDone], 1) == sh.n_tiles - 1) {
-            __hip_atomic_store(&sync[kCntV], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&sync[kCntDone], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_sleep(1);
         }
+        if (gave_up) s_fail = 1;
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // staging complete (no fence: nobody has to wait for the mailbox stores here)
+    asm volatile("" ::: "memory");
+    TRACE(6);  // pieces in
+    if (s_fail == 0) {
+        // add in fixed order, round once, store each row at its own position
+        for (int cell = tid; cell < n_cells; cell += kThreads) {
+            const int t = cell >> sh.lgG, qo = cell & (sh.G - 1);
+            const int n = nc0 + qo * 4;
+            if (n >= N) continue;
+            floatx4 o = *reinterpret_cast<const floatx4 *>(stage + (size_t)cell * 4);
+            for (int sd = 1; sd < sh.split; ++sd) {
+                const floatx4 pc = *reinterpret_cast<const floatx4 *>(stage + ((size_t)sd * n_cells + cell) * 4);
+                o[0] += pc[0];
+                o[1] += pc[1];
+                o[2] += pc[2];
+                o[3] += pc[3];
+            }
+            if (has_pool) {
+                const floatx4 dd = *reinterpret_cast<const floatx4 *>(dsum + (size_t)cell * 4);
+                o[0] += dd[0];
+                o[1] += dd[1];
+                o[2] += dd[2];
+                o[3] += dd[3];
+            }
+            const uint64_t packed = (uint64_t)f32_to_bf16(o[0]) | ((uint64_t)f32_to_bf16(o[1]) << 16) |
+                                    ((uint64_t)f32_to_bf16(o[2]) << 32) | ((uint64_t)f32_to_bf16(o[3]) << 48);
+            *reinterpret_cast<uint64_t *>(y + (size_t)t * N + n) = packed;
+        }
+    } else {
+        // some piece did not arrive in time: this workgroup computes its columns from the inputs, and the pieces that
+        // are still on their way are removed when the call ends
+        if (tid == 0) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        recompute_columns(sh, x, W, pool, route, has_pool, y, nc0, ncols, wave, lane);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+    }
+    }
+    TRACE(7);  // y written
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // what this workgroup posted has been acknowledged
+    __syncthreads();
+    finish_call();
 }
 
-int pick_split(int K, int n_tiles)
+// K-slices = owners per tile: the largest of 1, 2, 4, 8 that keeps all workgroups of the call resident at once
+int pick_split(int K, int n_tiles, int tt)
 {
-    // aim at about two workgroups per compute unit (512), K-slices of whole 256-wide chunks
-    int chunks = K / kChunk;
+    const int chunks = K / kChunk;
+    (void)tt;
+    const int target = ELORA_DEC_TARGET_WGS;
     int best = 1;
-    for (int s = 1; s <= kDecodeMaxSplit; ++s) {
-        if (chunks % s) continue;
-        if (n_tiles * s <= ELORA_DEC_TARGET_WGS) best = s;
-    }
+    for (int s = 2; s <= kDecodeMaxSplit; s *= 2)
+        if (s <= chunks && n_tiles * s <= target) best = s;
     return best;
 }
 
-DecodeShape make_shape(int T, int K, int N, int max_rank, bool has_pool)
+DecodeShape make_shape(int T, int K, int N, int max_rank)
 {
     DecodeShape sh;
     sh.T = T;
     sh.K = K;
     sh.N = N;
+    sh.chunks = K / kChunk;
     sh.n_tiles = (N + kTileRows - 1) / kTileRows;
-    sh.split = pick_split(K, sh.n_tiles);
-    sh.chunks_per_split = K / kChunk / sh.split;
     sh.jgroups = (max_rank + 1) / 2;
-    sh.n_shrink_wgs = 0;
-    if (has_pool) {
-        int wgs = (T * sh.jgroups + kWaves - 1) / kWaves;  // one (row, rank-row pair) unit per wave
-        sh.n_shrink_wgs = wgs < ELORA_DEC_MAX_SHRINK_WGS ? wgs : ELORA_DEC_MAX_SHRINK_WGS;
-    }
+    const int tt = (T + 15) / 16;
+    sh.split = pick_split(K, sh.n_tiles, tt);
+    sh.total = sh.n_tiles * sh.split;
+    const int unit = kXcds * sh.split;
+    sh.grid = (sh.total + unit - 1) / unit * unit;
+    // the workgroups that share the shrink must all be running before anybody can wait for them
+    const int resident = 512;  // 2 workgroups per compute unit (registers, and LDS with more than 32 rows)
+    sh.n_pub = sh.grid < resident ? sh.grid : resident;
+    sh.G = kGranules / sh.split;
+    sh.lgG = 0;
+    while ((1 << sh.lgG) < sh.G) ++sh.lgG;
+    sh.lgRp = 0;
+    while ((1 << sh.lgRp) < max_rank) ++sh.lgRp;
     sh.spin_limit = g_spin_limit;
+    sh.zero = 0;
     return sh;
 }
 
@@ -494,41 +1089,45 @@ bool elora::decode_eligible(const elora_linear_desc_t &d, int max_rank)
 {
     (void)max_rank;
     return d.dtype == ELORA_BF16 && d.wfmt == ELORA_W_SAME && d.n_tokens >= 1 && d.n_tokens <= kDecodeMaxTokens &&
-           d.d_in % kChunk == 0 && d.d_out % 16 == 0 && (d.d_out + kTileRows - 1) / kTileRows <= kSyncInts - kCntTile;
+           d.d_in % kChunk == 0 && d.d_out % 16 == 0;
+}
+
+// bytes of the piece mailboxes for d_out output columns: up to 8 K-slices, up to 64 rows
+size_t elora::decode_mail_bytes(int d_out)
+{
+    const size_t n_tiles = ((size_t)d_out + kTileRows - 1) / kTileRows;
+    return n_tiles * kDecodeMaxSplit * kDecodeMaxTokens * kTileRows * sizeof(float);
 }
 
 void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 {
-    DecodeShape sh = make_shape(d.n_tokens, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, d.pool != nullptr);
+    DecodeShape sh = make_shape(d.n_tokens, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1);
     plan->n_launches = 1;
     plan->split_k = sh.split;
     plan->tile_rows = kTileRows;
     plan->tile_cols = 0;
-    plan->grid = sh.n_tiles * sh.split + sh.n_shrink_wgs;
+    plan->grid = sh.grid;
 }
 
 int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream)
 {
     (void)plan;
-    DecodeShape sh = make_shape(a.T, a.K, a.N, a.pool.max_rank, a.has_pool);
-    float *partial = reinterpret_cast<float *>(a.ws + a.wsl.partial);
-    float *v = reinterpret_cast<float *>(a.ws + a.wsl.v);
+    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1);
+    float *mail = reinterpret_cast<float *>(a.ws + a.wsl.mail);
+    float *vmail = reinterpret_cast<float *>(a.ws + a.wsl.vmail);
     int *sync = reinterpret_cast<int *>(a.ws + a.wsl.sync);
-    int *row_slot = reinterpret_cast<int *>(a.ws + a.wsl.row_slot);
-    int *row_rank = reinterpret_cast<int *>(a.ws + a.wsl.row_rank);
-    float *row_scale = reinterpret_cast<float *>(a.ws + a.wsl.row_scale);
     const uint16_t *x = static_cast<const uint16_t *>(a.x);
     const uint16_t *W = static_cast<const uint16_t *>(a.W);
     uint16_t *y = static_cast<uint16_t *>(a.y);
     int has_pool = a.has_pool ? 1 : 0;
-    dim3 grid(sh.n_tiles * sh.split + sh.n_shrink_wgs), block(kThreads);
+    dim3 grid(sh.grid), block(kThreads);
     int tt = (a.T + 15) / 16;
     profile_mark_begin(stream);
     switch (tt) {
-    case 1: hipLaunchKernelGGL((decode_kernel<1>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<2>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
-    case 3: hipLaunchKernelGGL((decode_kernel<3>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
-    default: hipLaunchKernelGGL((decode_kernel<4>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, partial, v, sync, row_slot, row_rank, row_scale, y); break;
+    case 1: hipLaunchKernelGGL((decode_kernel<1>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<2>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 3: hipLaunchKernelGGL((decode_kernel<3>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    default: hipLaunchKernelGGL((decode_kernel<4>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
     }
     ELORA_HIP_TRY(hipGetLastError());
     profile_mark_end(stream);

@@ -46,10 +46,13 @@ WsLayout elora::ws_layout(int T, int K, int N, int R)
     (void)K;
     WsLayout l;
     size_t t = (size_t)(T > 0 ? T : 1);
-    size_t td = t < (size_t)kDecodeMaxTokens ? t : (size_t)kDecodeMaxTokens;
     size_t off = 0;
     l.sync = off;
     off += align_up(sizeof(int) * kSyncInts);
+    l.vmail = off;
+    off += align_up(sizeof(float) * kDecodeMaxTokens * kMaxRank);
+    l.mail = off;
+    off += align_up(decode_mail_bytes(N));
     l.row_slot = off;
     off += align_up(t * sizeof(int32_t));
     l.row_scale = off;
@@ -58,12 +61,8 @@ WsLayout elora::ws_layout(int T, int K, int N, int R)
     off += align_up(t * sizeof(int32_t));
     l.v = off;
     size_t v_full = t * (size_t)R * sizeof(float);
-    size_t v_split = td * (size_t)R * sizeof(float) * kDecodeMaxVSplit;
     size_t v_gemm = gemm_v_bytes((int)t, R);
-    size_t v_max = v_full > v_split ? v_full : v_split;
-    off += align_up(v_max > v_gemm ? v_max : v_gemm);
-    l.partial = off;
-    off += align_up(td * (size_t)N * sizeof(float) * kDecodeMaxSplit);
+    off += align_up(v_full > v_gemm ? v_full : v_gemm);
     l.total = off;
     return l;
 }
@@ -156,10 +155,11 @@ size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank
 }
 
 namespace {
-__global__ void ws_clear_kernel(int *sync, int n)
+// counters to zero, everything behind them to all-ones (the idle state of the decode kernel's mailboxes)
+__global__ void ws_init_kernel(uint32_t *ws, size_t n_words, size_t n_sync)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) sync[i] = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x)
+        ws[i] = i < n_sync ? 0u : 0xFFFFFFFFu;
 }
 }  // namespace
 
@@ -168,8 +168,10 @@ int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t
     if (workspace == nullptr) return ELORA_E_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return ELORA_E_ALIGN;
     if (workspace_bytes < align_up(sizeof(int) * kSyncInts)) return ELORA_E_STORAGE;
-    hipLaunchKernelGGL(ws_clear_kernel, dim3((kSyncInts + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<int *>(workspace), kSyncInts);
+    const size_t n_words = workspace_bytes / sizeof(uint32_t);
+    const size_t blocks = (n_words + 255) / 256;
+    hipLaunchKernelGGL(ws_init_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<uint32_t *>(workspace), n_words, (size_t)kSyncInts);
     ELORA_HIP_TRY(hipGetLastError());
     return ELORA_OK;
 }

@@ -58,6 +58,11 @@ SMALL = [
     (33, 2048, 272, 6, 16, (5,)),
     (64, 4096, 144, 9, (8, 16, 32, 64), (63,)),
     (50, 1280, 4096 + 64, 7, (12, 24, 40), ()),
+    (32, 4096, 256, 8, 16, ()),
+    (20, 256, 32, 3, (8, 100, 256), (1,)),          # ranks up to the maximum: several passes of rows in the expand
+    (9, 1792, 64, 4, (40, 72, 9, 130), ()),         # 7 chunks of K: uneven K-slices
+    (32, 2304, 48, 5, 64, (0, 31)),                 # last tile only three quarters there
+    (48, 768, 16, 2, 8, ()),                        # one wave of the tile active
 ]
 
 
