@@ -168,6 +168,8 @@ size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank
  * writes the idle state (one fill kernel on `stream`), and every linear call leaves the workspace idle
  * again.  Call it again only after a call that used the workspace was aborted (device reset).
  * Two calls that may run at the same time (different streams) need different workspaces.
+ * The first call on a device also finds out how the device places workgroups on its XCDs (one tiny
+ * launch, a small temporary allocation and a wait for `stream`): set-up work, not to be captured in a graph.
  * Errors: E_NULL, E_ALIGN, E_STORAGE, E_HIP.
  */
 int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t stream);
@@ -214,6 +216,13 @@ int elora_force_path(int path);
  * that route at once.  Default 4194304.  Errors: E_SHAPE (limit < 0).
  */
 int elora_debug_spin_limit(int limit);
+
+/*
+ * Test hook: 0 makes the decode kernel run as if the device gave no guarantee that the workgroups
+ * which exchange partial sums share an XCD (every hand-over then goes through memory instead of that
+ * XCD's L2); -1 goes back to what the device was found to do.  Errors: E_SHAPE.
+ */
+int elora_debug_xcd_local(int mode);
 
 /* ------------------------------------------------------------- profiling ---
  * Kernel timing for benchmarks (the roofline figure of a run is quoted on the

@@ -36,7 +36,7 @@ EXPORTED = [
     "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
     "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
-    "elora_debug_spin_limit",
+    "elora_debug_spin_limit", "elora_debug_xcd_local",
 ]
 
 
@@ -91,6 +91,8 @@ lib.elora_workspace_init.restype = ctypes.c_int
 lib.elora_workspace_init.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 lib.elora_debug_spin_limit.restype = ctypes.c_int
 lib.elora_debug_spin_limit.argtypes = [ctypes.c_int]
+lib.elora_debug_xcd_local.restype = ctypes.c_int
+lib.elora_debug_xcd_local.argtypes = [ctypes.c_int]
 lib.elora_profile_arm.restype = ctypes.c_int
 lib.elora_profile_arm.argtypes = [ctypes.c_int]
 lib.elora_profile_read.restype = ctypes.c_int
@@ -212,6 +214,10 @@ def elora_workspace_init(workspace, workspace_bytes: int, stream=None) -> None:
 
 def elora_debug_spin_limit(limit: int) -> None:
     _check(lib.elora_debug_spin_limit(int(limit)), "elora_debug_spin_limit")
+
+
+def elora_debug_xcd_local(mode: int) -> None:
+    _check(lib.elora_debug_xcd_local(int(mode)), "elora_debug_xcd_local")
 
 
 def elora_profile_arm(n_calls: int) -> None:

@@ -99,6 +99,8 @@ int launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t str
 int launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
 
 void decode_set_spin_limit(int limit);
+void decode_set_local_override(int mode);  // 0: never assume XCD-local hand-overs, -1: as probed
+int decode_probe_device(hipStream_t stream);  // finds out, once per device, how workgroups are placed on the XCDs
 bool decode_eligible(const elora_linear_desc_t &d, int max_rank);
 void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
 size_t decode_mail_bytes(int d_out);  // mailboxes of the decode kernel for d_out output columns

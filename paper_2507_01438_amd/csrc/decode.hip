@@ -65,6 +65,9 @@ constexpr int kCntXcd = 32;       // + 32 x (a cache line of its own): workgroup
 constexpr int kGaveUp = 1 << 16;  // this much for every owner on XCD x that gave up (its piece mailboxes may hold pieces nobody took)
 
 int g_spin_limit = 1 << 22;
+int g_local_override = -1;
+constexpr int kMaxDevices = 64;
+int g_local[kMaxDevices];  // per device: is workgroup b placed on XCD b % 8?  0 not probed yet (treated as no), 1 yes, -1 no
 
 // tuning constants (overridable at compile time for experiments)
 #ifndef ELORA_DEC_AHEAD
@@ -105,6 +108,7 @@ struct DecodeShape {
     int lgRp;       // log2 of max_rank rounded up to a power of two
     int spin_limit;
     int zero;       // 0
+    int local;      // 1: workgroup b runs on XCD b % 8 (checked once per device), so a tile's workgroups share an L2
 };
 
 // ---- mailbox accesses (agent scope: past the per-XCD L2) -----------------------------------------
@@ -133,12 +137,19 @@ __device__ __forceinline__ void piece_clear(float *p)
     __hip_atomic_store(q, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(q + 1, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// `zero` is 0, but only the host knows (the compiler would turn an OR with a literal zero into a plain load)
-__device__ __forceinline__ u32x4 piece_load(const float *p, uint64_t zero)
+// `zero` is 0, but only the host knows (the compiler would turn an OR with a literal zero into a plain load).
+// Without the one-XCD guarantee the read-modify-write is done at agent scope (past the L2, in memory).
+__device__ __forceinline__ u32x4 piece_load(const float *p, uint64_t zero, bool local)
 {
     uint64_t *q = reinterpret_cast<uint64_t *>(const_cast<float *>(p));
-    const uint64_t lo = __hip_atomic_fetch_or(q, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    const uint64_t hi = __hip_atomic_fetch_or(q + 1, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    uint64_t lo, hi;
+    if (local) {
+        lo = __hip_atomic_fetch_or(q, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        hi = __hip_atomic_fetch_or(q + 1, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else {
+        lo = __hip_atomic_fetch_or(q, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        hi = __hip_atomic_fetch_or(q + 1, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     return u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
 }
 
@@ -235,10 +246,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         const int xcd = blockIdx.x % kXcds;
         if (tid == 0) {
             int flag = 0;
-            // (counted in the XCD's own L2: every workgroup that touches this counter runs on this XCD)
-            const int before = __hip_atomic_fetch_add(&sync[kCntXcd + 32 * xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            // (counted in the XCD's own L2 when every workgroup that touches this counter is known to run on this XCD)
+            const int before = sh.local ? __hip_atomic_fetch_add(&sync[kCntXcd + 32 * xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
+                                        : __hip_atomic_fetch_add(&sync[kCntXcd + 32 * xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((before & (kGaveUp - 1)) == per_xcd - 1) {
-                __hip_atomic_store(&sync[kCntXcd + 32 * xcd], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (sh.local) __hip_atomic_store(&sync[kCntXcd + 32 * xcd], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                else __hip_atomic_store(&sync[kCntXcd + 32 * xcd], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (before >= kGaveUp) flag |= 2;
                 if (atomicAdd(&sync[kCntAll], 1) == kXcds - 1) {
                     __hip_atomic_store(&sync[kCntAll], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -734,7 +747,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
 #pragma unroll
                 for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
                     if (sd < sh.split && (pv[sd][0] == kEmpty || pv[sd][1] == kEmpty || pv[sd][2] == kEmpty || pv[sd][3] == kEmpty))
-                        pv[sd] = piece_load(src0 + sd * pstride, (uint64_t)(uint32_t)sh.zero);
+                        pv[sd] = piece_load(src0 + sd * pstride, (uint64_t)(uint32_t)sh.zero, sh.local != 0);
             }
             if (gave_up) {
                 s_fail = 1;
@@ -772,7 +785,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         if (s_fail) {
             // some piece did not arrive in time: this workgroup computes its columns from the inputs, and the pieces
             // that are still on their way are removed when the call ends
-            if (tid == 0) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (tid == 0) {
+            if (sh.local) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            else __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
             recompute_columns(sh, x, W, pool, route, has_pool, y, nc0, ncols, wave, lane);
         }
     } else {
@@ -804,7 +820,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     auto p_load = [&]() {
 #pragma unroll
         for (int u = 0; u < PB; ++u)
-            if (pneed[u]) pval[u] = piece_load(psrc[u], (uint64_t)(uint32_t)sh.zero);
+            if (pneed[u]) pval[u] = piece_load(psrc[u], (uint64_t)(uint32_t)sh.zero, sh.local != 0);
     };
     // v: element e of the block of rows q0 .. q0 + qb - 1 is (row q0 + (e >> lgRp), rank column e & (Rp - 1))
     const int Rp = 1 << sh.lgRp;
@@ -1018,7 +1034,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     } else {
         // some piece did not arrive in time: this workgroup computes its columns from the inputs, and the pieces that
         // are still on their way are removed when the call ends
-        if (tid == 0) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (tid == 0) {
+            if (sh.local) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            else __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         recompute_columns(sh, x, W, pool, route, has_pool, y, nc0, ncols, wave, lane);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
@@ -1066,12 +1085,44 @@ DecodeShape make_shape(int T, int K, int N, int max_rank)
     while ((1 << sh.lgRp) < max_rank) ++sh.lgRp;
     sh.spin_limit = g_spin_limit;
     sh.zero = 0;
+    int dev = 0;
+    sh.local = (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices && g_local[dev] == 1 && g_local_override != 0) ? 1 : 0;
     return sh;
 }
 
+// ---- is workgroup b of a launch placed on XCD b % 8? -----------------------------------------------
+__global__ void xcc_probe_kernel(int *xcc_of_block) { xcc_of_block[blockIdx.x] = __builtin_amdgcn_s_getreg(20 | (31 << 11)) & 15; }  // HW_REG_XCC_ID
+
 }  // namespace
 
+// One small launch and a blocking copy: called from set-up code (workspace initialisation), never from a linear call.
+int elora::decode_probe_device(hipStream_t stream)
+{
+    int dev = 0;
+    ELORA_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices || g_local[dev] != 0) return ELORA_OK;
+    constexpr int n = 256;
+    int *d = nullptr;
+    int h[n];
+    ELORA_HIP_TRY(hipMalloc(&d, sizeof(h)));
+    hipLaunchKernelGGL(xcc_probe_kernel, dim3(n), dim3(64), 0, stream, d);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(h, d, sizeof(h), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(d);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return ELORA_E_HIP;
+    }
+    // blocks with the same b % 8 must share an XCD (one XCD in all is the degenerate case of that)
+    bool ok = true;
+    for (int b = kXcds; b < n; ++b) ok = ok && h[b] == h[b % kXcds];
+    g_local[dev] = ok ? 1 : -1;
+    return ELORA_OK;
+}
+
 void elora::decode_set_spin_limit(int limit) { g_spin_limit = limit; }
+void elora::decode_set_local_override(int mode) { g_local_override = mode; }
 
 #ifdef ELORA_TRACE
 extern "C" int elora_trace_read(long long *host_out, int n_values)

@@ -173,13 +173,20 @@ int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t
     hipLaunchKernelGGL(ws_init_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<uint32_t *>(workspace), n_words, (size_t)kSyncInts);
     ELORA_HIP_TRY(hipGetLastError());
-    return ELORA_OK;
+    return decode_probe_device(static_cast<hipStream_t>(stream));
 }
 
 int elora_debug_spin_limit(int limit)
 {
     if (limit < 0) return ELORA_E_SHAPE;
     decode_set_spin_limit(limit);
+    return ELORA_OK;
+}
+
+int elora_debug_xcd_local(int mode)
+{
+    if (mode != 0 && mode != -1) return ELORA_E_SHAPE;
+    decode_set_local_override(mode);
     return ELORA_OK;
 }
 

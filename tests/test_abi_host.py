@@ -141,5 +141,7 @@ def test_workspace_init_and_hooks_validate_arguments(B):
     assert B.lib.elora_workspace_init(FAKE, 100, 0) == B.ELORA_E_STORAGE
     assert B.lib.elora_debug_spin_limit(-1) == B.ELORA_E_SHAPE
     assert B.lib.elora_debug_spin_limit(1 << 22) == B.ELORA_OK
+    assert B.lib.elora_debug_xcd_local(1) == B.ELORA_E_SHAPE
+    assert B.lib.elora_debug_xcd_local(-1) == B.ELORA_OK
     assert B.lib.elora_profile_arm(-1) == B.ELORA_E_SHAPE
     assert B.lib.elora_profile_arm(0) == B.ELORA_OK

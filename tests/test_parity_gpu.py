@@ -230,6 +230,31 @@ def test_decode_epilogue_without_the_shrink_hand_off():
     case.close()
 
 
+def test_decode_without_the_one_xcd_guarantee():
+    """The hand-overs between workgroups normally meet in the L2 of the XCD they share; without that
+    guarantee they go through memory.  Same results either way, also when the waits are cut short."""
+    w = I.small_workload(62, I.BF16, 2048, 1040, 30, 6, (8, 16, 24, 32), no_adapter_rows=(4,))
+    case = DeviceCase(w, w.projections[0])
+    ref = case.reference()
+    y_local = case.run(force_path=DECODE)
+    case.B.elora_debug_xcd_local(0)
+    try:
+        y_mem = case.run(force_path=DECODE)
+        assert np.array_equal(y_local, y_mem)
+        case.B.elora_debug_spin_limit(0)
+        try:
+            y_slow = case.run(force_path=DECODE)
+        finally:
+            case.B.elora_debug_spin_limit(1 << 22)
+        _check(case, y_slow, ref)
+        y_again = case.run(force_path=DECODE)
+        assert np.array_equal(y_local, y_again)
+    finally:
+        case.B.elora_debug_xcd_local(-1)
+    _check(case, y_local, ref)
+    case.close()
+
+
 def test_decode_back_to_back_calls_share_one_workspace():
     """Many calls in a row on one stream and one workspace: the counters a call leaves behind
     must be exactly what the next call expects (checked on the last result and on a changed batch)."""
