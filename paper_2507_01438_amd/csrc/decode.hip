@@ -44,17 +44,15 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-#ifndef ELORA_DEC_SUB
-#define ELORA_DEC_SUB 128  // elements of K per sub-span (a base workgroup keeps two sub-spans in flight): 128 or 256
-#endif
-
 constexpr int kWaves = 4;         // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kRowsPerWave = 16;  // W rows per wave (one MFMA row block)
 constexpr int kTileRows = kWaves * kRowsPerWave;
 constexpr int kGranules = kTileRows / 4;  // a granule = 4 adjacent columns = what one lane holds of one row of x
 constexpr int kChunk = 256;               // K elements per register set of W (8 MFMA K steps)
-constexpr int kPitch = ELORA_DEC_SUB == 128 ? 520 : 776;  // LDS elements per row of x: room for the x ring (3 sub-spans) and for the staging afterwards
+// LDS elements per row of x: room for the x ring (5 sub-spans of 128 elements with up to 32 rows, else 3) and for the
+// staging afterwards
+__host__ __device__ constexpr int pitch_of(int tt) { return tt <= 2 ? 640 : 384; }
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 
 constexpr int kXcds = 8;                  // workgroup b runs on XCD b % 8
@@ -71,10 +69,10 @@ int g_local[kMaxDevices];  // per device: is workgroup b placed on XCD b % 8?  0
 
 // tuning constants (overridable at compile time for experiments)
 #ifndef ELORA_DEC_AHEAD
-#define ELORA_DEC_AHEAD 2  // sub-spans a base workgroup keeps in flight: 1 or 2
+#define ELORA_DEC_AHEAD 4  // sub-spans of K (128 elements) a workgroup keeps in flight with up to 32 rows of x: 2 or 4
 #endif
 #ifndef ELORA_DEC_TARGET_WGS
-#define ELORA_DEC_TARGET_WGS 256  // base workgroups aimed at: one per compute unit (two fit)
+#define ELORA_DEC_TARGET_WGS 512  // workgroups aimed at: two per compute unit, if that many fit
 #endif
 
 // Optional phase timestamps for tuning (compiled in only with -DELORA_TRACE): slot i of workgroup b.  The stamps are
@@ -211,6 +209,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                                                                            uint16_t *__restrict__ y)
 {
     // x ring during the contraction; staging of pieces, v and d afterwards
+    constexpr int kPitch = pitch_of(TT);
     __shared__ __attribute__((aligned(16))) uint16_t xs[TT * 16 * kPitch];
     __shared__ int s_slot[kDecodeMaxTokens], s_rank[kDecodeMaxTokens];
     __shared__ float s_scale[kDecodeMaxTokens];
@@ -287,21 +286,21 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     // the rows of x global -> LDS; kDepth sub-spans are on their way at any time, no more: requests a compute unit
     // has queued beyond what the memory system is working on only delay whatever that unit asks for next (the
     // helper workgroups live on latency), without adding bandwidth.
-    constexpr int kSub = ELORA_DEC_SUB, kSubSteps = kSub / 32;
-    constexpr int kAhead = ELORA_DEC_AHEAD;          // sub-spans in flight while one is being multiplied: 1 or 2
-    constexpr int kBufs = 3;                         // the sub-spans in flight and the one being multiplied
-    constexpr int kRowsPerInstr = 512 / kSub;        // a direct-to-LDS instruction moves 1 KiB: 4 rows of 128 or 2 rows of 256 elements
+    constexpr int kSub = 128, kSubSteps = kSub / 32;
+    constexpr int kAhead = TT <= 2 ? ELORA_DEC_AHEAD : 2;  // sub-spans in flight while one is being multiplied
+    constexpr int kBufs = kAhead + 1;                      // the sub-spans in flight and the one being multiplied
+    constexpr int kRowsPerInstr = 512 / kSub;              // a direct-to-LDS instruction moves 1 KiB: 4 rows of 128 elements
     constexpr int kLanesPerRow = 64 / kRowsPerInstr;
     constexpr int kXInstr = TT * 16 / kRowsPerInstr / kWaves;  // such instructions per wave and sub-span
     constexpr int kOps = kXInstr + kSubSteps;                  // vector-memory operations per wave and sub-span
-    static_assert(kSub == 128 || kSub == 256, "sub-span");
+    static_assert(kAhead == 2 || kAhead == 4, "ring depth");
     static_assert(sizeof(xs) >= (size_t)kBufs * TT * 16 * kSub * 2, "x ring fits");
-    static_assert(kOps < 64, "vmcnt range");
-    u32x4 wset[2][kSubSteps];
+    static_assert(kAhead * kOps + 8 < 64, "vmcnt range");
+    u32x4 wset[kAhead][kSubSteps];
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
     uint16_t *const xring = &xs[0];  // [kBufs][TT * 16 rows][kSub / 8 slots of 8 elements]; slot = chunk ^ (row % 16)
-    const int nsub = nchunks * (kChunk / kSub);  // >= 2 when kSub == 128; >= 1 otherwise
+    const int nsub = nchunks * (kChunk / kSub);  // even, at least 2
 
     // x first, then W: when the wave's W loads of a sub-span are back, so is its share of x (in-order counter).
     // Rows past the batch repeat the last row, and waves whose 16 rows of W lie past d_out load row 0: what they
@@ -326,12 +325,19 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
 
     // wait until at most `later` sub-spans are still on their way, meet the other waves (their shares of x for
     // sub-span p are in LDS then, and everybody is done with sub-span p - 1), multiply
-    auto arrive = [&](bool one_later) {
-        if (one_later) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOps));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    // wait until at most `later` younger sub-spans are still on their way, then meet the other waves: their shares of x
+    // for the oldest sub-span are in LDS then, and everybody is done with the one before it
+    auto meet = [&]() {
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+    };
+    auto arrive = [&](int later) {
+        if (later >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * kOps));
+        else if (later == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
+        else if (later == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 * kOps));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        meet();
     };
     auto multiply = [&](int p, const u32x4 *wc) {
         // The LDS reads are written as assembly: the compiler holds every LDS read back until ALL direct-to-LDS
@@ -356,15 +362,30 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                 acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[j][tt]), acc[tt], 0, 0, 0);
         }
     };
-    auto step = [&](int p, const u32x4 *wc, bool one_later) {
-        arrive(one_later);
-        multiply(p, wc);
+    // the first sub-spans go out (2 or 4: nsub is even); `extra` older requests of this wave are to stay in flight as
+    // well when the wait that follows returns, i.e. it returns when everything older than those has arrived
+    auto first_issue_then_wait = [&](bool with_unit_loads) {
+        issue(0, wset[0]);
+        issue(1, wset[1]);
+        if (kAhead == 4 && nsub >= 4) {
+            issue(2, wset[2 % kAhead]);
+            issue(3, wset[3 % kAhead]);
+            if (with_unit_loads) __builtin_amdgcn_s_waitcnt(vmcnt_imm(6 + 4 * kOps));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * kOps));
+        } else {
+            if (with_unit_loads) __builtin_amdgcn_s_waitcnt(vmcnt_imm(6 + 2 * kOps));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
+        }
+    };
+    auto wait_older_than_first_issue = [&]() {
+        if (kAhead == 4 && nsub >= 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * kOps));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
     };
 
     // ---- phase 1: routes of all rows, and this workgroup's share of the shrink ---------------------------
     // A unit = (row t, rank rows j0 and j0 + 1) is worked on by the whole workgroup: thread = 16-byte pieces tid,
     // tid + 256, ... of the three rows involved (x_t and two rows of A_i), 1024 pieces (K = 4096 elements) a round.
-    constexpr int UL = 2;  // pieces per thread and round
+    constexpr int UL = 2;  // pieces per thread and round (3 * UL = 6 loads: see first_issue_then_wait)
     const int pieces = K >> 3;
     auto unit_load = [&](const uint16_t *A0, const uint16_t *A1, const uint16_t *xt, int pb, u32x4 *xv, u32x4 *a0, u32x4 *a1) {
 #pragma unroll
@@ -409,25 +430,24 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         }
     };
     const int n_units = has_pool ? T * sh.jgroups : 0;
-    // units number n_first on of this workgroup (the routes are in LDS), each from its loads to its v in one go
+    // Units number n_first on of this workgroup (the routes are in LDS): one per wave at a time, 24 loads of 16 bytes per
+    // lane in flight (a workgroup with many units has four of them under way instead of one after the other).
     auto units_from = [&](int n_first) {
         if ((int)blockIdx.x >= sh.n_pub) return;
-        int n = n_first;
-        for (int u = blockIdx.x + sh.n_pub * n_first; u < n_units; u += sh.n_pub, ++n) {
-            const int t = u / sh.jgroups, j0 = (u - t * sh.jgroups) * 2;
+        for (int n = n_first + wave;; n += kWaves) {
+            const long long u = (long long)blockIdx.x + (long long)sh.n_pub * n;
+            if (u >= n_units) break;
+            const int t = (int)u / sh.jgroups, j0 = ((int)u - t * sh.jgroups) * 2;
             const int slot = s_slot[t], rank = s_rank[t];
-            const bool valid = slot >= 0 && j0 < rank, two = (j0 + 1) < rank;
-            float s0 = 0.0f, s1 = 0.0f;
-            if (valid) {
-                const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
-                const uint16_t *A1 = two ? A0 + K : A0;
-                for (int pb = 0; pb < pieces; pb += UL * kThreads) {
-                    u32x4 xv[UL], a0[UL], a1[UL];
-                    unit_load(A0, A1, x + (size_t)t * K, pb, xv, a0, a1);
-                    unit_dot(pb, xv, a0, a1, s0, s1);
-                }
+            if (slot < 0 || j0 >= rank) continue;
+            const bool two = (j0 + 1) < rank;
+            const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
+            float r0, r1;
+            shrink_pair(A0, two ? A0 + K : A0, x + (size_t)t * K, K, lane, r0, r1);
+            if (lane == 0) {
+                mb_store_f32(&vmail[(size_t)t * R + j0], r0);
+                if (two) mb_store_f32(&vmail[(size_t)t * R + j0 + 1], r1);
             }
-            unit_finish(n, t, j0, valid, two, s0, s1);
         }
     };
     if (idle) {
@@ -465,21 +485,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             const int slot0 = (r0i.idx >= 0 && r0i.idx < pool.capacity) ? r0i.idx : 0;  // any slot is memory that may be read
             const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot0)) + (size_t)j00 * K;
             unit_load(A0, (j00 + 1 < R) ? A0 + K : A0, x + (size_t)t0 * K, 0, uxv, ua0, ua1);
-            issue(0, wset[0]);
-            if (kAhead == 2 && (kSub == 128 || nsub > 1)) {
-                issue(1, wset[1]);
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * UL + 2 * kOps));  // everything older: the table entry
-            } else {
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * UL + kOps));
-            }
+            first_issue_then_wait(true);   // returns when everything older than the unit's loads is here: the table entry
         } else {
-            issue(0, wset[0]);
-            if (kAhead == 2 && (kSub == 128 || nsub > 1)) {
-                issue(1, wset[1]);
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
-            } else {
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOps));
-            }
+            first_issue_then_wait(false);
         }
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" : "+v"(mt.rank), "+v"(mt.scale), "+v"(mt.loaded), "+v"(so));  // not looked at before this point
@@ -499,8 +507,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             const int slot = s_slot[t0], rank = s_rank[t0];
             const bool valid = slot >= 0 && j00 < rank, two = (j00 + 1) < rank;
             float s0 = 0.0f, s1 = 0.0f;
-            if (kAhead == 2 && (kSub == 128 || nsub > 1)) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));  // the unit's loads are back
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOps));
+            wait_older_than_first_issue();  // the unit's loads are back
             unit_dot(0, uxv, ua0, ua1, s0, s1);
             if (valid) {
                 const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j00 * K;
@@ -517,44 +524,40 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         TRACE(1);
     } else {
         issue(0, wset[0]);
-        if (kAhead == 2 && (kSub == 128 || nsub > 1)) issue(1, wset[1]);
+        issue(1, wset[1]);
+        if (kAhead == 4 && nsub >= 4) {
+            issue(2, wset[2 % kAhead]);
+            issue(3, wset[3 % kAhead]);
+        }
     }
 
     // ---- phase 2: base contraction -------------------------------------------------------------------------
-    // Two sub-spans in flight, no more: requests a compute unit has queued beyond what the memory system is
-    // working on only delay whatever that unit asks for next, without adding bandwidth.
-    if (kAhead == 1) {
-        // one sub-span on its way: the next one is asked for as soon as the waves have met, then the current one is multiplied
-        for (int p = 0; p < nsub; p += 2) {
-            arrive(false);
-            if (p == 0) TRACE(4);
-            if (p + 1 < nsub) issue(p + 1, wset[1]);
-            multiply(p, wset[0]);
-            if (p + 1 < nsub) {
-                arrive(false);
-                if (p + 2 < nsub) issue(p + 2, wset[0]);
-                multiply(p + 1, wset[1]);
+    // kAhead sub-spans are in flight, no more: requests a compute unit has queued beyond what the memory system is
+    // working on only delay whatever that unit asks for next, without adding bandwidth.  The steady-state loop is
+    // straight-line code (the compiler then knows exactly which loads a register set is still waiting for).
+    {
+        int p = 0;
+        if (nsub >= kAhead) {
+            for (; p + 2 * kAhead <= nsub; p += kAhead) {
+#pragma unroll
+                for (int d = 0; d < kAhead; ++d) {
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAhead - 1) * kOps));
+                    meet();
+                    if (p == 0 && d == 0) TRACE(4);
+                    multiply(p + d, wset[d]);
+                    issue(p + d + kAhead, wset[d]);
+                }
             }
         }
-    } else if (nsub == 1) {  // only with 256-element sub-spans
-        step(0, wset[0], false);
-    } else {
-        int p = 0;
-        for (; p + 3 < nsub; p += 2) {
-            step(p, wset[0], true);
-            if (p == 0) TRACE(4);
-            issue(p + 2, wset[0]);
-            step(p + 1, wset[1], true);
-            issue(p + 3, wset[1]);
-        }
-        if (p + 2 < nsub) {  // three left
-            step(p, wset[0], true);
-            issue(p + 2, wset[0]);
-            step(p + 1, wset[1], true);
-            step(p + 2, wset[0], false);
-        } else {  // two left
-            step(p, wset[0], true);
-            step(p + 1, wset[1], false);
+        // what is left: at most 2 kAhead - 1 sub-spans, the first kAhead of them (or all) already asked for
+#pragma unroll
+        for (int i = 0; i < 2 * kAhead - 1; ++i) {
+            const int q = p + i;
+            if (q < nsub) {
+                arrive(min(kAhead - 1, nsub - 1 - q));
+                multiply(q, wset[i % kAhead]);
+                if (q + kAhead < nsub) issue(q + kAhead, wset[i % kAhead]);
+            }
         }
     }
     TRACE(5);  // contraction done
@@ -1049,12 +1052,36 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     finish_call();
 }
 
+// workgroups of decode_kernel<tt> the device holds at once (registers and LDS decide; asked once per instance)
+int resident_workgroups(int tt)
+{
+    static int cached[5] = {0, 0, 0, 0, 0};
+    if (cached[tt] == 0) {
+        int per_cu = 0, cus = 0, dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) {
+            switch (tt) {
+            case 1: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<1>, kThreads, 0); break;
+            case 2: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<2>, kThreads, 0); break;
+            case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<3>, kThreads, 0); break;
+            default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<4>, kThreads, 0); break;
+            }
+        }
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return 64;  // not cached: a cautious figure for this call (e.g. no device in this process yet)
+        }
+        cached[tt] = per_cu * cus > 0 ? per_cu * cus : 64;
+    }
+    return cached[tt];
+}
+
 // K-slices = owners per tile: the largest of 1, 2, 4, 8 that keeps all workgroups of the call resident at once
-int pick_split(int K, int n_tiles, int tt)
+int pick_split(int K, int n_tiles, int resident)
 {
     const int chunks = K / kChunk;
-    (void)tt;
-    const int target = ELORA_DEC_TARGET_WGS;
+    const int target = resident < ELORA_DEC_TARGET_WGS ? resident : ELORA_DEC_TARGET_WGS;
     int best = 1;
     for (int s = 2; s <= kDecodeMaxSplit; s *= 2)
         if (s <= chunks && n_tiles * s <= target) best = s;
@@ -1071,12 +1098,12 @@ DecodeShape make_shape(int T, int K, int N, int max_rank)
     sh.n_tiles = (N + kTileRows - 1) / kTileRows;
     sh.jgroups = (max_rank + 1) / 2;
     const int tt = (T + 15) / 16;
-    sh.split = pick_split(K, sh.n_tiles, tt);
+    const int resident = resident_workgroups(tt);
+    sh.split = pick_split(K, sh.n_tiles, resident);
     sh.total = sh.n_tiles * sh.split;
     const int unit = kXcds * sh.split;
     sh.grid = (sh.total + unit - 1) / unit * unit;
     // the workgroups that share the shrink must all be running before anybody can wait for them
-    const int resident = 512;  // 2 workgroups per compute unit (registers, and LDS with more than 32 rows)
     sh.n_pub = sh.grid < resident ? sh.grid : resident;
     sh.G = kGranules / sh.split;
     sh.lgG = 0;

@@ -118,7 +118,9 @@ def test_kernel_family_selection(B):
     n = B.elora_pool_storage_bytes(4096, 4096, 16, 64, B.ELORA_BF16)
     h = B.elora_pool_create(4096, 4096, 16, 64, B.ELORA_BF16, FAKE, n)
     p = B.elora_linear_plan(_desc(B, h))
-    assert p.path == B.ELORA_PATH_DECODE and p.n_launches == 1 and p.grid >= 256 and p.split_k >= 1
+    # (the K-split depends on how many workgroups the device holds at once; without a device the plan is a cautious one)
+    assert p.path == B.ELORA_PATH_DECODE and p.n_launches == 1 and p.split_k in (1, 2, 4, 8)
+    assert p.grid >= 64 * p.split_k and p.grid % (8 * p.split_k) == 0 and p.tile_rows == 64
     # fp32 and odd shapes go to the plain-ALU kernels
     p = B.elora_linear_plan(_desc(B, None, dtype=B.ELORA_F32, d_in=512, d_out=512, n_tokens=8))
     assert p.path == B.ELORA_PATH_GENERIC
