@@ -208,6 +208,24 @@ __device__ __forceinline__ RowRoute resolve_row(int t, const RouteView &r, const
 typedef uint32_t elora_u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 elora_bf16x2 __attribute__((ext_vector_type(2)));
 
+// Sum over the 64 lanes of a wave, the same value in every lane, with cross-lane operations of the vector ALU only
+// (quad permutes and row mirrors inside rows of 16 lanes, then one lane of each row).  Unlike a shuffle it is no
+// LDS-pipeline instruction, so it does not wait for direct-to-LDS loads that happen to be in flight.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    int b = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, b, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+    b = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, b, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+    b = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, b, 0x141, 0xF, 0xF, false));  // row_half_mirror
+    b = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, b, 0x140, 0xF, 0xF, false));  // row_mirror
+    b = __float_as_int(v);
+    return (__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48)));
+}
+
 // One wave: v[t][j0], v[t][j0+1] = A_i[j0..j0+1, :] . x[t, :] over the whole of K (K % 256 == 0).
 __device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, const uint16_t *__restrict__ A1,
                                             const uint16_t *__restrict__ xt, int K, int lane, float &r0, float &r1)
@@ -239,12 +257,8 @@ __device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, con
             }
         }
     }
-    for (int off = 32; off > 0; off >>= 1) {
-        s0 += __shfl_xor(s0, off);
-        s1 += __shfl_xor(s1, off);
-    }
-    r0 = s0;
-    r1 = s1;
+    r0 = wave_sum(s0);
+    r1 = wave_sum(s1);
 }
 
 __device__ __forceinline__ const char *slot_A(const PoolView &p, int slot) { return p.slots + (size_t)slot * p.slot_bytes; }

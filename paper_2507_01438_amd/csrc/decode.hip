@@ -36,6 +36,8 @@
 // Summation order is fixed (no float atomics): results are bit-identical from run to run.
 #include "common.h"
 
+#include <type_traits>
+
 using namespace elora;
 
 namespace {
@@ -54,6 +56,7 @@ constexpr int kChunk = 256;               // K elements per register set of W (8
 // staging afterwards
 __host__ __device__ constexpr int pitch_of(int tt) { return tt <= 2 ? 640 : 384; }
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
+constexpr int kMetaLds = 512;  // slot tables up to this many entries are copied to LDS whole
 
 constexpr int kXcds = 8;                  // workgroup b runs on XCD b % 8
 
@@ -123,17 +126,17 @@ __host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | 0x0F70 | 
 // the end of the kernel) and leave the line in the L2; reads are plain loads the first time (nothing of these lines
 // can be in the first-level cache yet) and atomic read-modify-writes (OR with zero) when they have to be repeated:
 // those always execute in the L2, so they can neither see a stale first-level line nor have to go out to memory.
+// (one 16-byte store per lane, so that a wave writes whole cache lines: written through in 8-byte halves the same data
+// costs four times the memory traffic)
 __device__ __forceinline__ void piece_store(float *p, float a, float b, float c, float d)
 {
-    uint64_t *q = reinterpret_cast<uint64_t *>(p);
-    __hip_atomic_store(q, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(q + 1, (uint64_t)__float_as_uint(c) | ((uint64_t)__float_as_uint(d) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u32x4 v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void piece_clear(float *p)
 {
-    uint64_t *q = reinterpret_cast<uint64_t *>(p);
-    __hip_atomic_store(q, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(q + 1, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u32x4 v = {kEmpty, kEmpty, kEmpty, kEmpty};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
 // `zero` is 0, but only the host knows (the compiler would turn an OR with a literal zero into a plain load).
 // Without the one-XCD guarantee the read-modify-write is done at agent scope (past the L2, in memory).
@@ -149,6 +152,22 @@ __device__ __forceinline__ u32x4 piece_load(const float *p, uint64_t zero, bool 
         hi = __hip_atomic_fetch_or(q + 1, zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     return u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+}
+
+// LDS reads the compiler does not see as such.  While direct-to-LDS loads are in flight it holds EVERY LDS read back
+// until all of them have landed (it cannot tell what they overwrite), which would stall whatever reads LDS between the
+// first requests of the stream and the stream's own loop.  These reads wait for nothing but themselves.
+__device__ __forceinline__ int lds_read_i32(const int *p)
+{
+    int v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p) : "memory");
+    return v;
+}
+__device__ __forceinline__ float lds_read_f32(const float *p)
+{
+    float v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p) : "memory");
+    return v;
 }
 
 // piece (tile, owner, sender): [T][G][4] floats
@@ -215,6 +234,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     __shared__ float s_scale[kDecodeMaxTokens];
     __shared__ int s_flag, s_fail, s_vfail, s_odd;
     __shared__ float s_red[2][kWaves][2];
+    __shared__ __attribute__((aligned(16))) SlotMeta s_meta[kMetaLds];  // the pool's slot table, if it is small enough
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = sh.T, K = sh.K, N = sh.N;
@@ -241,7 +261,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     // workgroup of the call empties the v mailbox (everybody has read what it needed).  Counters and flags go back
     // to zero.  Everything this workgroup posted has been acknowledged before it counts itself.
     auto finish_call = [&]() {
-        TRACE_DUMP;
         const int xcd = blockIdx.x % kXcds;
         if (tid == 0) {
             int flag = 0;
@@ -259,7 +278,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             }
             s_flag = flag;
         }
-        __syncthreads();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         if ((s_flag & 1) && has_pool)
             for (int e = tid; e < T * R; e += kThreads) mb_store_f32(&vmail[e], __uint_as_float(kEmpty));
         if (s_flag & 2) {
@@ -269,6 +290,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             const size_t n = p1 > p0 ? (size_t)(p1 - p0) * sh.split * piece_floats(sh) : 0;
             for (size_t e = (size_t)tid * 4; e < n; e += (size_t)kThreads * 4) piece_clear(base + e);
         }
+        TRACE(14);
+        TRACE_DUMP;
     };
 
     // ---- set-up of the base contraction (its first loads go out in the middle of phase 1) ----------------------
@@ -362,25 +385,6 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                 acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[j][tt]), acc[tt], 0, 0, 0);
         }
     };
-    // the first sub-spans go out (2 or 4: nsub is even); `extra` older requests of this wave are to stay in flight as
-    // well when the wait that follows returns, i.e. it returns when everything older than those has arrived
-    auto first_issue_then_wait = [&](bool with_unit_loads) {
-        issue(0, wset[0]);
-        issue(1, wset[1]);
-        if (kAhead == 4 && nsub >= 4) {
-            issue(2, wset[2 % kAhead]);
-            issue(3, wset[3 % kAhead]);
-            if (with_unit_loads) __builtin_amdgcn_s_waitcnt(vmcnt_imm(6 + 4 * kOps));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * kOps));
-        } else {
-            if (with_unit_loads) __builtin_amdgcn_s_waitcnt(vmcnt_imm(6 + 2 * kOps));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
-        }
-    };
-    auto wait_older_than_first_issue = [&]() {
-        if (kAhead == 4 && nsub >= 4) __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * kOps));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
-    };
 
     // ---- phase 1: routes of all rows, and this workgroup's share of the shrink ---------------------------
     // A unit = (row t, rank rows j0 and j0 + 1) is worked on by the whole workgroup: thread = 16-byte pieces tid,
@@ -411,10 +415,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     };
     // the four waves' sums of one unit meet in LDS (two sets, used in turn: one barrier per unit); thread 0 posts v
     auto unit_finish = [&](int n, int t, int j0, bool valid, bool two, float s0, float s1) {
-        for (int off = 32; off > 0; off >>= 1) {
-            s0 += __shfl_xor(s0, off);
-            s1 += __shfl_xor(s1, off);
-        }
+        s0 = wave_sum(s0);
+        s1 = wave_sum(s1);
         if (lane == 0) {
             s_red[n & 1][wave][0] = s0;
             s_red[n & 1][wave][1] = s1;
@@ -423,8 +425,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (tid == 0 && valid) {
-            const float r0 = (s_red[n & 1][0][0] + s_red[n & 1][1][0]) + (s_red[n & 1][2][0] + s_red[n & 1][3][0]);
-            const float r1 = (s_red[n & 1][0][1] + s_red[n & 1][1][1]) + (s_red[n & 1][2][1] + s_red[n & 1][3][1]);
+            const float(*rd)[2] = s_red[n & 1];
+            const float r0 = (lds_read_f32(&rd[0][0]) + lds_read_f32(&rd[1][0])) + (lds_read_f32(&rd[2][0]) + lds_read_f32(&rd[3][0]));
+            const float r1 = (lds_read_f32(&rd[0][1]) + lds_read_f32(&rd[1][1])) + (lds_read_f32(&rd[2][1]) + lds_read_f32(&rd[3][1]));
             mb_store_f32(&vmail[(size_t)t * R + j0], r0);
             if (two) mb_store_f32(&vmail[(size_t)t * R + j0 + 1], r1);
         }
@@ -438,7 +441,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             const long long u = (long long)blockIdx.x + (long long)sh.n_pub * n;
             if (u >= n_units) break;
             const int t = (int)u / sh.jgroups, j0 = ((int)u - t * sh.jgroups) * 2;
-            const int slot = s_slot[t], rank = s_rank[t];
+            const int slot = lds_read_i32(&s_slot[t]), rank = lds_read_i32(&s_rank[t]);
             if (slot < 0 || j0 >= rank) continue;
             const bool two = (j0 + 1) < rank;
             const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
@@ -465,62 +468,90 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         finish_call();
         return;
     }
-    // A route takes two dependent loads (index, then the slot's table entry) that have nothing to hide behind, so
-    // everything that can be asked for meanwhile is: the first round of the workgroup's first shrink unit (its A_i is
-    // known with the index; whether the rank reaches that far is checked afterwards) and the first sub-spans of W
-    // and x.  In-order return then delivers the routes first, the unit next and the stream right after.  (Straight-
-    // line code on purpose: the compiler then counts the loads in flight exactly.)
+    // A route takes two dependent loads: index, then the slot's table entry.  A small slot table is fetched whole
+    // alongside the index, so that the second one is an LDS read.  Nothing of the stream is asked for before the routes
+    // are known: what a compute unit asks for queues behind what it has asked for, so the table entry would come back
+    // when most of the stream's first requests have, and at very different times in different workgroups (those that
+    // have it start streaming and are in the way of those that do not).  After the first direct-to-LDS request the
+    // compiler holds every ordinary LDS read back until all such requests have landed, so from there to the end of the
+    // contraction LDS is only read through lds_read_* and the assembly in multiply().
     if (has_pool) {
         const int tr = min(tid, T - 1);  // threads past the batch repeat its last row and keep nothing
+#ifdef ELORA_DBG_NOUNIT
+        const bool unit0 = false;
+#else
         const bool unit0 = (int)blockIdx.x < sh.n_pub && (int)blockIdx.x < n_units;
+#endif
         const int t0 = unit0 ? (int)blockIdx.x / sh.jgroups : 0, j00 = ((int)blockIdx.x - t0 * sh.jgroups) * 2;
-        const RouteIndex ri = route_index(tr, route);
-        const RouteIndex r0i = route_index(t0, route);
-        SlotMeta mt = pool.meta[(ri.idx >= 0 && ri.idx < pool.capacity) ? ri.idx : 0];
-        float so = (route.scales != nullptr && ri.idx != -1) ? route.scales[ri.scale_at] : 0.0f;
-        u32x4 uxv[UL], ua0[UL], ua1[UL];
-        __builtin_amdgcn_sched_barrier(0);
-        TRACE(11);  // index known, table entry asked for
-        if (unit0) {
-            const int slot0 = (r0i.idx >= 0 && r0i.idx < pool.capacity) ? r0i.idx : 0;  // any slot is memory that may be read
-            const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot0)) + (size_t)j00 * K;
-            unit_load(A0, (j00 + 1 < R) ? A0 + K : A0, x + (size_t)t0 * K, 0, uxv, ua0, ua1);
-            first_issue_then_wait(true);   // returns when everything older than the unit's loads is here: the table entry
-        } else {
-            first_issue_then_wait(false);
+        const bool table = pool.capacity <= kMetaLds;
+        u32x4 tab[kMetaLds / kThreads];
+        if (table) {
+#pragma unroll
+            for (int i = 0; i < kMetaLds / kThreads; ++i)
+                if (tid + i * kThreads < pool.capacity) tab[i] = reinterpret_cast<const u32x4 *>(pool.meta)[tid + i * kThreads];
         }
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("" : "+v"(mt.rank), "+v"(mt.scale), "+v"(mt.loaded), "+v"(so));  // not looked at before this point
-        TRACE(12);  // table entry here
+        const RouteIndex ri = route_index(tr, route);
+        const int idx_c = (ri.idx >= 0 && ri.idx < pool.capacity) ? ri.idx : 0;
+        const float so = (route.scales != nullptr && ri.idx != -1) ? route.scales[ri.scale_at] : 0.0f;
+        SlotMeta mt;
+        TRACE(11);  // index known
+        if (table) {
+#pragma unroll
+            for (int i = 0; i < kMetaLds / kThreads; ++i)
+                if (tid + i * kThreads < pool.capacity) reinterpret_cast<u32x4 *>(s_meta)[tid + i * kThreads] = tab[i];
+            __syncthreads();
+            mt = s_meta[idx_c];
+        } else {
+            mt = pool.meta[idx_c];
+        }
         const RowRoute rr = route_finish(tr, ri, mt, so, route, pool, blockIdx.x == 0 && tid < T);
+        TRACE(12);  // table entry here
         if (tid < T) {
             s_slot[tid] = rr.slot;
             s_rank[tid] = rr.rank;
             s_scale[tid] = rr.scale;
             if (rr.rank & 7) s_odd = 1;  // rows of this B_i are not 16-byte aligned
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the routes are in LDS (a full fence would also wait for the stream)
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
+        __syncthreads();
         TRACE(13);  // routes in LDS
-        if (unit0) {
-            const int slot = s_slot[t0], rank = s_rank[t0];
-            const bool valid = slot >= 0 && j00 < rank, two = (j00 + 1) < rank;
-            float s0 = 0.0f, s1 = 0.0f;
-            wait_older_than_first_issue();  // the unit's loads are back
-            unit_dot(0, uxv, ua0, ua1, s0, s1);
-            if (valid) {
-                const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j00 * K;
-                const uint16_t *A1 = two ? A0 + K : A0;
+        // The workgroup's first shrink unit and the first sub-spans of the stream go out together.  (One straight-line
+        // copy of this per case: across a branch the compiler stops counting loads in flight and waits for all of them.)
+        const int slot0 = s_slot[t0], rank0 = s_rank[t0];
+        const bool valid0 = unit0 && slot0 >= 0 && j00 < rank0, two0 = (j00 + 1) < rank0;
+        auto first_requests = [&](auto four, auto with_unit) {
+            constexpr int n_first = decltype(four)::value ? 4 : 2;
+            u32x4 uxv[UL], ua0[UL], ua1[UL];
+            const uint16_t *uA0 = nullptr, *uA1 = nullptr;
+            if constexpr (decltype(with_unit)::value) {
+                uA0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot0)) + (size_t)j00 * K;
+                uA1 = two0 ? uA0 + K : uA0;
+                unit_load(uA0, uA1, x + (size_t)t0 * K, 0, uxv, ua0, ua1);
+            }
+#pragma unroll
+            for (int p = 0; p < n_first; ++p) issue(p, wset[p % kAhead]);
+            if constexpr (decltype(with_unit)::value) {
+                float s0 = 0.0f, s1 = 0.0f;
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(n_first * kOps));  // the unit's loads are back
+                __builtin_amdgcn_sched_barrier(0);
+                unit_dot(0, uxv, ua0, ua1, s0, s1);
                 for (int pb = UL * kThreads; pb < pieces; pb += UL * kThreads) {  // K above 4096: the other rounds
                     u32x4 xv[UL], a0[UL], a1[UL];
-                    unit_load(A0, A1, x + (size_t)t0 * K, pb, xv, a0, a1);
+                    unit_load(uA0, uA1, x + (size_t)t0 * K, pb, xv, a0, a1);
                     unit_dot(pb, xv, a0, a1, s0, s1);
                 }
+                unit_finish(0, t0, j00, true, two0, s0, s1);
             }
-            unit_finish(0, t0, j00, valid, two, s0, s1);
-            units_from(1);
+        };
+        const bool four = kAhead == 4 && nsub >= 4;
+        if (valid0) {
+            if (four) first_requests(std::true_type{}, std::true_type{});
+            else first_requests(std::false_type{}, std::true_type{});
+        } else {
+            if (four) first_requests(std::true_type{}, std::false_type{});
+            else first_requests(std::false_type{}, std::false_type{});
         }
+        if (unit0) units_from(1);
         TRACE(1);
     } else {
         issue(0, wset[0]);
@@ -582,6 +613,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     // What follows runs on four waves with nothing to overlap it, and a wave on its own issues an instruction only
     // every 8 to 10 clocks: the number of instructions on this path is what the tail of the kernel costs.  The common
     // case (every rank a multiple of 8, none above 64) therefore has a short path of its own.
+    bool acked = false;  // everything this thread posted to other workgroups has been acknowledged
     const bool lean = !has_pool || (s_odd == 0 && R <= 64 && sh.lgRp >= 3);
     if (lean) {
         const int lgRp = sh.lgRp, Rp = 1 << lgRp;  // pitch of v in LDS: max_rank rounded up to a power of two, 8 .. 64
@@ -727,6 +759,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             asm volatile("" ::: "memory");
         }
         TRACE(2);  // adapter term formed
+        // Everything this thread has posted so far (pieces, shrink results) is acknowledged once the piece loads that
+        // are needed next are back; the workgroup can then count itself done right after its last stores, without
+        // waiting for those.
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        acked = true;
         // every (row, granule) cell of the own columns: the piece of each K-slice (again through L2 atomics while one
         // is missing), added in fixed order, plus d, rounded once, stored at the row's own position
         for (int cell = tid; cell < n_cells; cell += kThreads) {
@@ -749,8 +786,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                 __builtin_amdgcn_s_sleep(1);
 #pragma unroll
                 for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
-                    if (sd < sh.split && (pv[sd][0] == kEmpty || pv[sd][1] == kEmpty || pv[sd][2] == kEmpty || pv[sd][3] == kEmpty))
+                    if (sd < sh.split && (pv[sd][0] == kEmpty || pv[sd][1] == kEmpty || pv[sd][2] == kEmpty || pv[sd][3] == kEmpty)) {
                         pv[sd] = piece_load(src0 + sd * pstride, (uint64_t)(uint32_t)sh.zero, sh.local != 0);
+                    }
             }
             if (gave_up) {
                 s_fail = 1;
@@ -793,6 +831,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             else __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
             recompute_columns(sh, x, W, pool, route, has_pool, y, nc0, ncols, wave, lane);
+            acked = false;
         }
     } else {
     const int n_items = sh.split * n_cells;  // (sender, cell) = 16 T: at most four per thread
@@ -1047,8 +1086,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     }
     }
     TRACE(7);  // y written
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // what this workgroup posted has been acknowledged
-    __syncthreads();
+    if (!acked) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // what this workgroup posted has been acknowledged
+        __syncthreads();
+    }
     finish_call();
 }
 
