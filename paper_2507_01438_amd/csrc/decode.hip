@@ -170,6 +170,13 @@ __device__ __forceinline__ float lds_read_f32(const float *p)
     return v;
 }
 
+__device__ __forceinline__ u32x4 lds_read_b128(const void *p)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p) : "memory");
+    return v;
+}
+
 // piece (tile, owner, sender): [T][G][4] floats
 __device__ __forceinline__ size_t piece_floats(const DecodeShape &sh) { return (size_t)sh.T * sh.G * 4; }
 __device__ __forceinline__ float *piece_ptr(float *mail, const DecodeShape &sh, int tile, int owner, int sender)
@@ -469,12 +476,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         return;
     }
     // A route takes two dependent loads: index, then the slot's table entry.  A small slot table is fetched whole
-    // alongside the index, so that the second one is an LDS read.  Nothing of the stream is asked for before the routes
-    // are known: what a compute unit asks for queues behind what it has asked for, so the table entry would come back
-    // when most of the stream's first requests have, and at very different times in different workgroups (those that
-    // have it start streaming and are in the way of those that do not).  After the first direct-to-LDS request the
-    // compiler holds every ordinary LDS read back until all such requests have landed, so from there to the end of the
-    // contraction LDS is only read through lds_read_* and the assembly in multiply().
+    // alongside the index, so that the second one is an LDS read.  (Left to itself that load comes back when most of the
+    // stream's first requests have, and at very different times in different workgroups: those that have it start
+    // streaming and are in the way of those that do not.)
     if (has_pool) {
         const int tr = min(tid, T - 1);  // threads past the batch repeat its last row and keep nothing
 #ifdef ELORA_DBG_NOUNIT
@@ -495,12 +499,25 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         const float so = (route.scales != nullptr && ri.idx != -1) ? route.scales[ri.scale_at] : 0.0f;
         SlotMeta mt;
         TRACE(11);  // index known
+        // the first two sub-spans of the stream go out now; from here to the end of the contraction LDS is only read
+        // through lds_read_* and the assembly in multiply()
+        issue(0, wset[0]);
+        issue(1, wset[1]);
+        auto meet_lds = [&]() {  // LDS writes visible to the workgroup (no fence: that would wait for the stream, too)
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        };
         if (table) {
 #pragma unroll
             for (int i = 0; i < kMetaLds / kThreads; ++i)
                 if (tid + i * kThreads < pool.capacity) reinterpret_cast<u32x4 *>(s_meta)[tid + i * kThreads] = tab[i];
-            __syncthreads();
-            mt = s_meta[idx_c];
+            meet_lds();
+            const u32x4 m4 = lds_read_b128(&s_meta[idx_c]);
+            mt.rank = (int)m4[0];
+            mt.scale = __uint_as_float(m4[1]);
+            mt.loaded = (int)m4[2];
+            mt.pad = 0;
         } else {
             mt = pool.meta[idx_c];
         }
@@ -512,11 +529,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             s_scale[tid] = rr.scale;
             if (rr.rank & 7) s_odd = 1;  // rows of this B_i are not 16-byte aligned
         }
-        __syncthreads();
+        meet_lds();
         TRACE(13);  // routes in LDS
-        // The workgroup's first shrink unit and the first sub-spans of the stream go out together.  (One straight-line
+        // The workgroup's first shrink unit and the next sub-spans of the stream go out together.  (One straight-line
         // copy of this per case: across a branch the compiler stops counting loads in flight and waits for all of them.)
-        const int slot0 = s_slot[t0], rank0 = s_rank[t0];
+        const int slot0 = lds_read_i32(&s_slot[t0]), rank0 = lds_read_i32(&s_rank[t0]);
         const bool valid0 = unit0 && slot0 >= 0 && j00 < rank0, two0 = (j00 + 1) < rank0;
         auto first_requests = [&](auto four, auto with_unit) {
             constexpr int n_first = decltype(four)::value ? 4 : 2;
@@ -528,11 +545,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                 unit_load(uA0, uA1, x + (size_t)t0 * K, 0, uxv, ua0, ua1);
             }
 #pragma unroll
-            for (int p = 0; p < n_first; ++p) issue(p, wset[p % kAhead]);
+            for (int p = 2; p < n_first; ++p) issue(p, wset[p % kAhead]);
             if constexpr (decltype(with_unit)::value) {
                 float s0 = 0.0f, s1 = 0.0f;
                 __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(n_first * kOps));  // the unit's loads are back
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm((n_first - 2) * kOps));  // the unit's loads are back
                 __builtin_amdgcn_sched_barrier(0);
                 unit_dot(0, uxv, ua0, ua1, s0, s1);
                 for (int pb = UL * kThreads; pb < pieces; pb += UL * kThreads) {  // K above 4096: the other rounds
