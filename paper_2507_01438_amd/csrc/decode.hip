@@ -98,12 +98,14 @@ __device__ long long elora_trace_buf[4096 * 16];
 struct DecodeShape {
     int T, K, N;
     int split;      // K-slices of the base contraction = owners per tile: 1, 2, 4 or 8
+    int lgS;        // log2 split
     int chunks;     // K / 256; slice ks covers chunks [ks * chunks / split, (ks + 1) * chunks / split)
     int n_tiles;
     int total;      // n_tiles * split (tile, ks) pairs
     int grid;       // total rounded up to a multiple of 8 * split: workgroups launched (the surplus only shares in the shrink)
     int n_pub;      // the first n_pub workgroups of the grid share the shrink units
     int jgroups;    // pairs of rank rows per row of x: ceil(max_rank / 2)
+    unsigned jg_inv;  // floor(2^32 / jgroups) + 1: u / jgroups == (u * jg_inv) >> 32 for every u below 2^24 (jgroups <= 128)
     int G;          // granules per owner: 16 / split
     int lgG;        // log2 G
     int lgRp;       // log2 of max_rank rounded up to a power of two
@@ -128,15 +130,18 @@ __host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | 0x0F70 | 
 // those always execute in the L2, so they can neither see a stale first-level line nor have to go out to memory.
 // (one 16-byte store per lane, so that a wave writes whole cache lines: written through in 8-byte halves the same data
 // costs four times the memory traffic)
+// The wait states after the store are part of the statement: the hardware reads the data registers of a store of more
+// than 8 bytes a little after it is issued, the compiler inserts the idle cycles this needs only for stores it knows
+// of, and what follows an assembly statement may well overwrite its operands at once.
 __device__ __forceinline__ void piece_store(float *p, float a, float b, float c, float d)
 {
     const u32x4 v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 2" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void piece_clear(float *p)
 {
     const u32x4 v = {kEmpty, kEmpty, kEmpty, kEmpty};
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 2" ::"v"(p), "v"(v) : "memory");
 }
 // `zero` is 0, but only the host knows (the compiler would turn an OR with a literal zero into a plain load).
 // Without the one-XCD guarantee the read-modify-write is done at agent scope (past the L2, in memory).
@@ -170,6 +175,15 @@ __device__ __forceinline__ float lds_read_f32(const float *p)
     return v;
 }
 
+// LDS writes the compiler does not see as such, for the same reason (it holds a write back, too)
+__device__ __forceinline__ void lds_write_b32(void *p, uint32_t v)
+{
+    asm volatile("ds_write_b32 %0, %1" ::"v"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_b128(void *p, u32x4 v)
+{
+    asm volatile("ds_write_b128 %0, %1\n\ts_nop 2" ::"v"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)p), "v"(v) : "memory");
+}
 __device__ __forceinline__ u32x4 lds_read_b128(const void *p)
 {
     u32x4 v;
@@ -243,6 +257,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     __shared__ float s_red[2][kWaves][2];
     __shared__ __attribute__((aligned(16))) SlotMeta s_meta[kMetaLds];  // the pool's slot table, if it is small enough
 
+    // Every argument is wanted within the first few hundred instructions.  Left alone the compiler fetches each one
+    // where it is first used, one round trip to the scalar cache after the other; named here, they are all asked for
+    // at once.
+    asm volatile("" ::"s"(sh.T), "s"(sh.K), "s"(sh.N), "s"(sh.split), "s"(sh.lgS), "s"(sh.chunks), "s"(sh.n_tiles), "s"(sh.total),
+                 "s"(sh.grid), "s"(sh.n_pub), "s"(sh.jgroups), "s"(sh.jg_inv), "s"(sh.G), "s"(sh.lgG), "s"(sh.lgRp), "s"(sh.spin_limit),
+                 "s"(sh.zero), "s"(sh.local), "s"(x), "s"(W), "s"(y), "s"(mail), "s"(vmail), "s"(sync), "s"(has_pool));
+    asm volatile("" ::"s"(pool.meta), "s"(pool.slots), "s"(pool.err), "s"(pool.slot_bytes), "s"(pool.b_offset), "s"(pool.capacity),
+                 "s"(pool.max_rank), "s"(route.adapter_idx), "s"(route.seg_offsets), "s"(route.seg_adapter), "s"(route.n_segments),
+                 "s"(route.scales));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = sh.T, K = sh.K, N = sh.N;
     const int R = pool.max_rank;
@@ -261,7 +284,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     const int per_xcd = sh.grid / kXcds;
     const int pair = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
     const bool idle = pair >= sh.total;  // surplus workgroup: only shares in the shrink
-    const int tile = idle ? 0 : pair / sh.split, ks = idle ? 0 : pair - tile * sh.split;
+    const int tile = idle ? 0 : pair >> sh.lgS, ks = idle ? 0 : pair & (sh.split - 1);
 
     // Finishing is counted per XCD and then over the XCDs.  The last workgroup of an XCD empties, if some owner there
     // gave up, the piece mailboxes of the XCD's tiles (through the same L2 the pieces went through); the last
@@ -306,8 +329,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     const int n0 = tile * kTileRows;
     const int row = n0 + wave * kRowsPerWave + m;                    // W row this lane feeds
     const bool wave_active = !idle && (n0 + wave * kRowsPerWave) < N;  // N % 16 == 0: all 16 rows in or out
-    const int c_begin = (int)((long long)ks * sh.chunks / sh.split);
-    const int nchunks = (int)((long long)(ks + 1) * sh.chunks / sh.split) - c_begin;  // >= 1: split <= chunks
+    const int c_begin = (ks * sh.chunks) >> sh.lgS;
+    const int nchunks = (((ks + 1) * sh.chunks) >> sh.lgS) - c_begin;  // >= 1: split <= chunks
     const int k_begin = c_begin * kChunk;
     const uint16_t *wrow = W + (size_t)(wave_active ? row : 0) * K + k_begin + g * 8;
 
@@ -371,19 +394,53 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     };
     auto multiply = [&](int p, const u32x4 *wc) {
         // The LDS reads are written as assembly: the compiler holds every LDS read back until ALL direct-to-LDS
-        // loads in flight have landed (it cannot tell the ring's buffers apart), which would undo the prefetch.
+        // loads in flight have landed (it cannot tell the ring's buffers apart), which would undo the prefetch.  All
+        // reads of a sub-span and the wait for them sit in ONE statement: the compiler takes an output of an assembly
+        // statement for valid as soon as the statement is over, and may copy or spill it right there.
         const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)(xring + (size_t)(p % kBufs) * (TT * 16 * kSub)) + (uint32_t)m * (kSub * 2);
+        static_assert(kSubSteps == 4 && kSub * 2 * 16 == 4096, "operand lists below");
+        const uint32_t a0 = base + (uint32_t)(((0 * 4 + g) ^ m) << 4), a1 = base + (uint32_t)(((1 * 4 + g) ^ m) << 4);
+        const uint32_t a2 = base + (uint32_t)(((2 * 4 + g) ^ m) << 4), a3 = base + (uint32_t)(((3 * 4 + g) ^ m) << 4);
         u32x4 b[kSubSteps][TT];
-#pragma unroll
-        for (int j = 0; j < kSubSteps; ++j)
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-                asm volatile("ds_read_b128 %0, %1" : "=v"(b[j][tt]) : "v"(base + (uint32_t)(tt * 16 * kSub * 2) + (uint32_t)(((j * 4 + g) ^ m) << 4)) : "memory");
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int j = 0; j < kSubSteps; ++j)
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) asm volatile("" : "+v"(b[j][tt]));  // nothing may use b before the wait above
+        if constexpr (TT == 1) {
+            asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(b[0][0]), "=&v"(b[1][0]), "=&v"(b[2][0]), "=&v"(b[3][0])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                         : "memory");
+        } else if constexpr (TT == 2) {
+            asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:4096\n\t"
+                         "ds_read_b128 %2, %9\n\tds_read_b128 %3, %9 offset:4096\n\t"
+                         "ds_read_b128 %4, %10\n\tds_read_b128 %5, %10 offset:4096\n\t"
+                         "ds_read_b128 %6, %11\n\tds_read_b128 %7, %11 offset:4096\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[3][0]),
+                           "=&v"(b[3][1])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                         : "memory");
+        } else if constexpr (TT == 3) {
+            asm volatile("ds_read_b128 %0, %12\n\tds_read_b128 %1, %12 offset:4096\n\tds_read_b128 %2, %12 offset:8192\n\t"
+                         "ds_read_b128 %3, %13\n\tds_read_b128 %4, %13 offset:4096\n\tds_read_b128 %5, %13 offset:8192\n\t"
+                         "ds_read_b128 %6, %14\n\tds_read_b128 %7, %14 offset:4096\n\tds_read_b128 %8, %14 offset:8192\n\t"
+                         "ds_read_b128 %9, %15\n\tds_read_b128 %10, %15 offset:4096\n\tds_read_b128 %11, %15 offset:8192\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[1][2]), "=&v"(b[2][0]),
+                           "=&v"(b[2][1]), "=&v"(b[2][2]), "=&v"(b[3][0]), "=&v"(b[3][1]), "=&v"(b[3][2])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                         : "memory");
+        } else {
+            static_assert(TT == 4, "operand lists");
+            asm volatile("ds_read_b128 %0, %16\n\tds_read_b128 %1, %16 offset:4096\n\tds_read_b128 %2, %16 offset:8192\n\tds_read_b128 %3, %16 offset:12288\n\t"
+                         "ds_read_b128 %4, %17\n\tds_read_b128 %5, %17 offset:4096\n\tds_read_b128 %6, %17 offset:8192\n\tds_read_b128 %7, %17 offset:12288\n\t"
+                         "ds_read_b128 %8, %18\n\tds_read_b128 %9, %18 offset:4096\n\tds_read_b128 %10, %18 offset:8192\n\tds_read_b128 %11, %18 offset:12288\n\t"
+                         "ds_read_b128 %12, %19\n\tds_read_b128 %13, %19 offset:4096\n\tds_read_b128 %14, %19 offset:8192\n\tds_read_b128 %15, %19 offset:12288\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[0][3]), "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[1][2]),
+                           "=&v"(b[1][3]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[2][2]), "=&v"(b[2][3]), "=&v"(b[3][0]), "=&v"(b[3][1]),
+                           "=&v"(b[3][2]), "=&v"(b[3][3])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                         : "memory");
+        }
 #pragma unroll
         for (int j = 0; j < kSubSteps; ++j) {
             const bf16x8 a = __builtin_bit_cast(bf16x8, wc[j]);
@@ -425,8 +482,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         s0 = wave_sum(s0);
         s1 = wave_sum(s1);
         if (lane == 0) {
-            s_red[n & 1][wave][0] = s0;
-            s_red[n & 1][wave][1] = s1;
+            lds_write_b32(&s_red[n & 1][wave][0], __float_as_uint(s0));
+            lds_write_b32(&s_red[n & 1][wave][1], __float_as_uint(s1));
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
@@ -447,7 +504,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         for (int n = n_first + wave;; n += kWaves) {
             const long long u = (long long)blockIdx.x + (long long)sh.n_pub * n;
             if (u >= n_units) break;
-            const int t = (int)u / sh.jgroups, j0 = ((int)u - t * sh.jgroups) * 2;
+            const int t = sh.jgroups == 1 ? (int)u : (int)__umulhi((unsigned)u, sh.jg_inv), j0 = ((int)u - t * sh.jgroups) * 2;
             const int slot = lds_read_i32(&s_slot[t]), rank = lds_read_i32(&s_rank[t]);
             if (slot < 0 || j0 >= rank) continue;
             const bool two = (j0 + 1) < rank;
@@ -481,12 +538,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     // streaming and are in the way of those that do not.)
     if (has_pool) {
         const int tr = min(tid, T - 1);  // threads past the batch repeat its last row and keep nothing
-#ifdef ELORA_DBG_NOUNIT
-        const bool unit0 = false;
-#else
         const bool unit0 = (int)blockIdx.x < sh.n_pub && (int)blockIdx.x < n_units;
-#endif
-        const int t0 = unit0 ? (int)blockIdx.x / sh.jgroups : 0, j00 = ((int)blockIdx.x - t0 * sh.jgroups) * 2;
+        const int t0 = !unit0 ? 0 : sh.jgroups == 1 ? (int)blockIdx.x : (int)__umulhi(blockIdx.x, sh.jg_inv), j00 = ((int)blockIdx.x - t0 * sh.jgroups) * 2;
         const bool table = pool.capacity <= kMetaLds;
         u32x4 tab[kMetaLds / kThreads];
         if (table) {
@@ -497,7 +550,16 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         const RouteIndex ri = route_index(tr, route);
         const int idx_c = (ri.idx >= 0 && ri.idx < pool.capacity) ? ri.idx : 0;
         const float so = (route.scales != nullptr && ri.idx != -1) ? route.scales[ri.scale_at] : 0.0f;
-        SlotMeta mt;
+        SlotMeta mt{0, 0.0f, 0, 0};
+        if (!table) mt = pool.meta[idx_c];  // a big pool: the entry is fetched on its own, one more round trip
+        // Index, scale and table (or entry) are here before the stream starts.  They are used below, after the stream's
+        // first requests: without this the compiler would wait for them there, and for those requests with them; and
+        // no load may sit in a branch from here on, or it waits for everything at the next join.
+        asm volatile("" ::"v"(ri.idx), "v"(ri.scale_at), "v"(so), "v"(mt.rank), "v"(mt.scale), "v"(mt.loaded));
+        if (table) {
+#pragma unroll
+            for (int i = 0; i < kMetaLds / kThreads; ++i) asm volatile("" ::"v"(tab[i]));
+        }
         TRACE(11);  // index known
         // the first two sub-spans of the stream go out now; from here to the end of the contraction LDS is only read
         // through lds_read_* and the assembly in multiply()
@@ -511,29 +573,29 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         if (table) {
 #pragma unroll
             for (int i = 0; i < kMetaLds / kThreads; ++i)
-                if (tid + i * kThreads < pool.capacity) reinterpret_cast<u32x4 *>(s_meta)[tid + i * kThreads] = tab[i];
+                if (tid + i * kThreads < pool.capacity) lds_write_b128(&s_meta[tid + i * kThreads], tab[i]);
             meet_lds();
             const u32x4 m4 = lds_read_b128(&s_meta[idx_c]);
             mt.rank = (int)m4[0];
             mt.scale = __uint_as_float(m4[1]);
             mt.loaded = (int)m4[2];
             mt.pad = 0;
-        } else {
-            mt = pool.meta[idx_c];
         }
         const RowRoute rr = route_finish(tr, ri, mt, so, route, pool, blockIdx.x == 0 && tid < T);
         TRACE(12);  // table entry here
         if (tid < T) {
-            s_slot[tid] = rr.slot;
-            s_rank[tid] = rr.rank;
-            s_scale[tid] = rr.scale;
-            if (rr.rank & 7) s_odd = 1;  // rows of this B_i are not 16-byte aligned
+            lds_write_b32(&s_slot[tid], (uint32_t)rr.slot);
+            lds_write_b32(&s_rank[tid], (uint32_t)rr.rank);
+            lds_write_b32(&s_scale[tid], __float_as_uint(rr.scale));
+            if (rr.rank & 7) lds_write_b32(&s_odd, 1u);  // rows of this B_i are not 16-byte aligned
         }
         meet_lds();
         TRACE(13);  // routes in LDS
         // The workgroup's first shrink unit and the next sub-spans of the stream go out together.  (One straight-line
         // copy of this per case: across a branch the compiler stops counting loads in flight and waits for all of them.)
-        const int slot0 = lds_read_i32(&s_slot[t0]), rank0 = lds_read_i32(&s_rank[t0]);
+        // (made uniform for the compiler: otherwise the cases below become predicated code one after the other, and each
+        // waits for the loads the one before it might have issued)
+        const int slot0 = __builtin_amdgcn_readfirstlane(lds_read_i32(&s_slot[t0])), rank0 = __builtin_amdgcn_readfirstlane(lds_read_i32(&s_rank[t0]));
         const bool valid0 = unit0 && slot0 >= 0 && j00 < rank0, two0 = (j00 + 1) < rank0;
         auto first_requests = [&](auto four, auto with_unit) {
             constexpr int n_first = decltype(four)::value ? 4 : 2;
@@ -579,6 +641,56 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         }
     }
 
+    // own columns: granules og0 .. og0 + G - 1 of the tile, columns nc0 .. nc0 + 4 G - 1 of y
+    const int og0 = ks * sh.G, nc0 = n0 + og0 * 4, ncols = sh.G * 4;
+    const int n_cells = T * sh.G;  // (row, granule) cells of the owned columns
+    // What follows the contraction runs on four waves with nothing to overlap it, and a wave on its own issues an
+    // instruction only every 8 to 10 clocks: the number of instructions on that path is what the tail of the kernel
+    // costs.  The common case (every rank a multiple of 8, none above 64) therefore has a short path of its own.
+    const bool lean = !has_pool || (__builtin_amdgcn_readfirstlane(lds_read_i32(&s_odd)) == 0 && R <= 64 && sh.lgRp >= 3);
+    const int lgRp = sh.lgRp, Rp = 1 << lgRp;  // pitch of v in LDS: max_rank rounded up to a power of two, 8 .. 64
+    float *const vs = lds_f;                                     // [T][Rp]
+    constexpr int VV = kDecodeMaxTokens * 64 / 4 / kThreads;     // 16-byte vectors of v per thread, at most
+    const int nch = has_pool ? R >> 3 : 0;                       // 16-byte pieces of a row of B_i at the largest rank
+    const int n_bit = has_pool ? T << (sh.lgG + 2) : 0;          // (row, own column) items
+    u32x4 vv[VV];
+    bool vneed[VV];
+    u32x4 b[2][8];
+    const float *vrow[2];
+    bool valid[2];
+    // rows of B_i for two items (it0, it0 + 256); pieces of a row past its rank repeat its last piece (v is zero there)
+    auto b_issue = [&](int it0) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii) {
+            const int item = it0 + ii * kThreads;
+            const int t = item < n_bit ? item >> (sh.lgG + 2) : 0, c = item & (ncols - 1);
+            const int slot = lds_read_i32(&s_slot[t]), rank = lds_read_i32(&s_rank[t]);
+            valid[ii] = item < n_bit && slot >= 0 && nc0 + c < N;
+            const uint16_t *bp = reinterpret_cast<const uint16_t *>(slot_B(pool, valid[ii] ? slot : 0)) +
+                                 (valid[ii] ? (size_t)(nc0 + c) * rank : 0);
+            const int last = valid[ii] ? rank - 8 : 0;
+#pragma unroll
+            for (int hh = 0; hh < 8; ++hh)
+                if (hh < nch) b[ii][hh] = *reinterpret_cast<const u32x4 *>(bp + min(8 * hh, last));
+            vrow[ii] = vs + (t << lgRp);
+        }
+    };
+    // The adapter term's inputs.  v: through the L2 (the workgroups of an XCD all want the same values, and the L2 holds
+    // nothing from before this launch); what is not there yet is asked for again, past the L2.  The rows of B_i for
+    // this thread's first items go out with it: they only need the routes.  (Asking for all this before the last
+    // sub-span of the stream is waited for, so that it travels meanwhile, was slower: the contraction then ends later.)
+    auto tail_requests = [&]() {
+#pragma unroll
+        for (int i = 0; i < VV; ++i) {
+            const int vi = tid + i * kThreads;
+            const int t = vi >> (lgRp - 2), j = (vi & ((Rp >> 2) - 1)) * 4;
+            vneed[i] = t < T && j < lds_read_i32(&s_rank[min(t, T - 1)]);
+            vv[i] = u32x4{0, 0, 0, 0};
+            if (vneed[i]) vv[i] = *reinterpret_cast<const u32x4 *>(vmail + (size_t)t * R + j);
+        }
+        b_issue(tid);
+    };
+
     // ---- phase 2: base contraction -------------------------------------------------------------------------
     // kAhead sub-spans are in flight, no more: requests a compute unit has queued beyond what the memory system is
     // working on only delay whatever that unit asks for next, without adding bandwidth.  The steady-state loop is
@@ -616,6 +728,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     if (wave_active) {
         const int q16 = wave * 4 + g;
         float *dst0 = piece_ptr(mail, sh, tile, q16 >> sh.lgG, ks) + (size_t)(q16 & (sh.G - 1)) * 4;
+        // (the stores below are assembly statements: the idle cycles a store needs between a matrix instruction writing a
+        // register and the store reading it are not inserted for them)
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory");
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             const int t = tt * 16 + m;
@@ -623,46 +738,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         }
     }
 
-    // own columns: granules og0 .. og0 + G - 1 of the tile, columns nc0 .. nc0 + 4 G - 1 of y
-    const int og0 = ks * sh.G, nc0 = n0 + og0 * 4, ncols = sh.G * 4;
-    const int n_cells = T * sh.G;  // (row, granule) cells of the owned columns
-
-    // What follows runs on four waves with nothing to overlap it, and a wave on its own issues an instruction only
-    // every 8 to 10 clocks: the number of instructions on this path is what the tail of the kernel costs.  The common
-    // case (every rank a multiple of 8, none above 64) therefore has a short path of its own.
     bool acked = false;  // everything this thread posted to other workgroups has been acknowledged
-    const bool lean = !has_pool || (s_odd == 0 && R <= 64 && sh.lgRp >= 3);
     if (lean) {
-        const int lgRp = sh.lgRp, Rp = 1 << lgRp;  // pitch of v in LDS: max_rank rounded up to a power of two, 8 .. 64
-        float *const vs = lds_f;                                     // [T][Rp]
         float *const dsum = lds_f + (has_pool ? (T << lgRp) : 0);    // [T][ncols]
-        constexpr int VV = kDecodeMaxTokens * 64 / 4 / kThreads;     // 16-byte vectors of v per thread, at most
-        const int nch = has_pool ? R >> 3 : 0;                       // 16-byte pieces of a row of B_i at the largest rank
-        const int n_bit = has_pool ? T << (sh.lgG + 2) : 0;          // (row, own column) items
         const size_t pstride = piece_floats(sh);
-        u32x4 vv[VV];
-        bool vneed[VV];
-        u32x4 b[2][8];
-        const float *vrow[2];
-        bool valid[2];
         u32x4 pv[kDecodeMaxSplit];
-        // rows of B_i for two items (it0, it0 + 256); pieces of a row past its rank repeat its last piece (v is zero there)
-        auto b_issue = [&](int it0) {
-#pragma unroll
-            for (int ii = 0; ii < 2; ++ii) {
-                const int item = it0 + ii * kThreads;
-                const int t = item < n_bit ? item >> (sh.lgG + 2) : 0, c = item & (ncols - 1);
-                const int slot = s_slot[t], rank = s_rank[t];
-                valid[ii] = item < n_bit && slot >= 0 && nc0 + c < N;
-                const uint16_t *bp = reinterpret_cast<const uint16_t *>(slot_B(pool, valid[ii] ? slot : 0)) +
-                                     (valid[ii] ? (size_t)(nc0 + c) * rank : 0);
-                const int last = valid[ii] ? rank - 8 : 0;
-#pragma unroll
-                for (int hh = 0; hh < 8; ++hh)
-                    if (hh < nch) b[ii][hh] = *reinterpret_cast<const u32x4 *>(bp + min(8 * hh, last));
-                vrow[ii] = vs + (t << lgRp);
-            }
-        };
         // the pieces of one (row, granule) cell: plain loads
         auto p_issue = [&](int cell) {
             const float *src0 = piece_ptr(mail, sh, tile, ks, 0) + (size_t)cell * 4;
@@ -670,20 +750,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
                 if (sd < sh.split) pv[sd] = *reinterpret_cast<const u32x4 *>(src0 + sd * pstride);
         };
-        if (has_pool) {
-            // v: first through the L2 (the workgroups of an XCD all want the same values, and the L2 holds nothing
-            // from before this launch); what was not there yet is asked for again past the L2.  The rows of B_i for
-            // this thread's first items go out with it: they only need the routes.
-#pragma unroll
-            for (int i = 0; i < VV; ++i) {
-                const int vi = tid + i * kThreads;
-                const int t = vi >> (lgRp - 2), j = (vi & ((Rp >> 2) - 1)) * 4;
-                vneed[i] = t < T && j < s_rank[min(t, T - 1)];
-                vv[i] = u32x4{0, 0, 0, 0};
-                if (vneed[i]) vv[i] = *reinterpret_cast<const u32x4 *>(vmail + (size_t)t * R + j);
-            }
-            b_issue(tid);
-        }
+        if (has_pool) tail_requests();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();  // the x ring is reused below (no fence: the requests above stay in flight)
         asm volatile("" ::: "memory");
@@ -741,9 +808,29 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             }
             TRACE(10);
         }
-        // the pieces of this thread's first cell are asked for now: the other K-slices have had time to arrive, and the
-        // loads are under way while the adapter term is formed
-        if (tid < n_cells) p_issue(tid);
+        // With a pool: the pieces of this thread's first cell are asked for now (the other K-slices have had time to
+        // arrive), and the loads are under way while the adapter term is formed.
+        // Without one the other K-slices are mostly not done yet, and everybody polling every piece of its own with
+        // read-modify-writes keeps the L2's atomic units busy for microseconds.  Then one lane per K-slice waits
+        // (read-modify-writes in the L2) for the piece that slice posts last to this owner; once all are there, plain
+        // loads find every piece in the L2.
+        const bool use_probe = !has_pool;
+        if (!use_probe) {
+            if (tid < n_cells) p_issue(tid);
+        } else {
+            if (wave == 0 && lane < sh.split && nc0 < N) {
+                const float *probe = piece_ptr(mail, sh, tile, ks, lane) + ((size_t)(T - 1) * sh.G + min(sh.G - 1, ((N - nc0) >> 2) - 1)) * 4;
+                for (int spin = 0; spin < sh.spin_limit; ++spin) {
+                    const u32x4 pr = piece_load(probe, (uint64_t)(uint32_t)sh.zero, sh.local != 0);
+                    if (pr[0] != kEmpty && pr[1] != kEmpty && pr[2] != kEmpty && pr[3] != kEmpty) break;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (tid < n_cells) p_issue(tid);
+        }
         if (has_pool) {
             // d[t][c] = s_t * sum_j B_i[nc0 + c][j] v[t][j]: one (row, own column) item per thread, two items at a time
             for (int it0 = tid; it0 < n_bit; it0 += 2 * kThreads) {
@@ -1155,9 +1242,12 @@ DecodeShape make_shape(int T, int K, int N, int max_rank)
     sh.chunks = K / kChunk;
     sh.n_tiles = (N + kTileRows - 1) / kTileRows;
     sh.jgroups = (max_rank + 1) / 2;
+    sh.jg_inv = (unsigned)((1ull << 32) / (unsigned)sh.jgroups) + 1u;
     const int tt = (T + 15) / 16;
     const int resident = resident_workgroups(tt);
     sh.split = pick_split(K, sh.n_tiles, resident);
+    sh.lgS = 0;
+    while ((1 << sh.lgS) < sh.split) ++sh.lgS;
     sh.total = sh.n_tiles * sh.split;
     const int unit = kXcds * sh.split;
     sh.grid = (sh.total + unit - 1) / unit * unit;
