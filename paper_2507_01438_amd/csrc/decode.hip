@@ -52,9 +52,14 @@ constexpr int kRowsPerWave = 16;  // W rows per wave (one MFMA row block)
 constexpr int kTileRows = kWaves * kRowsPerWave;
 constexpr int kGranules = kTileRows / 4;  // a granule = 4 adjacent columns = what one lane holds of one row of x
 constexpr int kChunk = 256;               // K elements per register set of W (8 MFMA K steps)
-// LDS elements per row of x: room for the x ring (5 sub-spans of 128 elements with up to 32 rows, else 3) and for the
-// staging afterwards
-__host__ __device__ constexpr int pitch_of(int tt) { return tt <= 2 ? 640 : 384; }
+// The ring of sub-spans in LDS (dynamic LDS: the only such array of the kernel; the staging after the contraction reuses
+// it).  A sub-span is 128 elements of K.  Up to 32 rows of x: 5 slots, and W travels through the ring as well (64 rows
+// per slot: see the kernel); more rows: 3 slots of x alone, W goes straight into registers.
+constexpr int kSubSpan = 128;
+__host__ __device__ constexpr bool w_through_lds(int tt) { return tt <= 2; }
+__host__ __device__ constexpr int ring_slots(int tt) { return tt <= 2 ? 5 : 3; }
+__host__ __device__ constexpr int slot_rows(int tt) { return tt * 16 + (w_through_lds(tt) ? kTileRows : 0); }
+__host__ __device__ constexpr int ring_bytes(int tt) { return ring_slots(tt) * slot_rows(tt) * kSubSpan * 2; }
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kMetaLds = 512;  // slot tables up to this many entries are copied to LDS whole
 
@@ -249,8 +254,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                                                                            uint16_t *__restrict__ y)
 {
     // x ring during the contraction; staging of pieces, v and d afterwards
-    constexpr int kPitch = pitch_of(TT);
-    __shared__ __attribute__((aligned(16))) uint16_t xs[TT * 16 * kPitch];
+    extern __shared__ __attribute__((aligned(16))) uint16_t xs[];  // ring_bytes(TT)
     __shared__ int s_slot[kDecodeMaxTokens], s_rank[kDecodeMaxTokens];
     __shared__ float s_scale[kDecodeMaxTokens];
     __shared__ int s_flag, s_fail, s_vfail, s_odd;
@@ -270,7 +274,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     const int T = sh.T, K = sh.K, N = sh.N;
     const int R = pool.max_rank;
     float *const lds_f = reinterpret_cast<float *>(&xs[0]);
-    constexpr int kLdsFloats = TT * 16 * kPitch / 2;  // the area counted in floats
+    constexpr int kLdsFloats = ring_bytes(TT) / 4;  // the area counted in floats
     TRACE_DECL;
     TRACE(0);
     if (tid == 0) {
@@ -334,32 +338,43 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     const int k_begin = c_begin * kChunk;
     const uint16_t *wrow = W + (size_t)(wave_active ? row : 0) * K + k_begin + g * 8;
 
-    // The K-slice goes by in sub-spans of 128 elements (4 MFMA K steps).  Per sub-span every thread has 4 loads of
-    // W in flight (16 rows x 128 elements per wave, straight into registers) and every wave moves its share of
-    // the rows of x global -> LDS; kDepth sub-spans are on their way at any time, no more: requests a compute unit
-    // has queued beyond what the memory system is working on only delay whatever that unit asks for next (the
-    // helper workgroups live on latency), without adding bandwidth.
-    constexpr int kSub = 128, kSubSteps = kSub / 32;
-    constexpr int kAhead = TT <= 2 ? ELORA_DEC_AHEAD : 2;  // sub-spans in flight while one is being multiplied
-    constexpr int kBufs = kAhead + 1;                      // the sub-spans in flight and the one being multiplied
+    // The K-slice goes by in sub-spans of 128 elements (4 MFMA K steps).  Per sub-span every wave moves its share of
+    // the rows of x global -> LDS, and its own 16 rows of W either the same way (up to 32 rows of x: four
+    // instructions of 4 rows x 256 bytes, whole cache lines; fetched straight into the registers in the layout the
+    // matrix instruction wants, an instruction touches 16 rows x 64 bytes, half a cache line each, and the same
+    // stream takes about 1.7 us longer per 32 MiB) or, with more rows of x (the ring would not leave room for two
+    // workgroups per compute unit), as 4 register loads per thread.  kAhead sub-spans are on their way at any time.
+    constexpr int kSub = kSubSpan, kSubSteps = kSub / 32;
+    constexpr bool kWLds = w_through_lds(TT);
+    constexpr int kBufs = ring_slots(TT);                  // the sub-spans in flight and the one being multiplied
+    constexpr int kAhead = kBufs - 1;                      // sub-spans in flight while one is being multiplied
+    constexpr int kSlotElems = slot_rows(TT) * kSub;
+    static_assert(ELORA_DEC_AHEAD == 4, "ring depth for up to 32 rows");
     constexpr int kRowsPerInstr = 512 / kSub;              // a direct-to-LDS instruction moves 1 KiB: 4 rows of 128 elements
     constexpr int kLanesPerRow = 64 / kRowsPerInstr;
     constexpr int kXInstr = TT * 16 / kRowsPerInstr / kWaves;  // such instructions per wave and sub-span
     constexpr int kOps = kXInstr + kSubSteps;                  // vector-memory operations per wave and sub-span
     static_assert(kAhead == 2 || kAhead == 4, "ring depth");
-    static_assert(sizeof(xs) >= (size_t)kBufs * TT * 16 * kSub * 2, "x ring fits");
     static_assert(kAhead * kOps + 8 < 64, "vmcnt range");
     u32x4 wset[kAhead][kSubSteps];
     typedef const __attribute__((address_space(1))) void *gptr_t;
     typedef __attribute__((address_space(3))) void *lptr_t;
-    uint16_t *const xring = &xs[0];  // [kBufs][TT * 16 rows][kSub / 8 slots of 8 elements]; slot = chunk ^ (row % 16)
+    uint16_t *const xring = &xs[0];  // [kBufs][rows of x, then rows of W][kSub / 8 places of 8 elements]; place = chunk ^ (row % 16)
     const int nsub = nchunks * (kChunk / kSub);  // even, at least 2
 
     // x first, then W: when the wave's W loads of a sub-span are back, so is its share of x (in-order counter).
     // Rows past the batch repeat the last row, and waves whose 16 rows of W lie past d_out load row 0: what they
     // produce is never posted, but every wave issues the same number of operations.
+    // (W through LDS) instruction i of a wave moves rows wave * 16 + 4 i .. + 3 of the tile: lane = (row, place)
+    const uint16_t *wdma[kSubSteps];
+#pragma unroll
+    for (int i = 0; i < kSubSteps; ++i) {
+        const int r = i * kRowsPerInstr + lane / kLanesPerRow;  // row among the wave's 16
+        const int chunk = (lane % kLanesPerRow) ^ r;
+        wdma[i] = W + (size_t)min(n0 + wave * kRowsPerWave + r, N - 1) * K + k_begin + chunk * 8;
+    }
     auto issue = [&](int p, u32x4 *dst) {
-        uint16_t *buf = xring + (size_t)(p % kBufs) * (TT * 16 * kSub);
+        uint16_t *buf = xring + (size_t)(p % kBufs) * kSlotElems;
 #pragma unroll
         for (int i = 0; i < kXInstr; ++i) {
             const int r = (wave * kXInstr + i) * kRowsPerInstr + lane / kLanesPerRow;
@@ -367,9 +382,16 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
             const uint16_t *src = x + (size_t)min(r, T - 1) * K + k_begin + (size_t)p * kSub + chunk * 8;
             __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(buf + (wave * kXInstr + i) * 512), 16, 0, 0);
         }
-        const uint16_t *pw = wrow + (size_t)p * kSub;
+        if constexpr (kWLds) {
 #pragma unroll
-        for (int j = 0; j < kSubSteps; ++j) dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + j * 32));
+            for (int i = 0; i < kSubSteps; ++i)
+                __builtin_amdgcn_global_load_lds((gptr_t)(wdma[i] + (size_t)p * kSub),
+                                                 (lptr_t)(buf + (TT * 16 + wave * kRowsPerWave + i * kRowsPerInstr) * kSub), 16, 0, 0);
+        } else {
+            const uint16_t *pw = wrow + (size_t)p * kSub;
+#pragma unroll
+            for (int j = 0; j < kSubSteps; ++j) dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + j * 32));
+        }
     };
 
     floatx4 acc[TT];
@@ -397,26 +419,31 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         // loads in flight have landed (it cannot tell the ring's buffers apart), which would undo the prefetch.  All
         // reads of a sub-span and the wait for them sit in ONE statement: the compiler takes an output of an assembly
         // statement for valid as soon as the statement is over, and may copy or spill it right there.
-        const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)(xring + (size_t)(p % kBufs) * (TT * 16 * kSub)) + (uint32_t)m * (kSub * 2);
+        const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)(xring + (size_t)(p % kBufs) * kSlotElems) + (uint32_t)m * (kSub * 2);
         static_assert(kSubSteps == 4 && kSub * 2 * 16 == 4096, "operand lists below");
         const uint32_t a0 = base + (uint32_t)(((0 * 4 + g) ^ m) << 4), a1 = base + (uint32_t)(((1 * 4 + g) ^ m) << 4);
         const uint32_t a2 = base + (uint32_t)(((2 * 4 + g) ^ m) << 4), a3 = base + (uint32_t)(((3 * 4 + g) ^ m) << 4);
+        // (W through LDS) the wave's row m of W sits TT * 16 + wave * 16 rows below row m of x, in the same places
+        const uint32_t wofs = (uint32_t)((TT * 16 + wave * kRowsPerWave) * kSub * 2);
         u32x4 b[kSubSteps][TT];
+        u32x4 aw[kSubSteps];
         if constexpr (TT == 1) {
-            asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
+            asm volatile("ds_read_b128 %0, %12\n\tds_read_b128 %1, %13\n\tds_read_b128 %2, %14\n\tds_read_b128 %3, %15\n\t"
+                         "ds_read_b128 %4, %8\n\tds_read_b128 %5, %9\n\tds_read_b128 %6, %10\n\tds_read_b128 %7, %11\n\t"
                          "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(b[0][0]), "=&v"(b[1][0]), "=&v"(b[2][0]), "=&v"(b[3][0])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[1][0]), "=&v"(b[2][0]), "=&v"(b[3][0])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
                          : "memory");
         } else if constexpr (TT == 2) {
-            asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %8 offset:4096\n\t"
-                         "ds_read_b128 %2, %9\n\tds_read_b128 %3, %9 offset:4096\n\t"
-                         "ds_read_b128 %4, %10\n\tds_read_b128 %5, %10 offset:4096\n\t"
-                         "ds_read_b128 %6, %11\n\tds_read_b128 %7, %11 offset:4096\n\t"
+            asm volatile("ds_read_b128 %0, %16\n\tds_read_b128 %1, %17\n\tds_read_b128 %2, %18\n\tds_read_b128 %3, %19\n\t"
+                         "ds_read_b128 %4, %12\n\tds_read_b128 %5, %12 offset:4096\n\t"
+                         "ds_read_b128 %6, %13\n\tds_read_b128 %7, %13 offset:4096\n\t"
+                         "ds_read_b128 %8, %14\n\tds_read_b128 %9, %14 offset:4096\n\t"
+                         "ds_read_b128 %10, %15\n\tds_read_b128 %11, %15 offset:4096\n\t"
                          "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[3][0]),
-                           "=&v"(b[3][1])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[1][0]), "=&v"(b[1][1]),
+                           "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[3][0]), "=&v"(b[3][1])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
                          : "memory");
         } else if constexpr (TT == 3) {
             asm volatile("ds_read_b128 %0, %12\n\tds_read_b128 %1, %12 offset:4096\n\tds_read_b128 %2, %12 offset:8192\n\t"
@@ -443,7 +470,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         }
 #pragma unroll
         for (int j = 0; j < kSubSteps; ++j) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, wc[j]);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, kWLds ? aw[j] : wc[j]);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
                 acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[j][tt]), acc[tt], 0, 0, 0);
@@ -1208,11 +1235,24 @@ int resident_workgroups(int tt, int *n_cus)
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess) {
+            // (the ring may be larger than the LDS a kernel gets without asking)
             switch (tt) {
-            case 1: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<1>, kThreads, 0); break;
-            case 2: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<2>, kThreads, 0); break;
-            case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<3>, kThreads, 0); break;
-            default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<4>, kThreads, 0); break;
+            case 1:
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(1));
+                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<1>, kThreads, ring_bytes(1));
+                break;
+            case 2:
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(2));
+                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<2>, kThreads, ring_bytes(2));
+                break;
+            case 3:
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(3));
+                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<3>, kThreads, ring_bytes(3));
+                break;
+            default:
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(4));
+                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<4>, kThreads, ring_bytes(4));
+                break;
             }
         }
         if (e != hipSuccess) {
@@ -1362,10 +1402,10 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     int tt = (a.T + 15) / 16;
     profile_mark_begin(stream);
     switch (tt) {
-    case 1: hipLaunchKernelGGL((decode_kernel<1>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<2>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    case 3: hipLaunchKernelGGL((decode_kernel<3>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    default: hipLaunchKernelGGL((decode_kernel<4>), grid, block, 0, stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 1: hipLaunchKernelGGL((decode_kernel<1>), grid, block, ring_bytes(1), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<2>), grid, block, ring_bytes(2), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 3: hipLaunchKernelGGL((decode_kernel<3>), grid, block, ring_bytes(3), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    default: hipLaunchKernelGGL((decode_kernel<4>), grid, block, ring_bytes(4), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
     }
     ELORA_HIP_TRY(hipGetLastError());
     profile_mark_end(stream);
