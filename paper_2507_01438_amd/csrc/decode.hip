@@ -53,13 +53,12 @@ constexpr int kTileRows = kWaves * kRowsPerWave;
 constexpr int kGranules = kTileRows / 4;  // a granule = 4 adjacent columns = what one lane holds of one row of x
 constexpr int kChunk = 256;               // K elements per register set of W (8 MFMA K steps)
 // The ring of sub-spans in LDS (dynamic LDS: the only such array of the kernel; the staging after the contraction reuses
-// it).  A sub-span is 128 elements of K.  Up to 32 rows of x: 5 slots, and W travels through the ring as well (64 rows
-// per slot: see the kernel); more rows: 3 slots of x alone, W goes straight into registers.
+// it).  A sub-span is 128 elements of K.  Up to 32 rows of x: 5 slots, more rows: 3.  A slot holds the rows of x and,
+// where W travels through the ring as well (see the kernel), the tile's 64 rows of W.
 constexpr int kSubSpan = 128;
-__host__ __device__ constexpr bool w_through_lds(int tt) { return tt <= 2; }
 __host__ __device__ constexpr int ring_slots(int tt) { return tt <= 2 ? 5 : 3; }
-__host__ __device__ constexpr int slot_rows(int tt) { return tt * 16 + (w_through_lds(tt) ? kTileRows : 0); }
-__host__ __device__ constexpr int ring_bytes(int tt) { return ring_slots(tt) * slot_rows(tt) * kSubSpan * 2; }
+__host__ __device__ constexpr int slot_rows(int tt, bool wlds) { return tt * 16 + (wlds ? kTileRows : 0); }
+__host__ __device__ constexpr int ring_bytes(int tt, bool wlds) { return ring_slots(tt) * slot_rows(tt, wlds) * kSubSpan * 2; }
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kMetaLds = 512;  // slot tables up to this many entries are copied to LDS whole
 
@@ -246,7 +245,7 @@ __device__ void recompute_columns(const DecodeShape &sh, const uint16_t *__restr
     }
 }
 
-template <int TT>
+template <int TT, bool kWLds>
 __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
                                                                            const uint16_t *__restrict__ W, PoolView pool,
                                                                            RouteView route, int has_pool, float *__restrict__ mail,
@@ -254,7 +253,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                                                                            uint16_t *__restrict__ y)
 {
     // x ring during the contraction; staging of pieces, v and d afterwards
-    extern __shared__ __attribute__((aligned(16))) uint16_t xs[];  // ring_bytes(TT)
+    extern __shared__ __attribute__((aligned(16))) uint16_t xs[];  // ring_bytes(TT, kWLds)
     __shared__ int s_slot[kDecodeMaxTokens], s_rank[kDecodeMaxTokens];
     __shared__ float s_scale[kDecodeMaxTokens];
     __shared__ int s_flag, s_fail, s_vfail, s_odd;
@@ -274,7 +273,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     const int T = sh.T, K = sh.K, N = sh.N;
     const int R = pool.max_rank;
     float *const lds_f = reinterpret_cast<float *>(&xs[0]);
-    constexpr int kLdsFloats = ring_bytes(TT) / 4;  // the area counted in floats
+    constexpr int kLdsFloats = ring_bytes(TT, kWLds) / 4;  // the area counted in floats
     TRACE_DECL;
     TRACE(0);
     if (tid == 0) {
@@ -339,16 +338,15 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     const uint16_t *wrow = W + (size_t)(wave_active ? row : 0) * K + k_begin + g * 8;
 
     // The K-slice goes by in sub-spans of 128 elements (4 MFMA K steps).  Per sub-span every wave moves its share of
-    // the rows of x global -> LDS, and its own 16 rows of W either the same way (up to 32 rows of x: four
-    // instructions of 4 rows x 256 bytes, whole cache lines; fetched straight into the registers in the layout the
-    // matrix instruction wants, an instruction touches 16 rows x 64 bytes, half a cache line each, and the same
-    // stream takes about 1.7 us longer per 32 MiB) or, with more rows of x (the ring would not leave room for two
-    // workgroups per compute unit), as 4 register loads per thread.  kAhead sub-spans are on their way at any time.
+    // the rows of x global -> LDS, and its own 16 rows of W either the same way (kWLds: four instructions of 4 rows x
+    // 256 bytes, whole cache lines; fetched straight into the registers in the layout the matrix instruction wants,
+    // an instruction touches 16 rows x 64 bytes, half a cache line each, and the same stream takes about 1.7 us longer
+    // per 32 MiB) or as 4 register loads per thread (more than 32 rows of x and a shape that wants two workgroups per
+    // compute unit, for which the ring with W in it leaves no room).  kAhead sub-spans are on their way at any time.
     constexpr int kSub = kSubSpan, kSubSteps = kSub / 32;
-    constexpr bool kWLds = w_through_lds(TT);
     constexpr int kBufs = ring_slots(TT);                  // the sub-spans in flight and the one being multiplied
     constexpr int kAhead = kBufs - 1;                      // sub-spans in flight while one is being multiplied
-    constexpr int kSlotElems = slot_rows(TT) * kSub;
+    constexpr int kSlotElems = slot_rows(TT, kWLds) * kSub;
     static_assert(ELORA_DEC_AHEAD == 4, "ring depth for up to 32 rows");
     constexpr int kRowsPerInstr = 512 / kSub;              // a direct-to-LDS instruction moves 1 KiB: 4 rows of 128 elements
     constexpr int kLanesPerRow = 64 / kRowsPerInstr;
@@ -443,6 +441,30 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                          "s_waitcnt lgkmcnt(0)"
                          : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[1][0]), "=&v"(b[1][1]),
                            "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[3][0]), "=&v"(b[3][1])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
+                         : "memory");
+        } else if constexpr (TT == 3 && kWLds) {
+            asm volatile("ds_read_b128 %0, %20\n\tds_read_b128 %1, %21\n\tds_read_b128 %2, %22\n\tds_read_b128 %3, %23\n\t"
+                         "ds_read_b128 %4, %16\n\tds_read_b128 %5, %16 offset:4096\n\tds_read_b128 %6, %16 offset:8192\n\t"
+                         "ds_read_b128 %7, %17\n\tds_read_b128 %8, %17 offset:4096\n\tds_read_b128 %9, %17 offset:8192\n\t"
+                         "ds_read_b128 %10, %18\n\tds_read_b128 %11, %18 offset:4096\n\tds_read_b128 %12, %18 offset:8192\n\t"
+                         "ds_read_b128 %13, %19\n\tds_read_b128 %14, %19 offset:4096\n\tds_read_b128 %15, %19 offset:8192\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[1][0]),
+                           "=&v"(b[1][1]), "=&v"(b[1][2]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[2][2]), "=&v"(b[3][0]), "=&v"(b[3][1]),
+                           "=&v"(b[3][2])
+                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
+                         : "memory");
+        } else if constexpr (TT == 4 && kWLds) {
+            asm volatile("ds_read_b128 %0, %24\n\tds_read_b128 %1, %25\n\tds_read_b128 %2, %26\n\tds_read_b128 %3, %27\n\t"
+                         "ds_read_b128 %4, %20\n\tds_read_b128 %5, %20 offset:4096\n\tds_read_b128 %6, %20 offset:8192\n\tds_read_b128 %7, %20 offset:12288\n\t"
+                         "ds_read_b128 %8, %21\n\tds_read_b128 %9, %21 offset:4096\n\tds_read_b128 %10, %21 offset:8192\n\tds_read_b128 %11, %21 offset:12288\n\t"
+                         "ds_read_b128 %12, %22\n\tds_read_b128 %13, %22 offset:4096\n\tds_read_b128 %14, %22 offset:8192\n\tds_read_b128 %15, %22 offset:12288\n\t"
+                         "ds_read_b128 %16, %23\n\tds_read_b128 %17, %23 offset:4096\n\tds_read_b128 %18, %23 offset:8192\n\tds_read_b128 %19, %23 offset:12288\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[0][3]),
+                           "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[1][2]), "=&v"(b[1][3]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[2][2]),
+                           "=&v"(b[2][3]), "=&v"(b[3][0]), "=&v"(b[3][1]), "=&v"(b[3][2]), "=&v"(b[3][3])
                          : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
                          : "memory");
         } else if constexpr (TT == 3) {
@@ -1224,35 +1246,31 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     finish_call();
 }
 
-// workgroups of decode_kernel<tt> the device holds at once (registers and LDS decide; asked once per instance), and
-// its number of compute units
-int resident_workgroups(int tt, int *n_cus)
+// workgroups of decode_kernel<tt, wlds> the device holds at once (registers and LDS decide; asked once per instance),
+// and its number of compute units
+template <int TT, bool WL>
+hipError_t ask_occupancy(int *per_cu)
 {
-    static int cached[5] = {0, 0, 0, 0, 0};
+    // (the ring may be larger than the LDS a kernel gets without asking)
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<TT, WL>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       ring_bytes(TT, WL));
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, decode_kernel<TT, WL>, kThreads, ring_bytes(TT, WL));
+    return e;
+}
+int resident_workgroups(int tt, bool wlds, int *n_cus)
+{
+    static int cached[5][2] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}, {0, 0}};
     static int cached_cus = 0;
-    if (cached[tt] == 0) {
+    if (cached[tt][wlds] == 0) {
         int per_cu = 0, cus = 0, dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess) {
-            // (the ring may be larger than the LDS a kernel gets without asking)
             switch (tt) {
-            case 1:
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(1));
-                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<1>, kThreads, ring_bytes(1));
-                break;
-            case 2:
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(2));
-                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<2>, kThreads, ring_bytes(2));
-                break;
-            case 3:
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(3));
-                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<3>, kThreads, ring_bytes(3));
-                break;
-            default:
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(4));
-                if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<4>, kThreads, ring_bytes(4));
-                break;
+            case 1: e = ask_occupancy<1, true>(&per_cu); break;
+            case 2: e = ask_occupancy<2, true>(&per_cu); break;
+            case 3: e = wlds ? ask_occupancy<3, true>(&per_cu) : ask_occupancy<3, false>(&per_cu); break;
+            default: e = wlds ? ask_occupancy<4, true>(&per_cu) : ask_occupancy<4, false>(&per_cu); break;
             }
         }
         if (e != hipSuccess) {
@@ -1260,11 +1278,11 @@ int resident_workgroups(int tt, int *n_cus)
             *n_cus = 64;
             return 64;  // not cached: a cautious figure for this call (e.g. no device in this process yet)
         }
-        cached[tt] = per_cu * cus > 0 ? per_cu * cus : 64;
+        cached[tt][wlds] = per_cu * cus > 0 ? per_cu * cus : 64;
         cached_cus = cus > 0 ? cus : 64;
     }
     *n_cus = cached_cus;
-    return cached[tt];
+    return cached[tt][wlds];
 }
 
 // K-slices = owners per tile: 1, 2, 4 or 8.  All workgroups of the call have to be resident at once, and there are
@@ -1284,7 +1302,11 @@ int pick_split(int K, int n_tiles, int resident, int n_cus)
     return best;
 }
 
-DecodeShape make_shape(int T, int K, int N, int max_rank)
+// Up to 32 rows of x W always travels through LDS.  With more rows the ring with W in it leaves room for one workgroup
+// per compute unit only: taken if that costs no workgroups, or if the call then has (nearly) one per unit; else W goes
+// into registers and two workgroups share a unit (measured at 64 rows, 4096 x 4096: 27.4 against 28.9 us; 14336 x 4096:
+// 53.9 against 60.8; 4096 x 14336, 224 tiles: 63.8 against 61.8).
+DecodeShape make_shape(int T, int K, int N, int max_rank, bool *w_lds)
 {
     DecodeShape sh;
     sh.T = T;
@@ -1296,8 +1318,20 @@ DecodeShape make_shape(int T, int K, int N, int max_rank)
     sh.jg_inv = (unsigned)((1ull << 32) / (unsigned)sh.jgroups) + 1u;
     const int tt = (T + 15) / 16;
     int n_cus = 0;
-    const int resident = resident_workgroups(tt, &n_cus);
+    bool wlds = true;
+    int resident = resident_workgroups(tt, true, &n_cus);
     sh.split = pick_split(K, sh.n_tiles, resident, n_cus);
+    if (tt > 2) {
+        const int resident_r = resident_workgroups(tt, false, &n_cus);
+        const int split_r = pick_split(K, sh.n_tiles, resident_r, n_cus);
+        const int wgs = sh.n_tiles * sh.split;
+        if (split_r != sh.split && !(wgs <= n_cus && wgs * 20 >= n_cus * 19)) {
+            wlds = false;
+            resident = resident_r;
+            sh.split = split_r;
+        }
+    }
+    *w_lds = wlds;
     sh.lgS = 0;
     while ((1 << sh.lgS) < sh.split) ++sh.lgS;
     sh.total = sh.n_tiles * sh.split;
@@ -1379,7 +1413,8 @@ size_t elora::decode_mail_bytes(int d_out)
 
 void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 {
-    DecodeShape sh = make_shape(d.n_tokens, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1);
+    bool wlds = true;
+    DecodeShape sh = make_shape(d.n_tokens, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, &wlds);
     plan->n_launches = 1;
     plan->split_k = sh.split;
     plan->tile_rows = kTileRows;
@@ -1390,7 +1425,8 @@ void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream)
 {
     (void)plan;
-    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1);
+    bool wlds = true;
+    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, &wlds);
     float *mail = reinterpret_cast<float *>(a.ws + a.wsl.mail);
     float *vmail = reinterpret_cast<float *>(a.ws + a.wsl.vmail);
     int *sync = reinterpret_cast<int *>(a.ws + a.wsl.sync);
@@ -1402,10 +1438,16 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     int tt = (a.T + 15) / 16;
     profile_mark_begin(stream);
     switch (tt) {
-    case 1: hipLaunchKernelGGL((decode_kernel<1>), grid, block, ring_bytes(1), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<2>), grid, block, ring_bytes(2), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    case 3: hipLaunchKernelGGL((decode_kernel<3>), grid, block, ring_bytes(3), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    default: hipLaunchKernelGGL((decode_kernel<4>), grid, block, ring_bytes(4), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 1: hipLaunchKernelGGL((decode_kernel<1, true>), grid, block, ring_bytes(1, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<2, true>), grid, block, ring_bytes(2, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
+    case 3:
+        if (wlds) hipLaunchKernelGGL((decode_kernel<3, true>), grid, block, ring_bytes(3, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
+        else hipLaunchKernelGGL((decode_kernel<3, false>), grid, block, ring_bytes(3, false), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
+        break;
+    default:
+        if (wlds) hipLaunchKernelGGL((decode_kernel<4, true>), grid, block, ring_bytes(4, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
+        else hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, ring_bytes(4, false), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
+        break;
     }
     ELORA_HIP_TRY(hipGetLastError());
     profile_mark_end(stream);
