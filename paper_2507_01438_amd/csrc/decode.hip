@@ -713,7 +713,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         for (int ii = 0; ii < 2; ++ii) {
             const int item = it0 + ii * kThreads;
             const int t = item < n_bit ? item >> (sh.lgG + 2) : 0, c = item & (ncols - 1);
-            const int slot = lds_read_i32(&s_slot[t]), rank = lds_read_i32(&s_rank[t]);
+            const int slot = s_slot[t], rank = s_rank[t];  // (plain LDS reads: nothing of the stream is in flight any more)
             valid[ii] = item < n_bit && slot >= 0 && nc0 + c < N;
             const uint16_t *bp = reinterpret_cast<const uint16_t *>(slot_B(pool, valid[ii] ? slot : 0)) +
                                  (valid[ii] ? (size_t)(nc0 + c) * rank : 0);
@@ -733,7 +733,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         for (int i = 0; i < VV; ++i) {
             const int vi = tid + i * kThreads;
             const int t = vi >> (lgRp - 2), j = (vi & ((Rp >> 2) - 1)) * 4;
-            vneed[i] = t < T && j < lds_read_i32(&s_rank[min(t, T - 1)]);
+            vneed[i] = t < T && j < s_rank[min(t, T - 1)];
             vv[i] = u32x4{0, 0, 0, 0};
             if (vneed[i]) vv[i] = *reinterpret_cast<const u32x4 *>(vmail + (size_t)t * R + j);
         }
