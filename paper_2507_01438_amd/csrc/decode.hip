@@ -4,12 +4,14 @@
 // three phases:
 //
 //   1. shrink share.  The (row t, two rank rows j) units of  v[t][j] = sum_k A_i[j,k] x[t,k]  (A_i x_t of
-//      the row's own adapter, Sec. 3.4) are dealt out over the workgroups, one unit per wave: plain FMAs over
-//      the whole of d_in and one wavefront reduction.  Results go into the v mailbox.
+//      the row's own adapter, Sec. 3.4) are dealt out over the workgroups: bf16 dot products over the whole of
+//      d_in and one wavefront reduction.  Results go into the v mailbox.
 //   2. base contraction.  partial[ks][t][n] = sum_{k in slice ks} W[n,k] x[t,k]  (Sec. 3.4: W x [x_0..x_n],
-//      shared by the whole batch).  Each wave streams 16 rows of W straight from global memory into the
-//      A-operand of v_mfma_f32_16x16x32_bf16 (row = lane % 16, 8 consecutive k per lane); the rows of x
-//      are the B-operand, read from a small LDS ring that direct-to-LDS loads keep filled.
+//      shared by the whole batch) with v_mfma_f32_16x16x32_bf16: 16 rows of W per wave as A-operand, the rows
+//      of x as B-operand.  The K-slice goes by in sub-spans of 128 elements through a ring in LDS that
+//      direct-to-LDS loads keep filled: always the rows of x, and the tile's rows of W as well (whole cache
+//      lines per load instruction) unless the shape wants two workgroups per compute unit with more than 32
+//      rows of x; W then goes straight into the A-operand registers.
 //   3. exchange and expand.  Workgroup ks OWNS 64 / split of the tile's columns.  Every workgroup posts the
 //      pieces of its partial to their owners' mailboxes; each owner takes v, forms
 //          d[t][n] = s_t * sum_j B_i[n,j] v[t][j]      for its own columns,
@@ -22,8 +24,8 @@
 // fences on the way.  Piece mailboxes have one reader, who puts the empty pattern back; the v mailbox
 // is emptied by the last workgroup of the call to finish.  Arithmetic cannot produce the pattern: it is
 // a NaN whose low mantissa bits are set, while every NaN here descends from a bf16 (low 16 bits zero)
-// or is the default NaN.  All accesses to mailboxes are agent-scope, which on gfx950 go past the
-// per-XCD L2.
+// or is the default NaN.  The v mailbox is accessed at agent scope (past the per-XCD L2); the pieces of
+// a tile travel between workgroups of one XCD and meet in that XCD's L2.
 //
 // Every wait is bounded.  A reader whose bound runs out computes what it needs from the inputs on its
 // own (v of the rows it is working on, or its columns of y from scratch) and, for pieces, raises the
