@@ -276,6 +276,40 @@ def test_decode_back_to_back_calls_share_one_workspace():
     case.close()
 
 
+def test_decode_calls_replay_from_a_hip_graph():
+    """A layer's worth of decode calls captured once and replayed: every replay must leave the mailboxes and counters
+    as the next one expects them.  Replays alternate with eager work on the same workspace and a changed x, and every
+    replay is checked against the oracle (the eager result of the same inputs is checked by the other tests)."""
+    w = I.small_workload(777, I.BF16, 1024, 512, 24, 6, (8, 16, 16, 8, 16, 8), no_adapter_rows=(3,))
+    case = DeviceCase(w, w.projections[0])
+    d = case.desc()
+    case.B.elora_batched_lora_linear(d)  # warm-up outside the capture: one-time set-up of the kernel happens here
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for _ in range(3):
+            case.B.elora_batched_lora_linear(d, stream=side)
+    rng = np.random.default_rng(5)
+    for rep in range(4):
+        # new activations in place (same buffers, so the captured descriptor stays valid)
+        xn = I.f32_to_bf16_bits((rng.standard_normal(case.x_h.shape) * (0.5 + rep)).astype(np.float32))
+        case.x_h = xn
+        case.x.copy_(to_dev(xn))
+        case.y.fill_(7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        y = y_to_f64(case.y[: w.T], w.dtype)
+        assert rel_err(y, case.reference()) <= 1e-2, f"replay {rep}"
+        # eager work between the replays
+        y_eager = case.run()
+        assert rel_err(y_eager, case.reference()) <= 1e-2
+        np.testing.assert_array_equal(y, y_eager)  # fixed summation order: bit-identical
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # prefill / mixed path (LDS-tiled MFMA GEMM with the expand as K-extension)
 # ---------------------------------------------------------------------------------------------
