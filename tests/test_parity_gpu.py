@@ -63,6 +63,8 @@ SMALL = [
     (9, 1792, 64, 4, (40, 72, 9, 130), ()),         # 7 chunks of K: uneven K-slices
     (32, 2304, 48, 5, 64, (0, 31)),                 # last tile only three quarters there
     (48, 768, 16, 2, 8, ()),                        # one wave of the tile active
+    (40, 512, 14336, 3, (16, 8, 32), (7,)),         # 224 tiles, 3 row blocks: W straight into registers, two workgroups per CU
+    (24, 512, 4096, 3, 16, ()),                     # 64 tiles x 2 K-slices of 2 sub-spans: a ring that is never full
 ]
 
 
