@@ -561,6 +561,32 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
+// ------------------------------------------------------------------------------------------------
+// 4-bit W, many rows: W is converted to bf16 once per call, into the workspace, and the bf16 kernel runs on the copy.
+// Converted tile by tile inside the GEMM (WFMT = ELORA_W_INT4_G32 above) every row tile of the batch repeats the
+// conversion of the W tiles it meets, on the same vector units that feed the matrix cores, and the kernel runs at half
+// the bf16 rate; the copy costs one pass over W at memory speed (d_out x d_in x 2.6 bytes), which that saving repays
+// from a few hundred rows on.  Same arithmetic as park_codes: w = fma(code, scale, -8 scale) in fp32, rounded once.
+// One thread per 8 weights (4 bytes of codes in, 16 bytes out; four threads share a group's fp16 scale): a wave
+// reads 256 and writes 1024 consecutive bytes.
+// ------------------------------------------------------------------------------------------------
+constexpr int kDequantFirstRows = 768;
+
+__global__ __launch_bounds__(256) void w4_dequant_kernel(size_t n_pieces, const uint32_t *__restrict__ codes,
+                                                         const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_pieces) return;
+    const uint32_t q = codes[i];
+    const float sc = fp16_to_f32(scales[i >> 2]), c8 = -8.0f * sc;
+    const uint32_t lo = q & 0x0f0f0f0fu, hi = (q >> 4) & 0x0f0f0f0fu;
+    u32x4 o;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+        o[b] = pack_bf16x2(fmaf((float)((lo >> (8 * b)) & 0xffu), sc, c8), fmaf((float)((hi >> (8 * b)) & 0xffu), sc, c8));
+    out[i] = o;
+}
+
 }  // namespace
 
 bool elora::gemm_eligible(const elora_linear_desc_t &d, int max_rank)
@@ -571,10 +597,16 @@ bool elora::gemm_eligible(const elora_linear_desc_t &d, int max_rank)
 
 void elora::gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 {
-    plan->n_launches = d.pool ? 3 : 2;
+    const bool copy_first = d.wfmt == ELORA_W_INT4_G32 && gemm_w4_bytes(d.n_tokens, d.d_in, d.d_out) != 0;
+    plan->n_launches = (d.pool ? 3 : 2) + (copy_first ? 1 : 0);
     plan->tile_rows = BM;
     plan->tile_cols = BN;
     plan->grid = gemm_grid((d.n_tokens + BM - 1) / BM, (d.d_out + BN - 1) / BN);
+}
+
+size_t elora::gemm_w4_bytes(int n_tokens, int d_in, int d_out)
+{
+    return n_tokens >= kDequantFirstRows ? (size_t)d_in * (size_t)d_out * sizeof(uint16_t) : 0;
 }
 
 size_t elora::gemm_v_bytes(int n_tokens, int max_rank) { return (size_t)n_tokens * round_up(max_rank, BK) * sizeof(uint16_t); }
@@ -596,12 +628,21 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
                            static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
         ELORA_HIP_TRY(hipGetLastError());
     }
+    // 4-bit W and enough rows: the bf16 kernel on a copy made now
+    const bool copy_first = a.wfmt == ELORA_W_INT4_G32 && a.wsl.wdeq_bytes != 0;
+    if (copy_first) {
+        const size_t n_pieces = (size_t)a.N * (size_t)(a.K / 8);
+        hipLaunchKernelGGL(w4_dequant_kernel, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces,
+                           static_cast<const uint32_t *>(a.W), static_cast<const uint16_t *>(a.w_scales),
+                           reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
+        ELORA_HIP_TRY(hipGetLastError());
+    }
     GemmArgs ga;
     ga.T = a.T;
     ga.K = a.K;
     ga.N = a.N;
     ga.x = static_cast<const uint16_t *>(a.x);
-    ga.W = a.W;
+    ga.W = copy_first ? static_cast<const void *>(a.ws + a.wsl.wdeq) : a.W;
     ga.w_scales = static_cast<const uint16_t *>(a.w_scales);
     ga.row_slot = row_slot;
     ga.V = V;
@@ -612,7 +653,7 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
     const size_t lds = (size_t)2 * kStageElems * sizeof(uint16_t);
     dim3 grid(gemm_grid(ga.tiles_m, ga.tiles_n)), block(kGemmThreads);
     profile_mark_begin(stream);
-    if (a.wfmt == ELORA_W_SAME) {
+    if (a.wfmt == ELORA_W_SAME || copy_first) {
         static bool attr_done = false;
         if (!attr_done) {
             ELORA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(&lora_gemm_kernel<ELORA_W_SAME>),

@@ -43,7 +43,6 @@ void elora::profile_mark_end(hipStream_t stream)
 
 WsLayout elora::ws_layout(int T, int K, int N, int R)
 {
-    (void)K;
     WsLayout l;
     size_t t = (size_t)(T > 0 ? T : 1);
     size_t off = 0;
@@ -63,6 +62,10 @@ WsLayout elora::ws_layout(int T, int K, int N, int R)
     size_t v_full = t * (size_t)R * sizeof(float);
     size_t v_gemm = gemm_v_bytes((int)t, R);
     off += align_up(v_full > v_gemm ? v_full : v_gemm);
+    // last, and zero bytes for small row counts: a workspace sized for more rows holds every smaller layout
+    l.wdeq = off;
+    l.wdeq_bytes = gemm_w4_bytes(T, K, N);
+    off += align_up(l.wdeq_bytes);
     l.total = off;
     return l;
 }

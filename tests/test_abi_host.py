@@ -147,3 +147,13 @@ def test_workspace_init_and_hooks_validate_arguments(B):
     assert B.lib.elora_debug_xcd_local(-1) == B.ELORA_OK
     assert B.lib.elora_profile_arm(-1) == B.ELORA_E_SHAPE
     assert B.lib.elora_profile_arm(0) == B.ELORA_OK
+
+
+def test_workspace_grows_with_rows_and_holds_the_copy_of_a_4bit_w(B):
+    # a workspace sized for more rows must hold the layout of every smaller call; from 768 rows on it also holds
+    # a bf16 copy of W (d_out x d_in x 2 bytes) for the 4-bit path
+    K, N, R = 1024, 768, 16
+    sizes = [B.elora_workspace_bytes(t, K, N, R) for t in (1, 64, 65, 767, 768, 769, 4096)]
+    assert all(a <= b for a, b in zip(sizes, sizes[1:]))
+    assert sizes[4] - sizes[3] >= K * N * 2
+    assert sizes[5] - sizes[4] < 4096
