@@ -44,6 +44,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 TRAFFIC = {
     2: (46.0e6, "profiles/decode_kernel_config2.md"),
     4: (1.87e9, "profiles/lora_gemm_kernel_config4.md"),
+    5: (0.74e9, "profiles/lora_gemm_kernel_config5.md"),
 }
 WORKLOAD = {
     2: "Llama3.1-8B q_proj decode: W 4096x4096 bf16, 32 tokens, pool 64 adapters rank 16, adapter_idx power-law(1.1), scale 2.0",
