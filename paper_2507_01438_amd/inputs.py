@@ -103,6 +103,12 @@ def draw_adapters(rng: np.random.Generator, n_draws: int, pool: int, alpha: Opti
     return slot_of_rank[ranks].astype(np.int32)
 
 
+def request_trace(seed: int, n_adapters: int, alpha: Optional[float], length: int) -> np.ndarray:
+    """Adapter ids of `length` successive requests: power law over popularity ranks (Sec. 5.1; alpha None: uniform),
+    ranks mapped to ids through a seeded permutation."""
+    return draw_adapters(np.random.default_rng(seed), length, n_adapters, alpha)
+
+
 def draw_lengths(rng: np.random.Generator, n: int, lo: int, hi: int) -> np.ndarray:
     """Integer lengths uniform on [lo, hi] inclusive (Table "default_parameters": U[I_l, I_u])."""
     return rng.integers(lo, hi + 1, size=n).astype(np.int32)

@@ -1,0 +1,112 @@
+"""The cache oracle against what the mathematics of LRU fixes (no GPU, no product code)."""
+import numpy as np
+import pytest
+
+from oracle.cache_oracle import BUSY, LruCacheOracle, run_trace
+from paper_2507_01438_amd import inputs as I
+
+
+def _reuse_distance_hits(capacity, trace):
+    """Independent characterisation of LRU: a request hits iff fewer than `capacity` distinct OTHER adapters were
+    requested since the previous request for the same adapter."""
+    out = []
+    for i, a in enumerate(trace):
+        prev = max((j for j in range(i) if trace[j] == a), default=None)
+        out.append(prev is not None and len(set(trace[prev + 1:i])) < capacity)
+    return out
+
+
+def _optimal_misses(capacity, trace):
+    """Belady's policy by brute force: evict the adapter whose next request lies farthest ahead."""
+    cached, misses = set(), 0
+    for i, a in enumerate(trace):
+        if a in cached:
+            continue
+        misses += 1
+        if len(cached) == capacity:
+            def next_use(b):
+                return next((j for j in range(i + 1, len(trace)) if trace[j] == b), len(trace) + 1)
+            cached.remove(max(cached, key=next_use))
+        cached.add(a)
+    return misses
+
+
+def _fifo_misses(capacity, trace):
+    queue, misses = [], 0
+    for a in trace:
+        if a not in queue:
+            misses += 1
+            if len(queue) == capacity:
+                queue.pop(0)
+            queue.append(a)
+    return misses
+
+
+# The 20-request example used in operating-systems textbooks for page replacement with three frames: 12 misses under
+# LRU, 15 under first-in-first-out, 9 under the optimal policy.
+CLASSIC = [7, 0, 1, 2, 0, 3, 0, 4, 2, 3, 0, 3, 2, 1, 2, 0, 1, 7, 0, 1]
+
+
+def test_classic_three_block_example():
+    hits, _, _ = run_trace(3, CLASSIC)
+    assert hits.count(False) == 12
+    assert _fifo_misses(3, CLASSIC) == 15 and _optimal_misses(3, CLASSIC) == 9   # the helpers used below agree with it too
+
+
+def test_cyclic_trace_never_hits_and_single_adapter_always_does():
+    l = 5
+    hits, _, evicted = run_trace(l, [i % (l + 1) for i in range(60)])
+    assert not any(hits)
+    assert evicted[:l] == [-1] * l and evicted[l:] == [(i - l) % (l + 1) for i in range(l, 60)]  # always the oldest
+    hits, blocks, _ = run_trace(l, [42] * 30)
+    assert hits == [False] + [True] * 29 and set(blocks) == {0}
+
+
+@pytest.mark.parametrize("seed,capacity,alpha", [(1, 1, None), (2, 3, None), (3, 4, 1.0), (4, 8, 0.5), (5, 6, 1.5)])
+def test_hits_are_exactly_the_short_reuse_distances(seed, capacity, alpha):
+    trace = list(I.request_trace(seed, 20, alpha, 300))
+    assert run_trace(capacity, trace)[0] == _reuse_distance_hits(capacity, trace)
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_inclusion_property_and_optimal_bound(seed):
+    trace = list(I.request_trace(seed, 12, 1.0, 200))
+    prev_sets = None
+    for capacity in (1, 2, 3, 5, 8):
+        c = LruCacheOracle(capacity)
+        sets = []
+        for a in trace:
+            c.acquire(a)
+            c.release(a)
+            sets.append(set(c.block))
+            assert len(c.block) <= capacity and sorted(c.order) == sorted(c.block)
+            assert sorted(list(c.block.values()) + c.free) == list(range(capacity))   # every block is somewhere, once
+        if prev_sets is not None:   # what a smaller LRU cache holds, a larger one holds too
+            assert all(s <= t for s, t in zip(prev_sets, sets))
+        prev_sets = sets
+        assert c.requests - c.hits >= _optimal_misses(capacity, trace)
+        assert c.hit_rate() == c.hits / len(trace)
+
+
+def test_blocks_come_off_a_stack():
+    c = LruCacheOracle(4)
+    assert [c.acquire(a)[0] for a in (10, 11, 12)] == [0, 1, 2]
+    for a in (10, 11, 12):
+        c.release(a)
+    assert c.drop(11) is True and c.drop(10) is True and c.drop(99) is False
+    assert c.acquire(20)[0] == 0 and c.acquire(21)[0] == 1 and c.acquire(22)[0] == 3   # last returned first, then the untouched one
+    assert c.lookup(12) == 2 and c.lookup(11) == -1
+
+
+def test_pinned_adapters_are_never_the_victim():
+    c = LruCacheOracle(2)
+    c.acquire(1)
+    c.acquire(2)                         # both pinned
+    assert c.acquire(3) == (None, False, -1) and c.requests == 2
+    assert c.drop(1) == BUSY
+    c.release(2)
+    assert c.acquire(3) == (1, False, 2)  # 1 is older but pinned: 2 goes
+    c.release(1)
+    c.release(3)
+    assert c.acquire(4) == (0, False, 1)
+    assert not c.release(2)               # not cached any more
