@@ -40,6 +40,7 @@ extern "C" {
 typedef void *elora_stream_t; /* hipStream_t; NULL = the default stream */
 
 typedef struct elora_pool elora_pool_t; /* opaque host object; holds metadata only */
+typedef struct elora_cache elora_cache_t; /* opaque host object: which adapter sits in which block */
 
 typedef enum {
     ELORA_OK = 0,
@@ -52,7 +53,8 @@ typedef enum {
     ELORA_E_NOT_LOADED = 7, /* the slot holds no adapter */
     ELORA_E_STORAGE = 8,    /* pool storage or workspace smaller than required */
     ELORA_E_SEGMENTS = 9,   /* routing tables: both or neither of adapter_idx / seg_offsets given, or n_segments < 0 */
-    ELORA_E_HIP = 10        /* a HIP runtime call failed (no device, bad launch, ...) */
+    ELORA_E_HIP = 10,       /* a HIP runtime call failed (no device, bad launch, ...) */
+    ELORA_E_BUSY = 11       /* adapter cache: every cached adapter is in use by an outstanding request */
 } elora_status_t;
 
 typedef enum { ELORA_F32 = 0, ELORA_BF16 = 1 } elora_dtype_t; /* element type of x, y, A, B (and W if ELORA_W_SAME) */
@@ -129,6 +131,65 @@ int elora_pool_slot_info(const elora_pool_t *pool, int slot, int *rank, float *s
  */
 int elora_pool_poll_error(elora_pool_t *pool, int clear, int *n_bad_rows, int *first_bad_row,
                           elora_stream_t stream);
+
+/* ----------------------------------------------------------------- cache ---
+ * The adapter memory manager of Sec. 3.3 / 4.2: a memory cache C of at most l
+ * adapters over the l blocks of the pre-allocated pool.  An adapter that is
+ * requested and cached is served from the cache; otherwise it is assigned to a
+ * free block, and when none is free the least recently used adapter is evicted
+ * and its block is reused (Sec. 4.2 states LRU).  Free blocks form a stack
+ * (Sec. 4.2) that hands out 0, 1, 2, ... at first.  Block numbers are the slot
+ * numbers of elora_pool_*: one cache can stand for the pools of all linear
+ * layers of a model, each holding that layer's part of an adapter in the same
+ * slot.  Host logic only: the cache decides, the caller loads
+ * (elora_pool_load_adapter) what it reports as missing.  Not thread-safe.
+ *
+ * A request pins its adapter until elora_cache_release: a pinned adapter is
+ * never the victim (its rows may still be waiting to run).
+ */
+
+/* Errors: E_NULL, E_SHAPE (capacity < 1). */
+int elora_cache_create(int capacity, elora_cache_t **out);
+int elora_cache_destroy(elora_cache_t *cache);
+
+/*
+ * One request for adapter `adapter_id` (>= 0).  *slot = its block; *hit = 1 if it was cached (no load needed),
+ * 0 if the block was just assigned and the caller has to load the adapter into it; *evicted_id = the adapter that
+ * lost the block, -1 if none did.  The adapter becomes the most recently used one and its pin count rises by one.
+ * Errors: E_NULL, E_SHAPE (adapter_id < 0), E_BUSY (not cached, no free block, all cached adapters pinned:
+ * nothing changes and the request is not counted).
+ */
+int elora_cache_acquire(elora_cache_t *cache, int adapter_id, int *slot, int *hit, int *evicted_id);
+
+/* The request is over.  Errors: E_NULL, E_NOT_LOADED (not cached, or not pinned). */
+int elora_cache_release(elora_cache_t *cache, int adapter_id);
+
+/* *slot = the adapter's block or -1; changes nothing (no request is counted).  Errors: E_NULL. */
+int elora_cache_lookup(const elora_cache_t *cache, int adapter_id, int *slot);
+
+/* Evict on purpose; the block goes back on the stack.  Errors: E_NULL, E_NOT_LOADED, E_BUSY (pinned). */
+int elora_cache_drop(elora_cache_t *cache, int adapter_id);
+
+/* Hit rate H = hits / requests (Sec. 3.3).  Any out-pointer may be NULL.  Errors: E_NULL (cache). */
+int elora_cache_stats(const elora_cache_t *cache, long long *hits, long long *requests, long long *evictions);
+int elora_cache_reset_stats(elora_cache_t *cache);
+
+/*
+ * Device-side order between the stream that loads adapters and the stream that computes, so that loads overlap
+ * the linear calls of other batches and neither side waits on the host:
+ *   load_begin   before elora_pool_load_adapter into `slot`: the copy stream waits for the last batch that used
+ *                the block (it may still be reading the adapter that is being replaced)
+ *   load_end     after it: marks the block's content as arriving on the copy stream
+ *   batch_begin  before the linear calls of a batch whose rows use `slots[0..n)`: the compute stream waits for
+ *                the loads of those blocks that it has not waited for yet
+ *   batch_end    after them: remembers the batch as the last user of those blocks
+ * Events are created on first use (these four calls need a device; the functions above do not).
+ * Errors: E_NULL, E_SLOT, E_HIP.
+ */
+int elora_cache_load_begin(elora_cache_t *cache, int slot, elora_stream_t copy_stream);
+int elora_cache_load_end(elora_cache_t *cache, int slot, elora_stream_t copy_stream);
+int elora_cache_batch_begin(elora_cache_t *cache, const int *slots, int n, elora_stream_t compute_stream);
+int elora_cache_batch_end(elora_cache_t *cache, const int *slots, int n, elora_stream_t compute_stream);
 
 /* ---------------------------------------------------------------- linear --- */
 

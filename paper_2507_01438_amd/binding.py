@@ -37,6 +37,9 @@ EXPORTED = [
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
     "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
     "elora_debug_spin_limit", "elora_debug_xcd_local",
+    "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
+    "elora_cache_drop", "elora_cache_stats", "elora_cache_reset_stats", "elora_cache_load_begin",
+    "elora_cache_load_end", "elora_cache_batch_begin", "elora_cache_batch_end",
 ]
 
 
@@ -97,6 +100,30 @@ lib.elora_profile_arm.restype = ctypes.c_int
 lib.elora_profile_arm.argtypes = [ctypes.c_int]
 lib.elora_profile_read.restype = ctypes.c_int
 lib.elora_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+_ip = ctypes.POINTER(ctypes.c_int)
+_llp = ctypes.POINTER(ctypes.c_longlong)
+lib.elora_cache_create.restype = ctypes.c_int
+lib.elora_cache_create.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p)]
+lib.elora_cache_destroy.restype = ctypes.c_int
+lib.elora_cache_destroy.argtypes = [ctypes.c_void_p]
+lib.elora_cache_acquire.restype = ctypes.c_int
+lib.elora_cache_acquire.argtypes = [ctypes.c_void_p, ctypes.c_int, _ip, _ip, _ip]
+lib.elora_cache_release.restype = ctypes.c_int
+lib.elora_cache_release.argtypes = [ctypes.c_void_p, ctypes.c_int]
+lib.elora_cache_lookup.restype = ctypes.c_int
+lib.elora_cache_lookup.argtypes = [ctypes.c_void_p, ctypes.c_int, _ip]
+lib.elora_cache_drop.restype = ctypes.c_int
+lib.elora_cache_drop.argtypes = [ctypes.c_void_p, ctypes.c_int]
+lib.elora_cache_stats.restype = ctypes.c_int
+lib.elora_cache_stats.argtypes = [ctypes.c_void_p, _llp, _llp, _llp]
+lib.elora_cache_reset_stats.restype = ctypes.c_int
+lib.elora_cache_reset_stats.argtypes = [ctypes.c_void_p]
+for _name in ("elora_cache_load_begin", "elora_cache_load_end"):
+    getattr(lib, _name).restype = ctypes.c_int
+    getattr(lib, _name).argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+for _name in ("elora_cache_batch_begin", "elora_cache_batch_end"):
+    getattr(lib, _name).restype = ctypes.c_int
+    getattr(lib, _name).argtypes = [ctypes.c_void_p, _ip, ctypes.c_int, ctypes.c_void_p]
 
 
 class EloraError(RuntimeError):
@@ -235,6 +262,78 @@ def elora_profile_read(n: int):
 # ---- small holders that keep device memory alive (no arithmetic) ----------------------
 
 _TORCH_DTYPE = {ELORA_F32: torch.float32, ELORA_BF16: torch.bfloat16}
+
+
+# ---- adapter cache (Sec. 3.3 / 4.2): argument marshalling only ----------------------
+
+ELORA_E_NOT_LOADED = 7
+ELORA_E_BUSY = 11
+
+
+def elora_cache_create(capacity: int) -> int:
+    out = ctypes.c_void_p()
+    _check(lib.elora_cache_create(int(capacity), ctypes.byref(out)), "elora_cache_create")
+    return out.value
+
+
+def elora_cache_destroy(cache: int) -> None:
+    _check(lib.elora_cache_destroy(cache), "elora_cache_destroy")
+
+
+def elora_cache_acquire(cache: int, adapter_id: int):
+    """(slot, hit, evicted adapter id or -1)"""
+    slot, hit, ev = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib.elora_cache_acquire(cache, int(adapter_id), ctypes.byref(slot), ctypes.byref(hit), ctypes.byref(ev)),
+           "elora_cache_acquire")
+    return slot.value, bool(hit.value), ev.value
+
+
+def elora_cache_release(cache: int, adapter_id: int) -> None:
+    _check(lib.elora_cache_release(cache, int(adapter_id)), "elora_cache_release")
+
+
+def elora_cache_lookup(cache: int, adapter_id: int) -> int:
+    slot = ctypes.c_int()
+    _check(lib.elora_cache_lookup(cache, int(adapter_id), ctypes.byref(slot)), "elora_cache_lookup")
+    return slot.value
+
+
+def elora_cache_drop(cache: int, adapter_id: int) -> None:
+    _check(lib.elora_cache_drop(cache, int(adapter_id)), "elora_cache_drop")
+
+
+def elora_cache_stats(cache: int):
+    """(hits, requests, evictions)"""
+    h, r, e = ctypes.c_longlong(), ctypes.c_longlong(), ctypes.c_longlong()
+    _check(lib.elora_cache_stats(cache, ctypes.byref(h), ctypes.byref(r), ctypes.byref(e)), "elora_cache_stats")
+    return h.value, r.value, e.value
+
+
+def elora_cache_reset_stats(cache: int) -> None:
+    _check(lib.elora_cache_reset_stats(cache), "elora_cache_reset_stats")
+
+
+def elora_cache_load_begin(cache: int, slot: int, copy_stream) -> None:
+    _check(lib.elora_cache_load_begin(cache, int(slot), _stream(copy_stream)), "elora_cache_load_begin")
+
+
+def elora_cache_load_end(cache: int, slot: int, copy_stream) -> None:
+    _check(lib.elora_cache_load_end(cache, int(slot), _stream(copy_stream)), "elora_cache_load_end")
+
+
+def _int_array(values):
+    values = [int(v) for v in values]
+    return (ctypes.c_int * len(values))(*values), len(values)
+
+
+def elora_cache_batch_begin(cache: int, slots, compute_stream=None) -> None:
+    arr, n = _int_array(slots)
+    _check(lib.elora_cache_batch_begin(cache, arr, n, _stream(compute_stream)), "elora_cache_batch_begin")
+
+
+def elora_cache_batch_end(cache: int, slots, compute_stream=None) -> None:
+    arr, n = _int_array(slots)
+    _check(lib.elora_cache_batch_end(cache, arr, n, _stream(compute_stream)), "elora_cache_batch_end")
 
 
 class AdapterPool:

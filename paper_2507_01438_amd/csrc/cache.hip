@@ -1,0 +1,224 @@
+// The adapter memory manager (Sec. 3.3 / 4.2 of the paper): which adapter sits in which block of the pre-allocated
+// pool, least-recently-used replacement, a stack of free blocks, and the events that order adapter loads on one
+// stream against linear calls on another.  Host code only; no kernel here.
+//
+// Recency is a doubly linked list threaded through per-block arrays (head = least recently used), adapter id ->
+// block is a hash map: a request costs O(1) unless pinned adapters have to be skipped on the way to a victim.
+#include <unordered_map>
+#include <vector>
+
+#include "common.h"
+
+using namespace elora;
+
+namespace {
+constexpr int kBatchRing = 64;  // batches whose "done" event is kept; an older batch is stood in for by a later one
+}
+
+struct elora_cache {
+    int capacity = 0;
+    std::unordered_map<int, int> block_of;  // adapter id -> block
+    std::vector<int> id, prev, next, pins;  // per block: adapter (-1 free), neighbours in recency order, pin count
+    std::vector<int> free_stack;
+    int head = -1, tail = -1;               // least / most recently used block
+    long long hits = 0, requests = 0, evictions = 0;
+    // device-side order
+    std::vector<hipEvent_t> loaded;         // per block: its last load (nullptr: none yet)
+    std::vector<char> load_pending;         // the compute stream has not waited for that load yet
+    std::vector<int> last_batch;            // per block: ring index of the last batch that used it, -1 none
+    hipEvent_t batch_done[kBatchRing] = {};
+    long long n_batches = 0;
+
+    void unlink(int b)
+    {
+        if (prev[b] >= 0) next[prev[b]] = next[b]; else head = next[b];
+        if (next[b] >= 0) prev[next[b]] = prev[b]; else tail = prev[b];
+        prev[b] = next[b] = -1;
+    }
+    void push_most_recent(int b)
+    {
+        prev[b] = tail;
+        next[b] = -1;
+        if (tail >= 0) next[tail] = b; else head = b;
+        tail = b;
+    }
+};
+
+extern "C" {
+
+int elora_cache_create(int capacity, elora_cache_t **out)
+{
+    if (!out) return ELORA_E_NULL;
+    if (capacity < 1) return ELORA_E_SHAPE;
+    elora_cache *c = new (std::nothrow) elora_cache;
+    if (!c) return ELORA_E_STORAGE;
+    c->capacity = capacity;
+    c->id.assign(capacity, -1);
+    c->prev.assign(capacity, -1);
+    c->next.assign(capacity, -1);
+    c->pins.assign(capacity, 0);
+    c->free_stack.resize(capacity);
+    for (int i = 0; i < capacity; ++i) c->free_stack[i] = capacity - 1 - i;  // block 0 comes off first
+    c->loaded.assign(capacity, nullptr);
+    c->load_pending.assign(capacity, 0);
+    c->last_batch.assign(capacity, -1);
+    *out = c;
+    return ELORA_OK;
+}
+
+int elora_cache_destroy(elora_cache_t *c)
+{
+    if (!c) return ELORA_E_NULL;
+    for (hipEvent_t e : c->loaded)
+        if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->batch_done)
+        if (e) (void)hipEventDestroy(e);
+    delete c;
+    return ELORA_OK;
+}
+
+int elora_cache_acquire(elora_cache_t *c, int adapter_id, int *slot, int *hit, int *evicted_id)
+{
+    if (!c || !slot || !hit || !evicted_id) return ELORA_E_NULL;
+    if (adapter_id < 0) return ELORA_E_SHAPE;
+    auto it = c->block_of.find(adapter_id);
+    if (it != c->block_of.end()) {
+        const int b = it->second;
+        c->unlink(b);
+        c->push_most_recent(b);
+        ++c->pins[b];
+        ++c->requests;
+        ++c->hits;
+        *slot = b;
+        *hit = 1;
+        *evicted_id = -1;
+        return ELORA_OK;
+    }
+    int b, victim_id = -1;
+    if (!c->free_stack.empty()) {
+        b = c->free_stack.back();
+        c->free_stack.pop_back();
+    } else {
+        b = c->head;
+        while (b >= 0 && c->pins[b] > 0) b = c->next[b];
+        if (b < 0) return ELORA_E_BUSY;
+        victim_id = c->id[b];
+        c->block_of.erase(victim_id);
+        c->unlink(b);
+        ++c->evictions;
+    }
+    c->id[b] = adapter_id;
+    c->pins[b] = 1;
+    c->block_of.emplace(adapter_id, b);
+    c->push_most_recent(b);
+    ++c->requests;
+    *slot = b;
+    *hit = 0;
+    *evicted_id = victim_id;
+    return ELORA_OK;
+}
+
+int elora_cache_release(elora_cache_t *c, int adapter_id)
+{
+    if (!c) return ELORA_E_NULL;
+    auto it = c->block_of.find(adapter_id);
+    if (it == c->block_of.end() || c->pins[it->second] <= 0) return ELORA_E_NOT_LOADED;
+    --c->pins[it->second];
+    return ELORA_OK;
+}
+
+int elora_cache_lookup(const elora_cache_t *c, int adapter_id, int *slot)
+{
+    if (!c || !slot) return ELORA_E_NULL;
+    auto it = c->block_of.find(adapter_id);
+    *slot = it == c->block_of.end() ? -1 : it->second;
+    return ELORA_OK;
+}
+
+int elora_cache_drop(elora_cache_t *c, int adapter_id)
+{
+    if (!c) return ELORA_E_NULL;
+    auto it = c->block_of.find(adapter_id);
+    if (it == c->block_of.end()) return ELORA_E_NOT_LOADED;
+    const int b = it->second;
+    if (c->pins[b] > 0) return ELORA_E_BUSY;
+    c->block_of.erase(it);
+    c->unlink(b);
+    c->id[b] = -1;
+    c->free_stack.push_back(b);
+    return ELORA_OK;
+}
+
+int elora_cache_stats(const elora_cache_t *c, long long *hits, long long *requests, long long *evictions)
+{
+    if (!c) return ELORA_E_NULL;
+    if (hits) *hits = c->hits;
+    if (requests) *requests = c->requests;
+    if (evictions) *evictions = c->evictions;
+    return ELORA_OK;
+}
+
+int elora_cache_reset_stats(elora_cache_t *c)
+{
+    if (!c) return ELORA_E_NULL;
+    c->hits = c->requests = c->evictions = 0;
+    return ELORA_OK;
+}
+
+// ---- device-side order ------------------------------------------------------------------------------------------
+// A batch's "done" event sits in a ring.  When the ring comes round, the event object of an old batch is recorded
+// again for a new one; a block that still names the old batch then waits for the new one instead, which (same
+// compute stream) ends later: never too early.  Every wait refers to records made earlier in host order, so the two
+// streams cannot wait for each other in a circle.
+
+int elora_cache_load_begin(elora_cache_t *c, int slot, elora_stream_t copy_stream)
+{
+    if (!c) return ELORA_E_NULL;
+    if (slot < 0 || slot >= c->capacity) return ELORA_E_SLOT;
+    if (c->last_batch[slot] >= 0) {
+        ELORA_HIP_TRY(hipStreamWaitEvent(static_cast<hipStream_t>(copy_stream), c->batch_done[c->last_batch[slot]], 0));
+        c->last_batch[slot] = -1;  // later loads into the block follow this one on the copy stream
+    }
+    return ELORA_OK;
+}
+
+int elora_cache_load_end(elora_cache_t *c, int slot, elora_stream_t copy_stream)
+{
+    if (!c) return ELORA_E_NULL;
+    if (slot < 0 || slot >= c->capacity) return ELORA_E_SLOT;
+    if (!c->loaded[slot]) ELORA_HIP_TRY(hipEventCreateWithFlags(&c->loaded[slot], hipEventDisableTiming));
+    ELORA_HIP_TRY(hipEventRecord(c->loaded[slot], static_cast<hipStream_t>(copy_stream)));
+    c->load_pending[slot] = 1;
+    return ELORA_OK;
+}
+
+int elora_cache_batch_begin(elora_cache_t *c, const int *slots, int n, elora_stream_t compute_stream)
+{
+    if (!c || (n > 0 && !slots)) return ELORA_E_NULL;
+    for (int i = 0; i < n; ++i)
+        if (slots[i] < 0 || slots[i] >= c->capacity) return ELORA_E_SLOT;
+    for (int i = 0; i < n; ++i) {
+        const int b = slots[i];
+        if (c->load_pending[b]) {
+            ELORA_HIP_TRY(hipStreamWaitEvent(static_cast<hipStream_t>(compute_stream), c->loaded[b], 0));
+            c->load_pending[b] = 0;  // whatever this stream runs from now on comes after that load
+        }
+    }
+    return ELORA_OK;
+}
+
+int elora_cache_batch_end(elora_cache_t *c, const int *slots, int n, elora_stream_t compute_stream)
+{
+    if (!c || (n > 0 && !slots)) return ELORA_E_NULL;
+    for (int i = 0; i < n; ++i)
+        if (slots[i] < 0 || slots[i] >= c->capacity) return ELORA_E_SLOT;
+    if (n == 0) return ELORA_OK;
+    const int r = (int)(c->n_batches % kBatchRing);
+    if (!c->batch_done[r]) ELORA_HIP_TRY(hipEventCreateWithFlags(&c->batch_done[r], hipEventDisableTiming));
+    ELORA_HIP_TRY(hipEventRecord(c->batch_done[r], static_cast<hipStream_t>(compute_stream)));
+    ++c->n_batches;
+    for (int i = 0; i < n; ++i) c->last_batch[slots[i]] = r;
+    return ELORA_OK;
+}
+
+}  // extern "C"

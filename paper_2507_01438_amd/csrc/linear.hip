@@ -145,6 +145,7 @@ const char *elora_status_string(int status)
     case ELORA_E_STORAGE: return "pool storage or workspace too small";
     case ELORA_E_SEGMENTS: return "routing tables: give exactly one of adapter_idx / segment tables";
     case ELORA_E_HIP: return "HIP runtime call failed";
+    case ELORA_E_BUSY: return "every cached adapter is in use";
     default: return "unknown status";
     }
 }

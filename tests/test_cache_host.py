@@ -1,0 +1,108 @@
+"""The C++ adapter cache (host logic of libelora) against the oracle: bit-exact on seeded request traces.  No GPU."""
+import numpy as np
+import pytest
+
+from oracle.cache_oracle import BUSY, LruCacheOracle
+from paper_2507_01438_amd import inputs as I
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2507_01438_amd import build
+    if build.is_stale():
+        build.build()
+    from paper_2507_01438_amd import binding
+    return binding
+
+
+@pytest.mark.parametrize("seed,n_adapters,alpha,capacity", [(1, 50, 1.0, 8), (2, 200, 0.5, 16), (3, 30, None, 30),
+                                                           (4, 30, 1.5, 1), (5, 1000, 1.0, 64)])
+def test_traces_match_the_oracle_request_by_request(B, seed, n_adapters, alpha, capacity):
+    trace = I.request_trace(seed, n_adapters, alpha, 4000)
+    ref = LruCacheOracle(capacity)
+    c = B.elora_cache_create(capacity)
+    for a in trace:
+        a = int(a)
+        want = ref.acquire(a)
+        ref.release(a)
+        got = B.elora_cache_acquire(c, a)
+        B.elora_cache_release(c, a)
+        assert got == want, (a, got, want)
+    assert B.elora_cache_stats(c) == (ref.hits, ref.requests, ref.evictions)
+    for a in range(n_adapters):
+        assert B.elora_cache_lookup(c, a) == ref.lookup(a)
+    B.elora_cache_reset_stats(c)
+    assert B.elora_cache_stats(c) == (0, 0, 0)
+    B.elora_cache_destroy(c)
+
+
+@pytest.mark.parametrize("seed", [7, 8, 9])
+def test_random_mix_of_requests_releases_and_drops(B, seed):
+    rng = np.random.default_rng(seed)
+    capacity, n_adapters = 6, 14
+    ref = LruCacheOracle(capacity)
+    c = B.elora_cache_create(capacity)
+    held = []   # outstanding requests
+    for step in range(5000):
+        op = rng.integers(0, 10)
+        a = int(rng.integers(0, n_adapters))
+        if op < 5:
+            want = ref.acquire(a)
+            if want[0] is None:
+                with pytest.raises(B.EloraError) as e:
+                    B.elora_cache_acquire(c, a)
+                assert e.value.status == B.ELORA_E_BUSY
+            else:
+                assert B.elora_cache_acquire(c, a) == want
+                held.append(a)
+        elif op < 8 and held:
+            a = held.pop(int(rng.integers(0, len(held))))
+            assert ref.release(a)
+            B.elora_cache_release(c, a)
+        elif op == 8:
+            want = ref.drop(a)
+            if want is True:
+                B.elora_cache_drop(c, a)
+            else:
+                with pytest.raises(B.EloraError) as e:
+                    B.elora_cache_drop(c, a)
+                assert e.value.status == (B.ELORA_E_BUSY if want == BUSY else B.ELORA_E_NOT_LOADED)
+        else:
+            assert B.elora_cache_lookup(c, a) == ref.lookup(a)
+    assert B.elora_cache_stats(c) == (ref.hits, ref.requests, ref.evictions)
+    B.elora_cache_destroy(c)
+
+
+def test_argument_errors(B):
+    with pytest.raises(B.EloraError):
+        B.elora_cache_create(0)
+    c = B.elora_cache_create(2)
+    with pytest.raises(B.EloraError):
+        B.elora_cache_acquire(c, -1)
+    with pytest.raises(B.EloraError) as e:
+        B.elora_cache_release(c, 5)
+    assert e.value.status == B.ELORA_E_NOT_LOADED
+    B.elora_cache_acquire(c, 5)
+    B.elora_cache_release(c, 5)
+    with pytest.raises(B.EloraError):
+        B.elora_cache_release(c, 5)   # not pinned any more
+    assert B.lib.elora_cache_acquire(None, 1, None, None, None) == 1
+    assert "in use" in B.elora_status_string(B.ELORA_E_BUSY)
+    B.elora_cache_destroy(c)
+
+
+def test_hit_rate_under_the_paper_like_power_law(B):
+    # Sec. 5.1: requests follow a power law over the adapters; a cache of a tenth of them serves most requests
+    n_adapters, capacity = 1000, 100
+    trace = I.request_trace(21, n_adapters, 1.2, 20000)
+    c = B.elora_cache_create(capacity)
+    for a in trace:
+        B.elora_cache_acquire(c, int(a))
+        B.elora_cache_release(c, int(a))
+    hits, requests, _ = B.elora_cache_stats(c)
+    B.elora_cache_destroy(c)
+    ref = LruCacheOracle(capacity)
+    for a in trace:
+        ref.acquire(int(a)); ref.release(int(a))
+    assert (hits, requests) == (ref.hits, ref.requests)
+    assert 0.5 < hits / requests < 0.95
