@@ -164,6 +164,21 @@ int elora_cache_acquire(elora_cache_t *cache, int adapter_id, int *slot, int *hi
 /* The request is over.  Errors: E_NULL, E_NOT_LOADED (not cached, or not pinned). */
 int elora_cache_release(elora_cache_t *cache, int adapter_id);
 
+/*
+ * The requests of one batch, row by row in order (host arrays): slots[t] = the block of row t's adapter
+ * (adapter_ids[t] < 0: no adapter, slots[t] = -1, not a request).  The adapters that have to be loaded come back
+ * as miss_ids[0..*n_miss) / miss_slots[0..*n_miss), each once, in the order their blocks were assigned (room for
+ * n entries each).  Later rows of the batch that name an adapter assigned by an earlier row count as hits.
+ * On E_BUSY (more distinct adapters in flight than blocks) the requests this call had made are released again and
+ * the arrays hold nothing of use; evictions it made on the way stay.  Errors: E_NULL, E_SHAPE (n < 0), E_BUSY.
+ */
+int elora_cache_acquire_batch(elora_cache_t *cache, const int *adapter_ids, int n, int *slots, int *miss_ids,
+                              int *miss_slots, int *n_miss);
+
+/* Releases what elora_cache_acquire_batch acquired for the same rows.  Errors: E_NULL, E_SHAPE, E_NOT_LOADED
+ * (some row's adapter was not cached or not pinned; the other rows are still released). */
+int elora_cache_release_batch(elora_cache_t *cache, const int *adapter_ids, int n);
+
 /* *slot = the adapter's block or -1; changes nothing (no request is counted).  Errors: E_NULL. */
 int elora_cache_lookup(const elora_cache_t *cache, int adapter_id, int *slot);
 

@@ -11,6 +11,7 @@ import ctypes
 import os
 from typing import Optional
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -38,6 +39,7 @@ EXPORTED = [
     "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
     "elora_debug_spin_limit", "elora_debug_xcd_local",
     "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
+    "elora_cache_acquire_batch", "elora_cache_release_batch",
     "elora_cache_drop", "elora_cache_stats", "elora_cache_reset_stats", "elora_cache_load_begin",
     "elora_cache_load_end", "elora_cache_batch_begin", "elora_cache_batch_end",
 ]
@@ -110,6 +112,11 @@ lib.elora_cache_acquire.restype = ctypes.c_int
 lib.elora_cache_acquire.argtypes = [ctypes.c_void_p, ctypes.c_int, _ip, _ip, _ip]
 lib.elora_cache_release.restype = ctypes.c_int
 lib.elora_cache_release.argtypes = [ctypes.c_void_p, ctypes.c_int]
+lib.elora_cache_acquire_batch.restype = ctypes.c_int
+lib.elora_cache_acquire_batch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, _ip]
+lib.elora_cache_release_batch.restype = ctypes.c_int
+lib.elora_cache_release_batch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
 lib.elora_cache_lookup.restype = ctypes.c_int
 lib.elora_cache_lookup.argtypes = [ctypes.c_void_p, ctypes.c_int, _ip]
 lib.elora_cache_drop.restype = ctypes.c_int
@@ -290,6 +297,24 @@ def elora_cache_acquire(cache: int, adapter_id: int):
 
 def elora_cache_release(cache: int, adapter_id: int) -> None:
     _check(lib.elora_cache_release(cache, int(adapter_id)), "elora_cache_release")
+
+
+def elora_cache_acquire_batch(cache: int, adapter_ids: np.ndarray, slots: np.ndarray, miss_ids: np.ndarray,
+                              miss_slots: np.ndarray) -> int:
+    """Host int32 arrays of the same length (adapter_ids in; the others out).  Returns the number of misses."""
+    n = int(adapter_ids.shape[0])
+    for a in (adapter_ids, slots, miss_ids, miss_slots):
+        assert a.dtype == np.int32 and a.flags.c_contiguous and a.shape[0] >= n
+    n_miss = ctypes.c_int()
+    _check(lib.elora_cache_acquire_batch(cache, adapter_ids.ctypes.data, n, slots.ctypes.data, miss_ids.ctypes.data,
+                                         miss_slots.ctypes.data, ctypes.byref(n_miss)), "elora_cache_acquire_batch")
+    return n_miss.value
+
+
+def elora_cache_release_batch(cache: int, adapter_ids: np.ndarray) -> None:
+    assert adapter_ids.dtype == np.int32 and adapter_ids.flags.c_contiguous
+    _check(lib.elora_cache_release_batch(cache, adapter_ids.ctypes.data, int(adapter_ids.shape[0])),
+           "elora_cache_release_batch")
 
 
 def elora_cache_lookup(cache: int, adapter_id: int) -> int:

@@ -127,6 +127,44 @@ int elora_cache_release(elora_cache_t *c, int adapter_id)
     return ELORA_OK;
 }
 
+int elora_cache_acquire_batch(elora_cache_t *c, const int *adapter_ids, int n, int *slots, int *miss_ids, int *miss_slots,
+                              int *n_miss)
+{
+    if (!c || !n_miss || (n > 0 && (!adapter_ids || !slots || !miss_ids || !miss_slots))) return ELORA_E_NULL;
+    if (n < 0) return ELORA_E_SHAPE;
+    int misses = 0;
+    for (int t = 0; t < n; ++t) {
+        if (adapter_ids[t] < 0) {
+            slots[t] = -1;
+            continue;
+        }
+        int hit = 0, evicted = -1;
+        const int rc = elora_cache_acquire(c, adapter_ids[t], &slots[t], &hit, &evicted);
+        if (rc != ELORA_OK) {
+            for (int u = 0; u < t; ++u)
+                if (adapter_ids[u] >= 0) (void)elora_cache_release(c, adapter_ids[u]);
+            return rc;
+        }
+        if (!hit) {
+            miss_ids[misses] = adapter_ids[t];
+            miss_slots[misses] = slots[t];
+            ++misses;
+        }
+    }
+    *n_miss = misses;
+    return ELORA_OK;
+}
+
+int elora_cache_release_batch(elora_cache_t *c, const int *adapter_ids, int n)
+{
+    if (!c || (n > 0 && !adapter_ids)) return ELORA_E_NULL;
+    if (n < 0) return ELORA_E_SHAPE;
+    int rc = ELORA_OK;
+    for (int t = 0; t < n; ++t)
+        if (adapter_ids[t] >= 0 && elora_cache_release(c, adapter_ids[t]) != ELORA_OK) rc = ELORA_E_NOT_LOADED;
+    return rc;
+}
+
 int elora_cache_lookup(const elora_cache_t *c, int adapter_id, int *slot)
 {
     if (!c || !slot) return ELORA_E_NULL;

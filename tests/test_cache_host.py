@@ -106,3 +106,40 @@ def test_hit_rate_under_the_paper_like_power_law(B):
         ref.acquire(int(a)); ref.release(int(a))
     assert (hits, requests) == (ref.hits, ref.requests)
     assert 0.5 < hits / requests < 0.95
+
+
+def test_batches_of_rows_match_the_oracle(B):
+    # every row is a request; a batch's adapters stay pinned until the batch is released
+    capacity, rows = 8, 6
+    trace = I.request_trace(31, 40, 1.0, 600 * rows).reshape(600, rows).astype(np.int32)
+    trace[5, 2] = -1                                   # a row without adapter is no request
+    ref = LruCacheOracle(capacity)
+    c = B.elora_cache_create(capacity)
+    slots, miss_ids, miss_slots = (np.zeros(rows, np.int32) for _ in range(3))
+    for ids in trace:
+        want_slots, want_miss = [], []
+        for a in ids:
+            if a < 0:
+                want_slots.append(-1)
+                continue
+            blk, hit, _ = ref.acquire(int(a))
+            want_slots.append(blk)
+            if not hit:
+                want_miss.append((int(a), blk))
+        n_miss = B.elora_cache_acquire_batch(c, ids, slots, miss_ids, miss_slots)
+        assert slots.tolist() == want_slots
+        assert list(zip(miss_ids[:n_miss].tolist(), miss_slots[:n_miss].tolist())) == want_miss
+        B.elora_cache_release_batch(c, ids)
+        for a in ids:
+            if a >= 0:
+                assert ref.release(int(a))
+    assert B.elora_cache_stats(c) == (ref.hits, ref.requests, ref.evictions)
+    # more distinct adapters in one batch than blocks: refused, and nothing stays pinned
+    too_many = np.arange(100, 100 + capacity + 1, dtype=np.int32)
+    big = [np.zeros(capacity + 1, np.int32) for _ in range(3)]
+    with pytest.raises(B.EloraError) as e:
+        B.elora_cache_acquire_batch(c, too_many, *big)
+    assert e.value.status == B.ELORA_E_BUSY
+    for a in too_many[:capacity]:
+        B.elora_cache_drop(c, int(a))                  # droppable: not pinned
+    B.elora_cache_destroy(c)
