@@ -63,9 +63,106 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="distinct (W, pool, x) copies the decode steps rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--cache-trace", action="store_true",
+                    help="instead of the headline metric: config 2's decode call behind the adapter cache, with misses "
+                         "loaded from pinned host memory (one JSON line of its own)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that profiler byte counters can be scaled")
     return ap.parse_args()
+
+
+def cache_trace(args, B, I, dev):
+    """Config 2's call (q_proj, 32 rows, rank 16) with the adapter memory manager in front of it (Sec. 3.3 / 4.2):
+    requests follow a power law over a universe of adapters held in pinned host memory, the pool has config 2's 64
+    blocks, every row's adapter goes through the LRU cache, misses are loaded into their blocks.  Three legs over the
+    same request trace: everything resident (a pool as large as the universe), misses loaded on a second stream
+    (overlapping the linear calls of earlier batches), misses loaded on the compute stream."""
+    import ctypes
+    import numpy as np
+    import torch
+    from gpu_harness import to_dev
+
+    universe, capacity, alpha, rows, K, N, rank = 512, 64, 1.1, 32, 4096, 4096, 16
+    steps = args.steps if args.steps is not None else 2000
+    warmup = args.warmup if args.warmup is not None else 200
+    w = I.small_workload(7, I.BF16, K, N, rows, universe, (rank,), alpha=alpha)
+    proj = w.projections[0]
+    x, W = to_dev(w.x(proj)), to_dev(w.W(proj)[0])
+    host = []
+    for a in range(universe):
+        A, Bm, sc = w.adapter(proj, a)
+        host.append((torch.from_numpy(A.view(np.int16)).pin_memory(), torch.from_numpy(Bm.view(np.int16)).pin_memory(), sc))
+    trace = I.request_trace(8, universe, alpha, (warmup + steps) * rows).reshape(warmup + steps, rows).astype(np.int32)
+    comp = torch.cuda.Stream()
+    copy = torch.cuda.Stream()
+
+    def leg(n_blocks, copy_stream):
+        pool = B.AdapterPool(K, N, rank, n_blocks, I.BF16, dev)
+        lin = B.LoraLinear(K, N, I.BF16, pool, rows, dev)
+        y = torch.zeros((rows, N), dtype=torch.int16, device=dev)
+        n_all = warmup + steps
+        idx_dev = torch.zeros((n_all, rows), dtype=torch.int32, device=dev)
+        idx_pin = torch.zeros((n_all, rows), dtype=torch.int32).pin_memory()
+        idx_np = idx_pin.numpy()
+        descs = [lin.desc(x, W, y, adapter_idx=idx_dev[i]) for i in range(n_all)]
+        cache = B.elora_cache_create(n_blocks)
+        miss_ids, miss_slots = np.zeros(rows, np.int32), np.zeros(rows, np.int32)
+        n_miss = ctypes.c_int()
+        miss_slots_p = miss_slots.ctypes.data_as(ctypes.POINTER(ctypes.c_int))
+        pa, pb = (ctypes.c_void_p * rows)(), (ctypes.c_void_p * rows)()
+        ranks_c, scales_c = (ctypes.c_int * rows)(*[rank] * rows), (ctypes.c_float * rows)(*[host[0][2]] * rows)
+        a_ptr, b_ptr = [h[0].data_ptr() for h in host], [h[1].data_ptr() for h in host]
+        cs, ps = copy_stream.cuda_stream, comp.cuda_stream
+        torch.cuda.synchronize()
+        loads = 0
+        t0 = None
+        with torch.cuda.stream(comp):
+            for i in range(n_all):
+                if i == warmup:
+                    torch.cuda.synchronize()
+                    B.elora_cache_reset_stats(cache)
+                    loads = 0
+                    t0 = time.perf_counter()
+                ids, slots = trace[i], idx_np[i]
+                rc = B.lib.elora_cache_acquire_batch(cache, ids.ctypes.data, rows, slots.ctypes.data, miss_ids.ctypes.data,
+                                                     miss_slots.ctypes.data, ctypes.byref(n_miss))
+                assert rc == 0, rc
+                nm = n_miss.value
+                if nm:
+                    for m in range(nm):
+                        pa[m], pb[m] = a_ptr[miss_ids[m]], b_ptr[miss_ids[m]]
+                    B.lib.elora_cache_load_begin(cache, miss_slots_p, nm, cs)
+                    rc = B.lib.elora_pool_load_adapters(pool.handle, nm, miss_slots.ctypes.data, ranks_c, scales_c, pa, pb, cs)
+                    assert rc == 0, rc
+                    B.lib.elora_cache_load_end(cache, miss_slots_p, nm, cs)
+                loads += nm
+                B.lib.elora_cache_batch_begin(cache, slots.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), rows, ps)
+                idx_dev[i].copy_(idx_pin[i], non_blocking=True)
+                rc = B.lib.elora_batched_lora_linear(descs[i], ps)
+                assert rc == 0, rc
+                B.lib.elora_cache_batch_end(cache, slots.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), rows, ps)
+                B.lib.elora_cache_release_batch(cache, ids.ctypes.data, rows)
+            torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        hits, requests, evictions = B.elora_cache_stats(cache)
+        bad = pool.poll_error()
+        B.elora_cache_destroy(cache)
+        pool.close()
+        return {"tokens_per_s": rows * steps / dt, "us_per_step": dt / steps * 1e6, "hit_rate": hits / requests,
+                "loads_per_step": loads / steps, "evictions": evictions, "bad_rows": bad[0]}
+
+    resident = leg(universe, copy)
+    overlapped = leg(capacity, copy)
+    serial = leg(capacity, comp)
+    adapter_bytes = 2 * rank * (K + N)
+    out = {"metric": "cached_decode_tokens_per_s", "value": overlapped["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": overlapped["us_per_step"] / 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"config 2's call behind the adapter cache: {universe} rank-{rank} adapters in pinned host "
+                                  f"memory ({adapter_bytes} bytes each), {capacity} blocks, requests power-law({alpha}), "
+                                  f"{rows} rows per step; host loop in Python"},
+           "all_resident": resident, "loads_on_copy_stream": overlapped, "loads_on_compute_stream": serial}
+    print(json.dumps(out))
 
 
 def main():
@@ -86,6 +183,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.cache_trace:
+        cache_trace(args, B, I, dev)
+        return
     cfg = args.config
     decode = cfg in (2, 3)
     steps = args.steps if args.steps is not None else {2: 4000, 3: 300, 4: 20, 5: 40}[cfg]

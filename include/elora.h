@@ -114,6 +114,17 @@ int elora_pool_destroy(elora_pool_t *pool);
 int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale,
                             const void *A, const void *B, int src_on_device, elora_stream_t stream);
 
+/*
+ * The same for n adapters at once (host arrays of n entries; slots distinct), as the misses of a batch come: when
+ * every source is device memory or pinned host memory (hipHostMalloc) and 16-byte aligned, with sizes that are
+ * multiples of 16 bytes, the GPU reads the sources itself and one launch per 16 adapters fills the blocks and
+ * their table entries; otherwise the adapters are placed one by one as above.  Nothing enqueued on other streams
+ * may read or write these blocks until this call's work on `stream` is done (elora_cache_load_begin / _end do
+ * that ordering).  Errors: E_NULL, E_SHAPE (n < 0), E_SLOT (out of range, or one slot twice), E_RANK, E_HIP.
+ */
+int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const int *ranks, const float *scales,
+                             const void *const *A, const void *const *B, elora_stream_t stream);
+
 /* Mark `slot` empty (its block returns to the pool, Sec. 4.2).  Rows that still refer to it are
  * treated like rows with an invalid index.  Errors: E_NULL, E_SLOT, E_NOT_LOADED, E_HIP. */
 int elora_pool_evict(elora_pool_t *pool, int slot, elora_stream_t stream);
@@ -191,18 +202,21 @@ int elora_cache_reset_stats(elora_cache_t *cache);
 
 /*
  * Device-side order between the stream that loads adapters and the stream that computes, so that loads overlap
- * the linear calls of other batches and neither side waits on the host:
- *   load_begin   before elora_pool_load_adapter into `slot`: the copy stream waits for the last batch that used
- *                the block (it may still be reading the adapter that is being replaced)
- *   load_end     after it: marks the block's content as arriving on the copy stream
- *   batch_begin  before the linear calls of a batch whose rows use `slots[0..n)`: the compute stream waits for
- *                the loads of those blocks that it has not waited for yet
- *   batch_end    after them: remembers the batch as the last user of those blocks
- * Events are created on first use (these four calls need a device; the functions above do not).
- * Errors: E_NULL, E_SLOT, E_HIP.
+ * the linear calls of other batches and neither side waits on the host.  Arrays of block numbers (host memory;
+ * negative entries, rows without adapter, are skipped):
+ *   load_begin   before loading into `slots` (elora_pool_load_adapter[s]): the copy stream waits for the last
+ *                batch that used any of these blocks (it may still be reading an adapter that is being replaced)
+ *   load_end     after it: remembers these blocks' content as arriving with this load
+ *   batch_begin  before the linear calls of a batch whose rows use `slots`: the compute stream waits for the
+ *                latest load into any of these blocks, unless it has already waited that far
+ *   batch_end    after them: remembers the batch as the last user of these blocks
+ * One cache = one copy stream and one compute stream (the same stream may play both parts): all loads are taken
+ * to run in the order of these calls on the one, all batches on the other, so one event wait per call covers
+ * everything earlier.  Events are created on first use (these four calls need a device; the functions above do
+ * not).  Errors: E_NULL, E_SHAPE (n < 0), E_SLOT, E_HIP.
  */
-int elora_cache_load_begin(elora_cache_t *cache, int slot, elora_stream_t copy_stream);
-int elora_cache_load_end(elora_cache_t *cache, int slot, elora_stream_t copy_stream);
+int elora_cache_load_begin(elora_cache_t *cache, const int *slots, int n, elora_stream_t copy_stream);
+int elora_cache_load_end(elora_cache_t *cache, const int *slots, int n, elora_stream_t copy_stream);
 int elora_cache_batch_begin(elora_cache_t *cache, const int *slots, int n, elora_stream_t compute_stream);
 int elora_cache_batch_end(elora_cache_t *cache, const int *slots, int n, elora_stream_t compute_stream);
 

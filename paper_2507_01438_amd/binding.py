@@ -34,7 +34,7 @@ ELORA_PATH_GENERIC, ELORA_PATH_DECODE, ELORA_PATH_GEMM = 0, 1, 2
 
 EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
-    "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_evict", "elora_pool_slot_info",
+    "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
     "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
     "elora_debug_spin_limit", "elora_debug_xcd_local",
@@ -75,6 +75,9 @@ lib.elora_pool_destroy.argtypes = [ctypes.c_void_p]
 lib.elora_pool_load_adapter.restype = ctypes.c_int
 lib.elora_pool_load_adapter.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float,
                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+lib.elora_pool_load_adapters.restype = ctypes.c_int
+lib.elora_pool_load_adapters.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 lib.elora_pool_evict.restype = ctypes.c_int
 lib.elora_pool_evict.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
 lib.elora_pool_slot_info.restype = ctypes.c_int
@@ -125,10 +128,7 @@ lib.elora_cache_stats.restype = ctypes.c_int
 lib.elora_cache_stats.argtypes = [ctypes.c_void_p, _llp, _llp, _llp]
 lib.elora_cache_reset_stats.restype = ctypes.c_int
 lib.elora_cache_reset_stats.argtypes = [ctypes.c_void_p]
-for _name in ("elora_cache_load_begin", "elora_cache_load_end"):
-    getattr(lib, _name).restype = ctypes.c_int
-    getattr(lib, _name).argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
-for _name in ("elora_cache_batch_begin", "elora_cache_batch_end"):
+for _name in ("elora_cache_load_begin", "elora_cache_load_end", "elora_cache_batch_begin", "elora_cache_batch_end"):
     getattr(lib, _name).restype = ctypes.c_int
     getattr(lib, _name).argtypes = [ctypes.c_void_p, _ip, ctypes.c_int, ctypes.c_void_p]
 
@@ -190,6 +190,17 @@ def elora_pool_destroy(pool: int) -> None:
 def elora_pool_load_adapter(pool, slot, rank, scale, A, B, src_on_device, stream=None) -> None:
     _check(lib.elora_pool_load_adapter(pool, slot, rank, scale, _ptr(A), _ptr(B), int(src_on_device),
                                        _stream(stream)), "elora_pool_load_adapter")
+
+
+def elora_pool_load_adapters(pool, slots, ranks, scales, A, B, stream=None) -> None:
+    """Sequences of equal length; A and B hold tensors (device or pinned host) or addresses."""
+    n = len(slots)
+    sl = (ctypes.c_int * n)(*[int(v) for v in slots])
+    rk = (ctypes.c_int * n)(*[int(v) for v in ranks])
+    sc = (ctypes.c_float * n)(*[float(v) for v in scales])
+    pa = (ctypes.c_void_p * n)(*[_ptr(t) for t in A])
+    pb = (ctypes.c_void_p * n)(*[_ptr(t) for t in B])
+    _check(lib.elora_pool_load_adapters(pool, n, sl, rk, sc, pa, pb, _stream(stream)), "elora_pool_load_adapters")
 
 
 def elora_pool_evict(pool, slot, stream=None) -> None:
@@ -338,17 +349,19 @@ def elora_cache_reset_stats(cache: int) -> None:
     _check(lib.elora_cache_reset_stats(cache), "elora_cache_reset_stats")
 
 
-def elora_cache_load_begin(cache: int, slot: int, copy_stream) -> None:
-    _check(lib.elora_cache_load_begin(cache, int(slot), _stream(copy_stream)), "elora_cache_load_begin")
-
-
-def elora_cache_load_end(cache: int, slot: int, copy_stream) -> None:
-    _check(lib.elora_cache_load_end(cache, int(slot), _stream(copy_stream)), "elora_cache_load_end")
-
-
 def _int_array(values):
     values = [int(v) for v in values]
     return (ctypes.c_int * len(values))(*values), len(values)
+
+
+def elora_cache_load_begin(cache: int, slots, copy_stream) -> None:
+    arr, n = _int_array(slots)
+    _check(lib.elora_cache_load_begin(cache, arr, n, _stream(copy_stream)), "elora_cache_load_begin")
+
+
+def elora_cache_load_end(cache: int, slots, copy_stream) -> None:
+    arr, n = _int_array(slots)
+    _check(lib.elora_cache_load_end(cache, arr, n, _stream(copy_stream)), "elora_cache_load_end")
 
 
 def elora_cache_batch_begin(cache: int, slots, compute_stream=None) -> None:

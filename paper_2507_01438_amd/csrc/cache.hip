@@ -12,7 +12,7 @@
 using namespace elora;
 
 namespace {
-constexpr int kBatchRing = 64;  // batches whose "done" event is kept; an older batch is stood in for by a later one
+constexpr int kRing = 64;  // loads (batches) whose "done" event is kept; an older one is stood in for by a later one
 }
 
 struct elora_cache {
@@ -23,11 +23,12 @@ struct elora_cache {
     int head = -1, tail = -1;               // least / most recently used block
     long long hits = 0, requests = 0, evictions = 0;
     // device-side order
-    std::vector<hipEvent_t> loaded;         // per block: its last load (nullptr: none yet)
-    std::vector<char> load_pending;         // the compute stream has not waited for that load yet
-    std::vector<int> last_batch;            // per block: ring index of the last batch that used it, -1 none
-    hipEvent_t batch_done[kBatchRing] = {};
-    long long n_batches = 0;
+    std::vector<long long> last_load;       // per block: number (from 1) of the load call that filled it last, 0 none
+    std::vector<long long> last_batch;      // per block: number (from 1) of the last batch that used it, 0 none
+    hipEvent_t load_done[kRing] = {}, batch_done[kRing] = {};
+    long long n_loads = 0, n_batches = 0;   // load calls and batches so far
+    long long compute_waited_load = 0;      // the compute stream has waited for every load up to this number
+    long long copy_waited_batch = 0;        // the copy stream has waited for every batch up to this number
 
     void unlink(int b)
     {
@@ -59,9 +60,8 @@ int elora_cache_create(int capacity, elora_cache_t **out)
     c->pins.assign(capacity, 0);
     c->free_stack.resize(capacity);
     for (int i = 0; i < capacity; ++i) c->free_stack[i] = capacity - 1 - i;  // block 0 comes off first
-    c->loaded.assign(capacity, nullptr);
-    c->load_pending.assign(capacity, 0);
-    c->last_batch.assign(capacity, -1);
+    c->last_load.assign(capacity, 0);
+    c->last_batch.assign(capacity, 0);
     *out = c;
     return ELORA_OK;
 }
@@ -69,7 +69,7 @@ int elora_cache_create(int capacity, elora_cache_t **out)
 int elora_cache_destroy(elora_cache_t *c)
 {
     if (!c) return ELORA_E_NULL;
-    for (hipEvent_t e : c->loaded)
+    for (hipEvent_t e : c->load_done)
         if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->batch_done)
         if (e) (void)hipEventDestroy(e);
@@ -204,58 +204,75 @@ int elora_cache_reset_stats(elora_cache_t *c)
 }
 
 // ---- device-side order ------------------------------------------------------------------------------------------
-// A batch's "done" event sits in a ring.  When the ring comes round, the event object of an old batch is recorded
-// again for a new one; a block that still names the old batch then waits for the new one instead, which (same
-// compute stream) ends later: never too early.  Every wait refers to records made earlier in host order, so the two
-// streams cannot wait for each other in a circle.
+// Loads all run on one stream and batches all on another, each in the order of the calls here, so "the compute
+// stream has waited for load number q" covers every earlier load as well, and likewise for batches: one wait per
+// call is enough, and none if an earlier call already waited that far.  Events sit in rings; when a ring comes
+// round, the event object of an old load (batch) is recorded again for a new one, and whoever still names the old
+// one waits for the new one instead, which ends later on the same stream: never too early.  Every wait refers to
+// records made earlier in host order, so the two streams cannot wait for each other in a circle.
 
-int elora_cache_load_begin(elora_cache_t *c, int slot, elora_stream_t copy_stream)
+static int check_slots(const elora_cache *c, const int *slots, int n)
 {
-    if (!c) return ELORA_E_NULL;
-    if (slot < 0 || slot >= c->capacity) return ELORA_E_SLOT;
-    if (c->last_batch[slot] >= 0) {
-        ELORA_HIP_TRY(hipStreamWaitEvent(static_cast<hipStream_t>(copy_stream), c->batch_done[c->last_batch[slot]], 0));
-        c->last_batch[slot] = -1;  // later loads into the block follow this one on the copy stream
+    if (!c || (n > 0 && !slots)) return ELORA_E_NULL;
+    if (n < 0) return ELORA_E_SHAPE;
+    for (int i = 0; i < n; ++i)
+        if (slots[i] >= c->capacity) return ELORA_E_SLOT;  // negative: a row without adapter, skipped
+    return ELORA_OK;
+}
+
+int elora_cache_load_begin(elora_cache_t *c, const int *slots, int n, elora_stream_t copy_stream)
+{
+    const int rc = check_slots(c, slots, n);
+    if (rc != ELORA_OK) return rc;
+    long long latest = 0;  // number (from 1) of the last batch that used any of these blocks
+    for (int i = 0; i < n; ++i)
+        if (slots[i] >= 0 && c->last_batch[slots[i]] > latest) latest = c->last_batch[slots[i]];
+    if (latest > c->copy_waited_batch) {
+        ELORA_HIP_TRY(hipStreamWaitEvent(static_cast<hipStream_t>(copy_stream), c->batch_done[(latest - 1) % kRing], 0));
+        c->copy_waited_batch = latest;
     }
     return ELORA_OK;
 }
 
-int elora_cache_load_end(elora_cache_t *c, int slot, elora_stream_t copy_stream)
+int elora_cache_load_end(elora_cache_t *c, const int *slots, int n, elora_stream_t copy_stream)
 {
-    if (!c) return ELORA_E_NULL;
-    if (slot < 0 || slot >= c->capacity) return ELORA_E_SLOT;
-    if (!c->loaded[slot]) ELORA_HIP_TRY(hipEventCreateWithFlags(&c->loaded[slot], hipEventDisableTiming));
-    ELORA_HIP_TRY(hipEventRecord(c->loaded[slot], static_cast<hipStream_t>(copy_stream)));
-    c->load_pending[slot] = 1;
+    const int rc = check_slots(c, slots, n);
+    if (rc != ELORA_OK) return rc;
+    if (n == 0) return ELORA_OK;
+    const int r = (int)(c->n_loads % kRing);
+    if (!c->load_done[r]) ELORA_HIP_TRY(hipEventCreateWithFlags(&c->load_done[r], hipEventDisableTiming));
+    ELORA_HIP_TRY(hipEventRecord(c->load_done[r], static_cast<hipStream_t>(copy_stream)));
+    ++c->n_loads;
+    for (int i = 0; i < n; ++i)
+        if (slots[i] >= 0) c->last_load[slots[i]] = c->n_loads;
     return ELORA_OK;
 }
 
 int elora_cache_batch_begin(elora_cache_t *c, const int *slots, int n, elora_stream_t compute_stream)
 {
-    if (!c || (n > 0 && !slots)) return ELORA_E_NULL;
+    const int rc = check_slots(c, slots, n);
+    if (rc != ELORA_OK) return rc;
+    long long latest = 0;
     for (int i = 0; i < n; ++i)
-        if (slots[i] < 0 || slots[i] >= c->capacity) return ELORA_E_SLOT;
-    for (int i = 0; i < n; ++i) {
-        const int b = slots[i];
-        if (c->load_pending[b]) {
-            ELORA_HIP_TRY(hipStreamWaitEvent(static_cast<hipStream_t>(compute_stream), c->loaded[b], 0));
-            c->load_pending[b] = 0;  // whatever this stream runs from now on comes after that load
-        }
+        if (slots[i] >= 0 && c->last_load[slots[i]] > latest) latest = c->last_load[slots[i]];
+    if (latest > c->compute_waited_load) {
+        ELORA_HIP_TRY(hipStreamWaitEvent(static_cast<hipStream_t>(compute_stream), c->load_done[(latest - 1) % kRing], 0));
+        c->compute_waited_load = latest;
     }
     return ELORA_OK;
 }
 
 int elora_cache_batch_end(elora_cache_t *c, const int *slots, int n, elora_stream_t compute_stream)
 {
-    if (!c || (n > 0 && !slots)) return ELORA_E_NULL;
-    for (int i = 0; i < n; ++i)
-        if (slots[i] < 0 || slots[i] >= c->capacity) return ELORA_E_SLOT;
+    const int rc = check_slots(c, slots, n);
+    if (rc != ELORA_OK) return rc;
     if (n == 0) return ELORA_OK;
-    const int r = (int)(c->n_batches % kBatchRing);
+    const int r = (int)(c->n_batches % kRing);
     if (!c->batch_done[r]) ELORA_HIP_TRY(hipEventCreateWithFlags(&c->batch_done[r], hipEventDisableTiming));
     ELORA_HIP_TRY(hipEventRecord(c->batch_done[r], static_cast<hipStream_t>(compute_stream)));
     ++c->n_batches;
-    for (int i = 0; i < n; ++i) c->last_batch[slots[i]] = r;
+    for (int i = 0; i < n; ++i)
+        if (slots[i] >= 0) c->last_batch[slots[i]] = c->n_batches;
     return ELORA_OK;
 }
 

@@ -43,6 +43,32 @@ __global__ void pool_set_meta_kernel(SlotMeta *meta, int slot, int rank, float s
     if (threadIdx.x == 0 && blockIdx.x == 0) meta[slot] = SlotMeta{rank, scale, loaded, 0};
 }
 
+// Several adapters in one launch: the GPU reads the sources itself (device memory, or pinned host memory across the
+// bus) and fills the blocks; entry blockIdx.y, 16 bytes per thread and step.  Nothing else may use these blocks
+// meanwhile (the caller orders that), so the table entries can be written by the same launch.
+constexpr int kLoadBatch = 16;
+struct LoadBatch {
+    int n;
+    int slot[kLoadBatch], rank[kLoadBatch];
+    float scale[kLoadBatch];
+    const uint4 *A[kLoadBatch], *B[kLoadBatch];
+    unsigned a_vecs[kLoadBatch], b_vecs[kLoadBatch];  // 16-byte pieces of A and of B
+};
+
+__global__ __launch_bounds__(256) void pool_load_batch_kernel(LoadBatch lb, char *slots, size_t slot_bytes, size_t b_offset,
+                                                              SlotMeta *meta)
+{
+    const int e = blockIdx.y;
+    uint4 *dst_a = reinterpret_cast<uint4 *>(slots + (size_t)lb.slot[e] * slot_bytes);
+    uint4 *dst_b = reinterpret_cast<uint4 *>(slots + (size_t)lb.slot[e] * slot_bytes + b_offset);
+    const unsigned na = lb.a_vecs[e], total = na + lb.b_vecs[e];
+    for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        if (i < na) dst_a[i] = lb.A[e][i];
+        else dst_b[i - na] = lb.B[e][i - na];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) meta[lb.slot[e]] = SlotMeta{lb.rank[e], lb.scale[e], 1, 0};
+}
+
 __global__ void pool_clear_err_kernel(int *err)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -155,6 +181,80 @@ int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale,
     hipLaunchKernelGGL(pool_set_meta_kernel, dim3(1), dim3(64), 0, stream, dmeta, slot, rank, scale, 1);
     ELORA_HIP_TRY(hipGetLastError());
     pool->host_meta[slot] = SlotMeta{rank, scale, 1, 0};
+    return ELORA_OK;
+}
+
+// Where the device can read `p` from: p itself for device memory, the device-side address for pinned host memory,
+// nullptr for anything else (ordinary host memory).
+static const void *device_readable(const void *p, bool *is_device)
+{
+    hipPointerAttribute_t attr;
+    *is_device = false;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (attr.type == hipMemoryTypeDevice) {
+        *is_device = true;
+        return p;
+    }
+    if (attr.type == hipMemoryTypeHost) return attr.devicePointer;
+    return nullptr;
+}
+
+int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const int *ranks, const float *scales,
+                             const void *const *A, const void *const *B, elora_stream_t stream_)
+{
+    if (pool == nullptr || (n > 0 && (!slots || !ranks || !scales || !A || !B))) return ELORA_E_NULL;
+    if (n < 0) return ELORA_E_SHAPE;
+    for (int i = 0; i < n; ++i) {
+        if (A[i] == nullptr || B[i] == nullptr) return ELORA_E_NULL;
+        if (slots[i] < 0 || slots[i] >= pool->capacity) return ELORA_E_SLOT;
+        if (ranks[i] < 1 || ranks[i] > pool->max_rank) return ELORA_E_RANK;
+        for (int j = 0; j < i; ++j)
+            if (slots[j] == slots[i]) return ELORA_E_SLOT;  // one block, two adapters
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int rc = pool_ensure_cleared(pool, stream);
+    if (rc != ELORA_OK) return rc;
+    const size_t e = elem_bytes(pool->dtype);
+    SlotMeta *dmeta = reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset);
+    for (int i0 = 0; i0 < n; i0 += kLoadBatch) {
+        LoadBatch lb;
+        lb.n = n - i0 < kLoadBatch ? n - i0 : kLoadBatch;
+        bool direct = true, on_device[kLoadBatch], b_on_device = false;
+        size_t most = 0;
+        for (int i = 0; i < lb.n; ++i) {
+            const size_t a_bytes = (size_t)ranks[i0 + i] * pool->d_in * e, b_bytes = (size_t)ranks[i0 + i] * pool->d_out * e;
+            const void *a = device_readable(A[i0 + i], &on_device[i]), *b = device_readable(B[i0 + i], &b_on_device);
+            if (on_device[i] != b_on_device) direct = false;  // (then the copy engine sorts it out, or reports it)
+            direct = direct && a && b && a_bytes % 16 == 0 && b_bytes % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(a) % 16 == 0 && reinterpret_cast<uintptr_t>(b) % 16 == 0;
+            lb.slot[i] = slots[i0 + i];
+            lb.rank[i] = ranks[i0 + i];
+            lb.scale[i] = scales[i0 + i];
+            lb.A[i] = static_cast<const uint4 *>(a);
+            lb.B[i] = static_cast<const uint4 *>(b);
+            lb.a_vecs[i] = (unsigned)(a_bytes / 16);
+            lb.b_vecs[i] = (unsigned)(b_bytes / 16);
+            most = a_bytes + b_bytes > most ? a_bytes + b_bytes : most;
+        }
+        if (!direct) {
+            // ordinary host memory, or sizes that are no multiple of 16 bytes: one by one through the copy engine
+            for (int i = 0; i < lb.n; ++i) {
+                rc = elora_pool_load_adapter(pool, slots[i0 + i], ranks[i0 + i], scales[i0 + i], A[i0 + i], B[i0 + i],
+                                             on_device[i] ? 1 : 0, stream_);
+                if (rc != ELORA_OK) return rc;
+            }
+            continue;
+        }
+        unsigned per = (unsigned)((most / 16 + 256 * 4 - 1) / (256 * 4));  // four pieces per thread
+        per = per < 1 ? 1 : per > 64 ? 64 : per;
+        hipLaunchKernelGGL(pool_load_batch_kernel, dim3(per, lb.n), dim3(256), 0, stream, lb, pool->storage + pool->slots_offset,
+                           pool->slot_bytes, pool->b_offset, dmeta);
+        ELORA_HIP_TRY(hipGetLastError());
+        for (int i = 0; i < lb.n; ++i) pool->host_meta[slots[i0 + i]] = SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0};
+    }
     return ELORA_OK;
 }
 

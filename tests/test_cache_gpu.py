@@ -17,8 +17,9 @@ def _pinned(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).pin_memory()
 
 
-@pytest.mark.parametrize("capacity,rows,n_batches,alpha", [(4, 4, 80, 1.0), (3, 8, 60, None)])
-def test_batches_through_the_cache_with_loads_on_a_second_stream(capacity, rows, n_batches, alpha):
+@pytest.mark.parametrize("capacity,rows,n_batches,alpha,batched_loads", [(4, 4, 80, 1.0, False), (3, 8, 60, None, False),
+                                                                          (4, 4, 80, 1.0, True), (5, 8, 60, 0.5, True)])
+def test_batches_through_the_cache_with_loads_on_a_second_stream(capacity, rows, n_batches, alpha, batched_loads):
     from paper_2507_01438_amd import binding as B
     n_adapters, K, N = 20, 512, 256
     w = I.small_workload(91, I.BF16, K, N, rows, n_adapters, (16, 8))
@@ -52,16 +53,23 @@ def test_batches_through_the_cache_with_loads_on_a_second_stream(capacity, rows,
     for b in range(n_batches):
         ids = [int(a) for a in trace[b]]
         uniq = list(dict.fromkeys(ids))
-        slot_of = {}
+        slot_of, missing = {}, []
         for a in uniq:
             slot, hit, evicted = B.elora_cache_acquire(cache, a)
             assert (slot, hit, evicted) == model.acquire(a)
             slot_of[a] = slot
             if not hit:
-                B.elora_cache_load_begin(cache, slot, copy_s)
-                pool.load(slot, pinned[a][0], pinned[a][1], host[a][2], stream=copy_s)
-                B.elora_cache_load_end(cache, slot, copy_s)
-                n_loads += 1
+                missing.append(a)
+        B.elora_cache_load_begin(cache, [slot_of[a] for a in missing], copy_s)
+        if batched_loads and missing:      # one launch: the GPU reads the pinned host memory itself
+            B.elora_pool_load_adapters(pool.handle, [slot_of[a] for a in missing], [host[a][0].shape[0] for a in missing],
+                                       [host[a][2] for a in missing], [pinned[a][0] for a in missing],
+                                       [pinned[a][1] for a in missing], copy_s)
+        else:
+            for a in missing:
+                pool.load(slot_of[a], pinned[a][0], pinned[a][1], host[a][2], stream=copy_s)
+        B.elora_cache_load_end(cache, [slot_of[a] for a in missing], copy_s)
+        n_loads += len(missing)
         slots = list(slot_of.values())
         idx_pin[b] = torch.tensor([slot_of[a] for a in ids], dtype=torch.int32)
         B.elora_cache_batch_begin(cache, slots, comp_s)
@@ -85,3 +93,38 @@ def test_batches_through_the_cache_with_loads_on_a_second_stream(capacity, rows,
     assert worst <= 1e-2
     B.elora_cache_destroy(cache)
     pool.close()
+
+
+def test_batched_load_from_device_pinned_and_ordinary_host_memory():
+    """elora_pool_load_adapters: the same adapters placed from device memory, pinned host memory (one launch each) and
+    ordinary host memory (falls back to one copy per adapter) give the same pool content as loading them one by one."""
+    from paper_2507_01438_amd import binding as B
+    n_adapters, K, N, rows = 19, 256, 192, 19       # 19 adapters: more than one launch of 16
+    w = I.small_workload(93, I.BF16, K, N, rows, n_adapters, (16, 8, 4))
+    w.adapter_idx = np.arange(n_adapters, dtype=np.int32)
+    proj = w.projections[0]
+    x_h, (W_h, _) = w.x(proj), w.W(proj)
+    host = [w.adapter(proj, a) for a in range(n_adapters)]
+    ref = oracle.linear(I.BF16, x_h, W_h, [oracle.Adapter(A, Bm, s) for A, Bm, s in host], w.adapter_idx)
+    x, W, idx = to_dev(x_h), to_dev(W_h), to_dev(w.adapter_idx)
+    sources = {
+        "device": [(to_dev(A), to_dev(Bm)) for A, Bm, _ in host],
+        "pinned": [(_pinned(A), _pinned(Bm)) for A, Bm, _ in host],
+        "ordinary": [(torch.from_numpy(A.view(np.int16).copy()), torch.from_numpy(Bm.view(np.int16).copy())) for A, Bm, _ in host],
+    }
+    for name, src in sources.items():
+        pool = B.AdapterPool(K, N, w.max_rank, n_adapters, I.BF16, DEV)
+        lin = B.LoraLinear(K, N, I.BF16, pool, rows, DEV)
+        y = torch.zeros((rows, N), dtype=torch.int16, device=DEV)
+        order = list(reversed(range(n_adapters)))
+        B.elora_pool_load_adapters(pool.handle, order, [host[a][0].shape[0] for a in order], [host[a][2] for a in order],
+                                   [src[a][0] for a in order], [src[a][1] for a in order])
+        assert [B.elora_pool_slot_info(pool.handle, a)[0] for a in range(n_adapters)] == [h[0].shape[0] for h in host]
+        B.elora_batched_lora_linear(lin.desc(x, W, y, adapter_idx=idx))
+        torch.cuda.synchronize()
+        e = rel_err(y_to_f64(y, I.BF16), ref)
+        print(f"batched load from {name} memory: rel err {e:.2e}")
+        assert e <= 1e-2 and pool.poll_error() == (0, -1)
+        with pytest.raises(B.EloraError):     # one block named twice
+            B.elora_pool_load_adapters(pool.handle, [1, 1], [4, 4], [1.0, 1.0], [src[0][0]] * 2, [src[0][1]] * 2)
+        pool.close()
