@@ -196,6 +196,17 @@ int elora_cache_lookup(const elora_cache_t *cache, int adapter_id, int *slot);
 /* Evict on purpose; the block goes back on the stack.  Errors: E_NULL, E_NOT_LOADED, E_BUSY (pinned). */
 int elora_cache_drop(elora_cache_t *cache, int adapter_id);
 
+/*
+ * Adaptive adapter selection after the router (Algorithm 1): explicit_id >= 0 names the adapter and is returned as
+ * it is.  Otherwise scores[0..n) are the router's confidence scores (host fp32, one per adapter id), the k most
+ * confident adapters are gone through in descending order of confidence and the first one that is cached is chosen;
+ * if none is, the most confident one.  Equal scores: the lower id first; NaN ranks below every number.  *resident =
+ * 1 if the chosen adapter is cached.  Only looks: the request itself is the elora_cache_acquire that follows.
+ * Errors: E_NULL, E_SHAPE (n < 1 or k < 1; k > n is taken as n).
+ */
+int elora_cache_select(const elora_cache_t *cache, int explicit_id, const float *scores, int n, int k, int *chosen,
+                       int *resident);
+
 /* Hit rate H = hits / requests (Sec. 3.3).  Any out-pointer may be NULL.  Errors: E_NULL (cache). */
 int elora_cache_stats(const elora_cache_t *cache, long long *hits, long long *requests, long long *evictions);
 int elora_cache_reset_stats(elora_cache_t *cache);

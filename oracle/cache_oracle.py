@@ -98,3 +98,21 @@ def run_trace(capacity: int, trace) -> Tuple[List[bool], List[int], List[int]]:
         blocks.append(b)
         evicted.append(e)
     return hits, blocks, evicted
+
+
+def select_adapter(cached, explicit_id: int, scores, k: int) -> int:
+    """Adaptive adapter selection, the part after the router (Algorithm 1 of the paper): an explicitly named adapter
+    is taken as it is; otherwise the k adapters with the highest confidence scores are gone through in descending
+    order of confidence and the first one that is in the memory cache is taken; if none is, the one with the highest
+    score (which then has to be loaded).  `cached`: anything with `in`.  Equal scores: the lower adapter id counts as
+    the more confident (the paper does not say); a NaN score counts as lower than every number."""
+    if explicit_id >= 0:
+        return explicit_id
+    def key(j):
+        s = float(scores[j])
+        return (1, 0.0, j) if s != s else (0, -s, j)
+    top = sorted(range(len(scores)), key=key)[:max(1, min(int(k), len(scores)))]
+    for j in top:
+        if j in cached:
+            return j
+    return top[0]

@@ -39,7 +39,7 @@ EXPORTED = [
     "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
     "elora_debug_spin_limit", "elora_debug_xcd_local",
     "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
-    "elora_cache_acquire_batch", "elora_cache_release_batch",
+    "elora_cache_acquire_batch", "elora_cache_release_batch", "elora_cache_select",
     "elora_cache_drop", "elora_cache_stats", "elora_cache_reset_stats", "elora_cache_load_begin",
     "elora_cache_load_end", "elora_cache_batch_begin", "elora_cache_batch_end",
 ]
@@ -120,6 +120,8 @@ lib.elora_cache_acquire_batch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctyp
                                           ctypes.c_void_p, _ip]
 lib.elora_cache_release_batch.restype = ctypes.c_int
 lib.elora_cache_release_batch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+lib.elora_cache_select.restype = ctypes.c_int
+lib.elora_cache_select.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, _ip, _ip]
 lib.elora_cache_lookup.restype = ctypes.c_int
 lib.elora_cache_lookup.argtypes = [ctypes.c_void_p, ctypes.c_int, _ip]
 lib.elora_cache_drop.restype = ctypes.c_int
@@ -326,6 +328,17 @@ def elora_cache_release_batch(cache: int, adapter_ids: np.ndarray) -> None:
     assert adapter_ids.dtype == np.int32 and adapter_ids.flags.c_contiguous
     _check(lib.elora_cache_release_batch(cache, adapter_ids.ctypes.data, int(adapter_ids.shape[0])),
            "elora_cache_release_batch")
+
+
+def elora_cache_select(cache: int, explicit_id: int, scores: Optional[np.ndarray], k: int):
+    """(chosen adapter id, resident?)  scores: host float32 array or None when explicit_id >= 0."""
+    chosen, resident = ctypes.c_int(), ctypes.c_int()
+    if scores is not None:
+        assert scores.dtype == np.float32 and scores.flags.c_contiguous
+    _check(lib.elora_cache_select(cache, int(explicit_id), None if scores is None else scores.ctypes.data,
+                                  0 if scores is None else int(scores.shape[0]), int(k), ctypes.byref(chosen),
+                                  ctypes.byref(resident)), "elora_cache_select")
+    return chosen.value, bool(resident.value)
 
 
 def elora_cache_lookup(cache: int, adapter_id: int) -> int:

@@ -203,6 +203,49 @@ int elora_cache_reset_stats(elora_cache_t *c)
     return ELORA_OK;
 }
 
+// Algorithm 1 of the paper after the router: an explicit adapter id wins; otherwise the first of the k most confident
+// adapters (descending score; equal scores: lower id first; NaN below everything) that is cached, else the most
+// confident one.  Looks only: no request is counted and recency does not change.
+int elora_cache_select(const elora_cache_t *c, int explicit_id, const float *scores, int n, int k, int *chosen, int *resident)
+{
+    if (!c || !chosen || !resident) return ELORA_E_NULL;
+    if (explicit_id >= 0) {
+        *chosen = explicit_id;
+        *resident = c->block_of.count(explicit_id) ? 1 : 0;
+        return ELORA_OK;
+    }
+    if (!scores) return ELORA_E_NULL;
+    if (n < 1 || k < 1) return ELORA_E_SHAPE;
+    if (k > n) k = n;
+    auto better = [&](int a, int b) {  // a before b
+        const float sa = scores[a], sb = scores[b];
+        const bool na = sa != sa, nb = sb != sb;
+        if (na != nb) return nb;
+        if (!na && sa != sb) return sa > sb;
+        return a < b;
+    };
+    // the k best, in order: k passes of selection (k is small, Sec. 5: three)
+    std::vector<int> top;
+    top.reserve(k);
+    int last = -1;
+    for (int r = 0; r < k; ++r) {
+        int best = -1;
+        for (int j = 0; j < n; ++j)
+            if ((last < 0 || better(last, j)) && (best < 0 || better(j, best))) best = j;
+        top.push_back(best);
+        last = best;
+    }
+    for (int j : top)
+        if (c->block_of.count(j)) {
+            *chosen = j;
+            *resident = 1;
+            return ELORA_OK;
+        }
+    *chosen = top[0];
+    *resident = 0;
+    return ELORA_OK;
+}
+
 // ---- device-side order ------------------------------------------------------------------------------------------
 // Loads all run on one stream and batches all on another, each in the order of the calls here, so "the compute
 // stream has waited for load number q" covers every earlier load as well, and likewise for batches: one wait per

@@ -143,3 +143,43 @@ def test_batches_of_rows_match_the_oracle(B):
     for a in too_many[:capacity]:
         B.elora_cache_drop(c, int(a))                  # droppable: not pinned
     B.elora_cache_destroy(c)
+
+
+def test_selection_matches_the_oracle_and_raises_the_hit_rate(B):
+    from oracle.cache_oracle import select_adapter
+    rng = np.random.default_rng(41)
+    n, capacity = 60, 8
+    c = B.elora_cache_create(capacity)
+    ref = LruCacheOracle(capacity)
+    for step in range(3000):
+        scores = rng.random(n).astype(np.float32)
+        if step % 7 == 0:
+            scores[rng.integers(0, n, size=5)] = scores[0]            # ties
+        if step % 11 == 0:
+            scores[int(rng.integers(0, n))] = np.nan
+        k = int(rng.integers(1, 6))
+        explicit = int(rng.integers(0, n)) if step % 5 == 0 else -1
+        want = select_adapter(ref.block, explicit, scores, k)
+        got, resident = B.elora_cache_select(c, explicit, None if explicit >= 0 and step % 2 else scores, k)
+        assert got == want and resident == (want in ref.block)
+        assert B.elora_cache_acquire(c, got) == ref.acquire(want)     # the request itself
+        B.elora_cache_release(c, got); ref.release(want)
+    B.elora_cache_destroy(c)
+
+    # every prompt has three suitable adapters (drawn from a power-law popularity) that the router scores well above
+    # the rest: looking at all three serves more requests from the cache than insisting on the most confident one
+    def hit_rate(k):
+        rng = np.random.default_rng(42)
+        pop = I.power_law_probs(200, 1.0)
+        c = B.elora_cache_create(20)
+        for _ in range(4000):
+            scores = (0.1 * rng.random(200)).astype(np.float32)
+            scores[rng.choice(200, size=3, replace=False, p=pop)] = (0.5 + 0.5 * rng.random(3)).astype(np.float32)
+            a, _ = B.elora_cache_select(c, -1, scores, k)
+            B.elora_cache_acquire(c, a); B.elora_cache_release(c, a)
+        h, r, _ = B.elora_cache_stats(c)
+        B.elora_cache_destroy(c)
+        return h / r
+    h1, h3 = hit_rate(1), hit_rate(3)
+    print(f"hit rate with the most confident adapter only {h1:.3f}, with the first cached of the top three {h3:.3f}")
+    assert h3 > h1 + 0.05

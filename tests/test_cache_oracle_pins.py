@@ -110,3 +110,33 @@ def test_pinned_adapters_are_never_the_victim():
     c.release(3)
     assert c.acquire(4) == (0, False, 1)
     assert not c.release(2)               # not cached any more
+
+
+# ---- adaptive adapter selection after the router (Algorithm 1) -------------------------------------------------------
+
+def test_selection_worked_examples():
+    from oracle.cache_oracle import select_adapter
+    scores = [0.10, 0.90, 0.30, 0.80, 0.85]            # confidence order: 1, 4, 3, 2, 0
+    assert select_adapter({3, 0}, -1, scores, 3) == 3  # 1 and 4 are not cached, 3 is
+    assert select_adapter({3, 4}, -1, scores, 3) == 4  # the more confident of the cached ones
+    assert select_adapter({0, 2}, -1, scores, 3) == 1  # none of the top three cached: the most confident, to be loaded
+    assert select_adapter({2}, -1, scores, 4) == 2 and select_adapter({2}, -1, scores, 3) == 1
+    assert select_adapter({3}, 0, scores, 3) == 0      # explicitly named: taken as it is
+    assert select_adapter({2, 3}, -1, [0.5, 0.5, 0.5, 0.5], 2) == 0      # ties: lower id first, top two are 0 and 1
+    assert select_adapter({1}, -1, [float("nan"), 0.1, 0.2], 2) == 1     # NaN ranks last: top two are 2 and 1
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_selection_against_an_independent_formulation(seed):
+    from oracle.cache_oracle import select_adapter
+    rng = np.random.default_rng(seed)
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        k = int(rng.integers(1, n + 1))
+        scores = rng.permutation(n).astype(np.float32) / n       # distinct
+        cached = set(rng.choice(n, size=int(rng.integers(0, n + 1)), replace=False).tolist())
+        rank = {j: int((scores > scores[j]).sum()) for j in range(n)}   # adapters with a higher score
+        eligible = [j for j in cached if rank[j] < k]
+        want = max(eligible, key=lambda j: scores[j]) if eligible else int(np.argmax(scores))
+        assert select_adapter(cached, -1, scores, k) == want
+        assert select_adapter(cached, -1, scores, 1) == int(np.argmax(scores))   # k = 1: the availability is not looked at
