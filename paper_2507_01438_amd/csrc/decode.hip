@@ -108,7 +108,8 @@ struct DecodeShape {
     int chunks;     // K / 256; slice ks covers chunks [ks * chunks / split, (ks + 1) * chunks / split)
     int n_tiles;
     int total;      // n_tiles * split (tile, ks) pairs
-    int grid;       // total rounded up to a multiple of 8 * split: workgroups launched (the surplus only shares in the shrink)
+    int grid;       // workgroups launched, a multiple of 8 * split, at least `total`: the surplus only shares in the shrink
+    int real_per_xcd;  // workgroups per XCD that have a (tile, ks) pair: total / 8 rounded up to a multiple of split
     int n_pub;      // the first n_pub workgroups of the grid share the shrink units
     int jgroups;    // pairs of rank rows per row of x: ceil(max_rank / 2)
     unsigned jg_inv;  // floor(2^32 / jgroups) + 1: u / jgroups == (u * jg_inv) >> 32 for every u below 2^24 (jgroups <= 128)
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
     // where it is first used, one round trip to the scalar cache after the other; named here, they are all asked for
     // at once.
     asm volatile("" ::"s"(sh.T), "s"(sh.K), "s"(sh.N), "s"(sh.split), "s"(sh.lgS), "s"(sh.chunks), "s"(sh.n_tiles), "s"(sh.total),
-                 "s"(sh.grid), "s"(sh.n_pub), "s"(sh.jgroups), "s"(sh.jg_inv), "s"(sh.G), "s"(sh.lgG), "s"(sh.lgRp), "s"(sh.spin_limit),
+                 "s"(sh.grid), "s"(sh.real_per_xcd), "s"(sh.n_pub), "s"(sh.jgroups), "s"(sh.jg_inv), "s"(sh.G), "s"(sh.lgG), "s"(sh.lgRp), "s"(sh.spin_limit),
                  "s"(sh.zero), "s"(sh.local), "s"(x), "s"(W), "s"(y), "s"(mail), "s"(vmail), "s"(sync), "s"(has_pool));
     asm volatile("" ::"s"(pool.meta), "s"(pool.slots), "s"(pool.err), "s"(pool.slot_bytes), "s"(pool.b_offset), "s"(pool.capacity),
                  "s"(pool.max_rank), "s"(route.adapter_idx), "s"(route.seg_offsets), "s"(route.seg_adapter), "s"(route.n_segments),
@@ -286,9 +287,10 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
 
     // Workgroup b runs on XCD b % 8.  The (tile, ks) pairs are numbered tile-major and every XCD takes a contiguous
     // eighth of them (a multiple of `split`), so the workgroups that exchange pieces share an XCD: they start together.
+    // (real_per_xcd of an XCD's workgroups, a multiple of `split`, have a pair; the others are surplus on every XCD alike)
     const int per_xcd = sh.grid / kXcds;
-    const int pair = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
-    const bool idle = pair >= sh.total;  // surplus workgroup: only shares in the shrink
+    const int pair = (int)(blockIdx.x % kXcds) * sh.real_per_xcd + (int)(blockIdx.x / kXcds);
+    const bool idle = (int)(blockIdx.x / kXcds) >= sh.real_per_xcd || pair >= sh.total;  // surplus workgroup: only shares in the shrink
     const int tile = idle ? 0 : pair >> sh.lgS, ks = idle ? 0 : pair & (sh.split - 1);
 
     // Finishing is counted per XCD and then over the XCDs.  The last workgroup of an XCD empties, if some owner there
@@ -319,8 +321,8 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
         if ((s_flag & 1) && has_pool)
             for (int e = tid; e < T * R; e += kThreads) mb_store_f32(&vmail[e], __uint_as_float(kEmpty));
         if (s_flag & 2) {
-            // pairs xcd * per_xcd .. + per_xcd - 1 (those below `total`): split pieces each
-            const int p0 = xcd * per_xcd, p1 = min(p0 + per_xcd, sh.total);
+            // pairs xcd * real_per_xcd .. + real_per_xcd - 1 (those below `total`): split pieces each
+            const int p0 = xcd * sh.real_per_xcd, p1 = min(p0 + sh.real_per_xcd, sh.total);
             float *base = mail + (size_t)p0 * sh.split * piece_floats(sh);
             const size_t n = p1 > p0 ? (size_t)(p1 - p0) * sh.split * piece_floats(sh) : 0;
             for (size_t e = (size_t)tid * 4; e < n; e += (size_t)kThreads * 4) piece_clear(base + e);
@@ -1339,6 +1341,16 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool *w_lds)
     sh.total = sh.n_tiles * sh.split;
     const int unit = kXcds * sh.split;
     sh.grid = (sh.total + unit - 1) / unit * unit;
+    sh.real_per_xcd = sh.grid / kXcds;
+    // A call that leaves compute units without a workgroup gets surplus ones for them: they only share in the shrink,
+    // which for few output columns is most of the work (k_proj / v_proj at 64 rows: 2048 units of two rank rows on 128
+    // workgroups).
+#ifndef ELORA_NO_SURPLUS
+    if (sh.jgroups > 1) {
+        const int room = (resident < n_cus ? resident : n_cus) / unit * unit;
+        if (room > sh.grid) sh.grid = room;
+    }
+#endif
     // the workgroups that share the shrink must all be running before anybody can wait for them
     sh.n_pub = sh.grid < resident ? sh.grid : resident;
     sh.G = kGranules / sh.split;
