@@ -159,7 +159,7 @@ int elora_pool_poll_error(elora_pool_t *pool, int clear, int *n_bad_rows, int *f
  * never the victim (its rows may still be waiting to run).
  */
 
-/* Errors: E_NULL, E_SHAPE (capacity < 1). */
+/* Errors: E_NULL, E_SHAPE (capacity < 1), E_STORAGE (out of host memory). */
 int elora_cache_create(int capacity, elora_cache_t **out);
 int elora_cache_destroy(elora_cache_t *cache);
 
@@ -168,7 +168,7 @@ int elora_cache_destroy(elora_cache_t *cache);
  * 0 if the block was just assigned and the caller has to load the adapter into it; *evicted_id = the adapter that
  * lost the block, -1 if none did.  The adapter becomes the most recently used one and its pin count rises by one.
  * Errors: E_NULL, E_SHAPE (adapter_id < 0), E_BUSY (not cached, no free block, all cached adapters pinned:
- * nothing changes and the request is not counted).
+ * nothing changes and the request is not counted), E_STORAGE (out of host memory).
  */
 int elora_cache_acquire(elora_cache_t *cache, int adapter_id, int *slot, int *hit, int *evicted_id);
 

@@ -53,15 +53,21 @@ int elora_cache_create(int capacity, elora_cache_t **out)
     if (capacity < 1) return ELORA_E_SHAPE;
     elora_cache *c = new (std::nothrow) elora_cache;
     if (!c) return ELORA_E_STORAGE;
-    c->capacity = capacity;
-    c->id.assign(capacity, -1);
-    c->prev.assign(capacity, -1);
-    c->next.assign(capacity, -1);
-    c->pins.assign(capacity, 0);
-    c->free_stack.resize(capacity);
-    for (int i = 0; i < capacity; ++i) c->free_stack[i] = capacity - 1 - i;  // block 0 comes off first
-    c->last_load.assign(capacity, 0);
-    c->last_batch.assign(capacity, 0);
+    try {  // (host memory: nothing is thrown across the C boundary)
+        c->capacity = capacity;
+        c->id.assign(capacity, -1);
+        c->prev.assign(capacity, -1);
+        c->next.assign(capacity, -1);
+        c->pins.assign(capacity, 0);
+        c->free_stack.resize(capacity);
+        for (int i = 0; i < capacity; ++i) c->free_stack[i] = capacity - 1 - i;  // block 0 comes off first
+        c->last_load.assign(capacity, 0);
+        c->last_batch.assign(capacity, 0);
+        c->block_of.reserve((size_t)capacity * 2);
+    } catch (...) {
+        delete c;
+        return ELORA_E_STORAGE;
+    }
     *out = c;
     return ELORA_OK;
 }
@@ -107,9 +113,16 @@ int elora_cache_acquire(elora_cache_t *c, int adapter_id, int *slot, int *hit, i
         c->unlink(b);
         ++c->evictions;
     }
+    try {
+        c->block_of.emplace(adapter_id, b);
+    } catch (...) {  // out of host memory: the block stays free (a victim, if there was one, stays evicted)
+        c->id[b] = -1;
+        c->pins[b] = 0;
+        c->free_stack.push_back(b);
+        return ELORA_E_STORAGE;
+    }
     c->id[b] = adapter_id;
     c->pins[b] = 1;
-    c->block_of.emplace(adapter_id, b);
     c->push_most_recent(b);
     ++c->requests;
     *slot = b;
