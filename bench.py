@@ -61,6 +61,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=None, help="distinct (W, pool, x) copies the decode steps rotate through")
+    ap.add_argument("--no-groups", action="store_true",
+                    help="config 3: one launch per projection instead of one for q/k/v and one for gate/up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cache-trace", action="store_true",
@@ -223,10 +225,30 @@ def main():
     plans = [B.elora_linear_plan(d) for d in layers[0]]
     stream = torch.cuda.current_stream().cuda_stream
     n_proj = len(projs)
+    # Projections that are due at the same time go out as one launch (config 3: q/k/v and gate/up).
+    names = [p.name for p in projs]
+    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if (decode and not args.no_groups) else []
+    units = []  # per launch of a step: the projection indices it covers
+    for pi, n in enumerate(names):
+        g = next((g for g in group_names if n in g), None)
+        if g is None:
+            units.append([pi])
+        elif n == g[0]:
+            units.append([names.index(m) for m in g])
+    layer_calls = []  # layer_calls[l] = [(descriptor array, n)] per launch
+    for descs in layers:
+        layer_calls.append([(B.desc_array([descs[pi] for pi in u]), len(u)) for u in units])
+    for arr, n in layer_calls[0]:
+        if n > 1:
+            assert B.elora_linear_group_launches(arr) == 1, "these projections were expected to share a launch"
+    n_launch = len(units)
 
     def step(i):
-        for d in layers[i % L]:
-            B.lib.elora_batched_lora_linear(d, stream)
+        for arr, n in layer_calls[i % L]:
+            if n == 1:
+                B.lib.elora_batched_lora_linear(arr, stream)
+            else:
+                B.lib.elora_batched_lora_linear_group(arr, n, stream)
 
     for i in range(warmup):
         step(i)
@@ -241,15 +263,15 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
     tokens_per_s = w.T * steps / (t1 - t0)
-    region_us_per_launch = ev0.elapsed_time(ev1) * 1e3 / (steps * n_proj)
+    region_us_per_launch = ev0.elapsed_time(ev1) * 1e3 / (steps * n_launch)
 
     # one pair of HIP events around every launch of each call's dominant kernel (second pass over the same steps)
     n_prof = min(steps, 1000)
-    B.elora_profile_arm(n_prof * n_proj)
+    B.elora_profile_arm(n_prof * n_launch)
     for i in range(n_prof):
         step(i)
     torch.cuda.synchronize()
-    per_launch_us = np.array(B.elora_profile_read(n_prof * n_proj)).reshape(n_prof, n_proj) * 1e3
+    per_launch_us = np.array(B.elora_profile_read(n_prof * n_launch)).reshape(n_prof, n_launch) * 1e3
     B.elora_profile_arm(0)
 
     flops_step = sum(w.algorithmic_flops(p) for p in projs)
@@ -260,18 +282,18 @@ def main():
         # around a ~20 us launch adds about 5 us of its own; that figure is reported next to it).
         assert all(pl.n_launches == 1 for pl in plans)
         kern_us = region_us_per_launch
-        achieved = bytes_step / n_proj / (kern_us * 1e-6) / 1e9
+        achieved = bytes_step / n_launch / (kern_us * 1e-6) / 1e9
         roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "bytes_per_launch": int(bytes_step / n_proj), "avg_us": kern_us,
+                    "bytes_per_launch": int(bytes_step / n_launch), "avg_us": kern_us,
                     "median_us_with_per_launch_events": float(np.median(per_launch_us))}
     else:
         kern_us = float(per_launch_us.mean())
-        achieved = flops_step / n_proj / (kern_us * 1e-6) / 1e12
+        achieved = flops_step / n_launch / (kern_us * 1e-6) / 1e12
         roofline = {"bound": "mfma", "kernel": "lora_gemm_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                    "flops_per_launch": int(flops_step / n_proj), "avg_us": kern_us}
-    roofline["launches_timed"] = int(steps * n_proj if decode else per_launch_us.size)
+                    "flops_per_launch": int(flops_step / n_launch), "avg_us": kern_us}
+    roofline["launches_timed"] = int(steps * n_launch if decode else per_launch_us.size)
     traffic, traffic_src = TRAFFIC.get(cfg, (None, None))
     roofline["traffic"] = traffic
     roofline["traffic_source"] = traffic_src
@@ -343,12 +365,13 @@ def main():
             "distinct_adapters": int(len(distinct)), "rotating_layers": L,
             "path": [int(pl.path) for pl in plans], "split_k": [int(pl.split_k) for pl in plans],
             "grid": [int(pl.grid) for pl in plans], "launches_per_call": [int(pl.n_launches) for pl in plans],
+            "launches_per_step": [[names[pi] for pi in u] for u in units],
         },
         "tflops": flops_step / (ms_per_step * 1e-3) / 1e12,
         "step_gbs": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_frac_of_mfma_peak": flops_step / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "dominant_kernel_us_per_projection": [float(v) for v in per_launch_us.mean(axis=0)],
+        "dominant_kernel_us_per_launch": [float(v) for v in per_launch_us.mean(axis=0)],
         "max_rel_err_vs_oracle": check,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -304,6 +304,21 @@ int elora_linear_plan(const elora_linear_desc_t *desc, elora_plan_t *plan);
 int elora_batched_lora_linear(const elora_linear_desc_t *desc, elora_stream_t stream);
 
 /*
+ * Several calls that are due at the same time (the projections that read the same activations: q / k / v, gate /
+ * up; Sec. 4.3 computes base and adapters of a batch in one graph), as an array of n descriptors.  Results are those
+ * of n calls of elora_batched_lora_linear up to the order of fp32 additions.  Two or three calls that all take the
+ * decode path with the same n_tokens run as ONE launch when their workgroups fit on the device together (each call
+ * then gets fewer K-slices than it would take alone); otherwise, and for any other mix, the calls are enqueued one
+ * after the other.  Every call needs a workspace and an output of its own.
+ * Errors: those of elora_batched_lora_linear for any descriptor (nothing is enqueued then), E_SHAPE (n < 1),
+ * E_STORAGE (two descriptors share a workspace or y).
+ */
+int elora_batched_lora_linear_group(const elora_linear_desc_t *descs, int n, elora_stream_t stream);
+
+/* How many kernels elora_batched_lora_linear_group would enqueue for these descriptors.  Errors: as above. */
+int elora_linear_group_launches(const elora_linear_desc_t *descs, int n, int *n_launches);
+
+/*
  * Test hook: when `path` is a valid elora_path_t, later calls use that kernel
  * family if the descriptor is eligible for it (otherwise the generic one);
  * -1 restores automatic selection.  Process-wide, not thread-safe.

@@ -36,7 +36,8 @@ EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
     "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
-    "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
+    "elora_batched_lora_linear_group", "elora_linear_group_launches",
+    "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
     "elora_debug_spin_limit", "elora_debug_xcd_local",
     "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
     "elora_cache_acquire_batch", "elora_cache_release_batch", "elora_cache_select",
@@ -91,6 +92,10 @@ lib.elora_linear_plan.restype = ctypes.c_int
 lib.elora_linear_plan.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.POINTER(elora_plan_t)]
 lib.elora_batched_lora_linear.restype = ctypes.c_int
 lib.elora_batched_lora_linear.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_void_p]
+lib.elora_batched_lora_linear_group.restype = ctypes.c_int
+lib.elora_batched_lora_linear_group.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_int, ctypes.c_void_p]
+lib.elora_linear_group_launches.restype = ctypes.c_int
+lib.elora_linear_group_launches.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
 lib.elora_force_path.restype = ctypes.c_int
 lib.elora_force_path.argtypes = [ctypes.c_int]
 
@@ -249,6 +254,26 @@ def elora_linear_plan(desc: elora_linear_desc_t) -> elora_plan_t:
 
 def elora_batched_lora_linear(desc: elora_linear_desc_t, stream=None) -> None:
     _check(lib.elora_batched_lora_linear(ctypes.byref(desc), _stream(stream)), "elora_batched_lora_linear")
+
+
+def desc_array(descs):
+    """A contiguous C array of descriptors (for the group calls); keep it alive while the call is enqueued."""
+    arr = (elora_linear_desc_t * len(descs))()
+    for i, d in enumerate(descs):
+        ctypes.memmove(ctypes.byref(arr[i]), ctypes.byref(d), ctypes.sizeof(elora_linear_desc_t))
+    return arr
+
+
+def elora_batched_lora_linear_group(descs, stream=None) -> None:
+    arr = descs if isinstance(descs, ctypes.Array) else desc_array(descs)
+    _check(lib.elora_batched_lora_linear_group(arr, len(arr), _stream(stream)), "elora_batched_lora_linear_group")
+
+
+def elora_linear_group_launches(descs) -> int:
+    arr = descs if isinstance(descs, ctypes.Array) else desc_array(descs)
+    n = ctypes.c_int()
+    _check(lib.elora_linear_group_launches(arr, len(arr), ctypes.byref(n)), "elora_linear_group_launches")
+    return n.value
 
 
 def elora_force_path(path: int) -> None:

@@ -99,6 +99,8 @@ struct LinearArgs {
 int launch_generic(const LinearArgs &a, hipStream_t stream);
 int launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
 int launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
+int launch_decode_group(const LinearArgs *a, int n, hipStream_t stream);  // -1: the calls do not fit into one launch
+bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds);  // K-slices per call if they fit
 
 void decode_set_spin_limit(int limit);
 void decode_set_local_override(int mode);  // 0: never assume XCD-local hand-overs, -1: as probed

@@ -255,999 +255,52 @@ __global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, con
                                                                            float *__restrict__ vmail, int *__restrict__ sync,
                                                                            uint16_t *__restrict__ y)
 {
-    // x ring during the contraction; staging of pieces, v and d afterwards
-    extern __shared__ __attribute__((aligned(16))) uint16_t xs[];  // ring_bytes(TT, kWLds)
-    __shared__ int s_slot[kDecodeMaxTokens], s_rank[kDecodeMaxTokens];
-    __shared__ float s_scale[kDecodeMaxTokens];
-    __shared__ int s_flag, s_fail, s_vfail, s_odd;
-    __shared__ float s_red[2][kWaves][2];
-    __shared__ __attribute__((aligned(16))) SlotMeta s_meta[kMetaLds];  // the pool's slot table, if it is small enough
+#define ELORA_WG blockIdx.x
+#include "decode_body.inc"
+#undef ELORA_WG
+}
 
-    // Every argument is wanted within the first few hundred instructions.  Left alone the compiler fetches each one
-    // where it is first used, one round trip to the scalar cache after the other; named here, they are all asked for
-    // at once.
-    asm volatile("" ::"s"(sh.T), "s"(sh.K), "s"(sh.N), "s"(sh.split), "s"(sh.lgS), "s"(sh.chunks), "s"(sh.n_tiles), "s"(sh.total),
-                 "s"(sh.grid), "s"(sh.real_per_xcd), "s"(sh.n_pub), "s"(sh.jgroups), "s"(sh.jg_inv), "s"(sh.G), "s"(sh.lgG), "s"(sh.lgRp), "s"(sh.spin_limit),
-                 "s"(sh.zero), "s"(sh.local), "s"(x), "s"(W), "s"(y), "s"(mail), "s"(vmail), "s"(sync), "s"(has_pool));
-    asm volatile("" ::"s"(pool.meta), "s"(pool.slots), "s"(pool.err), "s"(pool.slot_bytes), "s"(pool.b_offset), "s"(pool.capacity),
-                 "s"(pool.max_rank), "s"(route.adapter_idx), "s"(route.seg_offsets), "s"(route.seg_adapter), "s"(route.n_segments),
-                 "s"(route.scales));
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int T = sh.T, K = sh.K, N = sh.N;
-    const int R = pool.max_rank;
-    float *const lds_f = reinterpret_cast<float *>(&xs[0]);
-    constexpr int kLdsFloats = ring_bytes(TT, kWLds) / 4;  // the area counted in floats
-    TRACE_DECL;
-    TRACE(0);
-    if (tid == 0) {
-        s_fail = 0;
-        s_vfail = 0;
-        s_odd = 0;
-    }
+// Several calls in one launch (projections that are due at the same time: q/k/v, gate/up): call i owns workgroups
+// first[i] .. first[i + 1) and every workgroup does exactly what it would do in a launch of its call alone.  The
+// calls share nothing (each has its own workspace), so the body is the same text; what is saved is the start and
+// the end of a launch, which for a small projection is most of its time.  All workgroups of the launch are resident.
+// (The body is included rather than called: as a function of its own the single-call kernel came out 1 us slower.)
+constexpr int kGroupMax = 3;
+struct DecodeCall {
+    DecodeShape sh;
+    const uint16_t *x, *W;
+    PoolView pool;
+    RouteView route;
+    int has_pool;
+    float *mail, *vmail;
+    int *sync;
+    uint16_t *y;
+};
+struct DecodeGroup {
+    int n;
+    int first[kGroupMax + 1];  // multiples of 8: workgroup b of the launch and workgroup b - first[i] of its call share b % 8
+    DecodeCall call[kGroupMax];
+};
 
-    // Workgroup b runs on XCD b % 8.  The (tile, ks) pairs are numbered tile-major and every XCD takes a contiguous
-    // eighth of them (a multiple of `split`), so the workgroups that exchange pieces share an XCD: they start together.
-    // (real_per_xcd of an XCD's workgroups, a multiple of `split`, have a pair; the others are surplus on every XCD alike)
-    const int per_xcd = sh.grid / kXcds;
-    const int pair = (int)(blockIdx.x % kXcds) * sh.real_per_xcd + (int)(blockIdx.x / kXcds);
-    const bool idle = (int)(blockIdx.x / kXcds) >= sh.real_per_xcd || pair >= sh.total;  // surplus workgroup: only shares in the shrink
-    const int tile = idle ? 0 : pair >> sh.lgS, ks = idle ? 0 : pair & (sh.split - 1);
-
-    // Finishing is counted per XCD and then over the XCDs.  The last workgroup of an XCD empties, if some owner there
-    // gave up, the piece mailboxes of the XCD's tiles (through the same L2 the pieces went through); the last
-    // workgroup of the call empties the v mailbox (everybody has read what it needed).  Counters and flags go back
-    // to zero.  Everything this workgroup posted has been acknowledged before it counts itself.
-    auto finish_call = [&]() {
-        const int xcd = blockIdx.x % kXcds;
-        if (tid == 0) {
-            int flag = 0;
-            // (counted in the XCD's own L2 when every workgroup that touches this counter is known to run on this XCD)
-            const int before = sh.local ? __hip_atomic_fetch_add(&sync[kCntXcd + 32 * xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)
-                                        : __hip_atomic_fetch_add(&sync[kCntXcd + 32 * xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((before & (kGaveUp - 1)) == per_xcd - 1) {
-                if (sh.local) __hip_atomic_store(&sync[kCntXcd + 32 * xcd], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                else __hip_atomic_store(&sync[kCntXcd + 32 * xcd], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (before >= kGaveUp) flag |= 2;
-                if (atomicAdd(&sync[kCntAll], 1) == kXcds - 1) {
-                    __hip_atomic_store(&sync[kCntAll], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    flag |= 1;
-                }
-            }
-            s_flag = flag;
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        if ((s_flag & 1) && has_pool)
-            for (int e = tid; e < T * R; e += kThreads) mb_store_f32(&vmail[e], __uint_as_float(kEmpty));
-        if (s_flag & 2) {
-            // pairs xcd * real_per_xcd .. + real_per_xcd - 1 (those below `total`): split pieces each
-            const int p0 = xcd * sh.real_per_xcd, p1 = min(p0 + sh.real_per_xcd, sh.total);
-            float *base = mail + (size_t)p0 * sh.split * piece_floats(sh);
-            const size_t n = p1 > p0 ? (size_t)(p1 - p0) * sh.split * piece_floats(sh) : 0;
-            for (size_t e = (size_t)tid * 4; e < n; e += (size_t)kThreads * 4) piece_clear(base + e);
-        }
-        TRACE(14);
-        TRACE_DUMP;
-    };
-
-    // ---- set-up of the base contraction (its first loads go out in the middle of phase 1) ----------------------
-    const int m = lane & 15, g = lane >> 4;
-    const int n0 = tile * kTileRows;
-    const int row = n0 + wave * kRowsPerWave + m;                    // W row this lane feeds
-    const bool wave_active = !idle && (n0 + wave * kRowsPerWave) < N;  // N % 16 == 0: all 16 rows in or out
-    const int c_begin = (ks * sh.chunks) >> sh.lgS;
-    const int nchunks = (((ks + 1) * sh.chunks) >> sh.lgS) - c_begin;  // >= 1: split <= chunks
-    const int k_begin = c_begin * kChunk;
-    const uint16_t *wrow = W + (size_t)(wave_active ? row : 0) * K + k_begin + g * 8;
-
-    // The K-slice goes by in sub-spans of 128 elements (4 MFMA K steps).  Per sub-span every wave moves its share of
-    // the rows of x global -> LDS, and its own 16 rows of W either the same way (kWLds: four instructions of 4 rows x
-    // 256 bytes, whole cache lines; fetched straight into the registers in the layout the matrix instruction wants,
-    // an instruction touches 16 rows x 64 bytes, half a cache line each, and the same stream takes about 1.7 us longer
-    // per 32 MiB) or as 4 register loads per thread (more than 32 rows of x and a shape that wants two workgroups per
-    // compute unit, for which the ring with W in it leaves no room).  kAhead sub-spans are on their way at any time.
-    constexpr int kSub = kSubSpan, kSubSteps = kSub / 32;
-    constexpr int kBufs = ring_slots(TT);                  // the sub-spans in flight and the one being multiplied
-    constexpr int kAhead = kBufs - 1;                      // sub-spans in flight while one is being multiplied
-    constexpr int kSlotElems = slot_rows(TT, kWLds) * kSub;
-    static_assert(ELORA_DEC_AHEAD == 4, "ring depth for up to 32 rows");
-    constexpr int kRowsPerInstr = 512 / kSub;              // a direct-to-LDS instruction moves 1 KiB: 4 rows of 128 elements
-    constexpr int kLanesPerRow = 64 / kRowsPerInstr;
-    constexpr int kXInstr = TT * 16 / kRowsPerInstr / kWaves;  // such instructions per wave and sub-span
-    constexpr int kOps = kXInstr + kSubSteps;                  // vector-memory operations per wave and sub-span
-    static_assert(kAhead == 2 || kAhead == 4, "ring depth");
-    static_assert(kAhead * kOps + 8 < 64, "vmcnt range");
-    u32x4 wset[kAhead][kSubSteps];
-    typedef const __attribute__((address_space(1))) void *gptr_t;
-    typedef __attribute__((address_space(3))) void *lptr_t;
-    uint16_t *const xring = &xs[0];  // [kBufs][rows of x, then rows of W][kSub / 8 places of 8 elements]; place = chunk ^ (row % 16)
-    const int nsub = nchunks * (kChunk / kSub);  // even, at least 2
-
-    // x first, then W: when the wave's W loads of a sub-span are back, so is its share of x (in-order counter).
-    // Rows past the batch repeat the last row, and waves whose 16 rows of W lie past d_out load row 0: what they
-    // produce is never posted, but every wave issues the same number of operations.
-    // (W through LDS) instruction i of a wave moves rows wave * 16 + 4 i .. + 3 of the tile: lane = (row, place)
-    const uint16_t *wdma[kSubSteps];
-#pragma unroll
-    for (int i = 0; i < kSubSteps; ++i) {
-        const int r = i * kRowsPerInstr + lane / kLanesPerRow;  // row among the wave's 16
-        const int chunk = (lane % kLanesPerRow) ^ r;
-        wdma[i] = W + (size_t)min(n0 + wave * kRowsPerWave + r, N - 1) * K + k_begin + chunk * 8;
-    }
-    auto issue = [&](int p, u32x4 *dst) {
-        uint16_t *buf = xring + (size_t)(p % kBufs) * kSlotElems;
-#pragma unroll
-        for (int i = 0; i < kXInstr; ++i) {
-            const int r = (wave * kXInstr + i) * kRowsPerInstr + lane / kLanesPerRow;
-            const int chunk = (lane % kLanesPerRow) ^ (r & 15);
-            const uint16_t *src = x + (size_t)min(r, T - 1) * K + k_begin + (size_t)p * kSub + chunk * 8;
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(buf + (wave * kXInstr + i) * 512), 16, 0, 0);
-        }
-        if constexpr (kWLds) {
-#pragma unroll
-            for (int i = 0; i < kSubSteps; ++i)
-                __builtin_amdgcn_global_load_lds((gptr_t)(wdma[i] + (size_t)p * kSub),
-                                                 (lptr_t)(buf + (TT * 16 + wave * kRowsPerWave + i * kRowsPerInstr) * kSub), 16, 0, 0);
-        } else {
-            const uint16_t *pw = wrow + (size_t)p * kSub;
-#pragma unroll
-            for (int j = 0; j < kSubSteps; ++j) dst[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pw + j * 32));
-        }
-    };
-
-    floatx4 acc[TT];
-#pragma unroll
-    for (int i = 0; i < TT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    // wait until at most `later` sub-spans are still on their way, meet the other waves (their shares of x for
-    // sub-span p are in LDS then, and everybody is done with sub-span p - 1), multiply
-    // wait until at most `later` younger sub-spans are still on their way, then meet the other waves: their shares of x
-    // for the oldest sub-span are in LDS then, and everybody is done with the one before it
-    auto meet = [&]() {
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-    };
-    auto arrive = [&](int later) {
-        if (later >= 3) __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * kOps));
-        else if (later == 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * kOps));
-        else if (later == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 * kOps));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        meet();
-    };
-    auto multiply = [&](int p, const u32x4 *wc) {
-        // The LDS reads are written as assembly: the compiler holds every LDS read back until ALL direct-to-LDS
-        // loads in flight have landed (it cannot tell the ring's buffers apart), which would undo the prefetch.  All
-        // reads of a sub-span and the wait for them sit in ONE statement: the compiler takes an output of an assembly
-        // statement for valid as soon as the statement is over, and may copy or spill it right there.
-        const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)(xring + (size_t)(p % kBufs) * kSlotElems) + (uint32_t)m * (kSub * 2);
-        static_assert(kSubSteps == 4 && kSub * 2 * 16 == 4096, "operand lists below");
-        const uint32_t a0 = base + (uint32_t)(((0 * 4 + g) ^ m) << 4), a1 = base + (uint32_t)(((1 * 4 + g) ^ m) << 4);
-        const uint32_t a2 = base + (uint32_t)(((2 * 4 + g) ^ m) << 4), a3 = base + (uint32_t)(((3 * 4 + g) ^ m) << 4);
-        // (W through LDS) the wave's row m of W sits TT * 16 + wave * 16 rows below row m of x, in the same places
-        const uint32_t wofs = (uint32_t)((TT * 16 + wave * kRowsPerWave) * kSub * 2);
-        u32x4 b[kSubSteps][TT];
-        u32x4 aw[kSubSteps];
-        if constexpr (TT == 1) {
-            asm volatile("ds_read_b128 %0, %12\n\tds_read_b128 %1, %13\n\tds_read_b128 %2, %14\n\tds_read_b128 %3, %15\n\t"
-                         "ds_read_b128 %4, %8\n\tds_read_b128 %5, %9\n\tds_read_b128 %6, %10\n\tds_read_b128 %7, %11\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[1][0]), "=&v"(b[2][0]), "=&v"(b[3][0])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
-                         : "memory");
-        } else if constexpr (TT == 2) {
-            asm volatile("ds_read_b128 %0, %16\n\tds_read_b128 %1, %17\n\tds_read_b128 %2, %18\n\tds_read_b128 %3, %19\n\t"
-                         "ds_read_b128 %4, %12\n\tds_read_b128 %5, %12 offset:4096\n\t"
-                         "ds_read_b128 %6, %13\n\tds_read_b128 %7, %13 offset:4096\n\t"
-                         "ds_read_b128 %8, %14\n\tds_read_b128 %9, %14 offset:4096\n\t"
-                         "ds_read_b128 %10, %15\n\tds_read_b128 %11, %15 offset:4096\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[1][0]), "=&v"(b[1][1]),
-                           "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[3][0]), "=&v"(b[3][1])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
-                         : "memory");
-        } else if constexpr (TT == 3 && kWLds) {
-            asm volatile("ds_read_b128 %0, %20\n\tds_read_b128 %1, %21\n\tds_read_b128 %2, %22\n\tds_read_b128 %3, %23\n\t"
-                         "ds_read_b128 %4, %16\n\tds_read_b128 %5, %16 offset:4096\n\tds_read_b128 %6, %16 offset:8192\n\t"
-                         "ds_read_b128 %7, %17\n\tds_read_b128 %8, %17 offset:4096\n\tds_read_b128 %9, %17 offset:8192\n\t"
-                         "ds_read_b128 %10, %18\n\tds_read_b128 %11, %18 offset:4096\n\tds_read_b128 %12, %18 offset:8192\n\t"
-                         "ds_read_b128 %13, %19\n\tds_read_b128 %14, %19 offset:4096\n\tds_read_b128 %15, %19 offset:8192\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[1][0]),
-                           "=&v"(b[1][1]), "=&v"(b[1][2]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[2][2]), "=&v"(b[3][0]), "=&v"(b[3][1]),
-                           "=&v"(b[3][2])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
-                         : "memory");
-        } else if constexpr (TT == 4 && kWLds) {
-            asm volatile("ds_read_b128 %0, %24\n\tds_read_b128 %1, %25\n\tds_read_b128 %2, %26\n\tds_read_b128 %3, %27\n\t"
-                         "ds_read_b128 %4, %20\n\tds_read_b128 %5, %20 offset:4096\n\tds_read_b128 %6, %20 offset:8192\n\tds_read_b128 %7, %20 offset:12288\n\t"
-                         "ds_read_b128 %8, %21\n\tds_read_b128 %9, %21 offset:4096\n\tds_read_b128 %10, %21 offset:8192\n\tds_read_b128 %11, %21 offset:12288\n\t"
-                         "ds_read_b128 %12, %22\n\tds_read_b128 %13, %22 offset:4096\n\tds_read_b128 %14, %22 offset:8192\n\tds_read_b128 %15, %22 offset:12288\n\t"
-                         "ds_read_b128 %16, %23\n\tds_read_b128 %17, %23 offset:4096\n\tds_read_b128 %18, %23 offset:8192\n\tds_read_b128 %19, %23 offset:12288\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(aw[0]), "=&v"(aw[1]), "=&v"(aw[2]), "=&v"(aw[3]), "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[0][3]),
-                           "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[1][2]), "=&v"(b[1][3]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[2][2]),
-                           "=&v"(b[2][3]), "=&v"(b[3][0]), "=&v"(b[3][1]), "=&v"(b[3][2]), "=&v"(b[3][3])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a0 + wofs), "v"(a1 + wofs), "v"(a2 + wofs), "v"(a3 + wofs)
-                         : "memory");
-        } else if constexpr (TT == 3) {
-            asm volatile("ds_read_b128 %0, %12\n\tds_read_b128 %1, %12 offset:4096\n\tds_read_b128 %2, %12 offset:8192\n\t"
-                         "ds_read_b128 %3, %13\n\tds_read_b128 %4, %13 offset:4096\n\tds_read_b128 %5, %13 offset:8192\n\t"
-                         "ds_read_b128 %6, %14\n\tds_read_b128 %7, %14 offset:4096\n\tds_read_b128 %8, %14 offset:8192\n\t"
-                         "ds_read_b128 %9, %15\n\tds_read_b128 %10, %15 offset:4096\n\tds_read_b128 %11, %15 offset:8192\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[1][2]), "=&v"(b[2][0]),
-                           "=&v"(b[2][1]), "=&v"(b[2][2]), "=&v"(b[3][0]), "=&v"(b[3][1]), "=&v"(b[3][2])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
-                         : "memory");
-        } else {
-            static_assert(TT == 4, "operand lists");
-            asm volatile("ds_read_b128 %0, %16\n\tds_read_b128 %1, %16 offset:4096\n\tds_read_b128 %2, %16 offset:8192\n\tds_read_b128 %3, %16 offset:12288\n\t"
-                         "ds_read_b128 %4, %17\n\tds_read_b128 %5, %17 offset:4096\n\tds_read_b128 %6, %17 offset:8192\n\tds_read_b128 %7, %17 offset:12288\n\t"
-                         "ds_read_b128 %8, %18\n\tds_read_b128 %9, %18 offset:4096\n\tds_read_b128 %10, %18 offset:8192\n\tds_read_b128 %11, %18 offset:12288\n\t"
-                         "ds_read_b128 %12, %19\n\tds_read_b128 %13, %19 offset:4096\n\tds_read_b128 %14, %19 offset:8192\n\tds_read_b128 %15, %19 offset:12288\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(b[0][0]), "=&v"(b[0][1]), "=&v"(b[0][2]), "=&v"(b[0][3]), "=&v"(b[1][0]), "=&v"(b[1][1]), "=&v"(b[1][2]),
-                           "=&v"(b[1][3]), "=&v"(b[2][0]), "=&v"(b[2][1]), "=&v"(b[2][2]), "=&v"(b[2][3]), "=&v"(b[3][0]), "=&v"(b[3][1]),
-                           "=&v"(b[3][2]), "=&v"(b[3][3])
-                         : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
-                         : "memory");
-        }
-#pragma unroll
-        for (int j = 0; j < kSubSteps; ++j) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, kWLds ? aw[j] : wc[j]);
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-                acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[j][tt]), acc[tt], 0, 0, 0);
-        }
-    };
-
-    // ---- phase 1: routes of all rows, and this workgroup's share of the shrink ---------------------------
-    // A unit = (row t, rank rows j0 and j0 + 1) is worked on by the whole workgroup: thread = 16-byte pieces tid,
-    // tid + 256, ... of the three rows involved (x_t and two rows of A_i), 1024 pieces (K = 4096 elements) a round.
-    constexpr int UL = 2;  // pieces per thread and round (3 * UL = 6 loads: see first_issue_then_wait)
-    const int pieces = K >> 3;
-    auto unit_load = [&](const uint16_t *A0, const uint16_t *A1, const uint16_t *xt, int pb, u32x4 *xv, u32x4 *a0, u32x4 *a1) {
-#pragma unroll
-        for (int i = 0; i < UL; ++i) {
-            const int pc = pb + i * kThreads + tid;
-            const size_t off = (size_t)(pc < pieces ? pc : 0) * 8;  // past the row: some piece of it, dropped below
-            xv[i] = *reinterpret_cast<const u32x4 *>(xt + off);
-            a0[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(A0 + off));
-            a1[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(A1 + off));
-        }
-    };
-    auto unit_dot = [&](int pb, const u32x4 *xv, const u32x4 *a0, const u32x4 *a1, float &s0, float &s1) {
-#pragma unroll
-        for (int i = 0; i < UL; ++i) {
-            const bool in = pb + i * kThreads + tid < pieces;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t xw = in ? xv[i][q] : 0u, aw0 = a0[i][q], aw1 = a1[i][q];
-                s0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw0), __builtin_bit_cast(elora_bf16x2, xw), s0, false);
-                s1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw1), __builtin_bit_cast(elora_bf16x2, xw), s1, false);
-            }
-        }
-    };
-    // the four waves' sums of one unit meet in LDS (two sets, used in turn: one barrier per unit); thread 0 posts v
-    auto unit_finish = [&](int n, int t, int j0, bool valid, bool two, float s0, float s1) {
-        s0 = wave_sum(s0);
-        s1 = wave_sum(s1);
-        if (lane == 0) {
-            lds_write_b32(&s_red[n & 1][wave][0], __float_as_uint(s0));
-            lds_write_b32(&s_red[n & 1][wave][1], __float_as_uint(s1));
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        if (tid == 0 && valid) {
-            const float(*rd)[2] = s_red[n & 1];
-            const float r0 = (lds_read_f32(&rd[0][0]) + lds_read_f32(&rd[1][0])) + (lds_read_f32(&rd[2][0]) + lds_read_f32(&rd[3][0]));
-            const float r1 = (lds_read_f32(&rd[0][1]) + lds_read_f32(&rd[1][1])) + (lds_read_f32(&rd[2][1]) + lds_read_f32(&rd[3][1]));
-            mb_store_f32(&vmail[(size_t)t * R + j0], r0);
-            if (two) mb_store_f32(&vmail[(size_t)t * R + j0 + 1], r1);
-        }
-    };
-    const int n_units = has_pool ? T * sh.jgroups : 0;
-    // Units number n_first on of this workgroup (the routes are in LDS): one per wave at a time, 24 loads of 16 bytes per
-    // lane in flight (a workgroup with many units has four of them under way instead of one after the other).
-    auto units_from = [&](int n_first) {
-        if ((int)blockIdx.x >= sh.n_pub) return;
-        for (int n = n_first + wave;; n += kWaves) {
-            const long long u = (long long)blockIdx.x + (long long)sh.n_pub * n;
-            if (u >= n_units) break;
-            const int t = sh.jgroups == 1 ? (int)u : (int)__umulhi((unsigned)u, sh.jg_inv), j0 = ((int)u - t * sh.jgroups) * 2;
-            const int slot = lds_read_i32(&s_slot[t]), rank = lds_read_i32(&s_rank[t]);
-            if (slot < 0 || j0 >= rank) continue;
-            const bool two = (j0 + 1) < rank;
-            const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
-            float r0, r1;
-            shrink_pair(A0, two ? A0 + K : A0, x + (size_t)t * K, K, lane, r0, r1);
-            if (lane == 0) {
-                mb_store_f32(&vmail[(size_t)t * R + j0], r0);
-                if (two) mb_store_f32(&vmail[(size_t)t * R + j0 + 1], r1);
-            }
-        }
-    };
-    if (idle) {
-        if (has_pool) {
-            if (tid < T) {
-                const RowRoute rr = resolve_row(tid, route, pool, blockIdx.x == 0);
-                s_slot[tid] = rr.slot;
-                s_rank[tid] = rr.rank;
-            }
-            __syncthreads();
-            units_from(0);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this workgroup's stores have been acknowledged
-        __syncthreads();
-        finish_call();
-        return;
-    }
-    // A route takes two dependent loads: index, then the slot's table entry.  A small slot table is fetched whole
-    // alongside the index, so that the second one is an LDS read.  (Left to itself that load comes back when most of the
-    // stream's first requests have, and at very different times in different workgroups: those that have it start
-    // streaming and are in the way of those that do not.)
-    if (has_pool) {
-        const int tr = min(tid, T - 1);  // threads past the batch repeat its last row and keep nothing
-        const bool unit0 = (int)blockIdx.x < sh.n_pub && (int)blockIdx.x < n_units;
-        const int t0 = !unit0 ? 0 : sh.jgroups == 1 ? (int)blockIdx.x : (int)__umulhi(blockIdx.x, sh.jg_inv), j00 = ((int)blockIdx.x - t0 * sh.jgroups) * 2;
-        const bool table = pool.capacity <= kMetaLds;
-        u32x4 tab[kMetaLds / kThreads];
-        if (table) {
-#pragma unroll
-            for (int i = 0; i < kMetaLds / kThreads; ++i)
-                if (tid + i * kThreads < pool.capacity) tab[i] = reinterpret_cast<const u32x4 *>(pool.meta)[tid + i * kThreads];
-        }
-        const RouteIndex ri = route_index(tr, route);
-        const int idx_c = (ri.idx >= 0 && ri.idx < pool.capacity) ? ri.idx : 0;
-        const float so = (route.scales != nullptr && ri.idx != -1) ? route.scales[ri.scale_at] : 0.0f;
-        SlotMeta mt{0, 0.0f, 0, 0};
-        if (!table) mt = pool.meta[idx_c];  // a big pool: the entry is fetched on its own, one more round trip
-        // Index, scale and table (or entry) are here before the stream starts.  They are used below, after the stream's
-        // first requests: without this the compiler would wait for them there, and for those requests with them; and
-        // no load may sit in a branch from here on, or it waits for everything at the next join.
-        asm volatile("" ::"v"(ri.idx), "v"(ri.scale_at), "v"(so), "v"(mt.rank), "v"(mt.scale), "v"(mt.loaded));
-        if (table) {
-#pragma unroll
-            for (int i = 0; i < kMetaLds / kThreads; ++i) asm volatile("" ::"v"(tab[i]));
-        }
-        TRACE(11);  // index known
-        // the first two sub-spans of the stream go out now; from here to the end of the contraction LDS is only read
-        // through lds_read_* and the assembly in multiply()
-        issue(0, wset[0]);
-        issue(1, wset[1]);
-        auto meet_lds = [&]() {  // LDS writes visible to the workgroup (no fence: that would wait for the stream, too)
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-        };
-        if (table) {
-#pragma unroll
-            for (int i = 0; i < kMetaLds / kThreads; ++i)
-                if (tid + i * kThreads < pool.capacity) lds_write_b128(&s_meta[tid + i * kThreads], tab[i]);
-            meet_lds();
-            const u32x4 m4 = lds_read_b128(&s_meta[idx_c]);
-            mt.rank = (int)m4[0];
-            mt.scale = __uint_as_float(m4[1]);
-            mt.loaded = (int)m4[2];
-            mt.pad = 0;
-        }
-        const RowRoute rr = route_finish(tr, ri, mt, so, route, pool, blockIdx.x == 0 && tid < T);
-        TRACE(12);  // table entry here
-        if (tid < T) {
-            lds_write_b32(&s_slot[tid], (uint32_t)rr.slot);
-            lds_write_b32(&s_rank[tid], (uint32_t)rr.rank);
-            lds_write_b32(&s_scale[tid], __float_as_uint(rr.scale));
-            if (rr.rank & 7) lds_write_b32(&s_odd, 1u);  // rows of this B_i are not 16-byte aligned
-        }
-        meet_lds();
-        TRACE(13);  // routes in LDS
-        // The workgroup's first shrink unit and the next sub-spans of the stream go out together.  (One straight-line
-        // copy of this per case: across a branch the compiler stops counting loads in flight and waits for all of them.)
-        // (made uniform for the compiler: otherwise the cases below become predicated code one after the other, and each
-        // waits for the loads the one before it might have issued)
-        const int slot0 = __builtin_amdgcn_readfirstlane(lds_read_i32(&s_slot[t0])), rank0 = __builtin_amdgcn_readfirstlane(lds_read_i32(&s_rank[t0]));
-        const bool valid0 = unit0 && slot0 >= 0 && j00 < rank0, two0 = (j00 + 1) < rank0;
-        auto first_requests = [&](auto four, auto with_unit) {
-            constexpr int n_first = decltype(four)::value ? 4 : 2;
-            u32x4 uxv[UL], ua0[UL], ua1[UL];
-            const uint16_t *uA0 = nullptr, *uA1 = nullptr;
-            if constexpr (decltype(with_unit)::value) {
-                uA0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot0)) + (size_t)j00 * K;
-                uA1 = two0 ? uA0 + K : uA0;
-                unit_load(uA0, uA1, x + (size_t)t0 * K, 0, uxv, ua0, ua1);
-            }
-#pragma unroll
-            for (int p = 2; p < n_first; ++p) issue(p, wset[p % kAhead]);
-            if constexpr (decltype(with_unit)::value) {
-                float s0 = 0.0f, s1 = 0.0f;
-                __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm((n_first - 2) * kOps));  // the unit's loads are back
-                __builtin_amdgcn_sched_barrier(0);
-                unit_dot(0, uxv, ua0, ua1, s0, s1);
-                for (int pb = UL * kThreads; pb < pieces; pb += UL * kThreads) {  // K above 4096: the other rounds
-                    u32x4 xv[UL], a0[UL], a1[UL];
-                    unit_load(uA0, uA1, x + (size_t)t0 * K, pb, xv, a0, a1);
-                    unit_dot(pb, xv, a0, a1, s0, s1);
-                }
-                unit_finish(0, t0, j00, true, two0, s0, s1);
-            }
-        };
-        const bool four = kAhead == 4 && nsub >= 4;
-        if (valid0) {
-            if (four) first_requests(std::true_type{}, std::true_type{});
-            else first_requests(std::false_type{}, std::true_type{});
-        } else {
-            if (four) first_requests(std::true_type{}, std::false_type{});
-            else first_requests(std::false_type{}, std::false_type{});
-        }
-        if (unit0) units_from(1);
-        TRACE(1);
-    } else {
-        issue(0, wset[0]);
-        issue(1, wset[1]);
-        if (kAhead == 4 && nsub >= 4) {
-            issue(2, wset[2 % kAhead]);
-            issue(3, wset[3 % kAhead]);
-        }
-    }
-
-    // own columns: granules og0 .. og0 + G - 1 of the tile, columns nc0 .. nc0 + 4 G - 1 of y
-    const int og0 = ks * sh.G, nc0 = n0 + og0 * 4, ncols = sh.G * 4;
-    const int n_cells = T * sh.G;  // (row, granule) cells of the owned columns
-    // What follows the contraction runs on four waves with nothing to overlap it, and a wave on its own issues an
-    // instruction only every 8 to 10 clocks: the number of instructions on that path is what the tail of the kernel
-    // costs.  The common case (every rank a multiple of 8, none above 64) therefore has a short path of its own.
-    const bool lean = !has_pool || (__builtin_amdgcn_readfirstlane(lds_read_i32(&s_odd)) == 0 && R <= 64 && sh.lgRp >= 3);
-    const int lgRp = sh.lgRp, Rp = 1 << lgRp;  // pitch of v in LDS: max_rank rounded up to a power of two, 8 .. 64
-    float *const vs = lds_f;                                     // [T][Rp]
-    constexpr int VV = kDecodeMaxTokens * 64 / 4 / kThreads;     // 16-byte vectors of v per thread, at most
-    const int nch = has_pool ? R >> 3 : 0;                       // 16-byte pieces of a row of B_i at the largest rank
-    const int n_bit = has_pool ? T << (sh.lgG + 2) : 0;          // (row, own column) items
-    u32x4 vv[VV];
-    bool vneed[VV];
-    u32x4 b[2][8];
-    const float *vrow[2];
-    bool valid[2];
-    // rows of B_i for two items (it0, it0 + 256); pieces of a row past its rank repeat its last piece (v is zero there)
-    auto b_issue = [&](int it0) {
-#pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
-            const int item = it0 + ii * kThreads;
-            const int t = item < n_bit ? item >> (sh.lgG + 2) : 0, c = item & (ncols - 1);
-            const int slot = s_slot[t], rank = s_rank[t];  // (plain LDS reads: nothing of the stream is in flight any more)
-            valid[ii] = item < n_bit && slot >= 0 && nc0 + c < N;
-            const uint16_t *bp = reinterpret_cast<const uint16_t *>(slot_B(pool, valid[ii] ? slot : 0)) +
-                                 (valid[ii] ? (size_t)(nc0 + c) * rank : 0);
-            const int last = valid[ii] ? rank - 8 : 0;
-#pragma unroll
-            for (int hh = 0; hh < 8; ++hh)
-                if (hh < nch) b[ii][hh] = *reinterpret_cast<const u32x4 *>(bp + min(8 * hh, last));
-            vrow[ii] = vs + (t << lgRp);
-        }
-    };
-    // The adapter term's inputs.  v: through the L2 (the workgroups of an XCD all want the same values, and the L2 holds
-    // nothing from before this launch); what is not there yet is asked for again, past the L2.  The rows of B_i for
-    // this thread's first items go out with it: they only need the routes.  (Asking for all this before the last
-    // sub-span of the stream is waited for, so that it travels meanwhile, was slower: the contraction then ends later.)
-    auto tail_requests = [&]() {
-#pragma unroll
-        for (int i = 0; i < VV; ++i) {
-            const int vi = tid + i * kThreads;
-            const int t = vi >> (lgRp - 2), j = (vi & ((Rp >> 2) - 1)) * 4;
-            vneed[i] = t < T && j < s_rank[min(t, T - 1)];
-            vv[i] = u32x4{0, 0, 0, 0};
-            if (vneed[i]) vv[i] = *reinterpret_cast<const u32x4 *>(vmail + (size_t)t * R + j);
-        }
-        b_issue(tid);
-    };
-
-    // ---- phase 2: base contraction -------------------------------------------------------------------------
-    // kAhead sub-spans are in flight, no more: requests a compute unit has queued beyond what the memory system is
-    // working on only delay whatever that unit asks for next, without adding bandwidth.  The steady-state loop is
-    // straight-line code (the compiler then knows exactly which loads a register set is still waiting for).
-    {
-        int p = 0;
-        if (nsub >= kAhead) {
-            for (; p + 2 * kAhead <= nsub; p += kAhead) {
-#pragma unroll
-                for (int d = 0; d < kAhead; ++d) {
-                    __builtin_amdgcn_s_waitcnt(vmcnt_imm((kAhead - 1) * kOps));
-                    meet();
-                    if (p == 0 && d == 0) TRACE(4);
-                    multiply(p + d, wset[d]);
-                    issue(p + d + kAhead, wset[d]);
-                }
-            }
-        }
-        // what is left: at most 2 kAhead - 1 sub-spans, the first kAhead of them (or all) already asked for
-#pragma unroll
-        for (int i = 0; i < 2 * kAhead - 1; ++i) {
-            const int q = p + i;
-            if (q < nsub) {
-                arrive(min(kAhead - 1, nsub - 1 - q));
-                multiply(q, wset[i % kAhead]);
-                if (q + kAhead < nsub) issue(q + kAhead, wset[i % kAhead]);
-            }
-        }
-    }
-    TRACE(5);  // contraction done
-
-    // ---- phase 3: post the pieces of this K-slice to their owners ---------------------------------------------
-    // C layout of the 16x16 MFMA: lane holds column (lane % 16) = row t of x, rows (lane / 16) * 4 + 0..3 = W rows,
-    // i.e. granule wave * 4 + g of the tile
-    if (wave_active) {
-        const int q16 = wave * 4 + g;
-        float *dst0 = piece_ptr(mail, sh, tile, q16 >> sh.lgG, ks) + (size_t)(q16 & (sh.G - 1)) * 4;
-        // (the stores below are assembly statements: the idle cycles a store needs between a matrix instruction writing a
-        // register and the store reading it are not inserted for them)
-        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" ::: "memory");
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            const int t = tt * 16 + m;
-            if (t < T) piece_store(dst0 + (size_t)t * sh.G * 4, acc[tt][0], acc[tt][1], acc[tt][2], acc[tt][3]);
-        }
-    }
-
-    bool acked = false;  // everything this thread posted to other workgroups has been acknowledged
-    if (lean) {
-        float *const dsum = lds_f + (has_pool ? (T << lgRp) : 0);    // [T][ncols]
-        const size_t pstride = piece_floats(sh);
-        u32x4 pv[kDecodeMaxSplit];
-        // the pieces of one (row, granule) cell: plain loads
-        auto p_issue = [&](int cell) {
-            const float *src0 = piece_ptr(mail, sh, tile, ks, 0) + (size_t)cell * 4;
-#pragma unroll
-            for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
-                if (sd < sh.split) pv[sd] = *reinterpret_cast<const u32x4 *>(src0 + sd * pstride);
-        };
-        if (has_pool) tail_requests();
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();  // the x ring is reused below (no fence: the requests above stay in flight)
-        asm volatile("" ::: "memory");
-        TRACE(8);
-        if (has_pool) {
-            bool gave_up = sh.spin_limit == 0;
-            for (int spin = 0; !gave_up; ++spin) {
-                bool all = true;
-#pragma unroll
-                for (int i = 0; i < VV; ++i)
-                    all = all && !(vneed[i] && (vv[i][0] == kEmpty || vv[i][1] == kEmpty || vv[i][2] == kEmpty || vv[i][3] == kEmpty));
-                if (all) break;
-                if (spin >= sh.spin_limit) {
-                    gave_up = true;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(2);
-#pragma unroll
-                for (int i = 0; i < VV; ++i) {
-                    const int vi = tid + i * kThreads;
-                    const float *src = vmail + (size_t)(vi >> (lgRp - 2)) * R + (vi & ((Rp >> 2) - 1)) * 4;
-                    if (vneed[i])
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            if (vv[i][u] == kEmpty) vv[i][u] = mb_load_u32(src + u);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < VV; ++i) {
-                const int vi = tid + i * kThreads;
-                if (vi < (T << (lgRp - 2))) *reinterpret_cast<u32x4 *>(vs + (size_t)vi * 4) = vv[i];  // zeros at and above the rank
-            }
-            if (gave_up) s_vfail = 1;
-            TRACE(9);
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            if (s_vfail) {
-                // the shrink results did not arrive in time: compute v here
-                for (int wu = wave; wu < T * sh.jgroups; wu += kWaves) {
-                    const int t = wu / sh.jgroups, j0 = (wu - t * sh.jgroups) * 2;
-                    const int slot = s_slot[t], rank = s_rank[t];
-                    float r0 = 0.0f, r1 = 0.0f;
-                    if (slot >= 0 && j0 < rank) {
-                        const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
-                        shrink_pair(A0, (j0 + 1 < rank) ? A0 + K : A0, x + (size_t)t * K, K, lane, r0, r1);
-                        if (j0 + 1 >= rank) r1 = 0.0f;
-                    }
-                    if (lane == 0) {
-                        vs[(t << lgRp) + j0] = r0;
-                        if (j0 + 1 < Rp) vs[(t << lgRp) + j0 + 1] = r1;
-                    }
-                }
-                __syncthreads();
-            }
-            TRACE(10);
-        }
-        // With a pool: the pieces of this thread's first cell are asked for now (the other K-slices have had time to
-        // arrive), and the loads are under way while the adapter term is formed.
-        // Without one the other K-slices are mostly not done yet, and everybody polling every piece of its own with
-        // read-modify-writes keeps the L2's atomic units busy for microseconds.  Then one lane per K-slice waits
-        // (read-modify-writes in the L2) for the piece that slice posts last to this owner; once all are there, plain
-        // loads find every piece in the L2.
-        const bool use_probe = !has_pool;
-        if (!use_probe) {
-            if (tid < n_cells) p_issue(tid);
-        } else {
-            if (wave == 0 && lane < sh.split && nc0 < N) {
-                const float *probe = piece_ptr(mail, sh, tile, ks, lane) + ((size_t)(T - 1) * sh.G + min(sh.G - 1, ((N - nc0) >> 2) - 1)) * 4;
-                for (int spin = 0; spin < sh.spin_limit; ++spin) {
-                    const u32x4 pr = piece_load(probe, (uint64_t)(uint32_t)sh.zero, sh.local != 0);
-                    if (pr[0] != kEmpty && pr[1] != kEmpty && pr[2] != kEmpty && pr[3] != kEmpty) break;
-                    __builtin_amdgcn_s_sleep(1);
-                }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            if (tid < n_cells) p_issue(tid);
-        }
-        if (has_pool) {
-            // d[t][c] = s_t * sum_j B_i[nc0 + c][j] v[t][j]: one (row, own column) item per thread, two items at a time
-            for (int it0 = tid; it0 < n_bit; it0 += 2 * kThreads) {
-                if (it0 != tid) b_issue(it0);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ii = 0; ii < 2; ++ii) {
-                    float d = 0.0f;
-#pragma unroll
-                    for (int hh = 0; hh < 8; ++hh) {
-                        if (hh < nch) {
-                            const floatx4 v0 = *reinterpret_cast<const floatx4 *>(vrow[ii] + 8 * hh);
-                            const floatx4 v1 = *reinterpret_cast<const floatx4 *>(vrow[ii] + 8 * hh + 4);
-                            d = fmaf(__uint_as_float(b[ii][hh][0] << 16), v0[0], d);
-                            d = fmaf(__uint_as_float(b[ii][hh][0] & 0xffff0000u), v0[1], d);
-                            d = fmaf(__uint_as_float(b[ii][hh][1] << 16), v0[2], d);
-                            d = fmaf(__uint_as_float(b[ii][hh][1] & 0xffff0000u), v0[3], d);
-                            d = fmaf(__uint_as_float(b[ii][hh][2] << 16), v1[0], d);
-                            d = fmaf(__uint_as_float(b[ii][hh][2] & 0xffff0000u), v1[1], d);
-                            d = fmaf(__uint_as_float(b[ii][hh][3] << 16), v1[2], d);
-                            d = fmaf(__uint_as_float(b[ii][hh][3] & 0xffff0000u), v1[3], d);
-                        }
-                    }
-                    const int item = it0 + ii * kThreads;
-                    if (item < n_bit) dsum[item] = valid[ii] ? d * s_scale[item >> (sh.lgG + 2)] : 0.0f;
-                }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-        }
-        TRACE(2);  // adapter term formed
-        // Everything this thread has posted so far (pieces, shrink results) is acknowledged once the piece loads that
-        // are needed next are back; the workgroup can then count itself done right after its last stores, without
-        // waiting for those.
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        acked = true;
-        // every (row, granule) cell of the own columns: the piece of each K-slice (again through L2 atomics while one
-        // is missing), added in fixed order, plus d, rounded once, stored at the row's own position
-        for (int cell = tid; cell < n_cells; cell += kThreads) {
-            const int t = cell >> sh.lgG, qo = cell & (sh.G - 1);
-            const int n = nc0 + qo * 4;
-            if (cell != tid) p_issue(cell);
-            if (n >= N) continue;
-            float *src0 = piece_ptr(mail, sh, tile, ks, 0) + (size_t)cell * 4;
-            bool gave_up = sh.spin_limit == 0;
-            for (int spin = 0; !gave_up; ++spin) {
-                bool all = true;
-#pragma unroll
-                for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
-                    if (sd < sh.split) all = all && pv[sd][0] != kEmpty && pv[sd][1] != kEmpty && pv[sd][2] != kEmpty && pv[sd][3] != kEmpty;
-                if (all) break;
-                if (spin >= sh.spin_limit) {
-                    gave_up = true;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-#pragma unroll
-                for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
-                    if (sd < sh.split && (pv[sd][0] == kEmpty || pv[sd][1] == kEmpty || pv[sd][2] == kEmpty || pv[sd][3] == kEmpty)) {
-                        pv[sd] = piece_load(src0 + sd * pstride, (uint64_t)(uint32_t)sh.zero, sh.local != 0);
-                    }
-            }
-            if (gave_up) {
-                s_fail = 1;
-                continue;
-            }
-            floatx4 o = __builtin_bit_cast(floatx4, pv[0]);
-#pragma unroll
-            for (int sd = 1; sd < kDecodeMaxSplit; ++sd) {
-                if (sd < sh.split) {
-                    const floatx4 pc = __builtin_bit_cast(floatx4, pv[sd]);
-                    o[0] += pc[0];
-                    o[1] += pc[1];
-                    o[2] += pc[2];
-                    o[3] += pc[3];
-                }
-            }
-            if (has_pool) {
-                const floatx4 dd = *reinterpret_cast<const floatx4 *>(dsum + (size_t)cell * 4);
-                o[0] += dd[0];
-                o[1] += dd[1];
-                o[2] += dd[2];
-                o[3] += dd[3];
-            }
-            const uint64_t packed = (uint64_t)f32_to_bf16(o[0]) | ((uint64_t)f32_to_bf16(o[1]) << 16) |
-                                    ((uint64_t)f32_to_bf16(o[2]) << 32) | ((uint64_t)f32_to_bf16(o[3]) << 48);
-            *reinterpret_cast<uint64_t *>(y + (size_t)t * N + n) = packed;
-#pragma unroll
-            for (int sd = 0; sd < kDecodeMaxSplit; ++sd)
-                if (sd < sh.split) piece_clear(src0 + sd * pstride);  // empty again for the next call
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        TRACE(6);
-        if (s_fail) {
-            // some piece did not arrive in time: this workgroup computes its columns from the inputs, and the pieces
-            // that are still on their way are removed when the call ends
-            if (tid == 0) {
-            if (sh.local) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            else __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-            recompute_columns(sh, x, W, pool, route, has_pool, y, nc0, ncols, wave, lane);
-            acked = false;
-        }
-    } else {
-    const int n_items = sh.split * n_cells;  // (sender, cell) = 16 T: at most four per thread
-    // LDS: [pieces: n_items x 4][d: n_cells x 4][v of a block of rows: qb x R]
-    float *const stage = lds_f, *const dsum = stage + (size_t)n_items * 4, *const vs = dsum + (size_t)n_cells * 4;
-    const int qb_max = (kLdsFloats - (n_items + n_cells) * 4) / (has_pool ? R : 1);  // rows of v that fit: at least 8
-
-    // Three hand-overs end here: the pieces of the other K-slices, v, and (plain loads) the rows of B_i.  All first
-    // requests go out together, before anything is waited for.
-    // (index spaces are laid out so that they come apart with shifts and divisions by constants: this part of the
-    // kernel runs on four waves per workgroup with nothing to overlap it)
-    constexpr int PB = TT, VB = 8, IB = 2;
-    u32x4 pval[PB];
-    bool pneed[PB];
-    const float *psrc[PB];
-    int pdst[PB];
-#pragma unroll
-    for (int u = 0; u < PB; ++u) {
-        // item = (sender, row of the 16 TT, granule): TT * 256 items, TT per thread
-        const int item = tid + u * kThreads;
-        const int qo = item & (sh.G - 1), rs = item >> sh.lgG;
-        const int sd = rs / (TT * 16), t = rs - sd * (TT * 16);
-        const int cell = t * sh.G + qo;
-        pneed[u] = t < T && nc0 + qo * 4 < N;
-        psrc[u] = piece_ptr(mail, sh, tile, ks, sd) + (size_t)(pneed[u] ? cell : 0) * 4;
-        pdst[u] = (sd * n_cells + cell) * 4;
-    }
-    auto p_load = [&]() {
-#pragma unroll
-        for (int u = 0; u < PB; ++u)
-            if (pneed[u]) pval[u] = piece_load(psrc[u], (uint64_t)(uint32_t)sh.zero, sh.local != 0);
-    };
-    // v: element e of the block of rows q0 .. q0 + qb - 1 is (row q0 + (e >> lgRp), rank column e & (Rp - 1))
-    const int Rp = 1 << sh.lgRp;
-    auto v_load = [&](int q0, int qb, int e0, uint32_t *val, bool *need) {
-#pragma unroll
-        for (int i = 0; i < VB; ++i) {
-            const int e = e0 + i * kThreads + tid;
-            const int q = e >> sh.lgRp, j = e & (Rp - 1);
-            need[i] = q < qb && j < s_rank[q0 + min(q, qb - 1)];
-            // first through the L2 (the workgroups of an XCD all want the same values; the L2 holds nothing from before
-            // this launch); a value that was not there yet is asked for again past the L2
-            val[i] = need[i] ? reinterpret_cast<const uint32_t *>(vmail)[(size_t)(q0 + q) * R + j] : 0u;
-        }
-    };
-    // B_i: item = (row q of the block, own column c); 16-byte pieces of the row, 8 at a time, from rank column j on
-    struct BItem {
-        const uint16_t *bp;  // row nc0 + c of B_i (or some valid address if the item has nothing to add)
-        int q, rank;         // rank 0: nothing to add
-        bool vec;            // rows of B_i are 16-byte aligned
-    };
-    auto b_item = [&](int q0, int qb, int item) {
-        BItem it;
-        const int q1 = item >> (sh.lgG + 2), c = item & (ncols - 1);
-        const bool in = q1 < qb;
-        const int q = in ? q1 : 0;
-        const int slot = s_slot[q0 + q], rank = s_rank[q0 + q];
-        const bool use = in && slot >= 0 && nc0 + c < N;
-        it.q = q;
-        it.rank = use ? rank : 0;
-        it.vec = (rank & 7) == 0;
-        it.bp = reinterpret_cast<const uint16_t *>(slot_B(pool, use ? slot : 0)) + (use ? (size_t)(nc0 + c) * rank : 0);
-        return it;
-    };
-    auto b_load = [&](const BItem &it, int j, u32x4 *b) {
-#pragma unroll
-        for (int hh = 0; hh < 8; ++hh) {
-            if (j + 8 * hh >= R) continue;  // nobody's rank reaches this far
-            const bool in = it.vec && j + 8 * hh < it.rank;
-            b[hh] = *reinterpret_cast<const u32x4 *>(in ? it.bp + j + 8 * hh : reinterpret_cast<const uint16_t *>(slot_B(pool, 0)));
-        }
-    };
-
-    uint32_t vval[VB];
-    bool vneed[VB];
-    BItem bit[IB];
-    u32x4 bpre[IB][8];
-    if (has_pool) {
-        const int qb = min(qb_max, T);
-        v_load(0, qb, 0, vval, vneed);
-#pragma unroll
-        for (int ii = 0; ii < IB; ++ii) {
-            bit[ii] = b_item(0, qb, tid + ii * kThreads);
-            b_load(bit[ii], 0, bpre[ii]);
-        }
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();  // the x ring is reused below (no fence: the requests above stay in flight)
-    asm volatile("" ::: "memory");
-    TRACE(8);
-
-    // ---- the adapter term of the own columns -------------------------------------------------------------------
-    if (has_pool) {
-        for (int q0 = 0; q0 < T; q0 += qb_max) {
-            const int qb = min(qb_max, T - q0);
-            if (q0 > 0) __syncthreads();
-            // v of these rows out of the mailbox (entries below the row's rank; the others count as zero)
-            bool gave_up = false;
-            for (int e0 = 0; e0 < (qb << sh.lgRp) && !gave_up; e0 += kThreads * VB) {
-                if (q0 > 0 || e0 > 0) v_load(q0, qb, e0, vval, vneed);
-                for (int spin = 0;; ++spin) {
-                    bool all = true;
-#pragma unroll
-                    for (int i = 0; i < VB; ++i) all = all && !(vneed[i] && vval[i] == kEmpty);
-                    if (all) break;
-                    if (spin >= sh.spin_limit) {
-                        gave_up = true;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(2);
-#pragma unroll
-                    for (int i = 0; i < VB; ++i) {
-                        const int e = e0 + i * kThreads + tid;
-                        if (vneed[i] && vval[i] == kEmpty) vval[i] = mb_load_u32(&vmail[(size_t)(q0 + (e >> sh.lgRp)) * R + (e & (Rp - 1))]);
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < VB; ++i) {
-                    const int e = e0 + i * kThreads + tid;
-                    const int q = e >> sh.lgRp, j = e & (Rp - 1);
-                    if (q < qb && j < R) vs[q * R + j] = vneed[i] ? __uint_as_float(vval[i]) : 0.0f;
-                }
-            }
-            if (gave_up || sh.spin_limit == 0) s_vfail = 1;
-            TRACE(9);
-            __syncthreads();
-            TRACE(10);
-            if (s_vfail) {
-                // the shrink results did not arrive in time: compute v of these rows here
-                for (int wu = wave; wu < qb * sh.jgroups; wu += kWaves) {
-                    const int q = wu / sh.jgroups, j0 = (wu - q * sh.jgroups) * 2;
-                    const int slot = s_slot[q0 + q], rank = s_rank[q0 + q];
-                    float r0 = 0.0f, r1 = 0.0f;
-                    if (slot >= 0 && j0 < rank) {
-                        const uint16_t *A0 = reinterpret_cast<const uint16_t *>(slot_A(pool, slot)) + (size_t)j0 * K;
-                        shrink_pair(A0, (j0 + 1 < rank) ? A0 + K : A0, x + (size_t)(q0 + q) * K, K, lane, r0, r1);
-                        if (j0 + 1 >= rank) r1 = 0.0f;
-                    }
-                    if (lane == 0) {
-                        vs[q * R + j0] = r0;
-                        if (j0 + 1 < R) vs[q * R + j0 + 1] = r1;
-                    }
-                }
-                __syncthreads();
-            }
-            // d[t][c] = s_t * sum_j B_i[nc0 + c][j] v[t][j]: one (row, column) item per thread, two items at a time
-            for (int it0 = tid; it0 < qb * ncols; it0 += kThreads * IB) {
-                const bool first = q0 == 0 && it0 == tid;
-                float d[IB];
-                int rmax = 0;
-#pragma unroll
-                for (int ii = 0; ii < IB; ++ii) {
-                    if (!first) bit[ii] = b_item(q0, qb, it0 + ii * kThreads);
-                    d[ii] = 0.0f;
-                    rmax = max(rmax, bit[ii].vec ? bit[ii].rank : 0);
-                }
-                for (int j = 0; j < rmax; j += 64) {
-                    if (!first || j > 0) {
-#pragma unroll
-                        for (int ii = 0; ii < IB; ++ii) b_load(bit[ii], j, bpre[ii]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int ii = 0; ii < IB; ++ii) {
-                        const float *vq = vs + bit[ii].q * R + j;
-#pragma unroll
-                        for (int hh = 0; hh < 8; ++hh) {
-                            if (!bit[ii].vec || j + 8 * hh >= bit[ii].rank) continue;
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) {
-                                d[ii] = fmaf(__uint_as_float(bpre[ii][hh][u] << 16), vq[8 * hh + 2 * u], d[ii]);
-                                d[ii] = fmaf(__uint_as_float(bpre[ii][hh][u] & 0xffff0000u), vq[8 * hh + 2 * u + 1], d[ii]);
-                            }
-                        }
-                    }
-                }
-#pragma unroll
-                for (int ii = 0; ii < IB; ++ii) {
-                    if (!bit[ii].vec)  // rows of B_i not 16-byte aligned: element by element
-                        for (int j = 0; j < bit[ii].rank; ++j) d[ii] = fmaf(bf16_to_f32(bit[ii].bp[j]), vs[bit[ii].q * R + j], d[ii]);
-                    const int item = it0 + ii * kThreads;
-                    if (item < qb * ncols) dsum[(size_t)q0 * ncols + item] = d[ii] * s_scale[q0 + bit[ii].q];
-                }
-            }
-        }
-    }
-    TRACE(2);  // adapter term formed
-
-    // ---- take the pieces of every (row, granule) cell --------------------------------------------------------------
-    {
-        bool gave_up = sh.spin_limit == 0;
-        for (int spin = 0; !gave_up; ++spin) {
-            p_load();
-            bool all = true;
-#pragma unroll
-            for (int u = 0; u < PB; ++u) {
-                if (pneed[u] && pval[u][0] != kEmpty && pval[u][1] != kEmpty && pval[u][2] != kEmpty && pval[u][3] != kEmpty) {
-                    pneed[u] = false;
-                    *reinterpret_cast<u32x4 *>(stage + pdst[u]) = pval[u];
-                    piece_clear(const_cast<float *>(psrc[u]));  // empty again for the next call
-                }
-                all = all && !pneed[u];
-            }
-            if (all) break;
-            if (spin >= sh.spin_limit) {
-                gave_up = true;
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-        }
-        if (gave_up) s_fail = 1;
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();  // staging complete (no fence: nobody has to wait for the mailbox stores here)
-    asm volatile("" ::: "memory");
-    TRACE(6);  // pieces in
-    if (s_fail == 0) {
-        // add in fixed order, round once, store each row at its own position
-        for (int cell = tid; cell < n_cells; cell += kThreads) {
-            const int t = cell >> sh.lgG, qo = cell & (sh.G - 1);
-            const int n = nc0 + qo * 4;
-            if (n >= N) continue;
-            floatx4 o = *reinterpret_cast<const floatx4 *>(stage + (size_t)cell * 4);
-            for (int sd = 1; sd < sh.split; ++sd) {
-                const floatx4 pc = *reinterpret_cast<const floatx4 *>(stage + ((size_t)sd * n_cells + cell) * 4);
-                o[0] += pc[0];
-                o[1] += pc[1];
-                o[2] += pc[2];
-                o[3] += pc[3];
-            }
-            if (has_pool) {
-                const floatx4 dd = *reinterpret_cast<const floatx4 *>(dsum + (size_t)cell * 4);
-                o[0] += dd[0];
-                o[1] += dd[1];
-                o[2] += dd[2];
-                o[3] += dd[3];
-            }
-            const uint64_t packed = (uint64_t)f32_to_bf16(o[0]) | ((uint64_t)f32_to_bf16(o[1]) << 16) |
-                                    ((uint64_t)f32_to_bf16(o[2]) << 32) | ((uint64_t)f32_to_bf16(o[3]) << 48);
-            *reinterpret_cast<uint64_t *>(y + (size_t)t * N + n) = packed;
-        }
-    } else {
-        // some piece did not arrive in time: this workgroup computes its columns from the inputs, and the pieces that
-        // are still on their way are removed when the call ends
-        if (tid == 0) {
-            if (sh.local) __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            else __hip_atomic_fetch_add(&sync[kCntXcd + 32 * (blockIdx.x % kXcds)], kGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        recompute_columns(sh, x, W, pool, route, has_pool, y, nc0, ncols, wave, lane);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __syncthreads();
-    }
-    }
-    TRACE(7);  // y written
-    if (!acked) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // what this workgroup posted has been acknowledged
-        __syncthreads();
-    }
-    finish_call();
+template <int TT, bool kWLds>
+__global__ __launch_bounds__(kThreads, 2) void decode_group_kernel(DecodeGroup grp_)
+{
+    int call_i = 0;
+    if (grp_.n > 1 && (int)blockIdx.x >= grp_.first[1]) call_i = 1;
+    if (grp_.n > 2 && (int)blockIdx.x >= grp_.first[2]) call_i = 2;
+    const DecodeCall &c_ = grp_.call[call_i];
+    const DecodeShape sh = c_.sh;
+    const uint16_t *__restrict__ x = c_.x, *__restrict__ W = c_.W;
+    const PoolView pool = c_.pool;
+    const RouteView route = c_.route;
+    const int has_pool = c_.has_pool;
+    float *__restrict__ mail = c_.mail, *__restrict__ vmail = c_.vmail;
+    int *__restrict__ sync = c_.sync;
+    uint16_t *__restrict__ y = c_.y;
+    const unsigned wg_ = blockIdx.x - (unsigned)grp_.first[call_i];
+#define ELORA_WG wg_
+#include "decode_body.inc"
+#undef ELORA_WG
 }
 
 // workgroups of decode_kernel<tt, wlds> the device holds at once (registers and LDS decide; asked once per instance),
@@ -1261,6 +314,39 @@ hipError_t ask_occupancy(int *per_cu)
     if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, decode_kernel<TT, WL>, kThreads, ring_bytes(TT, WL));
     return e;
 }
+template <int TT, bool WL>
+hipError_t ask_group_occupancy(int *per_cu)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_group_kernel<TT, WL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL));
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, decode_group_kernel<TT, WL>, kThreads, ring_bytes(TT, WL));
+    return e;
+}
+// the same for the kernel that carries several calls; 0 if it cannot be asked (then calls are launched one by one)
+int resident_group_workgroups(int tt, bool wlds)
+{
+    static int cached[5][2] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}, {0, 0}};
+    if (cached[tt][wlds] == 0) {
+        int per_cu = 0, cus = 0, dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) {
+            switch (tt) {
+            case 1: e = ask_group_occupancy<1, true>(&per_cu); break;
+            case 2: e = ask_group_occupancy<2, true>(&per_cu); break;
+            case 3: e = wlds ? ask_group_occupancy<3, true>(&per_cu) : ask_group_occupancy<3, false>(&per_cu); break;
+            default: e = wlds ? ask_group_occupancy<4, true>(&per_cu) : ask_group_occupancy<4, false>(&per_cu); break;
+            }
+        }
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return 0;
+        }
+        cached[tt][wlds] = per_cu * cus;
+    }
+    return cached[tt][wlds];
+}
+
 int resident_workgroups(int tt, bool wlds, int *n_cus)
 {
     static int cached[5][2] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}, {0, 0}};
@@ -1310,6 +396,8 @@ int pick_split(int K, int n_tiles, int resident, int n_cus)
 // per compute unit only: taken if that costs no workgroups, or if the call then has (nearly) one per unit; else W goes
 // into registers and two workgroups share a unit (measured at 64 rows, 4096 x 4096: 27.4 against 28.9 us; 14336 x 4096:
 // 53.9 against 60.8; 4096 x 14336, 224 tiles: 63.8 against 61.8).
+void finish_shape(DecodeShape &sh, int max_rank, int resident, int n_cus, bool surplus);
+
 DecodeShape make_shape(int T, int K, int N, int max_rank, bool *w_lds)
 {
     DecodeShape sh;
@@ -1336,6 +424,13 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool *w_lds)
         }
     }
     *w_lds = wlds;
+    finish_shape(sh, max_rank, resident, n_cus, true);
+    return sh;
+}
+
+// everything that follows from T, K, N, jgroups and split
+void finish_shape(DecodeShape &sh, int max_rank, int resident, int n_cus, bool surplus)
+{
     sh.lgS = 0;
     while ((1 << sh.lgS) < sh.split) ++sh.lgS;
     sh.total = sh.n_tiles * sh.split;
@@ -1346,7 +441,7 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool *w_lds)
     // which for few output columns is most of the work (k_proj / v_proj at 64 rows: 2048 units of two rank rows on 128
     // workgroups).
 #ifndef ELORA_NO_SURPLUS
-    if (sh.jgroups > 1) {
+    if (surplus && sh.jgroups > 1) {
         const int room = (resident < n_cus ? resident : n_cus) / unit * unit;
         if (room > sh.grid) sh.grid = room;
     }
@@ -1362,7 +457,6 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool *w_lds)
     sh.zero = 0;
     int dev = 0;
     sh.local = (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices && g_local[dev] == 1 && g_local_override != 0) ? 1 : 0;
-    return sh;
 }
 
 // ---- is workgroup b of a launch placed on XCD b % 8? -----------------------------------------------
@@ -1393,6 +487,111 @@ int elora::decode_probe_device(hipStream_t stream)
     bool ok = true;
     for (int b = kXcds; b < n; ++b) ok = ok && h[b] == h[b % kXcds];
     g_local[dev] = ok ? 1 : -1;
+    return ELORA_OK;
+}
+
+// Several decode calls with the same number of rows in one launch, if K-slice counts can be found with which all
+// their workgroups are resident together: starting from what each call would take alone, the call whose workgroups
+// have the least to stream gives up half of its K-slices until the sum fits.  W through LDS (one workgroup per
+// compute unit) is tried first, then (more than 32 rows) W into registers, which leaves room for two per unit.
+bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds)
+{
+    if (n < 2 || n > kGroupMax || T < 1 || T > kDecodeMaxTokens) return false;
+    const int tt = (T + 15) / 16;
+    for (int attempt = 0; attempt < (tt > 2 ? 2 : 1); ++attempt) {
+        const bool wlds = attempt == 0;
+        int n_cus = 0;
+        (void)resident_workgroups(tt, wlds, &n_cus);
+        const int resident = resident_group_workgroups(tt, wlds);
+        if (resident <= 0) return false;
+        int tiles[kGroupMax];
+        auto grid_of = [&](int i) { return (tiles[i] * split[i] + kXcds * split[i] - 1) / (kXcds * split[i]) * (kXcds * split[i]); };
+        for (int i = 0; i < n; ++i) {
+            tiles[i] = (N[i] + kTileRows - 1) / kTileRows;
+            split[i] = pick_split(K[i], tiles[i], resident, n_cus);
+        }
+        for (;;) {
+            int total = 0;
+            for (int i = 0; i < n; ++i) total += grid_of(i);
+            if (total <= resident) {
+                *w_lds = wlds;
+                return true;
+            }
+            int pick = -1;  // least K per workgroup; among equals the larger grid
+            for (int i = 0; i < n; ++i) {
+                if (split[i] == 1) continue;
+                if (pick < 0 || (long long)K[i] * split[pick] < (long long)K[pick] * split[i] ||
+                    ((long long)K[i] * split[pick] == (long long)K[pick] * split[i] && grid_of(i) > grid_of(pick)))
+                    pick = i;
+            }
+            if (pick < 0) break;
+            split[pick] /= 2;
+        }
+    }
+    return false;
+}
+
+// Returns ELORA_OK after the launch, -1 if the calls do not fit together (nothing enqueued).
+int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
+{
+    if (n < 2 || n > kGroupMax) return -1;
+    const int T = a[0].T, tt = (T + 15) / 16;
+    int Ks[kGroupMax], Ns[kGroupMax], split[kGroupMax];
+    for (int i = 0; i < n; ++i) {
+        if (a[i].T != T) return -1;
+        Ks[i] = a[i].K;
+        Ns[i] = a[i].N;
+    }
+    bool wlds = true;
+    if (!decode_group_splits(T, n, Ks, Ns, split, &wlds)) return -1;
+    int n_cus = 0;
+    (void)resident_workgroups(tt, wlds, &n_cus);
+    const int resident = resident_group_workgroups(tt, wlds);
+    DecodeGroup grp;
+    grp.n = n;
+    int first = 0;
+    for (int i = 0; i < n; ++i) {
+        DecodeCall &c = grp.call[i];
+        const int max_rank = a[i].has_pool ? a[i].pool.max_rank : 1;
+        c.sh.T = T;
+        c.sh.K = a[i].K;
+        c.sh.N = a[i].N;
+        c.sh.chunks = a[i].K / kChunk;
+        c.sh.n_tiles = (a[i].N + kTileRows - 1) / kTileRows;
+        c.sh.jgroups = (max_rank + 1) / 2;
+        c.sh.jg_inv = (unsigned)((1ull << 32) / (unsigned)c.sh.jgroups) + 1u;
+        c.sh.split = split[i];
+        finish_shape(c.sh, max_rank, resident, n_cus, false);
+        c.sh.n_pub = c.sh.grid;  // the whole launch is resident
+        c.x = static_cast<const uint16_t *>(a[i].x);
+        c.W = static_cast<const uint16_t *>(a[i].W);
+        c.pool = a[i].pool;
+        c.route = a[i].route;
+        c.has_pool = a[i].has_pool ? 1 : 0;
+        c.mail = reinterpret_cast<float *>(a[i].ws + a[i].wsl.mail);
+        c.vmail = reinterpret_cast<float *>(a[i].ws + a[i].wsl.vmail);
+        c.sync = reinterpret_cast<int *>(a[i].ws + a[i].wsl.sync);
+        c.y = static_cast<uint16_t *>(a[i].y);
+        grp.first[i] = first;
+        first += c.sh.grid;
+    }
+    for (int i = n; i <= kGroupMax; ++i) grp.first[i] = first;
+    dim3 grid(first), block(kThreads);
+    profile_mark_begin(stream);
+    switch (tt) {
+    case 1: hipLaunchKernelGGL((decode_group_kernel<1, true>), grid, block, ring_bytes(1, true), stream, grp); break;
+    case 2: hipLaunchKernelGGL((decode_group_kernel<2, true>), grid, block, ring_bytes(2, true), stream, grp); break;
+    case 3:
+        if (wlds) hipLaunchKernelGGL((decode_group_kernel<3, true>), grid, block, ring_bytes(3, true), stream, grp);
+        else hipLaunchKernelGGL((decode_group_kernel<3, false>), grid, block, ring_bytes(3, false), stream, grp);
+        break;
+    default:
+        if (wlds) hipLaunchKernelGGL((decode_group_kernel<4, true>), grid, block, ring_bytes(4, true), stream, grp);
+        else hipLaunchKernelGGL((decode_group_kernel<4, false>), grid, block, ring_bytes(4, false), stream, grp);
+        break;
+    }
+    ELORA_HIP_TRY(hipGetLastError());
+    profile_mark_end(stream);
     return ELORA_OK;
 }
 

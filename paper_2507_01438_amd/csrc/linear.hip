@@ -241,17 +241,10 @@ int elora_linear_plan(const elora_linear_desc_t *desc, elora_plan_t *plan)
     return ELORA_OK;
 }
 
-int elora_batched_lora_linear(const elora_linear_desc_t *d, elora_stream_t stream_)
+// everything a launch needs of a validated descriptor
+static int fill_args(const elora_linear_desc_t *d, const WsLayout &wsl, hipStream_t stream, LinearArgs &a)
 {
-    WsLayout wsl;
-    int rc = validate(d, &wsl);
-    if (rc != ELORA_OK) return rc;
-    if (d->n_tokens == 0) return ELORA_OK;
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    elora_plan_t plan;
-    make_plan(d, &plan);
-
-    LinearArgs a;
+    int rc = ELORA_OK;
     a.T = d->n_tokens;
     a.K = d->d_in;
     a.N = d->d_out;
@@ -275,11 +268,89 @@ int elora_batched_lora_linear(const elora_linear_desc_t *d, elora_stream_t strea
         a.pool = PoolView{nullptr, nullptr, nullptr, 0, 0, 0, 1};
         a.route = RouteView{nullptr, nullptr, nullptr, 0, nullptr};
     }
+    return ELORA_OK;
+}
+
+int elora_batched_lora_linear(const elora_linear_desc_t *d, elora_stream_t stream_)
+{
+    WsLayout wsl;
+    int rc = validate(d, &wsl);
+    if (rc != ELORA_OK) return rc;
+    if (d->n_tokens == 0) return ELORA_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    elora_plan_t plan;
+    make_plan(d, &plan);
+    LinearArgs a;
+    rc = fill_args(d, wsl, stream, a);
+    if (rc != ELORA_OK) return rc;
     switch (plan.path) {
     case ELORA_PATH_DECODE: return launch_decode(a, plan, stream);
     case ELORA_PATH_GEMM: return launch_gemm(a, plan, stream);
     default: return launch_generic(a, stream);
     }
+}
+
+int elora_batched_lora_linear_group(const elora_linear_desc_t *descs, int n, elora_stream_t stream_)
+{
+    if (descs == nullptr) return ELORA_E_NULL;
+    if (n < 1) return ELORA_E_SHAPE;
+    constexpr int kMaxGroup = 3;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    // everything is validated before anything is enqueued
+    for (int i = 0; i < n; ++i) {
+        const int rc = validate(&descs[i], nullptr);
+        if (rc != ELORA_OK) return rc;
+        for (int j = 0; j < i; ++j)
+            if (descs[i].workspace == descs[j].workspace || descs[i].y == descs[j].y) return ELORA_E_STORAGE;
+    }
+    bool together = n >= 2 && n <= kMaxGroup && descs[0].n_tokens > 0;
+    LinearArgs a[kMaxGroup];
+    for (int i = 0; i < n && together; ++i) {
+        elora_plan_t plan;
+        make_plan(&descs[i], &plan);
+        together = plan.path == ELORA_PATH_DECODE && descs[i].n_tokens == descs[0].n_tokens;
+        if (!together) break;
+        WsLayout wsl;
+        (void)validate(&descs[i], &wsl);
+        const int rc = fill_args(&descs[i], wsl, stream, a[i]);
+        if (rc != ELORA_OK) return rc;
+    }
+    if (together) {
+        const int rc = launch_decode_group(a, n, stream);
+        if (rc >= 0) return rc;
+    }
+    for (int i = 0; i < n; ++i) {
+        const int rc = elora_batched_lora_linear(&descs[i], stream_);
+        if (rc != ELORA_OK) return rc;
+    }
+    return ELORA_OK;
+}
+
+int elora_linear_group_launches(const elora_linear_desc_t *descs, int n, int *n_launches)
+{
+    if (descs == nullptr || n_launches == nullptr) return ELORA_E_NULL;
+    if (n < 1) return ELORA_E_SHAPE;
+    int sum = 0;
+    bool together = n >= 2 && n <= 3 && descs[0].n_tokens > 0;
+    for (int i = 0; i < n; ++i) {
+        const int rc = validate(&descs[i], nullptr);
+        if (rc != ELORA_OK) return rc;
+        elora_plan_t plan;
+        make_plan(&descs[i], &plan);
+        sum += descs[i].n_tokens > 0 ? plan.n_launches : 0;
+        together = together && plan.path == ELORA_PATH_DECODE && descs[i].n_tokens == descs[0].n_tokens;
+    }
+    if (together) {
+        int K[3], N[3], split[3];
+        bool wlds = true;
+        for (int i = 0; i < n; ++i) {
+            K[i] = descs[i].d_in;
+            N[i] = descs[i].d_out;
+        }
+        together = decode_group_splits(descs[0].n_tokens, n, K, N, split, &wlds);
+    }
+    *n_launches = together ? 1 : sum;
+    return ELORA_OK;
 }
 
 }  // extern "C"
