@@ -269,6 +269,12 @@ size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank
  * writes the idle state (one fill kernel on `stream`), and every linear call leaves the workspace idle
  * again.  Call it again only after a call that used the workspace was aborted (device reset).
  * Two calls that may run at the same time (different streams) need different workspaces.
+ * Calls on the decode path should not run at the same time at all: the workgroups of such a call wait for each
+ * other, which takes all of them to be on the device together, and two such launches that each hold part of the
+ * compute units keep each other's remaining workgroups out.  Every wait is bounded (a workgroup whose wait runs out
+ * computes what it needs from the inputs, see elora_debug_spin_limit), so the results stay right, but the calls
+ * then take seconds.  Issue them on one stream, or as one group (elora_batched_lora_linear_group); kernels
+ * that do not fill the device (adapter loads, copies) may overlap them freely.
  * The first call on a device also finds out how the device places workgroups on its XCDs (one tiny
  * launch, a small temporary allocation and a wait for `stream`): set-up work, not to be captured in a graph.
  * Errors: E_NULL, E_ALIGN, E_STORAGE, E_HIP.
