@@ -90,15 +90,19 @@ def cache_trace(args, B, I, dev):
     w = I.small_workload(7, I.BF16, K, N, rows, universe, (rank,), alpha=alpha)
     proj = w.projections[0]
     x, W = to_dev(w.x(proj)), to_dev(w.W(proj)[0])
-    host = []
+    host, host_q8 = [], []
     for a in range(universe):
         A, Bm, sc = w.adapter(proj, a)
         host.append((torch.from_numpy(A.view(np.int16)).pin_memory(), torch.from_numpy(Bm.view(np.int16)).pin_memory(), sc))
+        Ac, As = I.quantize_q8_blocks(I.bf16_bits_to_f32(A))
+        Bc, Bs = I.quantize_q8_blocks(I.bf16_bits_to_f32(Bm))
+        host_q8.append(tuple(torch.from_numpy(t.view(np.int8 if t.dtype == np.int8 else np.int16)).pin_memory()
+                             for t in (Ac, As, Bc, Bs)))
     trace = I.request_trace(8, universe, alpha, (warmup + steps) * rows).reshape(warmup + steps, rows).astype(np.int32)
     comp = torch.cuda.Stream()
     copy = torch.cuda.Stream()
 
-    def leg(n_blocks, copy_stream):
+    def leg(n_blocks, copy_stream, q8=False):
         pool = B.AdapterPool(K, N, rank, n_blocks, I.BF16, dev)
         lin = B.LoraLinear(K, N, I.BF16, pool, rows, dev)
         y = torch.zeros((rows, N), dtype=torch.int16, device=dev)
@@ -114,6 +118,8 @@ def cache_trace(args, B, I, dev):
         pa, pb = (ctypes.c_void_p * rows)(), (ctypes.c_void_p * rows)()
         ranks_c, scales_c = (ctypes.c_int * rows)(*[rank] * rows), (ctypes.c_float * rows)(*[host[0][2]] * rows)
         a_ptr, b_ptr = [h[0].data_ptr() for h in host], [h[1].data_ptr() for h in host]
+        q_ptr = [[h[k].data_ptr() for h in host_q8] for k in range(4)]
+        pq = [(ctypes.c_void_p * rows)() for _ in range(4)]
         cs, ps = copy_stream.cuda_stream, comp.cuda_stream
         torch.cuda.synchronize()
         loads = 0
@@ -131,10 +137,16 @@ def cache_trace(args, B, I, dev):
                 assert rc == 0, rc
                 nm = n_miss.value
                 if nm:
-                    for m in range(nm):
-                        pa[m], pb[m] = a_ptr[miss_ids[m]], b_ptr[miss_ids[m]]
                     B.lib.elora_cache_load_begin(cache, miss_slots_p, nm, cs)
-                    rc = B.lib.elora_pool_load_adapters(pool.handle, nm, miss_slots.ctypes.data, ranks_c, scales_c, pa, pb, cs)
+                    if q8:
+                        for m in range(nm):
+                            for k in range(4):
+                                pq[k][m] = q_ptr[k][miss_ids[m]]
+                        rc = B.lib.elora_pool_load_adapters_q8(pool.handle, nm, miss_slots.ctypes.data, ranks_c, scales_c, *pq, cs)
+                    else:
+                        for m in range(nm):
+                            pa[m], pb[m] = a_ptr[miss_ids[m]], b_ptr[miss_ids[m]]
+                        rc = B.lib.elora_pool_load_adapters(pool.handle, nm, miss_slots.ctypes.data, ranks_c, scales_c, pa, pb, cs)
                     assert rc == 0, rc
                     B.lib.elora_cache_load_end(cache, miss_slots_p, nm, cs)
                 loads += nm
@@ -156,6 +168,7 @@ def cache_trace(args, B, I, dev):
     resident = leg(universe, copy)
     overlapped = leg(capacity, copy)
     serial = leg(capacity, comp)
+    overlapped_q8 = leg(capacity, copy, q8=True)
     adapter_bytes = 2 * rank * (K + N)
     out = {"metric": "cached_decode_tokens_per_s", "value": overlapped["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
            "steps": steps, "warmup": warmup, "ms_per_step": overlapped["us_per_step"] / 1e3, "higher_is_better": True,
@@ -163,7 +176,8 @@ def cache_trace(args, B, I, dev):
            "config": {"workload": f"config 2's call behind the adapter cache: {universe} rank-{rank} adapters in pinned host "
                                   f"memory ({adapter_bytes} bytes each), {capacity} blocks, requests power-law({alpha}), "
                                   f"{rows} rows per step; host loop in Python"},
-           "all_resident": resident, "loads_on_copy_stream": overlapped, "loads_on_compute_stream": serial}
+           "all_resident": resident, "loads_on_copy_stream": overlapped, "loads_on_compute_stream": serial,
+           "loads_of_8bit_blocks_on_copy_stream": overlapped_q8}
     print(json.dumps(out))
 
 

@@ -125,6 +125,21 @@ int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale,
 int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const int *ranks, const float *scales,
                              const void *const *A, const void *const *B, elora_stream_t stream);
 
+/*
+ * The same for adapters that are kept in 8-bit blocks, the storage format of the paper's adapters (Sec. 5 "Model"
+ * names it "Q8_0"; the layout here is this library's own): A_codes[i] int8 [rank, d_in] and B_codes[i] int8
+ * [d_out, rank], row-major, cut into blocks of 32 consecutive values in that order; A_scales[i] / B_scales[i] one
+ * fp16 per block; value = scale * code.  The blocks are converted on the way in: the pool (dtype bf16) receives
+ * bf16(scale * code), the product exact, one rounding to nearest even, so the linear calls see an ordinary bf16
+ * adapter while half the bytes cross the bus.  Sources: device memory or pinned host memory, codes 8-byte aligned;
+ * rank * d_in and rank * d_out multiples of 32.  One launch per 16 adapters.
+ * Errors: E_NULL, E_SHAPE, E_DTYPE (pool is not bf16), E_SLOT, E_RANK, E_ALIGN (a source the device cannot read, or
+ * misaligned), E_HIP.
+ */
+int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, const int *ranks, const float *scales,
+                                const void *const *A_codes, const void *const *A_scales, const void *const *B_codes,
+                                const void *const *B_scales, elora_stream_t stream);
+
 /* Mark `slot` empty (its block returns to the pool, Sec. 4.2).  Rows that still refer to it are
  * treated like rows with an invalid index.  Errors: E_NULL, E_SLOT, E_NOT_LOADED, E_HIP. */
 int elora_pool_evict(elora_pool_t *pool, int slot, elora_stream_t stream);

@@ -34,7 +34,7 @@ ELORA_PATH_GENERIC, ELORA_PATH_DECODE, ELORA_PATH_GEMM = 0, 1, 2
 
 EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
-    "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_evict", "elora_pool_slot_info",
+    "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_load_adapters_q8", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
     "elora_batched_lora_linear_group", "elora_linear_group_launches",
     "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
@@ -79,6 +79,8 @@ lib.elora_pool_load_adapter.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_
 lib.elora_pool_load_adapters.restype = ctypes.c_int
 lib.elora_pool_load_adapters.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+lib.elora_pool_load_adapters_q8.restype = ctypes.c_int
+lib.elora_pool_load_adapters_q8.argtypes = [ctypes.c_void_p, ctypes.c_int] + [ctypes.c_void_p] * 8
 lib.elora_pool_evict.restype = ctypes.c_int
 lib.elora_pool_evict.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
 lib.elora_pool_slot_info.restype = ctypes.c_int
@@ -208,6 +210,16 @@ def elora_pool_load_adapters(pool, slots, ranks, scales, A, B, stream=None) -> N
     pa = (ctypes.c_void_p * n)(*[_ptr(t) for t in A])
     pb = (ctypes.c_void_p * n)(*[_ptr(t) for t in B])
     _check(lib.elora_pool_load_adapters(pool, n, sl, rk, sc, pa, pb, _stream(stream)), "elora_pool_load_adapters")
+
+
+def elora_pool_load_adapters_q8(pool, slots, ranks, scales, A_codes, A_scales, B_codes, B_scales, stream=None) -> None:
+    """Sequences of equal length; the last four hold tensors (device or pinned host) or addresses."""
+    n = len(slots)
+    sl = (ctypes.c_int * n)(*[int(v) for v in slots])
+    rk = (ctypes.c_int * n)(*[int(v) for v in ranks])
+    sc = (ctypes.c_float * n)(*[float(v) for v in scales])
+    ptrs = [(ctypes.c_void_p * n)(*[_ptr(t) for t in seq]) for seq in (A_codes, A_scales, B_codes, B_scales)]
+    _check(lib.elora_pool_load_adapters_q8(pool, n, sl, rk, sc, *ptrs, _stream(stream)), "elora_pool_load_adapters_q8")
 
 
 def elora_pool_evict(pool, slot, stream=None) -> None:

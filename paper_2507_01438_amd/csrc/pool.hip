@@ -69,6 +69,47 @@ __global__ __launch_bounds__(256) void pool_load_batch_kernel(LoadBatch lb, char
     if (blockIdx.x == 0 && threadIdx.x == 0) meta[lb.slot[e]] = SlotMeta{lb.rank[e], lb.scale[e], 1, 0};
 }
 
+// The same for adapters kept in 8-bit blocks (32 consecutive values, one fp16 scale, value = scale * code): the
+// blocks are turned into the pool's bf16 on the way in.  One thread per 8 values: 8 bytes of codes in, 16 bytes out,
+// four threads share a scale.  scale * code is exact in fp32 (11-bit times 8-bit significand); one rounding to bf16.
+struct LoadBatchQ8 {
+    int n;
+    int slot[kLoadBatch], rank[kLoadBatch];
+    float scale[kLoadBatch];
+    const uint2 *A[kLoadBatch], *B[kLoadBatch];
+    const uint16_t *As[kLoadBatch], *Bs[kLoadBatch];
+    unsigned a_vecs[kLoadBatch], b_vecs[kLoadBatch];  // groups of 8 values of A and of B
+};
+
+__device__ __forceinline__ uint4 q8_to_bf16x8(uint2 codes, uint16_t scale_bits)
+{
+    const float sc = fp16_to_f32(scale_bits);
+    const uint32_t w[2] = {codes.x, codes.y};
+    uint32_t out[4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const float lo = sc * (float)(int8_t)((w[h] >> (16 * p)) & 0xffu), hi = sc * (float)(int8_t)((w[h] >> (16 * p + 8)) & 0xffu);
+            out[h * 2 + p] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+        }
+    return uint4{out[0], out[1], out[2], out[3]};
+}
+
+__global__ __launch_bounds__(256) void pool_load_q8_batch_kernel(LoadBatchQ8 lb, char *slots, size_t slot_bytes, size_t b_offset,
+                                                                 SlotMeta *meta)
+{
+    const int e = blockIdx.y;
+    uint4 *dst_a = reinterpret_cast<uint4 *>(slots + (size_t)lb.slot[e] * slot_bytes);
+    uint4 *dst_b = reinterpret_cast<uint4 *>(slots + (size_t)lb.slot[e] * slot_bytes + b_offset);
+    const unsigned na = lb.a_vecs[e], total = na + lb.b_vecs[e];
+    for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        if (i < na) dst_a[i] = q8_to_bf16x8(lb.A[e][i], lb.As[e][i >> 2]);
+        else dst_b[i - na] = q8_to_bf16x8(lb.B[e][i - na], lb.Bs[e][(i - na) >> 2]);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) meta[lb.slot[e]] = SlotMeta{lb.rank[e], lb.scale[e], 1, 0};
+}
+
 __global__ void pool_clear_err_kernel(int *err)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -252,6 +293,61 @@ int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const 
         per = per < 1 ? 1 : per > 64 ? 64 : per;
         hipLaunchKernelGGL(pool_load_batch_kernel, dim3(per, lb.n), dim3(256), 0, stream, lb, pool->storage + pool->slots_offset,
                            pool->slot_bytes, pool->b_offset, dmeta);
+        ELORA_HIP_TRY(hipGetLastError());
+        for (int i = 0; i < lb.n; ++i) pool->host_meta[slots[i0 + i]] = SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0};
+    }
+    return ELORA_OK;
+}
+
+int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, const int *ranks, const float *scales,
+                                const void *const *A_codes, const void *const *A_scales, const void *const *B_codes,
+                                const void *const *B_scales, elora_stream_t stream_)
+{
+    if (pool == nullptr || (n > 0 && (!slots || !ranks || !scales || !A_codes || !A_scales || !B_codes || !B_scales))) return ELORA_E_NULL;
+    if (n < 0) return ELORA_E_SHAPE;
+    if (pool->dtype != ELORA_BF16) return ELORA_E_DTYPE;
+    for (int i = 0; i < n; ++i) {
+        if (!A_codes[i] || !A_scales[i] || !B_codes[i] || !B_scales[i]) return ELORA_E_NULL;
+        if (slots[i] < 0 || slots[i] >= pool->capacity) return ELORA_E_SLOT;
+        if (ranks[i] < 1 || ranks[i] > pool->max_rank) return ELORA_E_RANK;
+        if (((size_t)ranks[i] * pool->d_in) % 32 || ((size_t)ranks[i] * pool->d_out) % 32) return ELORA_E_SHAPE;
+        for (int j = 0; j < i; ++j)
+            if (slots[j] == slots[i]) return ELORA_E_SLOT;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    // every source must be readable by the device (device memory or pinned host memory), codes 8-byte aligned
+    for (int i0 = 0; i0 < n; i0 += kLoadBatch) {
+        LoadBatchQ8 lb;
+        lb.n = n - i0 < kLoadBatch ? n - i0 : kLoadBatch;
+        size_t most = 0;
+        for (int i = 0; i < lb.n; ++i) {
+            bool dev = false;
+            const void *a = device_readable(A_codes[i0 + i], &dev), *as = device_readable(A_scales[i0 + i], &dev);
+            const void *b = device_readable(B_codes[i0 + i], &dev), *bs = device_readable(B_scales[i0 + i], &dev);
+            if (!a || !as || !b || !bs) return ELORA_E_ALIGN;
+            if (reinterpret_cast<uintptr_t>(a) % 8 || reinterpret_cast<uintptr_t>(b) % 8 || reinterpret_cast<uintptr_t>(as) % 2 ||
+                reinterpret_cast<uintptr_t>(bs) % 2)
+                return ELORA_E_ALIGN;
+            const size_t a_vals = (size_t)ranks[i0 + i] * pool->d_in, b_vals = (size_t)ranks[i0 + i] * pool->d_out;
+            lb.slot[i] = slots[i0 + i];
+            lb.rank[i] = ranks[i0 + i];
+            lb.scale[i] = scales[i0 + i];
+            lb.A[i] = static_cast<const uint2 *>(a);
+            lb.B[i] = static_cast<const uint2 *>(b);
+            lb.As[i] = static_cast<const uint16_t *>(as);
+            lb.Bs[i] = static_cast<const uint16_t *>(bs);
+            lb.a_vecs[i] = (unsigned)(a_vals / 8);
+            lb.b_vecs[i] = (unsigned)(b_vals / 8);
+            most = a_vals + b_vals > most ? a_vals + b_vals : most;
+        }
+        if (i0 == 0) {
+            const int rc = pool_ensure_cleared(pool, stream);
+            if (rc != ELORA_OK) return rc;
+        }
+        unsigned per = (unsigned)((most / 8 + 256 * 4 - 1) / (256 * 4));
+        per = per < 1 ? 1 : per > 64 ? 64 : per;
+        hipLaunchKernelGGL(pool_load_q8_batch_kernel, dim3(per, lb.n), dim3(256), 0, stream, lb, pool->storage + pool->slots_offset,
+                           pool->slot_bytes, pool->b_offset, reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset));
         ELORA_HIP_TRY(hipGetLastError());
         for (int i = 0; i < lb.n; ++i) pool->host_meta[slots[i0 + i]] = SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0};
     }

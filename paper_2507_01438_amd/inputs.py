@@ -103,6 +103,22 @@ def draw_adapters(rng: np.random.Generator, n_draws: int, pool: int, alpha: Opti
     return slot_of_rank[ranks].astype(np.int32)
 
 
+def quantize_q8_blocks(a: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """8-bit block storage of an adapter matrix (the paper's adapters are kept in such blocks, Sec. 5 "Model"): blocks of
+    32 consecutive values in row-major order, scale = absmax / 127 rounded to fp16, code = clamp(rne(a / scale), -127,
+    127).  Returns (int8 codes of a's shape, fp16 scale bit patterns uint16 [a.size / 32]).  How codes and scales were
+    chosen is input preparation: the library and the oracle both consume (codes, scales)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.size % 32:
+        raise ValueError("the number of values must be a multiple of 32")
+    g = a.reshape(-1, 32)
+    scale = (np.abs(g).max(axis=1) / np.float32(127.0)).astype(np.float16)
+    sf = scale.astype(np.float32)
+    sf_safe = np.where(sf == 0, np.float32(1.0), sf)
+    codes = np.clip(np.rint(g / sf_safe[:, None]), -127, 127).astype(np.int8)
+    return codes.reshape(a.shape), scale.view(np.uint16)
+
+
 def request_trace(seed: int, n_adapters: int, alpha: Optional[float], length: int) -> np.ndarray:
     """Adapter ids of `length` successive requests: power law over popularity ranks (Sec. 5.1; alpha None: uniform),
     ranks mapped to ids through a seeded permutation."""

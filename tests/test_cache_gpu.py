@@ -128,3 +128,64 @@ def test_batched_load_from_device_pinned_and_ordinary_host_memory():
         with pytest.raises(B.EloraError):     # one block named twice
             B.elora_pool_load_adapters(pool.handle, [1, 1], [4, 4], [1.0, 1.0], [src[0][0]] * 2, [src[0][1]] * 2)
         pool.close()
+
+
+def test_adapters_kept_in_8bit_blocks_are_converted_on_the_way_into_the_pool():
+    """elora_pool_load_adapters_q8: the block content is bit for bit what the oracle's dequantisation gives, from
+    device and from pinned host memory, and a linear call on it matches the oracle run with those bf16 adapters."""
+    from oracle.q8_oracle import dequant_q8_to_bf16
+    from paper_2507_01438_amd import binding as B
+    n_adapters, K, N, rows = 18, 256, 192, 18
+    w = I.small_workload(95, I.BF16, K, N, rows, n_adapters, (16, 8, 4))
+    w.adapter_idx = np.arange(n_adapters, dtype=np.int32)
+    proj = w.projections[0]
+    x_h, (W_h, _) = w.x(proj), w.W(proj)
+    q8, deq = [], []
+    for a in range(n_adapters):
+        A, Bm, s = w.adapter(proj, a)
+        Ac, As = I.quantize_q8_blocks(I.bf16_bits_to_f32(A))
+        Bc, Bs = I.quantize_q8_blocks(I.bf16_bits_to_f32(Bm))
+        q8.append((Ac, As, Bc, Bs, s))
+        deq.append(oracle.Adapter(dequant_q8_to_bf16(Ac, As), dequant_q8_to_bf16(Bc, Bs), s))
+    ref = oracle.linear(I.BF16, x_h, W_h, deq, w.adapter_idx)
+    x, W, idx = to_dev(x_h), to_dev(W_h), to_dev(w.adapter_idx)
+
+    def on_device(a):
+        return torch.from_numpy(a.view(np.int8 if a.dtype == np.int8 else np.int16)).to(DEV)
+
+    def pinned(a):
+        return torch.from_numpy(a.view(np.int8 if a.dtype == np.int8 else np.int16)).pin_memory()
+
+    for name, put in (("device", on_device), ("pinned", pinned)):
+        src = [tuple(put(t) for t in q[:4]) for q in q8]
+        pool = B.AdapterPool(K, N, w.max_rank, n_adapters, I.BF16, DEV)
+        order = list(reversed(range(n_adapters)))
+        B.elora_pool_load_adapters_q8(pool.handle, order, [q8[a][0].shape[0] for a in order], [q8[a][4] for a in order],
+                                      *[[src[a][k] for a in order] for k in range(4)])
+        torch.cuda.synchronize()
+        # the blocks as they sit in the pool's storage: header 256 B, the slot table, then one block per slot with A at
+        # its start and B (row stride = the adapter's rank) at a fixed offset
+        up = lambda v: (v + 255) // 256 * 256
+        slots_off = 256 + up(16 * n_adapters)
+        b_off = up(w.max_rank * K * 2)
+        slot_bytes = b_off + up(w.max_rank * N * 2)
+        raw = pool.storage.cpu().numpy()
+        for a in range(n_adapters):
+            r = q8[a][0].shape[0]
+            blk = raw[slots_off + a * slot_bytes: slots_off + (a + 1) * slot_bytes]
+            assert np.array_equal(blk[: r * K * 2].view(np.uint16).reshape(r, K), deq[a].A), (name, a)
+            assert np.array_equal(blk[b_off: b_off + N * r * 2].view(np.uint16).reshape(N, r), deq[a].B), (name, a)
+        lin = B.LoraLinear(K, N, I.BF16, pool, rows, DEV)
+        y = torch.zeros((rows, N), dtype=torch.int16, device=DEV)
+        B.elora_batched_lora_linear(lin.desc(x, W, y, adapter_idx=idx))
+        torch.cuda.synchronize()
+        e = rel_err(y_to_f64(y, I.BF16), ref)
+        print(f"8-bit block adapters from {name} memory: rel err {e:.2e}")
+        assert e <= 1e-2 and pool.poll_error() == (0, -1)
+        pool.close()
+    # ordinary host memory cannot be read by the device: refused
+    pool = B.AdapterPool(K, N, w.max_rank, 2, I.BF16, DEV)
+    plain = [torch.from_numpy(t.view(np.int8 if t.dtype == np.int8 else np.int16).copy()) for t in q8[0][:4]]
+    with pytest.raises(B.EloraError):
+        B.elora_pool_load_adapters_q8(pool.handle, [0], [q8[0][0].shape[0]], [1.0], [plain[0]], [plain[1]], [plain[2]], [plain[3]])
+    pool.close()
