@@ -493,31 +493,46 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     // step, so that the matrix cores drain step 2 while the waves meet.
     int blk0 = 0;
 #ifndef ELORA_GEMM_NO_INTERLEAVE
-    if (WFMT == ELORA_W_SAME) {
-        // While the block after this one is a base block too, nothing in an iteration is conditional: straight-line
-        // code, in which the sixteen direct loads of the next block and the address arithmetic of each are spread over
-        // the sixteen matrix instructions of the first K step (a matrix instruction keeps its pipe busy for 32 cycles,
-        // during which the wave can issue a handful of other instructions; issued ahead of them, as the general loop
-        // below does, they cost a fifth of the iteration).
-        for (; blk0 + 1 < base_blocks; ++blk0) {
-            const int buf = blk0 & 1;
-            // (the LDS reads of the next K step come first in program order: the compiler keeps direct loads, which
-            // write LDS, and LDS reads in the order they are written in)
-            read_frags(fr[1], buf, 1);
-            {
-                uint16_t *sa = stage0 + (buf ^ 1) * kStageElems;
-                uint16_t *sb = sa + BM * BK;
-                const int k0 = (blk0 + 1) * BK;
-                const uint16_t *W = static_cast<const uint16_t *>(ga.W);
+    if (WFMT == ELORA_W_SAME && base_blocks > 2) {
+        // While the two blocks after this one are base blocks, nothing in an iteration is conditional: straight-line
+        // code.  The direct loads of block b + 2 go out as soon as the barrier of iteration b has shown that everybody
+        // is done reading the stage they fill (the one block b sat in), a block and a quarter before they are waited
+        // for, and they and the address arithmetic of each are spread over the sixteen matrix instructions of the
+        // last K step (a matrix instruction keeps its pipe busy for 32 cycles, during which the wave can issue a
+        // handful of other instructions; issued ahead of them, at the top of an iteration, as the general loop below
+        // does, they cost a fifth of the iteration and have three quarters of a block to land).
+        // (the LDS reads come first in program order: the compiler keeps direct loads, which write LDS, and LDS reads in
+        // the order they are written in)
+        auto issue_base = [&](int blk, int buf) {
+            uint16_t *sa = stage0 + buf * kStageElems;
+            uint16_t *sb = sa + BM * BK;
+            const int k0 = blk * BK;
+            const uint16_t *W = static_cast<const uint16_t *>(ga.W);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int q = wave * 8 + i, row = 8 * q + (lane >> 3);
-                    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-                    __builtin_amdgcn_global_load_lds((gptr_t)(ga.x + (size_t)min(m0 + row, T - 1) * K + k0 + chunk * 8), (lptr_t)(sa + q * 512), 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((gptr_t)(W + (size_t)min(n0 + row, N - 1) * K + k0 + chunk * 8), (lptr_t)(sb + q * 512), 16, 0, 0);
-                }
+            for (int i = 0; i < 8; ++i) {
+                const int q = wave * 8 + i, row = 8 * q + (lane >> 3);
+                const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+                __builtin_amdgcn_global_load_lds((gptr_t)(ga.x + (size_t)min(m0 + row, T - 1) * K + k0 + chunk * 8), (lptr_t)(sa + q * 512), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(W + (size_t)min(n0 + row, N - 1) * K + k0 + chunk * 8), (lptr_t)(sb + q * 512), 16, 0, 0);
             }
+        };
+        issue_base(1, 1);
+        for (; blk0 + 2 < base_blocks; ++blk0) {
+            const int buf = blk0 & 1;
+            read_frags(fr[1], buf, 1);
             mfma_step(fr[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(fr[0], buf, 2);
+            mfma_step(fr[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(fr[1], buf, 3);
+            mfma_step(fr[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // block blk0 + 1 has landed
+            __syncthreads();
+            read_frags(fr[0], buf ^ 1, 0);
+            issue_base(blk0 + 2, buf);
+            mfma_step(fr[1]);
 #define ELORA_SLOT_R __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
 #define ELORA_SLOT   __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x006, 6, 0); \
                      __builtin_amdgcn_sched_group_barrier(0x010, 1, 0); __builtin_amdgcn_sched_group_barrier(0x006, 6, 0); \
@@ -527,19 +542,8 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
 #undef ELORA_SLOT_R
 #undef ELORA_SLOT
             __builtin_amdgcn_sched_barrier(0);
-            read_frags(fr[0], buf, 2);
-            mfma_step(fr[1]);
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(fr[1], buf, 3);
-            mfma_step(fr[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
-            read_frags(fr[0], buf ^ 1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_step(fr[1]);
-            __builtin_amdgcn_sched_barrier(0);
         }
+        // (block blk0 + 1 is on its way; the loop below asks for it once more, which is harmless: same bytes, same place)
     }
 #endif
     for (int blk = blk0; blk < total_blocks; ++blk) {
