@@ -12,6 +12,8 @@
 //           and B_i as B-operand in the same columns, so one block serves several short runs at once
 //           (decode rows of a mixed batch included).  The epilogue rounds once to bf16 and stores each
 //           row at its own position.
+#include <type_traits>
+
 #include "common.h"
 
 using namespace elora;
@@ -586,32 +588,34 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
 
     // ---- epilogue -------------------------------------------------------------------------------------
     // C layout of the 32x32 MFMA: lane holds column (lane % 32); value i sits in row (i / 4) * 8 + (lane / 32) * 4 + i % 4.
-    // Neighbouring lanes swap one value per row pair so that every lane stores two adjacent columns (4 bytes).
+    // Neighbouring lanes swap one value per row pair (one cross-lane move inside the quad, no LDS) so that every lane
+    // stores two adjacent columns (4 bytes).  A tile that lies wholly inside y, the usual case, stores without any
+    // test: 128 stores per lane, each of which would otherwise sit in a branch of its own.
     const bool odd = lane & 1;
+    auto store_tile = [&](auto checked) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+        for (int a = 0; a < 4; ++a) {
 #pragma unroll
-        for (int ip = 0; ip < 8; ++ip) {
-            float o[4][2];  // [b][row i0 / i1]
+            for (int ip = 0; ip < 8; ++ip) {
+                const int i_mine = 2 * ip + (odd ? 1 : 0);
+                const int rl = wm * 128 + a * 32 + (i_mine >> 2) * 8 + (lane >> 5) * 4 + (i_mine & 3);
+                const int row = m0 + rl;
+                uint16_t *yrow = ga.y + (size_t)row * N + n0 + wn * 128 + (lane & 30);  // even column of the pair
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) o[b][h] = acc[a][b][2 * ip + h];
-            const int i_mine = 2 * ip + (odd ? 1 : 0);
-            const int rl = wm * 128 + a * 32 + (i_mine >> 2) * 8 + (lane >> 5) * 4 + (i_mine & 3);
-            const int row = m0 + rl;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                // even lane keeps row i0 and gets the neighbour's i0 value; odd lane keeps row i1 and gets the neighbour's i1
-                const float send = odd ? o[b][0] : o[b][1];
-                const float recv = __shfl_xor(send, 1);
-                const float mine = odd ? o[b][1] : o[b][0];
-                const int col = n0 + wn * 128 + b * 32 + (lane & 30);  // even column of the pair
-                if (row < T && col < N)
-                    *reinterpret_cast<uint32_t *>(ga.y + (size_t)row * N + col) = odd ? pack_bf16x2(recv, mine) : pack_bf16x2(mine, recv);
+                for (int b = 0; b < 4; ++b) {
+                    // even lane keeps row i0 and gets the neighbour's i0 value; odd lane keeps row i1 and gets the neighbour's i1
+                    const float lo = acc[a][b][2 * ip], hi = acc[a][b][2 * ip + 1];
+                    const float send = odd ? lo : hi, mine = odd ? hi : lo;
+                    const float recv = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, false));  // quad_perm [1, 0, 3, 2]
+                    const uint32_t packed = odd ? pack_bf16x2(recv, mine) : pack_bf16x2(mine, recv);
+                    if (!decltype(checked)::value || (row < T && n0 + wn * 128 + b * 32 + (lane & 30) < N))
+                        *reinterpret_cast<uint32_t *>(yrow + b * 32) = packed;
+                }
             }
         }
-    }
+    };
+    if (m0 + BM <= T && n0 + BN <= N) store_tile(std::false_type{});
+    else store_tile(std::true_type{});
 }
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
