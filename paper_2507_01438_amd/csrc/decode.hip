@@ -440,12 +440,10 @@ void finish_shape(DecodeShape &sh, int max_rank, int resident, int n_cus, bool s
     // A call that leaves compute units without a workgroup gets surplus ones for them: they only share in the shrink,
     // which for few output columns is most of the work (k_proj / v_proj at 64 rows: 2048 units of two rank rows on 128
     // workgroups).
-#ifndef ELORA_NO_SURPLUS
     if (surplus && sh.jgroups > 1) {
         const int room = (resident < n_cus ? resident : n_cus) / unit * unit;
         if (room > sh.grid) sh.grid = room;
     }
-#endif
     // the workgroups that share the shrink must all be running before anybody can wait for them
     sh.n_pub = sh.grid < resident ? sh.grid : resident;
     sh.G = kGranules / sh.split;

@@ -494,7 +494,6 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     // converted and parked between the steps); the one barrier of the iteration sits before the last
     // step, so that the matrix cores drain step 2 while the waves meet.
     int blk0 = 0;
-#ifndef ELORA_GEMM_NO_INTERLEAVE
     if (WFMT == ELORA_W_SAME && base_blocks > 2) {
         // While the two blocks after this one are base blocks, nothing in an iteration is conditional: straight-line
         // code.  The direct loads of block b + 2 go out as soon as the barrier of iteration b has shown that everybody
@@ -547,7 +546,6 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
         }
         // (block blk0 + 1 is on its way; the loop below asks for it once more, which is harmless: same bytes, same place)
     }
-#endif
     for (int blk = blk0; blk < total_blocks; ++blk) {
         const int buf = blk & 1;
         const bool more = (blk + 1) < total_blocks;
