@@ -323,6 +323,8 @@ GEMM_SMALL = [
     (1024, 264, 4, (32, 16, 64, 8), [300, 20, 0, 257, 15], ()),          # runs crossing 256-row tiles
     (512, 520, 5, (5, 16, 3, 8, 12), [100, 64, 30, 16, 50], (1,)),        # odd ranks: per-row expand
     (256, 2048 + 40, 6, (16,), [1] * 70 + [130] + [1] * 60, (5, 100)),    # decode-like rows around a prompt
+    (192, 72, 3, (8, 16), [70, 10, 300], ()),                             # three K blocks: one straight-line iteration
+    (128, 264, 2, (16,), [260], ()),                                      # two K blocks: the general loop only
 ]
 
 
