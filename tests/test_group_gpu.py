@@ -96,3 +96,18 @@ def test_config3_projection_groups_full_shapes(names):
         assert e <= 1e-2
         assert c.pool.poll_error() == (0, -1)
         c.close()
+
+
+def test_group_with_every_wait_cut_short_still_matches_and_leaves_the_workspaces_idle():
+    """Bound of the internal waits at 0: every workgroup of every call of the group computes what it needs from the
+    inputs; results still match, and the next (normal) group launch on the same workspaces does too."""
+    from paper_2507_01438_amd import binding as B
+    cases = _cases(37, 1024, (528, 80, 272), [(8, 16, 24, 3), (16,), (5, 64, 16)], seed=320)
+    B.elora_debug_spin_limit(0)
+    try:
+        _run_group(B, cases, expect_launches=1)
+    finally:
+        B.elora_debug_spin_limit(1 << 22)
+    _run_group(B, cases, expect_launches=1)
+    for c in cases:
+        c.close()
