@@ -36,6 +36,11 @@
 // be replayed from a HIP graph.
 //
 // Summation order is fixed (no float atomics): results are bit-identical from run to run.
+//
+// The kernel body lives in decode_body.inc and is included into two kernels: decode_kernel (one call per launch) and
+// decode_group_kernel (two or three calls that are due together, each with a grid of its own inside the launch).
+// A call with a pool that would leave compute units without a workgroup gets surplus workgroups that only share
+// in the shrink.
 #include "common.h"
 
 #include <type_traits>
