@@ -60,10 +60,10 @@ constexpr int kTileRows = kWaves * kRowsPerWave;
 constexpr int kGranules = kTileRows / 4;  // a granule = 4 adjacent columns = what one lane holds of one row of x
 constexpr int kChunk = 256;               // K elements per register set of W (8 MFMA K steps)
 // The ring of sub-spans in LDS (dynamic LDS: the only such array of the kernel; the staging after the contraction reuses
-// it).  A sub-span is 128 elements of K.  Up to 32 rows of x: 5 slots, more rows: 3.  A slot holds the rows of x and,
+// it).  A sub-span is 128 elements of K.  Up to 32 rows of x: 5 slots, more rows: 4.  A slot holds the rows of x and,
 // where W travels through the ring as well (see the kernel), the tile's 64 rows of W.
 constexpr int kSubSpan = 128;
-__host__ __device__ constexpr int ring_slots(int tt) { return tt <= 2 ? 5 : 3; }
+__host__ __device__ constexpr int ring_slots(int tt) { return tt <= 2 ? 5 : 4; }
 __host__ __device__ constexpr int slot_rows(int tt, bool wlds) { return tt * 16 + (wlds ? kTileRows : 0); }
 __host__ __device__ constexpr int ring_bytes(int tt, bool wlds) { return ring_slots(tt) * slot_rows(tt, wlds) * kSubSpan * 2; }
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
