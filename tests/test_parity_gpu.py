@@ -65,6 +65,8 @@ SMALL = [
     (48, 768, 16, 2, 8, ()),                        # one wave of the tile active
     (40, 512, 14336, 3, (16, 8, 32), (7,)),         # 224 tiles, 3 row blocks: W straight into registers, two workgroups per CU
     (24, 512, 4096, 3, 16, ()),                     # 64 tiles x 2 K-slices of 2 sub-spans: a ring that is never full
+    (40, 512, 96, 4, (8, 20, 16, 3), (2,)),         # more than 32 rows, largest rank not a multiple of 8, mixed with odd ranks
+    (36, 256, 32, 3, (8, 136, 72), ()),             # more than 32 rows, ranks above 64: several rounds of the expand
 ]
 
 
