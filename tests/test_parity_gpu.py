@@ -67,6 +67,9 @@ SMALL = [
     (24, 512, 4096, 3, 16, ()),                     # 64 tiles x 2 K-slices of 2 sub-spans: a ring that is never full
     (40, 512, 96, 4, (8, 20, 16, 3), (2,)),         # more than 32 rows, largest rank not a multiple of 8, mixed with odd ranks
     (36, 256, 32, 3, (8, 136, 72), ()),             # more than 32 rows, ranks above 64: several rounds of the expand
+    (48, 512, 64, 3, (64, 8, 8), tuple(range(1, 48))),   # more than 32 rows, one of them with an adapter: 32 shrink units in all
+    (48, 512, 64, 3, (64, 8, 8), tuple(range(48))),      # a pool, and no row uses it: no shrink unit at all
+    (64, 1024, 128, 4, (1, 64, 3, 8), (10, 11)),         # ranks 1 to 64 side by side (one pair of rank rows to 32 per row)
 ]
 
 
