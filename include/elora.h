@@ -361,6 +361,20 @@ int elora_debug_spin_limit(int limit);
  */
 int elora_debug_xcd_local(int mode);
 
+/*
+ * Test hook: which decode calls with more than 32 rows run the kernel whose workgroups take 128 rows of W instead
+ * of 64.  -1 (default): those whose grid then still covers most of the device; 0: none; 1: all whose workgroups are
+ * resident together.  Errors: E_SHAPE.
+ */
+int elora_debug_decode_wide(int mode);
+
+/*
+ * Test hook: 0 makes every workgroup of the decode kernel walk its K-slice from the start; 1 (default) starts
+ * the workgroups of an XCD at different places of their slices, so that they do not ask the same memory channels
+ * for the same rows of x at the same moment.  Results differ only in the order of fp32 additions.  Errors: E_SHAPE.
+ */
+int elora_debug_k_rotate(int on);
+
 /* ------------------------------------------------------------- profiling ---
  * Kernel timing for benchmarks (the roofline figure of a run is quoted on the
  * call's dominant kernel: the streaming contraction on the decode path, the

@@ -36,9 +36,8 @@ EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
     "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_load_adapters_q8", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
-    "elora_batched_lora_linear_group", "elora_linear_group_launches",
     "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
-    "elora_debug_spin_limit", "elora_debug_xcd_local",
+    "elora_debug_spin_limit", "elora_debug_xcd_local", "elora_debug_k_rotate", "elora_debug_decode_wide",
     "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
     "elora_cache_acquire_batch", "elora_cache_release_batch", "elora_cache_select",
     "elora_cache_drop", "elora_cache_stats", "elora_cache_reset_stats", "elora_cache_load_begin",
@@ -108,6 +107,10 @@ lib.elora_debug_spin_limit.restype = ctypes.c_int
 lib.elora_debug_spin_limit.argtypes = [ctypes.c_int]
 lib.elora_debug_xcd_local.restype = ctypes.c_int
 lib.elora_debug_xcd_local.argtypes = [ctypes.c_int]
+lib.elora_debug_decode_wide.restype = ctypes.c_int
+lib.elora_debug_decode_wide.argtypes = [ctypes.c_int]
+lib.elora_debug_k_rotate.restype = ctypes.c_int
+lib.elora_debug_k_rotate.argtypes = [ctypes.c_int]
 lib.elora_profile_arm.restype = ctypes.c_int
 lib.elora_profile_arm.argtypes = [ctypes.c_int]
 lib.elora_profile_read.restype = ctypes.c_int
@@ -302,6 +305,14 @@ def elora_debug_spin_limit(limit: int) -> None:
 
 def elora_debug_xcd_local(mode: int) -> None:
     _check(lib.elora_debug_xcd_local(int(mode)), "elora_debug_xcd_local")
+
+
+def elora_debug_decode_wide(mode: int) -> None:
+    _check(lib.elora_debug_decode_wide(int(mode)), "elora_debug_decode_wide")
+
+
+def elora_debug_k_rotate(on: int) -> None:
+    _check(lib.elora_debug_k_rotate(int(on)), "elora_debug_k_rotate")
 
 
 def elora_profile_arm(n_calls: int) -> None:

@@ -103,6 +103,8 @@ int launch_decode_group(const LinearArgs *a, int n, hipStream_t stream);  // -1:
 bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds);  // K-slices per call if they fit
 
 void decode_set_spin_limit(int limit);
+void decode_set_wide(int mode);    // -1: 128-row tiles where they pay, 0: never, 1: wherever the shape allows
+void decode_set_k_rotate(int on);  // 0: every workgroup walks its K-slice from the start
 void decode_set_local_override(int mode);  // 0: never assume XCD-local hand-overs, -1: as probed
 int decode_probe_device(hipStream_t stream);  // finds out, once per device, how workgroups are placed on the XCDs
 bool decode_eligible(const elora_linear_desc_t &d, int max_rank);

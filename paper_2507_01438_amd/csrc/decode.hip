@@ -63,9 +63,10 @@ constexpr int kChunk = 256;               // K elements per register set of W (8
 // it).  A sub-span is 128 elements of K.  Up to 32 rows of x: 5 slots, more rows: 4.  A slot holds the rows of x and,
 // where W travels through the ring as well (see the kernel), the tile's 64 rows of W.
 constexpr int kSubSpan = 128;
-__host__ __device__ constexpr int ring_slots(int tt) { return tt <= 2 ? 5 : 4; }
-__host__ __device__ constexpr int slot_rows(int tt, bool wlds) { return tt * 16 + (wlds ? kTileRows : 0); }
-__host__ __device__ constexpr int ring_bytes(int tt, bool wlds) { return ring_slots(tt) * slot_rows(tt, wlds) * kSubSpan * 2; }
+// (nw = waves per workgroup: 4, or 8 for the wide kernel whose tile is 128 rows of W: 3 slots of 48 KiB)
+__host__ __device__ constexpr int ring_slots(int tt, int nw) { return nw > 4 ? 3 : tt <= 2 ? 5 : 4; }
+__host__ __device__ constexpr int slot_rows(int tt, bool wlds, int nw) { return tt * 16 + (wlds ? nw * kRowsPerWave : 0); }
+__host__ __device__ constexpr int ring_bytes(int tt, bool wlds, int nw) { return ring_slots(tt, nw) * slot_rows(tt, wlds, nw) * kSubSpan * 2; }
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kMetaLds = 512;  // slot tables up to this many entries are copied to LDS whole
 
@@ -78,6 +79,7 @@ constexpr int kGaveUp = 1 << 16;  // this much for every owner on XCD x that gav
 
 int g_spin_limit = 1 << 22;
 int g_local_override = -1;
+int g_k_rotate = 1;
 constexpr int kMaxDevices = 64;
 int g_local[kMaxDevices];  // per device: is workgroup b placed on XCD b % 8?  0 not probed yet (treated as no), 1 yes, -1 no
 
@@ -124,6 +126,8 @@ struct DecodeShape {
     int spin_limit;
     int zero;       // 0
     int local;      // 1: workgroup b runs on XCD b % 8 (checked once per device), so a tile's workgroups share an L2
+    int tile_rows;  // rows of W per tile: 64 (four waves) or 128 (the wide kernel, eight waves)
+    int rot_mask;   // a workgroup starts its K-slice (tile number on its XCD & rot_mask) sub-spans in: 2^n - 1, below every slice's length
 };
 
 // ---- mailbox accesses (agent scope: past the per-XCD L2) -----------------------------------------
@@ -213,10 +217,10 @@ __device__ __forceinline__ float *piece_ptr(float *mail, const DecodeShape &sh, 
 // Columns [nc0, nc0 + ncols) of y for all rows, from the inputs alone (after a wait ran out): slow, exact.
 __device__ void recompute_columns(const DecodeShape &sh, const uint16_t *__restrict__ x, const uint16_t *__restrict__ W,
                                   const PoolView &pool, const RouteView &route, int has_pool, uint16_t *__restrict__ y,
-                                  int nc0, int ncols, int wave, int lane)
+                                  int nc0, int ncols, int wave, int n_waves, int lane)
 {
     const int T = sh.T, K = sh.K, N = sh.N;
-    for (int t = wave; t < T; t += kWaves) {
+    for (int t = wave; t < T; t += n_waves) {
         RowRoute rr{-1, 0, 0.0f};
         if (has_pool) rr = resolve_row(t, route, pool, false);
         const uint16_t *xt = x + (size_t)t * K;
@@ -253,8 +257,8 @@ __device__ void recompute_columns(const DecodeShape &sh, const uint16_t *__restr
     }
 }
 
-template <int TT, bool kWLds>
-__global__ __launch_bounds__(kThreads, 2) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
+template <int TT, bool kWLds, int NW>
+__global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
                                                                            const uint16_t *__restrict__ W, PoolView pool,
                                                                            RouteView route, int has_pool, float *__restrict__ mail,
                                                                            float *__restrict__ vmail, int *__restrict__ sync,
@@ -287,8 +291,8 @@ struct DecodeGroup {
     DecodeCall call[kGroupMax];
 };
 
-template <int TT, bool kWLds>
-__global__ __launch_bounds__(kThreads, 2) void decode_group_kernel(DecodeGroup grp_)
+template <int TT, bool kWLds, int NW>
+__global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_group_kernel(DecodeGroup grp_)
 {
     int call_i = 0;
     if (grp_.n > 1 && (int)blockIdx.x >= grp_.first[1]) call_i = 1;
@@ -308,77 +312,70 @@ __global__ __launch_bounds__(kThreads, 2) void decode_group_kernel(DecodeGroup g
 #undef ELORA_WG
 }
 
-// workgroups of decode_kernel<tt, wlds> the device holds at once (registers and LDS decide; asked once per instance),
-// and its number of compute units
-template <int TT, bool WL>
-hipError_t ask_occupancy(int *per_cu)
+// The kernel instances: 16-row blocks of x (1..4), W through the LDS ring or into registers, waves per workgroup.
+// The wide kernel (8 waves, 128 rows of W per tile, x read once per 128 rows instead of once per 64) exists for more
+// than 32 rows of x only, with four blocks of x and W through the ring.
+struct Variant {
+    int tt;
+    bool wlds;
+    int nw;
+    int index() const { return nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0); }
+    int threads() const { return nw * 64; }
+    int tile_rows() const { return nw * kRowsPerWave; }
+    int lds() const { return ring_bytes(tt, wlds, nw); }
+};
+constexpr int kVariants = 11;
+template <int V> using ic = std::integral_constant<int, V>;
+template <typename F>
+auto with_variant(const Variant &v, F &&f)
 {
-    // (the ring may be larger than the LDS a kernel gets without asking)
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<TT, WL>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       ring_bytes(TT, WL));
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, decode_kernel<TT, WL>, kThreads, ring_bytes(TT, WL));
-    return e;
-}
-template <int TT, bool WL>
-hipError_t ask_group_occupancy(int *per_cu)
-{
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_group_kernel<TT, WL>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL));
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, decode_group_kernel<TT, WL>, kThreads, ring_bytes(TT, WL));
-    return e;
-}
-// the same for the kernel that carries several calls; 0 if it cannot be asked (then calls are launched one by one)
-int resident_group_workgroups(int tt, bool wlds)
-{
-    static int cached[5][2] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}, {0, 0}};
-    if (cached[tt][wlds] == 0) {
-        int per_cu = 0, cus = 0, dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) {
-            switch (tt) {
-            case 1: e = ask_group_occupancy<1, true>(&per_cu); break;
-            case 2: e = ask_group_occupancy<2, true>(&per_cu); break;
-            case 3: e = wlds ? ask_group_occupancy<3, true>(&per_cu) : ask_group_occupancy<3, false>(&per_cu); break;
-            default: e = wlds ? ask_group_occupancy<4, true>(&per_cu) : ask_group_occupancy<4, false>(&per_cu); break;
-            }
-        }
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            return 0;
-        }
-        cached[tt][wlds] = per_cu * cus;
+    if (v.nw > 4) return f(ic<4>{}, std::true_type{}, ic<8>{});
+    switch (v.tt) {
+    case 1: return f(ic<1>{}, std::true_type{}, ic<4>{});
+    case 2: return f(ic<2>{}, std::true_type{}, ic<4>{});
+    case 3: return v.wlds ? f(ic<3>{}, std::true_type{}, ic<4>{}) : f(ic<3>{}, std::false_type{}, ic<4>{});
+    default: return v.wlds ? f(ic<4>{}, std::true_type{}, ic<4>{}) : f(ic<4>{}, std::false_type{}, ic<4>{});
     }
-    return cached[tt][wlds];
 }
 
-int resident_workgroups(int tt, bool wlds, int *n_cus)
+// workgroups of a kernel instance the device holds at once (registers and LDS decide; asked once per instance), and
+// its number of compute units.  group: the kernel that carries several calls; 0 if it cannot be asked (then calls
+// are launched one by one).
+int resident_of(const Variant &v, bool group, int *n_cus)
 {
-    static int cached[5][2] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}, {0, 0}};
+    static int cached[2][kVariants];
     static int cached_cus = 0;
-    if (cached[tt][wlds] == 0) {
+    int &slot = cached[group ? 1 : 0][v.index()];
+    if (slot == 0) {
         int per_cu = 0, cus = 0, dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) {
-            switch (tt) {
-            case 1: e = ask_occupancy<1, true>(&per_cu); break;
-            case 2: e = ask_occupancy<2, true>(&per_cu); break;
-            case 3: e = wlds ? ask_occupancy<3, true>(&per_cu) : ask_occupancy<3, false>(&per_cu); break;
-            default: e = wlds ? ask_occupancy<4, true>(&per_cu) : ask_occupancy<4, false>(&per_cu); break;
-            }
-        }
+        if (e == hipSuccess)
+            e = with_variant(v, [&](auto tt, auto wl, auto nw) {
+                constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
+                constexpr bool WL = decltype(wl)::value;
+                // (the ring may be larger than the LDS a kernel gets without asking)
+                const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW>)
+                                       : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW>);
+                hipError_t e2 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW));
+                if (e2 != hipSuccess) return e2;
+                return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW>, NW * 64, ring_bytes(TT, WL, NW))
+                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW>, NW * 64, ring_bytes(TT, WL, NW));
+            });
         if (e != hipSuccess) {
             (void)hipGetLastError();
-            *n_cus = 64;
-            return 64;  // not cached: a cautious figure for this call (e.g. no device in this process yet)
+            if (n_cus) *n_cus = 64;
+            return group ? 0 : 64;  // not cached: a cautious figure for this call (e.g. no device in this process yet)
         }
-        cached[tt][wlds] = per_cu * cus > 0 ? per_cu * cus : 64;
+        slot = per_cu * cus > 0 ? per_cu * cus : (group ? 0 : 64);
         cached_cus = cus > 0 ? cus : 64;
+        if (slot == 0) return 0;
     }
-    *n_cus = cached_cus;
-    return cached[tt][wlds];
+    if (n_cus) *n_cus = cached_cus;
+    return slot;
 }
+int resident_group_workgroups(const Variant &v) { return resident_of(v, true, nullptr); }
+int resident_workgroups(const Variant &v, int *n_cus) { return resident_of(v, false, n_cus); }
 
 // K-slices = owners per tile: 1, 2, 4 or 8.  All workgroups of the call have to be resident at once, and there are
 // never more than ELORA_DEC_TARGET_WGS of them.  If some split gives (nearly) exactly one workgroup per compute unit,
@@ -401,39 +398,62 @@ int pick_split(int K, int n_tiles, int resident, int n_cus)
 // per compute unit only: taken if that costs no workgroups, or if the call then has (nearly) one per unit; else W goes
 // into registers and two workgroups share a unit (measured at 64 rows, 4096 x 4096: 27.4 against 28.9 us; 14336 x 4096:
 // 53.9 against 60.8; 4096 x 14336, 224 tiles: 63.8 against 61.8).
+// With more than 32 rows the wide kernel (128 rows of W per workgroup) is taken where its grid covers at least seven
+// eighths of the compute units: every workgroup re-reads its K-slice of x, and twice the rows of W per workgroup
+// halve that share of what a compute unit has to take in.
 void finish_shape(DecodeShape &sh, int max_rank, int resident, int n_cus, bool surplus);
 
-DecodeShape make_shape(int T, int K, int N, int max_rank, bool *w_lds)
+int g_wide_mode = -1;  // -1: where it pays, 0: never, 1: wherever the shape allows it
+
+bool wide_allowed(int T) { return g_wide_mode != 0 && T > 32; }
+
+DecodeShape make_shape(int T, int K, int N, int max_rank, Variant *var)
 {
     DecodeShape sh;
     sh.T = T;
     sh.K = K;
     sh.N = N;
     sh.chunks = K / kChunk;
-    sh.n_tiles = (N + kTileRows - 1) / kTileRows;
     sh.jgroups = (max_rank + 1) / 2;
     sh.jg_inv = (unsigned)((1ull << 32) / (unsigned)sh.jgroups) + 1u;
     const int tt = (T + 15) / 16;
     int n_cus = 0;
-    bool wlds = true;
-    int resident = resident_workgroups(tt, true, &n_cus);
+    if (wide_allowed(T)) {
+        const Variant wide{4, true, 8};
+        const int resident = resident_workgroups(wide, &n_cus);
+        const int n_tiles = (N + wide.tile_rows() - 1) / wide.tile_rows();
+        const int split = pick_split(K, n_tiles, resident, n_cus);
+        if (n_tiles * split <= resident && (g_wide_mode == 1 || n_tiles * split * 8 >= n_cus * 7)) {
+            sh.tile_rows = wide.tile_rows();
+            sh.n_tiles = n_tiles;
+            sh.split = split;
+            *var = wide;
+            finish_shape(sh, max_rank, resident, n_cus, true);
+            return sh;
+        }
+    }
+    Variant v{tt, true, 4};
+    sh.tile_rows = v.tile_rows();
+    sh.n_tiles = (N + sh.tile_rows - 1) / sh.tile_rows;
+    int resident = resident_workgroups(v, &n_cus);
     sh.split = pick_split(K, sh.n_tiles, resident, n_cus);
     if (tt > 2) {
-        const int resident_r = resident_workgroups(tt, false, &n_cus);
+        const Variant r{tt, false, 4};
+        const int resident_r = resident_workgroups(r, &n_cus);
         const int split_r = pick_split(K, sh.n_tiles, resident_r, n_cus);
         const int wgs = sh.n_tiles * sh.split;
         if (split_r != sh.split && !(wgs <= n_cus && wgs * 20 >= n_cus * 19)) {
-            wlds = false;
+            v = r;
             resident = resident_r;
             sh.split = split_r;
         }
     }
-    *w_lds = wlds;
+    *var = v;
     finish_shape(sh, max_rank, resident, n_cus, true);
     return sh;
 }
 
-// everything that follows from T, K, N, jgroups and split
+// everything that follows from T, K, N, jgroups, tile_rows, n_tiles and split
 void finish_shape(DecodeShape &sh, int max_rank, int resident, int n_cus, bool surplus)
 {
     sh.lgS = 0;
@@ -451,13 +471,20 @@ void finish_shape(DecodeShape &sh, int max_rank, int resident, int n_cus, bool s
     }
     // the workgroups that share the shrink must all be running before anybody can wait for them
     sh.n_pub = sh.grid < resident ? sh.grid : resident;
-    sh.G = kGranules / sh.split;
+    sh.G = sh.tile_rows / 4 / sh.split;
     sh.lgG = 0;
     while ((1 << sh.lgG) < sh.G) ++sh.lgG;
     sh.lgRp = 0;
     while ((1 << sh.lgRp) < max_rank) ++sh.lgRp;
     sh.spin_limit = g_spin_limit;
     sh.zero = 0;
+    // the shortest K-slice has 2 * (chunks / split) sub-spans (up to 32 rows the turn did not pay: 15.6 -> 15.8 us)
+    sh.rot_mask = 0;
+    if (g_k_rotate && sh.T > 32) {
+        int pow2 = 1;
+        while (pow2 * 2 <= 2 * (sh.chunks / sh.split)) pow2 *= 2;
+        sh.rot_mask = pow2 - 1;
+    }
     int dev = 0;
     sh.local = (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices && g_local[dev] == 1 && g_local_override != 0) ? 1 : 0;
 }
@@ -495,29 +522,37 @@ int elora::decode_probe_device(hipStream_t stream)
 
 // Several decode calls with the same number of rows in one launch, if K-slice counts can be found with which all
 // their workgroups are resident together: starting from what each call would take alone, the call whose workgroups
-// have the least to stream gives up half of its K-slices until the sum fits.  W through LDS (one workgroup per
-// compute unit) is tried first, then (more than 32 rows) W into registers, which leaves room for two per unit.
-bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds)
+// have the least to stream gives up half of its K-slices until the sum fits.  More than 32 rows: the wide kernel is
+// tried first if its workgroups then cover at least seven eighths of the compute units; then W through LDS (one
+// workgroup per compute unit); then W into registers, which leaves room for two per unit.
+namespace {
+bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant *var)
 {
     if (n < 2 || n > kGroupMax || T < 1 || T > kDecodeMaxTokens) return false;
     const int tt = (T + 15) / 16;
-    for (int attempt = 0; attempt < (tt > 2 ? 2 : 1); ++attempt) {
-        const bool wlds = attempt == 0;
+    Variant cand[3];
+    int n_cand = 0;
+    if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8};
+    cand[n_cand++] = Variant{tt, true, 4};
+    if (tt > 2) cand[n_cand++] = Variant{tt, false, 4};
+    for (int attempt = 0; attempt < n_cand; ++attempt) {
+        const Variant v = cand[attempt];
         int n_cus = 0;
-        (void)resident_workgroups(tt, wlds, &n_cus);
-        const int resident = resident_group_workgroups(tt, wlds);
+        (void)resident_workgroups(v, &n_cus);
+        const int resident = resident_group_workgroups(v);
         if (resident <= 0) return false;
         int tiles[kGroupMax];
         auto grid_of = [&](int i) { return (tiles[i] * split[i] + kXcds * split[i] - 1) / (kXcds * split[i]) * (kXcds * split[i]); };
         for (int i = 0; i < n; ++i) {
-            tiles[i] = (N[i] + kTileRows - 1) / kTileRows;
+            tiles[i] = (N[i] + v.tile_rows() - 1) / v.tile_rows();
             split[i] = pick_split(K[i], tiles[i], resident, n_cus);
         }
         for (;;) {
             int total = 0;
             for (int i = 0; i < n; ++i) total += grid_of(i);
             if (total <= resident) {
-                *w_lds = wlds;
+                if (v.nw > 4 && g_wide_mode != 1 && total * 8 < n_cus * 7) break;  // too few workgroups: the next kind
+                *var = v;
                 return true;
             }
             int pick = -1;  // least K per workgroup; among equals the larger grid
@@ -533,23 +568,32 @@ bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *s
     }
     return false;
 }
+}  // namespace
+
+bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds)
+{
+    Variant v{1, true, 4};
+    const bool ok = group_splits(T, n, K, N, split, &v);
+    if (ok) *w_lds = v.wlds;
+    return ok;
+}
 
 // Returns ELORA_OK after the launch, -1 if the calls do not fit together (nothing enqueued).
 int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
 {
     if (n < 2 || n > kGroupMax) return -1;
-    const int T = a[0].T, tt = (T + 15) / 16;
+    const int T = a[0].T;
     int Ks[kGroupMax], Ns[kGroupMax], split[kGroupMax];
     for (int i = 0; i < n; ++i) {
         if (a[i].T != T) return -1;
         Ks[i] = a[i].K;
         Ns[i] = a[i].N;
     }
-    bool wlds = true;
-    if (!decode_group_splits(T, n, Ks, Ns, split, &wlds)) return -1;
+    Variant var{1, true, 4};
+    if (!group_splits(T, n, Ks, Ns, split, &var)) return -1;
     int n_cus = 0;
-    (void)resident_workgroups(tt, wlds, &n_cus);
-    const int resident = resident_group_workgroups(tt, wlds);
+    (void)resident_workgroups(var, &n_cus);
+    const int resident = resident_group_workgroups(var);
     DecodeGroup grp;
     grp.n = n;
     int first = 0;
@@ -560,7 +604,8 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
         c.sh.K = a[i].K;
         c.sh.N = a[i].N;
         c.sh.chunks = a[i].K / kChunk;
-        c.sh.n_tiles = (a[i].N + kTileRows - 1) / kTileRows;
+        c.sh.tile_rows = var.tile_rows();
+        c.sh.n_tiles = (a[i].N + c.sh.tile_rows - 1) / c.sh.tile_rows;
         c.sh.jgroups = (max_rank + 1) / 2;
         c.sh.jg_inv = (unsigned)((1ull << 32) / (unsigned)c.sh.jgroups) + 1u;
         c.sh.split = split[i];
@@ -579,20 +624,14 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
         first += c.sh.grid;
     }
     for (int i = n; i <= kGroupMax; ++i) grp.first[i] = first;
-    dim3 grid(first), block(kThreads);
+    dim3 grid(first), block(var.threads());
     profile_mark_begin(stream);
-    switch (tt) {
-    case 1: hipLaunchKernelGGL((decode_group_kernel<1, true>), grid, block, ring_bytes(1, true), stream, grp); break;
-    case 2: hipLaunchKernelGGL((decode_group_kernel<2, true>), grid, block, ring_bytes(2, true), stream, grp); break;
-    case 3:
-        if (wlds) hipLaunchKernelGGL((decode_group_kernel<3, true>), grid, block, ring_bytes(3, true), stream, grp);
-        else hipLaunchKernelGGL((decode_group_kernel<3, false>), grid, block, ring_bytes(3, false), stream, grp);
-        break;
-    default:
-        if (wlds) hipLaunchKernelGGL((decode_group_kernel<4, true>), grid, block, ring_bytes(4, true), stream, grp);
-        else hipLaunchKernelGGL((decode_group_kernel<4, false>), grid, block, ring_bytes(4, false), stream, grp);
-        break;
-    }
+    with_variant(var, [&](auto tt, auto wl, auto nw) {
+        constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
+        constexpr bool WL = decltype(wl)::value;
+        hipLaunchKernelGGL((decode_group_kernel<TT, WL, NW>), grid, block, ring_bytes(TT, WL, NW), stream, grp);
+        return 0;
+    });
     ELORA_HIP_TRY(hipGetLastError());
     profile_mark_end(stream);
     return ELORA_OK;
@@ -600,6 +639,8 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
 
 void elora::decode_set_spin_limit(int limit) { g_spin_limit = limit; }
 void elora::decode_set_local_override(int mode) { g_local_override = mode; }
+void elora::decode_set_k_rotate(int on) { g_k_rotate = on; }
+void elora::decode_set_wide(int mode) { g_wide_mode = mode; }
 
 #ifdef ELORA_TRACE
 extern "C" int elora_trace_read(long long *host_out, int n_values)
@@ -620,20 +661,22 @@ bool elora::decode_eligible(const elora_linear_desc_t &d, int max_rank)
            d.d_in % kChunk == 0 && d.d_out % 16 == 0;
 }
 
-// bytes of the piece mailboxes for d_out output columns: up to 8 K-slices, up to 64 rows
+// bytes of the piece mailboxes for d_out output columns: up to 8 K-slices, up to 64 rows (columns rounded up to
+// whole tiles of the widest kernel)
 size_t elora::decode_mail_bytes(int d_out)
 {
-    const size_t n_tiles = ((size_t)d_out + kTileRows - 1) / kTileRows;
-    return n_tiles * kDecodeMaxSplit * kDecodeMaxTokens * kTileRows * sizeof(float);
+    constexpr size_t wide_rows = 8 * kRowsPerWave;
+    const size_t n_tiles = ((size_t)d_out + wide_rows - 1) / wide_rows;
+    return n_tiles * kDecodeMaxSplit * kDecodeMaxTokens * wide_rows * sizeof(float);
 }
 
 void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 {
-    bool wlds = true;
-    DecodeShape sh = make_shape(d.n_tokens, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, &wlds);
+    Variant var{1, true, 4};
+    DecodeShape sh = make_shape(d.n_tokens, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, &var);
     plan->n_launches = 1;
     plan->split_k = sh.split;
-    plan->tile_rows = kTileRows;
+    plan->tile_rows = sh.tile_rows;
     plan->tile_cols = 0;
     plan->grid = sh.grid;
 }
@@ -641,8 +684,8 @@ void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream)
 {
     (void)plan;
-    bool wlds = true;
-    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, &wlds);
+    Variant var{1, true, 4};
+    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, &var);
     float *mail = reinterpret_cast<float *>(a.ws + a.wsl.mail);
     float *vmail = reinterpret_cast<float *>(a.ws + a.wsl.vmail);
     int *sync = reinterpret_cast<int *>(a.ws + a.wsl.sync);
@@ -650,21 +693,15 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     const uint16_t *W = static_cast<const uint16_t *>(a.W);
     uint16_t *y = static_cast<uint16_t *>(a.y);
     int has_pool = a.has_pool ? 1 : 0;
-    dim3 grid(sh.grid), block(kThreads);
-    int tt = (a.T + 15) / 16;
+    dim3 grid(sh.grid), block(var.threads());
     profile_mark_begin(stream);
-    switch (tt) {
-    case 1: hipLaunchKernelGGL((decode_kernel<1, true>), grid, block, ring_bytes(1, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<2, true>), grid, block, ring_bytes(2, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y); break;
-    case 3:
-        if (wlds) hipLaunchKernelGGL((decode_kernel<3, true>), grid, block, ring_bytes(3, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
-        else hipLaunchKernelGGL((decode_kernel<3, false>), grid, block, ring_bytes(3, false), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
-        break;
-    default:
-        if (wlds) hipLaunchKernelGGL((decode_kernel<4, true>), grid, block, ring_bytes(4, true), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
-        else hipLaunchKernelGGL((decode_kernel<4, false>), grid, block, ring_bytes(4, false), stream, sh, x, W, a.pool, a.route, has_pool, mail, vmail, sync, y);
-        break;
-    }
+    with_variant(var, [&](auto tt, auto wl, auto nw) {
+        constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
+        constexpr bool WL = decltype(wl)::value;
+        hipLaunchKernelGGL((decode_kernel<TT, WL, NW>), grid, block, ring_bytes(TT, WL, NW), stream, sh, x, W, a.pool, a.route, has_pool, mail,
+                           vmail, sync, y);
+        return 0;
+    });
     ELORA_HIP_TRY(hipGetLastError());
     profile_mark_end(stream);
     return ELORA_OK;

@@ -194,6 +194,20 @@ int elora_debug_xcd_local(int mode)
     return ELORA_OK;
 }
 
+int elora_debug_decode_wide(int mode)
+{
+    if (mode < -1 || mode > 1) return ELORA_E_SHAPE;
+    decode_set_wide(mode);
+    return ELORA_OK;
+}
+
+int elora_debug_k_rotate(int on)
+{
+    if (on != 0 && on != 1) return ELORA_E_SHAPE;
+    decode_set_k_rotate(on);
+    return ELORA_OK;
+}
+
 int elora_force_path(int path)
 {
     if (path < -1 || path > ELORA_PATH_GEMM) return ELORA_E_DTYPE;
