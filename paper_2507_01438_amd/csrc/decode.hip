@@ -71,6 +71,7 @@ constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kMetaLds = 512;  // slot tables up to this many entries are copied to LDS whole
 
 constexpr int kXcds = 8;                  // workgroup b runs on XCD b % 8
+template <int V> using ic = std::integral_constant<int, V>;
 
 // sync area (ints) at the start of the workspace
 constexpr int kCntAll = 0;        // XCDs all of whose workgroups have finished
@@ -215,7 +216,7 @@ __device__ __forceinline__ float *piece_ptr(float *mail, const DecodeShape &sh, 
 }
 
 // Columns [nc0, nc0 + ncols) of y for all rows, from the inputs alone (after a wait ran out): slow, exact.
-__device__ void recompute_columns(const DecodeShape &sh, const uint16_t *__restrict__ x, const uint16_t *__restrict__ W,
+__device__ __forceinline__ void recompute_columns(const DecodeShape &sh, const uint16_t *__restrict__ x, const uint16_t *__restrict__ W,
                                   const PoolView &pool, const RouteView &route, int has_pool, uint16_t *__restrict__ y,
                                   int nc0, int ncols, int wave, int n_waves, int lane)
 {
@@ -325,7 +326,6 @@ struct Variant {
     int lds() const { return ring_bytes(tt, wlds, nw); }
 };
 constexpr int kVariants = 11;
-template <int V> using ic = std::integral_constant<int, V>;
 template <typename F>
 auto with_variant(const Variant &v, F &&f)
 {
