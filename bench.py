@@ -231,7 +231,7 @@ def main():
             pool = B.AdapterPool(p.K, p.N, w.max_rank, w.pool, w.dtype, dev)
             for i, (A_d, B_d, sc) in dev_adapters[pi].items():
                 pool.load(i, A_d, B_d, sc)
-            lin = B.LoraLinear(p.K, p.N, w.dtype, pool, w.T, dev)
+            lin = B.LoraLinear(p.K, p.N, w.dtype, pool, w.T, dev, wfmt=w.wfmt)
             keep += [Wc, xc, yc, pool, lin]
             descs.append(lin.desc(xc, Wc, yc, adapter_idx=case.adapter_idx, seg_offsets=case.seg_offsets,
                                   seg_adapter=case.seg_adapter, wfmt=w.wfmt, w_scales=case.w_scales))

@@ -22,7 +22,8 @@
  *     is IEEE binary16.
  *   - Every function returns an elora_status_t (0 = success) unless it returns
  *     a size.  Nothing aborts, throws or prints.  On failure no work has been
- *     enqueued by that call and out-parameters are untouched.
+ *     enqueued by that call and out-parameters are untouched (the one exception, a
+ *     HIP error in the middle of a batch of loads, is stated where it applies).
  *   - All device work is enqueued on the caller's stream and the call returns
  *     without waiting.  Calls that use the same pool must be ordered by the
  *     caller (same stream, or events).
@@ -93,7 +94,8 @@ size_t elora_pool_storage_bytes(int d_in, int d_out, int max_rank, int capacity,
  * device memory: the pool's device-side slot table is cleared by the first
  * stream-carrying call on this pool (load / evict / linear), on that call's
  * stream.  *out receives the handle.
- * Errors: E_NULL, E_ALIGN, E_DTYPE, E_SHAPE, E_RANK (max_rank < 1 or > 256), E_STORAGE.
+ * Errors: E_NULL, E_ALIGN, E_DTYPE, E_SHAPE, E_RANK (max_rank < 1 or > 256), E_STORAGE (storage too small, or out of
+ * host memory).
  */
 int elora_pool_create(int d_in, int d_out, int max_rank, int capacity, int dtype,
                       void *dev_storage, size_t storage_bytes, elora_pool_t **out);
@@ -120,7 +122,9 @@ int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale,
  * multiples of 16 bytes, the GPU reads the sources itself and one launch per 16 adapters fills the blocks and
  * their table entries; otherwise the adapters are placed one by one as above.  Nothing enqueued on other streams
  * may read or write these blocks until this call's work on `stream` is done (elora_cache_load_begin / _end do
- * that ordering).  Errors: E_NULL, E_SHAPE (n < 0), E_SLOT (out of range, or one slot twice), E_RANK, E_HIP.
+ * that ordering).  Errors: E_NULL, E_SHAPE (n < 0), E_SLOT (out of range, or one slot twice), E_RANK: nothing is
+ * enqueued; E_HIP (a launch or copy failed): adapters earlier in the arrays may already be enqueued and count as
+ * loaded, the one that failed and those after it do not.
  */
 int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const int *ranks, const float *scales,
                              const void *const *A, const void *const *B, elora_stream_t stream);
@@ -195,8 +199,10 @@ int elora_cache_release(elora_cache_t *cache, int adapter_id);
  * (adapter_ids[t] < 0: no adapter, slots[t] = -1, not a request).  The adapters that have to be loaded come back
  * as miss_ids[0..*n_miss) / miss_slots[0..*n_miss), each once, in the order their blocks were assigned (room for
  * n entries each).  Later rows of the batch that name an adapter assigned by an earlier row count as hits.
- * On E_BUSY (more distinct adapters in flight than blocks) the requests this call had made are released again and
- * the arrays hold nothing of use; evictions it made on the way stay.  Errors: E_NULL, E_SHAPE (n < 0), E_BUSY.
+ * On E_BUSY (more distinct adapters in flight than blocks) the call is undone: its requests are released and not
+ * counted, and the adapters it had assigned blocks to are not cached afterwards (their blocks are free again: nothing
+ * was loaded into them); the arrays hold nothing of use.  Evictions it made on the way stay.
+ * Errors: E_NULL, E_SHAPE (n < 0), E_BUSY.
  */
 int elora_cache_acquire_batch(elora_cache_t *cache, const int *adapter_ids, int n, int *slots, int *miss_ids,
                               int *miss_slots, int *n_miss);
@@ -270,12 +276,16 @@ typedef struct {
     const float *scales;        /* NULL: each adapter's own scale; else device fp32, one per row (decode
                                    form) or one per segment (prefill form), replacing it */
     /* scratch (device) */
-    void *workspace;            /* >= elora_workspace_bytes(n_tokens, d_in, d_out, max_rank), 256-byte aligned */
+    void *workspace;            /* >= elora_workspace_bytes_w(n_tokens, d_in, d_out, max_rank, wfmt), 256-byte aligned */
     size_t workspace_bytes;
 } elora_linear_desc_t;
 
-/* Device scratch one call may use, for up to n_tokens_max rows.  0 if an argument is invalid. */
+/* Device scratch one call may use, for up to n_tokens_max rows, with W in the dtype of x (ELORA_W_SAME).
+ * 0 if an argument is invalid. */
 size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank);
+/* The same for a given weight format (elora_wfmt_t): with a 4-bit W and 768 rows or more the workspace also holds the
+ * call's bf16 copy of W (d_out x d_in x 2 bytes). */
+size_t elora_workspace_bytes_w(int n_tokens_max, int d_in, int d_out, int max_rank, int wfmt);
 
 /*
  * A workspace must be initialised ONCE, over its whole size, before its first use in a linear call.
@@ -284,14 +294,18 @@ size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank
  * writes the idle state (one fill kernel on `stream`), and every linear call leaves the workspace idle
  * again.  Call it again only after a call that used the workspace was aborted (device reset).
  * Two calls that may run at the same time (different streams) need different workspaces.
+ * A workspace serves ONE d_out: the first linear call after its initialisation ties it to that call's d_out (the
+ * mailboxes' size follows d_out and what other kernels write lies behind them), and calls with another d_out are
+ * refused with E_STORAGE until it is initialised again.  d_in, the row count and the pool may vary from call to call.
  * Calls on the decode path should not run at the same time at all: the workgroups of such a call wait for each
  * other, which takes all of them to be on the device together, and two such launches that each hold part of the
- * compute units keep each other's remaining workgroups out.  Every wait is bounded (a workgroup whose wait runs out
- * computes what it needs from the inputs, see elora_debug_spin_limit), so the results stay right, but the calls
- * then take seconds.  Issue them on one stream, or as one group (elora_batched_lora_linear_group); kernels
+ * compute units keep each other's remaining workgroups out.  Every wait is bounded in time (about 200 us: a
+ * workgroup whose wait runs out computes what it needs from the inputs, see elora_debug_wait_limit_us), so the
+ * results stay right, but such calls are slow.  Issue them on one stream, or as one group (elora_batched_lora_linear_group); kernels
  * that do not fill the device (adapter loads, copies) may overlap them freely.
  * The first call on a device also finds out how the device places workgroups on its XCDs (one tiny
- * launch, a small temporary allocation and a wait for `stream`): set-up work, not to be captured in a graph.
+ * launch into the workspace that is being initialised, a 1 KiB copy to the host and a wait for `stream`): set-up
+ * work, not to be captured in a graph.  No device memory is allocated.
  * Errors: E_NULL, E_ALIGN, E_STORAGE, E_HIP.
  */
 int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t stream);
@@ -309,7 +323,7 @@ typedef struct {
  * Validate a descriptor exactly as elora_batched_lora_linear does (everything
  * that can be checked on the host without touching the device) and report
  * which kernels the call would run.  Touches no device memory.
- * Errors: E_NULL, E_ALIGN, E_DTYPE, E_SHAPE, E_SEGMENTS, E_STORAGE.
+ * Errors: E_NULL, E_ALIGN, E_DTYPE, E_SHAPE, E_SEGMENTS, E_STORAGE (workspace too small, or tied to another d_out).
  */
 int elora_linear_plan(const elora_linear_desc_t *desc, elora_plan_t *plan);
 
@@ -353,6 +367,13 @@ int elora_force_path(int path);
  * that route at once.  Default 4194304.  Errors: E_SHAPE (limit < 0).
  */
 int elora_debug_spin_limit(int limit);
+
+/*
+ * The bound that ends such a wait in practice is one in time: about `us` microseconds (default 200; the clock is
+ * looked at every 64 polls, so a wait may last a few tens of microseconds longer), whatever a poll costs on the
+ * machine and however busy it is.  Errors: E_SHAPE (us < 1 or > 10000000).
+ */
+int elora_debug_wait_limit_us(int us);
 
 /*
  * Test hook: 0 makes the decode kernel run as if the device gave no guarantee that the workgroups

@@ -63,6 +63,34 @@ class LruCacheOracle:
         self.pins[adapter_id] = 1
         return blk, False, evicted
 
+    def acquire_batch(self, adapter_ids):
+        """The requests of one batch in order (negative id: no request).  Returns (blocks per row, misses as
+        (adapter id, block) in the order the blocks were assigned), or BUSY with the call undone: its requests
+        released and not counted, the adapters it had assigned blocks to no longer cached (nothing was loaded into
+        those blocks), their blocks back on the stack, last assigned first; evictions made on the way stay."""
+        hits0, requests0 = self.hits, self.requests
+        blocks, misses, done = [], [], []
+        for a in adapter_ids:
+            a = int(a)
+            if a < 0:
+                blocks.append(-1)
+                continue
+            blk, hit, _ = self.acquire(a)
+            if blk is None:
+                for d in done:
+                    self.release(d)
+                for m, _b in reversed(misses):
+                    self.order.remove(m)
+                    self.free.append(self.block.pop(m))
+                    del self.pins[m]
+                self.hits, self.requests = hits0, requests0
+                return BUSY
+            done.append(a)
+            blocks.append(blk)
+            if not hit:
+                misses.append((a, blk))
+        return blocks, misses
+
     def release(self, adapter_id: int) -> bool:
         if self.pins.get(adapter_id, 0) <= 0:
             return False

@@ -35,9 +35,9 @@ ELORA_PATH_GENERIC, ELORA_PATH_DECODE, ELORA_PATH_GEMM = 0, 1, 2
 EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
     "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_load_adapters_q8", "elora_pool_evict", "elora_pool_slot_info",
-    "elora_pool_poll_error", "elora_workspace_bytes", "elora_linear_plan", "elora_batched_lora_linear",
+    "elora_pool_poll_error", "elora_workspace_bytes", "elora_workspace_bytes_w", "elora_linear_plan", "elora_batched_lora_linear",
     "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
-    "elora_debug_spin_limit", "elora_debug_xcd_local", "elora_debug_k_rotate", "elora_debug_decode_wide",
+    "elora_debug_spin_limit", "elora_debug_xcd_local", "elora_debug_k_rotate", "elora_debug_decode_wide", "elora_debug_wait_limit_us",
     "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
     "elora_cache_acquire_batch", "elora_cache_release_batch", "elora_cache_select",
     "elora_cache_drop", "elora_cache_stats", "elora_cache_reset_stats", "elora_cache_load_begin",
@@ -89,6 +89,8 @@ lib.elora_pool_poll_error.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POIN
                                       ctypes.POINTER(ctypes.c_int), ctypes.c_void_p]
 lib.elora_workspace_bytes.restype = ctypes.c_size_t
 lib.elora_workspace_bytes.argtypes = [ctypes.c_int] * 4
+lib.elora_workspace_bytes_w.restype = ctypes.c_size_t
+lib.elora_workspace_bytes_w.argtypes = [ctypes.c_int] * 5
 lib.elora_linear_plan.restype = ctypes.c_int
 lib.elora_linear_plan.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.POINTER(elora_plan_t)]
 lib.elora_batched_lora_linear.restype = ctypes.c_int
@@ -107,6 +109,8 @@ lib.elora_debug_spin_limit.restype = ctypes.c_int
 lib.elora_debug_spin_limit.argtypes = [ctypes.c_int]
 lib.elora_debug_xcd_local.restype = ctypes.c_int
 lib.elora_debug_xcd_local.argtypes = [ctypes.c_int]
+lib.elora_debug_wait_limit_us.restype = ctypes.c_int
+lib.elora_debug_wait_limit_us.argtypes = [ctypes.c_int]
 lib.elora_debug_decode_wide.restype = ctypes.c_int
 lib.elora_debug_decode_wide.argtypes = [ctypes.c_int]
 lib.elora_debug_k_rotate.restype = ctypes.c_int
@@ -247,6 +251,10 @@ def elora_workspace_bytes(n_tokens_max: int, d_in: int, d_out: int, max_rank: in
     return int(lib.elora_workspace_bytes(n_tokens_max, d_in, d_out, max_rank))
 
 
+def elora_workspace_bytes_w(n_tokens_max: int, d_in: int, d_out: int, max_rank: int, wfmt: int) -> int:
+    return int(lib.elora_workspace_bytes_w(n_tokens_max, d_in, d_out, max_rank, wfmt))
+
+
 def make_desc(*, n_tokens, d_in, d_out, dtype, x, W, y, workspace, workspace_bytes, wfmt=ELORA_W_SAME,
               w_scales=None, pool=None, adapter_idx=None, seg_offsets=None, seg_adapter=None, n_segments=0,
               scales=None) -> elora_linear_desc_t:
@@ -305,6 +313,10 @@ def elora_debug_spin_limit(limit: int) -> None:
 
 def elora_debug_xcd_local(mode: int) -> None:
     _check(lib.elora_debug_xcd_local(int(mode)), "elora_debug_xcd_local")
+
+
+def elora_debug_wait_limit_us(us: int) -> None:
+    _check(lib.elora_debug_wait_limit_us(int(us)), "elora_debug_wait_limit_us")
 
 
 def elora_debug_decode_wide(mode: int) -> None:
@@ -473,10 +485,10 @@ class AdapterPool:
 class LoraLinear:
     """Pre-allocated workspace + descriptor assembly for repeated calls on one layer."""
 
-    def __init__(self, d_in, d_out, dtype, pool: Optional[AdapterPool], n_tokens_max, device="cuda:0"):
+    def __init__(self, d_in, d_out, dtype, pool: Optional[AdapterPool], n_tokens_max, device="cuda:0", wfmt=ELORA_W_SAME):
         self.d_in, self.d_out, self.dtype, self.pool = d_in, d_out, dtype, pool
         self.n_tokens_max = n_tokens_max
-        self.ws_bytes = elora_workspace_bytes(n_tokens_max, d_in, d_out, pool.max_rank if pool else 1)
+        self.ws_bytes = elora_workspace_bytes_w(n_tokens_max, d_in, d_out, pool.max_rank if pool else 1, wfmt)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
         elora_workspace_init(self.workspace, self.ws_bytes)
 

@@ -146,6 +146,7 @@ int elora_cache_acquire_batch(elora_cache_t *c, const int *adapter_ids, int n, i
     if (!c || !n_miss || (n > 0 && (!adapter_ids || !slots || !miss_ids || !miss_slots))) return ELORA_E_NULL;
     if (n < 0) return ELORA_E_SHAPE;
     int misses = 0;
+    const long long hits0 = c->hits, requests0 = c->requests;
     for (int t = 0; t < n; ++t) {
         if (adapter_ids[t] < 0) {
             slots[t] = -1;
@@ -154,8 +155,23 @@ int elora_cache_acquire_batch(elora_cache_t *c, const int *adapter_ids, int n, i
         int hit = 0, evicted = -1;
         const int rc = elora_cache_acquire(c, adapter_ids[t], &slots[t], &hit, &evicted);
         if (rc != ELORA_OK) {
+            // Undo what this call did: its requests are released and not counted, and the adapters it had assigned
+            // blocks to leave the cache again (nothing was ever loaded into those blocks: a later request for one of
+            // them must not be a hit).  Their blocks go back on the stack, last assigned first.
             for (int u = 0; u < t; ++u)
                 if (adapter_ids[u] >= 0) (void)elora_cache_release(c, adapter_ids[u]);
+            for (int i = misses - 1; i >= 0; --i) {
+                auto it = c->block_of.find(miss_ids[i]);
+                if (it == c->block_of.end()) continue;
+                const int b = it->second;
+                c->block_of.erase(it);
+                c->unlink(b);
+                c->id[b] = -1;
+                c->pins[b] = 0;
+                c->free_stack.push_back(b);
+            }
+            c->hits = hits0;
+            c->requests = requests0;
             return rc;
         }
         if (!hit) {
@@ -237,24 +253,21 @@ int elora_cache_select(const elora_cache_t *c, int explicit_id, const float *sco
         if (!na && sa != sb) return sa > sb;
         return a < b;
     };
-    // the k best, in order: k passes of selection (k is small, Sec. 5: three)
-    std::vector<int> top;
-    top.reserve(k);
-    int last = -1;
+    // the k best, in order: k passes of selection (k is small, Sec. 5: three), each looked up as it is found
+    int last = -1, first = -1;
     for (int r = 0; r < k; ++r) {
         int best = -1;
         for (int j = 0; j < n; ++j)
             if ((last < 0 || better(last, j)) && (best < 0 || better(j, best))) best = j;
-        top.push_back(best);
-        last = best;
-    }
-    for (int j : top)
-        if (c->block_of.count(j)) {
-            *chosen = j;
+        if (r == 0) first = best;
+        if (c->block_of.count(best)) {
+            *chosen = best;
             *resident = 1;
             return ELORA_OK;
         }
-    *chosen = top[0];
+        last = best;
+    }
+    *chosen = first;
     *resident = 0;
     return ELORA_OK;
 }

@@ -63,7 +63,7 @@ constexpr int kDecodeMaxSplit = 8;    // K-splits of the base contraction
 constexpr int kMaxRank = 256;
 constexpr int kSyncInts = 1024;       // ints in the workspace's counter area
 
-WsLayout ws_layout(int n_tokens, int d_in, int d_out, int max_rank);
+WsLayout ws_layout(int n_tokens, int d_in, int d_out, int max_rank, int wfmt);
 
 // ---- host-side pool object --------------------------------------------------
 
@@ -103,10 +103,11 @@ int launch_decode_group(const LinearArgs *a, int n, hipStream_t stream);  // -1:
 bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds);  // K-slices per call if they fit
 
 void decode_set_spin_limit(int limit);
+void decode_set_wait_us(int us);
 void decode_set_wide(int mode);    // -1: 128-row tiles where they pay, 0: never, 1: wherever the shape allows
 void decode_set_k_rotate(int on);  // 0: every workgroup walks its K-slice from the start
 void decode_set_local_override(int mode);  // 0: never assume XCD-local hand-overs, -1: as probed
-int decode_probe_device(hipStream_t stream);  // finds out, once per device, how workgroups are placed on the XCDs
+int decode_probe_device(void *scratch, size_t scratch_bytes, hipStream_t stream);  // finds out, once per device, how workgroups are placed on the XCDs
 bool decode_eligible(const elora_linear_desc_t &d, int max_rank);
 void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
 size_t decode_mail_bytes(int d_out);  // mailboxes of the decode kernel for d_out output columns

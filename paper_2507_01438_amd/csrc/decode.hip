@@ -79,6 +79,7 @@ constexpr int kCntXcd = 32;       // + 32 x (a cache line of its own): workgroup
 constexpr int kGaveUp = 1 << 16;  // this much for every owner on XCD x that gave up (its piece mailboxes may hold pieces nobody took)
 
 int g_spin_limit = 1 << 22;
+int g_wait_us = 200;
 int g_local_override = -1;
 int g_k_rotate = 1;
 constexpr int kMaxDevices = 64;
@@ -127,6 +128,7 @@ struct DecodeShape {
     int spin_limit;
     int zero;       // 0
     int local;      // 1: workgroup b runs on XCD b % 8 (checked once per device), so a tile's workgroups share an L2
+    int wait_ticks; // a wait for another workgroup gives up after this many ticks of the 100 MHz clock
     int tile_rows;  // rows of W per tile: 64 (four waves) or 128 (the wide kernel, eight waves)
     int rot_mask;   // a workgroup starts its K-slice (tile number on its XCD & rot_mask) sub-spans in: 2^n - 1, below every slice's length
 };
@@ -477,6 +479,7 @@ void finish_shape(DecodeShape &sh, int max_rank, int resident, int n_cus, bool s
     sh.lgRp = 0;
     while ((1 << sh.lgRp) < max_rank) ++sh.lgRp;
     sh.spin_limit = g_spin_limit;
+    sh.wait_ticks = g_wait_us * 100;
     sh.zero = 0;
     // the shortest K-slice has 2 * (chunks / split) sub-spans (up to 32 rows the turn did not pay: 15.6 -> 15.8 us)
     sh.rot_mask = 0;
@@ -495,20 +498,21 @@ __global__ void xcc_probe_kernel(int *xcc_of_block) { xcc_of_block[blockIdx.x] =
 }  // namespace
 
 // One small launch and a blocking copy: called from set-up code (workspace initialisation), never from a linear call.
-int elora::decode_probe_device(hipStream_t stream)
+// `scratch`: device memory the probe may overwrite (a corner of the workspace that is being initialised); with less
+// than 1 KiB of it the device stays unprobed (such a workspace is too small for the decode kernel anyway).
+int elora::decode_probe_device(void *scratch, size_t scratch_bytes, hipStream_t stream)
 {
     int dev = 0;
     ELORA_HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices || g_local[dev] != 0) return ELORA_OK;
     constexpr int n = 256;
-    int *d = nullptr;
     int h[n];
-    ELORA_HIP_TRY(hipMalloc(&d, sizeof(h)));
+    if (scratch == nullptr || scratch_bytes < sizeof(h)) return ELORA_OK;
+    int *d = static_cast<int *>(scratch);
     hipLaunchKernelGGL(xcc_probe_kernel, dim3(n), dim3(64), 0, stream, d);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(h, d, sizeof(h), hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
-    (void)hipFree(d);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return ELORA_E_HIP;
@@ -638,6 +642,7 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
 }
 
 void elora::decode_set_spin_limit(int limit) { g_spin_limit = limit; }
+void elora::decode_set_wait_us(int us) { g_wait_us = us; }
 void elora::decode_set_local_override(int mode) { g_local_override = mode; }
 void elora::decode_set_k_rotate(int on) { g_k_rotate = on; }
 void elora::decode_set_wide(int mode) { g_wide_mode = mode; }

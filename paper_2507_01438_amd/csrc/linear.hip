@@ -1,4 +1,6 @@
 // Host side of elora_batched_lora_linear: validation, workspace layout, kernel-family selection.
+#include <unordered_map>
+
 #include "common.h"
 
 using namespace elora;
@@ -8,6 +10,12 @@ namespace {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 int g_forced_path = -1;
+
+// Which d_out a workspace serves.  The mailboxes of the decode kernel sit at the start of a workspace and their size
+// follows d_out; what the other kernels write lies behind them.  A call with a smaller d_out would write into the
+// area a decode call with a larger one takes for mailboxes, so a workspace is tied to the d_out of the first call that
+// uses it after its initialisation, and calls with another one are refused.
+std::unordered_map<const void *, int> g_ws_d_out;
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -41,7 +49,7 @@ void elora::profile_mark_end(hipStream_t stream)
         if (hipEventRecord(g_prof_events[2 * g_prof_ended + 1], stream) == hipSuccess) ++g_prof_ended;
 }
 
-WsLayout elora::ws_layout(int T, int K, int N, int R)
+WsLayout elora::ws_layout(int T, int K, int N, int R, int wfmt)
 {
     WsLayout l;
     size_t t = (size_t)(T > 0 ? T : 1);
@@ -64,7 +72,7 @@ WsLayout elora::ws_layout(int T, int K, int N, int R)
     off += align_up(v_full > v_gemm ? v_full : v_gemm);
     // last, and zero bytes for small row counts: a workspace sized for more rows holds every smaller layout
     l.wdeq = off;
-    l.wdeq_bytes = gemm_w4_bytes(T, K, N);
+    l.wdeq_bytes = wfmt == ELORA_W_INT4_G32 ? gemm_w4_bytes(T, K, N) : 0;
     off += align_up(l.wdeq_bytes);
     l.total = off;
     return l;
@@ -95,8 +103,10 @@ static int validate(const elora_linear_desc_t *d, WsLayout *wsl_out)
     if (!aligned16(d->x) || !aligned16(d->W) || !aligned16(d->y)) return ELORA_E_ALIGN;
     if (d->w_scales != nullptr && !aligned16(d->w_scales)) return ELORA_E_ALIGN;
     if (reinterpret_cast<uintptr_t>(d->workspace) % kAlign) return ELORA_E_ALIGN;
-    WsLayout wsl = ws_layout(d->n_tokens, d->d_in, d->d_out, max_rank);
+    WsLayout wsl = ws_layout(d->n_tokens, d->d_in, d->d_out, max_rank, d->wfmt);
     if (d->workspace_bytes < wsl.total) return ELORA_E_STORAGE;
+    const auto bound = g_ws_d_out.find(d->workspace);
+    if (bound != g_ws_d_out.end() && bound->second != d->d_out) return ELORA_E_STORAGE;
     if (wsl_out) *wsl_out = wsl;
     return ELORA_OK;
 }
@@ -152,10 +162,16 @@ const char *elora_status_string(int status)
 
 int elora_version(void) { return 1; }
 
-size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank)
+size_t elora_workspace_bytes_w(int n_tokens_max, int d_in, int d_out, int max_rank, int wfmt)
 {
     if (n_tokens_max < 0 || d_in <= 0 || d_out <= 0 || max_rank < 1 || max_rank > kMaxRank) return 0;
-    return ws_layout(n_tokens_max, d_in, d_out, max_rank).total;
+    if (wfmt != ELORA_W_SAME && wfmt != ELORA_W_INT4_G32) return 0;
+    return ws_layout(n_tokens_max, d_in, d_out, max_rank, wfmt).total;
+}
+
+size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank)
+{
+    return elora_workspace_bytes_w(n_tokens_max, d_in, d_out, max_rank, ELORA_W_SAME);
 }
 
 namespace {
@@ -172,18 +188,30 @@ int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t
     if (workspace == nullptr) return ELORA_E_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return ELORA_E_ALIGN;
     if (workspace_bytes < align_up(sizeof(int) * kSyncInts)) return ELORA_E_STORAGE;
+    g_ws_d_out.erase(workspace);  // free again for any d_out
+    // (before the fill: the probe borrows a corner of this workspace)
+    const int rc = decode_probe_device(static_cast<char *>(workspace) + align_up(sizeof(int) * kSyncInts),
+                                       workspace_bytes - align_up(sizeof(int) * kSyncInts), static_cast<hipStream_t>(stream));
+    if (rc != ELORA_OK) return rc;
     const size_t n_words = workspace_bytes / sizeof(uint32_t);
     const size_t blocks = (n_words + 255) / 256;
     hipLaunchKernelGGL(ws_init_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<uint32_t *>(workspace), n_words, (size_t)kSyncInts);
     ELORA_HIP_TRY(hipGetLastError());
-    return decode_probe_device(static_cast<hipStream_t>(stream));
+    return ELORA_OK;
 }
 
 int elora_debug_spin_limit(int limit)
 {
     if (limit < 0) return ELORA_E_SHAPE;
     decode_set_spin_limit(limit);
+    return ELORA_OK;
+}
+
+int elora_debug_wait_limit_us(int us)
+{
+    if (us < 1 || us > 10000000) return ELORA_E_SHAPE;
+    decode_set_wait_us(us);
     return ELORA_OK;
 }
 
@@ -255,6 +283,17 @@ int elora_linear_plan(const elora_linear_desc_t *desc, elora_plan_t *plan)
     return ELORA_OK;
 }
 
+// ties the workspace of a validated descriptor to its d_out (see g_ws_d_out)
+static int bind_workspace(const elora_linear_desc_t *d)
+{
+    try {
+        g_ws_d_out.emplace(d->workspace, d->d_out);
+    } catch (...) {  // out of host memory
+        return ELORA_E_STORAGE;
+    }
+    return ELORA_OK;
+}
+
 // everything a launch needs of a validated descriptor
 static int fill_args(const elora_linear_desc_t *d, const WsLayout &wsl, hipStream_t stream, LinearArgs &a)
 {
@@ -292,6 +331,8 @@ int elora_batched_lora_linear(const elora_linear_desc_t *d, elora_stream_t strea
     if (rc != ELORA_OK) return rc;
     if (d->n_tokens == 0) return ELORA_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    rc = bind_workspace(d);
+    if (rc != ELORA_OK) return rc;
     elora_plan_t plan;
     make_plan(d, &plan);
     LinearArgs a;
@@ -326,7 +367,8 @@ int elora_batched_lora_linear_group(const elora_linear_desc_t *descs, int n, elo
         if (!together) break;
         WsLayout wsl;
         (void)validate(&descs[i], &wsl);
-        const int rc = fill_args(&descs[i], wsl, stream, a[i]);
+        int rc = bind_workspace(&descs[i]);
+        if (rc == ELORA_OK) rc = fill_args(&descs[i], wsl, stream, a[i]);
         if (rc != ELORA_OK) return rc;
     }
     if (together) {

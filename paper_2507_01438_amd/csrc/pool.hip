@@ -168,11 +168,11 @@ int elora_pool_create(int d_in, int d_out, int max_rank, int capacity, int dtype
     if (storage_bytes < need) return ELORA_E_STORAGE;
 
     elora_pool *p = new (std::nothrow) elora_pool;
-    if (p == nullptr) return ELORA_E_NULL;
+    if (p == nullptr) return ELORA_E_STORAGE;  // out of host memory
     p->host_meta = new (std::nothrow) SlotMeta[capacity];
     if (p->host_meta == nullptr) {
         delete p;
-        return ELORA_E_NULL;
+        return ELORA_E_STORAGE;
     }
     for (int i = 0; i < capacity; ++i) p->host_meta[i] = SlotMeta{0, 0.0f, 0, 0};
     size_t e = elem_bytes(dtype);
@@ -315,7 +315,17 @@ int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, con
             if (slots[j] == slots[i]) return ELORA_E_SLOT;
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    // every source must be readable by the device (device memory or pinned host memory), codes 8-byte aligned
+    // every source must be readable by the device (device memory or pinned host memory), codes 8-byte aligned:
+    // all of them are looked at before anything is enqueued
+    for (int i = 0; i < n; ++i) {
+        bool dev = false;
+        const void *a = device_readable(A_codes[i], &dev), *as = device_readable(A_scales[i], &dev);
+        const void *b = device_readable(B_codes[i], &dev), *bs = device_readable(B_scales[i], &dev);
+        if (!a || !as || !b || !bs) return ELORA_E_ALIGN;
+        if (reinterpret_cast<uintptr_t>(a) % 8 || reinterpret_cast<uintptr_t>(b) % 8 || reinterpret_cast<uintptr_t>(as) % 2 ||
+            reinterpret_cast<uintptr_t>(bs) % 2)
+            return ELORA_E_ALIGN;
+    }
     for (int i0 = 0; i0 < n; i0 += kLoadBatch) {
         LoadBatchQ8 lb;
         lb.n = n - i0 < kLoadBatch ? n - i0 : kLoadBatch;

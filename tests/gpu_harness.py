@@ -52,7 +52,7 @@ class DeviceCase:
             self.pool.load(int(i), torch.from_numpy(A.view(np.int16) if A.dtype == np.uint16 else A),
                            torch.from_numpy(Bm.view(np.int16) if Bm.dtype == np.uint16 else Bm), s)
         torch.cuda.synchronize()
-        self.lin = B.LoraLinear(proj.K, proj.N, w.dtype, self.pool, n_tokens_max or max(w.T, 1), DEV)
+        self.lin = B.LoraLinear(proj.K, proj.N, w.dtype, self.pool, n_tokens_max or max(w.T, 1), DEV, wfmt=w.wfmt)
         self.y = torch.zeros((max(w.T, 1), proj.N), dtype=torch.float32 if w.dtype == I.F32 else torch.int16, device=DEV)
         self.adapter_idx = None if w.adapter_idx is None else to_dev(w.adapter_idx)
         self.seg_offsets = None if w.seg_offsets is None else to_dev(w.seg_offsets)

@@ -153,7 +153,18 @@ def test_workspace_grows_with_rows_and_holds_the_copy_of_a_4bit_w(B):
     # a workspace sized for more rows must hold the layout of every smaller call; from 768 rows on it also holds
     # a bf16 copy of W (d_out x d_in x 2 bytes) for the 4-bit path
     K, N, R = 1024, 768, 16
-    sizes = [B.elora_workspace_bytes(t, K, N, R) for t in (1, 64, 65, 767, 768, 769, 4096)]
+    sizes = [B.elora_workspace_bytes_w(t, K, N, R, B.ELORA_W_INT4_G32) for t in (1, 64, 65, 767, 768, 769, 4096)]
     assert all(a <= b for a, b in zip(sizes, sizes[1:]))
     assert sizes[4] - sizes[3] >= K * N * 2
     assert sizes[5] - sizes[4] < 4096
+    # a W in the dtype of x needs no such copy: the workspace stays small at any row count
+    same = [B.elora_workspace_bytes(t, K, N, R) for t in (1, 64, 65, 767, 768, 769, 4096)]
+    assert all(a <= b for a, b in zip(same, same[1:]))
+    assert same[4] - same[3] < 4096 and same[:4] == sizes[:4]
+    assert same == [B.elora_workspace_bytes_w(t, K, N, R, B.ELORA_W_SAME) for t in (1, 64, 65, 767, 768, 769, 4096)]
+    assert B.elora_workspace_bytes_w(64, K, N, R, 7) == 0
+    # a 4-bit call with the smaller workspace is refused
+    d = _desc(B, None, n_tokens=768, d_in=K, d_out=N, wfmt=B.ELORA_W_INT4_G32, w_scales=FAKE, workspace_bytes=same[4])
+    assert _plan_status(B, d) == B.ELORA_E_STORAGE
+    d = _desc(B, None, n_tokens=768, d_in=K, d_out=N, wfmt=B.ELORA_W_INT4_G32, w_scales=FAKE, workspace_bytes=sizes[4])
+    assert _plan_status(B, d) == B.ELORA_OK

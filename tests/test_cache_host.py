@@ -140,8 +140,41 @@ def test_batches_of_rows_match_the_oracle(B):
     with pytest.raises(B.EloraError) as e:
         B.elora_cache_acquire_batch(c, too_many, *big)
     assert e.value.status == B.ELORA_E_BUSY
-    for a in too_many[:capacity]:
-        B.elora_cache_drop(c, int(a))                  # droppable: not pinned
+    assert ref.acquire_batch(too_many) == BUSY
+    # the refused call is undone: none of its adapters is cached (nothing was loaded into the blocks it had assigned),
+    # a later request for one of them is a miss, and its requests were not counted
+    for a in too_many:
+        assert B.elora_cache_lookup(c, int(a)) == -1 == ref.lookup(int(a))
+    assert B.elora_cache_stats(c) == (ref.hits, ref.requests, ref.evictions)
+    slot, hit, _ = B.elora_cache_acquire(c, int(too_many[0]))
+    want_slot, want_hit, _ = ref.acquire(int(too_many[0]))
+    assert (slot, hit) == (want_slot, want_hit) == (want_slot, False)
+    B.elora_cache_release(c, int(too_many[0]))
+    B.elora_cache_destroy(c)
+
+
+def test_a_refused_batch_leaves_no_adapter_behind(B):
+    # capacity 2, three distinct adapters in one batch: the third finds both blocks pinned
+    c = B.elora_cache_create(2)
+    ids = np.array([7, 8, 9], dtype=np.int32)
+    out = [np.zeros(3, np.int32) for _ in range(3)]
+    with pytest.raises(B.EloraError) as e:
+        B.elora_cache_acquire_batch(c, ids, *out)
+    assert e.value.status == B.ELORA_E_BUSY
+    assert [B.elora_cache_lookup(c, a) for a in (7, 8, 9)] == [-1, -1, -1]
+    assert B.elora_cache_stats(c) == (0, 0, 0)
+    assert B.elora_cache_acquire(c, 7) == (0, False, -1)      # block 0 comes off the stack first again, and it is a miss
+    assert B.elora_cache_acquire(c, 8) == (1, False, -1)
+    assert B.elora_cache_stats(c) == (0, 2, 0)
+    # with adapters cached before: they stay, a miss of the refused batch that evicted one of them does not
+    B.elora_cache_release(c, 7)
+    B.elora_cache_release(c, 8)
+    with pytest.raises(B.EloraError):
+        B.elora_cache_acquire_batch(c, np.array([7, 20, 21], dtype=np.int32), *out)   # 20 evicts 8, 21 finds none
+    assert B.elora_cache_lookup(c, 7) == 0 and B.elora_cache_lookup(c, 8) == -1
+    assert B.elora_cache_lookup(c, 20) == -1 and B.elora_cache_lookup(c, 21) == -1
+    assert B.elora_cache_stats(c) == (0, 2, 1)
+    assert B.elora_cache_acquire(c, 20) == (1, False, -1)     # the freed block, as a miss
     B.elora_cache_destroy(c)
 
 

@@ -140,3 +140,21 @@ def test_selection_against_an_independent_formulation(seed):
         want = max(eligible, key=lambda j: scores[j]) if eligible else int(np.argmax(scores))
         assert select_adapter(cached, -1, scores, k) == want
         assert select_adapter(cached, -1, scores, 1) == int(np.argmax(scores))   # k = 1: the availability is not looked at
+
+
+def test_a_refused_batch_is_undone_by_hand():
+    # two blocks, a batch naming three adapters: the third finds both pinned.  Worked by hand: afterwards nothing is
+    # cached, both blocks are free (0 comes off first again), nothing was counted.
+    c = LruCacheOracle(2)
+    assert c.acquire_batch([7, 8, 9]) == BUSY
+    assert (c.block, c.order, c.pins, c.free) == ({}, [], {}, [1, 0])
+    assert (c.hits, c.requests, c.evictions) == (0, 0, 0)
+    # a batch that fits: rows 0 and 2 share an adapter (the second is a hit), row 1 has none
+    assert c.acquire_batch([7, -1, 7, 8]) == ([0, -1, 0, 1], [(7, 0), (8, 1)])
+    assert (c.hits, c.requests) == (1, 3)
+    for a in (7, 7, 8):
+        assert c.release(a)
+    # 7 stays (a hit), 20 evicts 8 (least recently used of the unpinned), 21 finds nothing: undone, but the eviction stays
+    assert c.acquire_batch([7, 20, 21]) == BUSY
+    assert c.block == {7: 0} and c.free == [1] and c.pins == {7: 0}
+    assert (c.hits, c.requests, c.evictions) == (1, 3, 1)
