@@ -343,7 +343,8 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         case, p = cases[0], projs[0]
-        ads, ra = case.oracle_adapters(), w.row_adapter()
+        ads = case.oracle_adapters()
+        ra = w.adapter_idx if w.adapter_idx is not None else oracle.rows_from_segments(w.T, w.seg_offsets, w.seg_adapter)
         # bounded sample: whole rows of the first projection (all of them for config 2), repeated for ~12 s
         n_rows = w.T if cfg == 2 else min(w.T, 16)
         rows = None if cfg == 2 else np.arange(n_rows, dtype=np.int32)

@@ -26,6 +26,22 @@ def y_to_f64(y: torch.Tensor, dtype: int) -> np.ndarray:
     return I.bf16_bits_to_f32(h.view(np.uint16)).astype(np.float64)
 
 
+def assert_close(y: np.ndarray, ref: np.ndarray, base_ref: np.ndarray, what: str = "") -> float:
+    """The stated tolerance on the whole result (max-norm 1e-2), and two sharper views of the same numbers: the
+    adapter term alone, (y - W x) against (ref - W x), within 4e-2 of its own largest entry (one bf16 rounding of y is
+    2^-9 of |y|, and the adapter term is about a fifth of y), and every row within 2e-2 of its own largest entry."""
+    e = rel_err(y, ref)
+    assert e <= 1e-2, f"{what}: rel err {e:.3e}"
+    lora_ref = ref - base_ref
+    if np.abs(lora_ref).max() > 0:
+        el = float(np.abs((y - base_ref) - lora_ref).max() / np.abs(lora_ref).max())
+        assert el <= 4e-2, f"{what}: adapter term off by {el:.3e} of its largest entry"
+    row_max = np.abs(ref).max(axis=1)
+    er = float((np.abs(y - ref).max(axis=1) / np.where(row_max > 0, row_max, 1.0)).max())
+    assert er <= 2e-2, f"{what}: worst row off by {er:.3e} of its largest entry"
+    return e
+
+
 def rel_err(y: np.ndarray, ref: np.ndarray) -> float:
     """max |y - ref| / max |ref| -- the metric the tolerances are stated in."""
     return float(np.abs(y - ref).max() / np.abs(ref).max())
@@ -88,9 +104,18 @@ class DeviceCase:
         return ads
 
     def reference(self, rows=None, cols=None, row_scale=None, row_adapter=None) -> np.ndarray:
-        ra = self.w.row_adapter() if row_adapter is None else row_adapter
-        return oracle.linear(self.w.dtype, self.x_h, self.W_h, self.oracle_adapters(), ra, wfmt=self.w.wfmt,
-                             w_scales=self.ws_h, rows=rows, cols=cols, row_scale=row_scale)
+        """The oracle's y for this case.  Routing comes from the workload's own tables: the per-row index as it is,
+        a segment table through the oracle's own segment -> row expansion; `row_adapter` replaces either."""
+        kw = dict(wfmt=self.w.wfmt, w_scales=self.ws_h, rows=rows, cols=cols, row_scale=row_scale)
+        if row_adapter is None and self.w.adapter_idx is None:
+            return oracle.linear_segments(self.w.dtype, self.x_h, self.W_h, self.oracle_adapters(), self.w.seg_offsets,
+                                          self.w.seg_adapter, **kw)
+        ra = self.w.adapter_idx if row_adapter is None else row_adapter
+        return oracle.linear(self.w.dtype, self.x_h, self.W_h, self.oracle_adapters(), ra, **kw)
+
+    def base_reference(self, rows=None, cols=None) -> np.ndarray:
+        """The oracle's W x alone (every row without adapter)."""
+        return self.reference(rows=rows, cols=cols, row_adapter=np.full(self.w.T, -1, dtype=np.int32))
 
     def close(self):
         self.pool.close()
