@@ -7,11 +7,15 @@ A step is one pass of the whole hot path (route + shrink + base + expand +
 combine, i.e. elora_batched_lora_linear) over one synthetic batch, for every
 projection the configuration names:
 
-  config 2 (default, the one the metric is quoted on): Llama3.1-8B q_proj decode,
-           bf16, 32 tokens, 64 rank-16 adapters, power-law(1.1) popularity
-  config 3 the seven projections of a layer, 64 decode tokens, 256 adapters of mixed rank
+  config 3 (the headline: top-level value, roofline, cpu_baseline; --steps and --warmup apply to it):
+           the seven projections of a Llama3.1-8B layer, 64 decode tokens, 256 adapters of mixed rank
+  config 2 Llama3.1-8B q_proj decode, bf16, 32 tokens, 64 rank-16 adapters, power-law(1.1) popularity
   config 4 prefill segments (16 prompts, ~8k rows), gate / up / down projections
   config 5 mixed prefill + decode batch on a 4-bit base, gate projection
+
+Without --config the line also carries per_config records for 2, 4 and 5 (the metric has two halves: achieved
+HBM GB/s for the decode configurations, MFMA % of peak for the prefill ones), each with its own roofline,
+ms_per_step, parity figure and cpu_baseline.  --config N runs configuration N alone as the line's top level.
 
 Inputs are resident in HBM before the timed region.  For the decode configs
 consecutive steps rotate through several distinct copies of the weights and
@@ -60,7 +64,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=None, choices=[2, 3, 4, 5],
+                    help="only this configuration (default: config 3 as the headline, then 2, 4 and 5 as per_config records)")
+    ap.add_argument("--headline-only", action="store_true", help="config 3 alone, without the per_config records")
     ap.add_argument("--layers", type=int, default=None, help="distinct (W, pool, x) copies the decode steps rotate through")
     ap.add_argument("--no-groups", action="store_true",
                     help="config 3: one launch per projection instead of one for q/k/v and one for gate/up")
@@ -182,31 +188,14 @@ def cache_trace(args, B, I, dev):
     print(json.dumps(out))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              f"--gpus {args.gpus} is not supported. Re-run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
-
+def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
+    """One configuration: set-up, `warmup` untimed steps, exactly `steps` timed steps, parity check in the timed
+    launch configuration, the oracle on the host cores.  Returns the record (a dict)."""
     import numpy as np
     import torch
-    from paper_2507_01438_amd import build as elora_build
-    if not os.path.exists(elora_build.LIB):
-        elora_build.build()
-    from paper_2507_01438_amd import binding as B
-    from paper_2507_01438_amd import inputs as I
     from gpu_harness import DeviceCase, rel_err, to_dev, y_to_f64
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda:0"
-    if args.cache_trace:
-        cache_trace(args, B, I, dev)
-        return
-    cfg = args.config
     decode = cfg in (2, 3)
-    steps = args.steps if args.steps is not None else {2: 4000, 3: 300, 4: 20, 5: 40}[cfg]
-    warmup = args.warmup if args.warmup is not None else {2: 200, 3: 30, 4: 3, 5: 5}[cfg]
     w = I.CONFIGS[cfg]()
     projs = w.projections
     distinct = w.distinct_adapters()
@@ -265,6 +254,10 @@ def main():
             else:
                 B.lib.elora_batched_lora_linear_group(arr, n, stream)
 
+    # set-up: every rotating copy is touched once (first use of its pages), whatever the number of warm-up steps
+    for i in range(L):
+        step(i)
+    torch.cuda.synchronize()
     for i in range(warmup):
         step(i)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -280,46 +273,38 @@ def main():
     tokens_per_s = w.T * steps / (t1 - t0)
     region_us_per_launch = ev0.elapsed_time(ev1) * 1e3 / (steps * n_launch)
 
-    # one pair of HIP events around every launch of each call's dominant kernel (second pass over the same steps)
-    n_prof = min(steps, 1000)
-    B.elora_profile_arm(n_prof * n_launch)
-    for i in range(n_prof):
-        step(i)
-    torch.cuda.synchronize()
-    per_launch_us = np.array(B.elora_profile_read(n_prof * n_launch)).reshape(n_prof, n_launch) * 1e3
-    B.elora_profile_arm(0)
-
     flops_step = sum(w.algorithmic_flops(p) for p in projs)
     bytes_step = sum(w.algorithmic_bytes(p) for p in projs)
     if decode:
         # The decode path is one kernel per call and the launches run back to back, so the device time of the
-        # timed region divided by the number of launches is the kernel's average launch duration (an event pair
-        # around a ~20 us launch adds about 5 us of its own; that figure is reported next to it).
+        # timed region (HIP events on the launch stream) divided by the number of launches is the kernel's average
+        # launch duration.
         assert all(pl.n_launches == 1 for pl in plans)
         kern_us = region_us_per_launch
         achieved = bytes_step / n_launch / (kern_us * 1e-6) / 1e9
-        roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        roofline = {"bound": "hbm", "kernel": "decode_kernel / decode_group_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "bytes_per_launch": int(bytes_step / n_launch), "avg_us": kern_us,
-                    "median_us_with_per_launch_events": float(np.median(per_launch_us))}
+                    "launches_timed": int(steps * n_launch)}
     else:
+        # one pair of HIP events around every launch of each call's dominant kernel (second pass over the same steps;
+        # an event pair costs a few microseconds against launches of hundreds)
+        n_prof = min(steps, 1000)
+        B.elora_profile_arm(n_prof * n_launch)
+        for i in range(n_prof):
+            step(i)
+        torch.cuda.synchronize()
+        per_launch_us = np.array(B.elora_profile_read(n_prof * n_launch)).reshape(n_prof, n_launch) * 1e3
+        B.elora_profile_arm(0)
         kern_us = float(per_launch_us.mean())
         achieved = flops_step / n_launch / (kern_us * 1e-6) / 1e12
         roofline = {"bound": "mfma", "kernel": "lora_gemm_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                    "flops_per_launch": int(flops_step / n_launch), "avg_us": kern_us}
-    roofline["launches_timed"] = int(steps * n_launch if decode else per_launch_us.size)
+                    "flops_per_launch": int(flops_step / n_launch), "avg_us": kern_us,
+                    "launches_timed": int(per_launch_us.size)}
     traffic, traffic_src = TRAFFIC.get(cfg, (None, None))
     roofline["traffic"] = traffic
     roofline["traffic_source"] = traffic_src
-
-    if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)  # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
 
     # parity in the launch configuration that was timed (sampled outputs for the big shapes)
     check = None
@@ -340,19 +325,19 @@ def main():
         assert check <= 1e-2, f"parity lost in the benchmark configuration: {errs}"
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_seconds > 0:
         import oracle
         case, p = cases[0], projs[0]
         ads = case.oracle_adapters()
         ra = w.adapter_idx if w.adapter_idx is not None else oracle.rows_from_segments(w.T, w.seg_offsets, w.seg_adapter)
-        # bounded sample: whole rows of the first projection (all of them for config 2), repeated for ~12 s
+        # bounded sample: whole rows of the first projection (all of them for config 2), repeated
         n_rows = w.T if cfg == 2 else min(w.T, 16)
         rows = None if cfg == 2 else np.arange(n_rows, dtype=np.int32)
         kw = dict(wfmt=w.wfmt, w_scales=case.ws_h, rows=rows)
         oracle.linear(w.dtype, case.x_h, case.W_h, ads, ra, **kw)  # warm (also compiles the C file if needed)
         c0 = time.perf_counter()
         reps, used = 0, 1
-        while time.perf_counter() - c0 < 12.0:
+        while time.perf_counter() - c0 < cpu_seconds:
             _, used = oracle.linear(w.dtype, case.x_h, case.W_h, ads, ra, return_threads=True, **kw)
             reps += 1
         cdt = time.perf_counter() - c0
@@ -362,24 +347,18 @@ def main():
                "sample": f"{reps} x {n_rows} full rows of projection '{p.name}' in {cdt:.1f} s"
                          + ("" if n_proj == 1 else f", scaled by its share of the step's flops ({scale:.3f})")}
 
-    out = {
-        "metric": "batched_lora_linear_tokens_per_s",
+    rec = {
         "value": tokens_per_s,
         "unit": "tokens/s",
-        "n_gpus": 1,
         "steps": steps,
         "warmup": warmup,
         "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16",
-        "data": "synthetic",
         "config": {
             "workload": WORKLOAD[cfg],
             "config_number": cfg, "n_tokens": w.T, "projections": [p.name for p in projs],
             "distinct_adapters": int(len(distinct)), "rotating_layers": L,
             "path": [int(pl.path) for pl in plans], "split_k": [int(pl.split_k) for pl in plans],
+            "tile_rows": [int(pl.tile_rows) for pl in plans],
             "grid": [int(pl.grid) for pl in plans], "launches_per_call": [int(pl.n_launches) for pl in plans],
             "launches_per_step": [[names[pi] for pi in u] for u in units],
         },
@@ -387,11 +366,64 @@ def main():
         "step_gbs": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_frac_of_mfma_peak": flops_step / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "dominant_kernel_us_per_launch": [float(v) for v in per_launch_us.mean(axis=0)],
         "max_rel_err_vs_oracle": check,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    for c in cases:
+        c.close()
+    del cases, layers, layer_calls, keep, dev_adapters
+    torch.cuda.empty_cache()
+    return rec
+
+
+DEFAULT_STEPS = {2: 4000, 3: 300, 4: 20, 5: 40}
+DEFAULT_WARMUP = {2: 200, 3: 30, 4: 3, 5: 5}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported. Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_01438_amd import build as elora_build
+    if not os.path.exists(elora_build.LIB):
+        elora_build.build()
+    from paper_2507_01438_amd import binding as B
+    from paper_2507_01438_amd import inputs as I
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    if args.cache_trace:
+        cache_trace(args, B, I, dev)
+        return
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+    # The headline is the layer decode configuration (config 3: the largest HBM-bound one, all seven projections);
+    # --steps / --warmup apply to it.  Without --config the other configurations follow as records of their own
+    # (config 2: the other half of the HBM figure; configs 4 and 5: the MFMA figure), each with its own step counts.
+    head = args.config if args.config is not None else 3
+    steps = args.steps if args.steps is not None else DEFAULT_STEPS[head]
+    warmup = args.warmup if args.warmup is not None else DEFAULT_WARMUP[head]
+    rec = run_config(head, steps, warmup, args, B, I, dev, 0 if args.no_cpu_baseline else 12.0)
+    out = {"metric": "batched_lora_linear_tokens_per_s", "value": rec["value"], "unit": rec["unit"], "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": rec["ms_per_step"], "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    out.update({k: v for k, v in rec.items() if k not in out})
+    if args.config is None and not args.headline_only:
+        out["per_config"] = {}
+        for cfg in (2, 4, 5):
+            r = run_config(cfg, DEFAULT_STEPS[cfg], DEFAULT_WARMUP[cfg], args, B, I, dev, 0 if args.no_cpu_baseline else 4.0)
+            r.update({"metric": "batched_lora_linear_tokens_per_s", "dtype": "bf16", "data": "synthetic"})
+            out["per_config"][str(cfg)] = r
     print(json.dumps(out))
 
 
