@@ -339,6 +339,22 @@ int elora_linear_plan(const elora_linear_desc_t *desc, elora_plan_t *plan);
 int elora_batched_lora_linear(const elora_linear_desc_t *desc, elora_stream_t stream);
 
 /*
+ * elora_batched_lora_linear for callers that cannot allocate device memory or have none to hand over as a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  desc->workspace and
+ * desc->workspace_bytes are ignored; the workspace is a 32 MiB array inside this library (one copy per GPU, held until
+ * the process ends), brought into its idle state by a fill kernel on `stream` where needed (before a GPU's first call,
+ * and when d_out differs from the previous call's).  Nothing is allocated or freed, on the device or through any
+ * library; inputs and outputs are the caller's as ever.  A call that needs more than 32 MiB of workspace
+ * (elora_workspace_bytes_w: about 2 KiB per output column on the decode path; a 4-bit W with 768 rows or more needs a
+ * copy of W) is refused with E_STORAGE.  Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ * one GPU race, so issue them on one stream.  Whether workgroups of a tile share an XCD is only found out by
+ * elora_workspace_init; until some workspace has been initialised on the GPU the decode kernel hands partial sums over
+ * through memory (same results).
+ * Errors: those of elora_batched_lora_linear, E_STORAGE as above.
+ */
+int elora_batched_lora_linear_noalloc(const elora_linear_desc_t *desc, elora_stream_t stream);
+
+/*
  * Several calls that are due at the same time (the projections that read the same activations: q / k / v, gate /
  * up; Sec. 4.3 computes base and adapters of a batch in one graph), as an array of n descriptors.  Results are those
  * of n calls of elora_batched_lora_linear up to the order of fp32 additions.  Two or three calls that all take the

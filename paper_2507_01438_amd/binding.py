@@ -36,7 +36,7 @@ EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
     "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_load_adapters_q8", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_workspace_bytes_w", "elora_linear_plan", "elora_batched_lora_linear",
-    "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
+    "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_batched_lora_linear_noalloc", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
     "elora_debug_spin_limit", "elora_debug_xcd_local", "elora_debug_k_rotate", "elora_debug_decode_wide", "elora_debug_wait_limit_us",
     "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
     "elora_cache_acquire_batch", "elora_cache_release_batch", "elora_cache_select",
@@ -95,6 +95,8 @@ lib.elora_linear_plan.restype = ctypes.c_int
 lib.elora_linear_plan.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.POINTER(elora_plan_t)]
 lib.elora_batched_lora_linear.restype = ctypes.c_int
 lib.elora_batched_lora_linear.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_void_p]
+lib.elora_batched_lora_linear_noalloc.restype = ctypes.c_int
+lib.elora_batched_lora_linear_noalloc.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_void_p]
 lib.elora_batched_lora_linear_group.restype = ctypes.c_int
 lib.elora_batched_lora_linear_group.argtypes = [ctypes.POINTER(elora_linear_desc_t), ctypes.c_int, ctypes.c_void_p]
 lib.elora_linear_group_launches.restype = ctypes.c_int
@@ -277,6 +279,10 @@ def elora_linear_plan(desc: elora_linear_desc_t) -> elora_plan_t:
 
 def elora_batched_lora_linear(desc: elora_linear_desc_t, stream=None) -> None:
     _check(lib.elora_batched_lora_linear(ctypes.byref(desc), _stream(stream)), "elora_batched_lora_linear")
+
+
+def elora_batched_lora_linear_noalloc(desc: elora_linear_desc_t, stream=None) -> None:
+    _check(lib.elora_batched_lora_linear_noalloc(ctypes.byref(desc), _stream(stream)), "elora_batched_lora_linear_noalloc")
 
 
 def desc_array(descs):

@@ -139,6 +139,15 @@ static void make_plan(const elora_linear_desc_t *d, elora_plan_t *plan)
     }
 }
 
+namespace {
+// counters to zero, everything behind them to all-ones (the idle state of the decode kernel's mailboxes)
+__global__ void ws_init_kernel(uint32_t *ws, size_t n_words, size_t n_sync)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x)
+        ws[i] = i < n_sync ? 0u : 0xFFFFFFFFu;
+}
+}  // namespace
+
 extern "C" {
 
 const char *elora_status_string(int status)
@@ -173,15 +182,6 @@ size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank
 {
     return elora_workspace_bytes_w(n_tokens_max, d_in, d_out, max_rank, ELORA_W_SAME);
 }
-
-namespace {
-// counters to zero, everything behind them to all-ones (the idle state of the decode kernel's mailboxes)
-__global__ void ws_init_kernel(uint32_t *ws, size_t n_words, size_t n_sync)
-{
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x)
-        ws[i] = i < n_sync ? 0u : 0xFFFFFFFFu;
-}
-}  // namespace
 
 int elora_workspace_init(void *workspace, size_t workspace_bytes, elora_stream_t stream)
 {
@@ -324,25 +324,80 @@ static int fill_args(const elora_linear_desc_t *d, const WsLayout &wsl, hipStrea
     return ELORA_OK;
 }
 
-int elora_batched_lora_linear(const elora_linear_desc_t *d, elora_stream_t stream_)
+// the launches of a validated descriptor with at least one row
+static int enqueue_linear(const elora_linear_desc_t *d, const WsLayout &wsl, hipStream_t stream)
 {
-    WsLayout wsl;
-    int rc = validate(d, &wsl);
-    if (rc != ELORA_OK) return rc;
-    if (d->n_tokens == 0) return ELORA_OK;
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    rc = bind_workspace(d);
-    if (rc != ELORA_OK) return rc;
     elora_plan_t plan;
     make_plan(d, &plan);
     LinearArgs a;
-    rc = fill_args(d, wsl, stream, a);
+    const int rc = fill_args(d, wsl, stream, a);
     if (rc != ELORA_OK) return rc;
     switch (plan.path) {
     case ELORA_PATH_DECODE: return launch_decode(a, plan, stream);
     case ELORA_PATH_GEMM: return launch_gemm(a, plan, stream);
     default: return launch_generic(a, stream);
     }
+}
+
+int elora_batched_lora_linear(const elora_linear_desc_t *d, elora_stream_t stream_)
+{
+    WsLayout wsl;
+    int rc = validate(d, &wsl);
+    if (rc != ELORA_OK) return rc;
+    if (d->n_tokens == 0) return ELORA_OK;
+    rc = bind_workspace(d);
+    if (rc != ELORA_OK) return rc;
+    return enqueue_linear(d, wsl, static_cast<hipStream_t>(stream_));
+}
+
+// ---- the same call for callers that cannot allocate: the workspace is an array of this library ---------------------
+namespace {
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];  // one copy per device, held until the process ends
+struct ScratchState {
+    char *ptr;     // this device's copy of `scratch` (hipGetSymbolAddress; the array's name is no device address in host code)
+    size_t idle;   // bytes from the start that are known to be in a workspace's idle state, 0: none yet
+    size_t used;   // bytes from the start that calls so far may have written
+    int d_out;     // the d_out the idle state was last used with
+};
+ScratchState g_scratch[64];
+}  // namespace
+
+int elora_batched_lora_linear_noalloc(const elora_linear_desc_t *desc, elora_stream_t stream_)
+{
+    if (desc == nullptr) return ELORA_E_NULL;
+    int dev = 0;
+    ELORA_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return ELORA_E_HIP;
+    ScratchState &st = g_scratch[dev];
+    if (st.ptr == nullptr) {
+        void *p = nullptr;
+        ELORA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) return ELORA_E_HIP;
+        st.ptr = static_cast<char *>(p);
+    }
+    elora_linear_desc_t d = *desc;
+    d.workspace = st.ptr;
+    d.workspace_bytes = kScratchBytes;
+    WsLayout wsl;
+    const int rc = validate(&d, &wsl);  // E_STORAGE: the call needs more than the array holds
+    if (rc != ELORA_OK) return rc;
+    if (d.n_tokens == 0) return ELORA_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    // The idle state (counters zero, everything else all-ones) is written by a fill kernel on the call's stream: over
+    // what this call's layout covers before the first call, and again, over everything calls have written so far, when
+    // d_out changes (what a call with another d_out wrote may lie where this one's mailboxes are).
+    if (st.idle < wsl.total || st.d_out != d.d_out) {
+        const size_t bytes = st.used > wsl.total ? st.used : wsl.total;
+        const size_t n_words = bytes / sizeof(uint32_t), blocks = (n_words + 255) / 256;
+        hipLaunchKernelGGL(ws_init_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
+                           reinterpret_cast<uint32_t *>(st.ptr), n_words, (size_t)kSyncInts);
+        ELORA_HIP_TRY(hipGetLastError());
+        st.idle = bytes;
+        st.d_out = d.d_out;
+    }
+    if (wsl.total > st.used) st.used = wsl.total;
+    return enqueue_linear(&d, wsl, stream);
 }
 
 int elora_batched_lora_linear_group(const elora_linear_desc_t *descs, int n, elora_stream_t stream_)
