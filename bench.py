@@ -203,7 +203,12 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     # One DeviceCase per projection from the seeded generators (only the adapters the batch uses are
     # generated for the big pools).  Decode: further "layers" are device copies of the same bytes at other
     # addresses (what matters to the caches), so every layer's output can be checked against the oracle.
-    cases = [DeviceCase(w, p, load_slots=None if cfg == 2 else distinct) for p in projs]
+    # Projections with the same d_in read the same activations: their cases share one device copy of x and of the routing
+    # tables (what lets a group of them share work).
+    cases = []
+    for p in projs:
+        first = next((c for c in cases if c.proj.K == p.K), None)
+        cases.append(DeviceCase(w, p, load_slots=None if cfg == 2 else distinct, share=first))
     layer_bytes = sum(p.N * p.K * 2 for p in projs)
     L = args.layers if args.layers is not None else (max(2, min(32, int(1.6e9 // layer_bytes))) if decode else 1)
     layers = []  # layers[l][pi] = descriptor
@@ -212,11 +217,14 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
                     for case in cases]
     for l in range(L):
         descs = []
+        x_of = {}  # this layer's copy of x per d_in
         for pi, (p, case) in enumerate(zip(projs, cases)):
             if l == 0:
                 descs.append(case.desc())
                 continue
-            Wc, xc, yc = case.W.clone(), case.x.clone(), torch.zeros_like(case.y)
+            if p.K not in x_of:
+                x_of[p.K] = case.x.clone()
+            Wc, xc, yc = case.W.clone(), x_of[p.K], torch.zeros_like(case.y)
             pool = B.AdapterPool(p.K, p.N, w.max_rank, w.pool, w.dtype, dev)
             for i, (A_d, B_d, sc) in dev_adapters[pi].items():
                 pool.load(i, A_d, B_d, sc)
@@ -231,7 +239,7 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     n_proj = len(projs)
     # Projections that are due at the same time go out as one launch (config 3: q/k/v and gate/up).
     names = [p.name for p in projs]
-    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if (decode and not args.no_groups) else []
+    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if not args.no_groups else []
     units = []  # per launch of a step: the projection indices it covers
     for pi, n in enumerate(names):
         g = next((g for g in group_names if n in g), None)
@@ -243,8 +251,10 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     for descs in layers:
         layer_calls.append([(B.desc_array([descs[pi] for pi in u]), len(u)) for u in units])
     for arr, n in layer_calls[0]:
-        if n > 1:
+        if n > 1 and decode:
             assert B.elora_linear_group_launches(arr) == 1, "these projections were expected to share a launch"
+        elif n > 1:
+            assert B.elora_linear_group_launches(arr) == 2 + n, "these projections were expected to share route and shrink"
     n_launch = len(units)
 
     def step(i):
@@ -289,18 +299,19 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     else:
         # one pair of HIP events around every launch of each call's dominant kernel (second pass over the same steps;
         # an event pair costs a few microseconds against launches of hundreds)
+        # (every projection has one GEMM launch, also where projections share their route and shrink launches)
         n_prof = min(steps, 1000)
-        B.elora_profile_arm(n_prof * n_launch)
+        B.elora_profile_arm(n_prof * n_proj)
         for i in range(n_prof):
             step(i)
         torch.cuda.synchronize()
-        per_launch_us = np.array(B.elora_profile_read(n_prof * n_launch)).reshape(n_prof, n_launch) * 1e3
+        per_launch_us = np.array(B.elora_profile_read(n_prof * n_proj)).reshape(n_prof, n_proj) * 1e3
         B.elora_profile_arm(0)
         kern_us = float(per_launch_us.mean())
-        achieved = flops_step / n_launch / (kern_us * 1e-6) / 1e12
+        achieved = flops_step / n_proj / (kern_us * 1e-6) / 1e12
         roofline = {"bound": "mfma", "kernel": "lora_gemm_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                    "flops_per_launch": int(flops_step / n_launch), "avg_us": kern_us,
+                    "flops_per_launch": int(flops_step / n_proj), "avg_us": kern_us,
                     "launches_timed": int(per_launch_us.size)}
     traffic, traffic_src = TRAFFIC.get(cfg, (None, None))
     roofline["traffic"] = traffic

@@ -359,8 +359,11 @@ int elora_batched_lora_linear_noalloc(const elora_linear_desc_t *desc, elora_str
  * up; Sec. 4.3 computes base and adapters of a batch in one graph), as an array of n descriptors.  Results are those
  * of n calls of elora_batched_lora_linear up to the order of fp32 additions.  Two or three calls that all take the
  * decode path with the same n_tokens run as ONE launch when their workgroups fit on the device together (each call
- * then gets fewer K-slices than it would take alone); otherwise, and for any other mix, the calls are enqueued one
- * after the other.  Every call needs a workspace and an output of its own.
+ * then gets fewer K-slices than it would take alone).  Two or three calls that all take the MFMA GEMM path, each with
+ * a pool, and name the SAME x, d_in and routing tables (the same pointers) share ONE route launch and ONE shrink
+ * launch, A_i x for the adapters of all of them with the rows of x fetched once, followed by each call's GEMM.
+ * Otherwise, and for any other mix, the calls are enqueued one after the other.  Every call needs a workspace and an
+ * output of its own.
  * Errors: those of elora_batched_lora_linear for any descriptor (nothing is enqueued then), E_SHAPE (n < 1),
  * E_STORAGE (two descriptors share a workspace or y).
  */

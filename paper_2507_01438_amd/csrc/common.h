@@ -99,6 +99,8 @@ struct LinearArgs {
 int launch_generic(const LinearArgs &a, hipStream_t stream);
 int launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
 int launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream);
+bool gemm_group_shares_shrink(const LinearArgs *a, int n);  // same x and routing tables, a pool each: one shrink launch serves all
+int launch_gemm_group(const LinearArgs *a, int n, hipStream_t stream);
 int launch_decode_group(const LinearArgs *a, int n, hipStream_t stream);  // -1: the calls do not fit into one launch
 bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds);  // K-slices per call if they fit
 

@@ -57,19 +57,17 @@ constexpr int kShrinkUnroll = 4;        // K steps of 32 whose loads are issued 
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
-__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int K, int n_tiles,
-                                                                     const uint16_t *__restrict__ x, PoolView pool,
-                                                                     const int32_t *__restrict__ row_slot,
-                                                                     const float *__restrict__ row_scale,
-                                                                     uint16_t *__restrict__ V, int Rpad)
+__device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tiles, const uint16_t *__restrict__ x,
+                                             const PoolView &pool, const int32_t *__restrict__ row_slot,
+                                             const float *__restrict__ row_scale, uint16_t *__restrict__ V, int Rpad)
 {
     __shared__ int s_slot[kShrinkRows];
     __shared__ float s_red[4][kShrinkRows][kShrinkColsPerPass + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    if ((int)blockIdx.x >= n_tiles) {
+    if (block >= n_tiles) {
         // ---- one row of a short run ---------------------------------------------------------------
-        const int t = blockIdx.x - n_tiles;
+        const int t = block - n_tiles;
         const int r0 = t / kShrinkRows * kShrinkRows, r1 = min(r0 + kShrinkRows, T);
         const int slot = row_slot[t];
         int lo = t, hi = t + 1;  // the run's piece inside this tile
@@ -98,7 +96,7 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int 
     }
 
     // ---- 32-row tile ------------------------------------------------------------------------------
-    const int r0 = blockIdx.x * kShrinkRows;
+    const int r0 = block * kShrinkRows;
     if (tid < kShrinkRows) s_slot[tid] = (r0 + tid < T) ? row_slot[r0 + tid] : -1;
     __syncthreads();
     // rows of long runs: zero now, the passes below fill in the rank columns (short-run rows belong to
@@ -186,6 +184,48 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int 
         }
         run_start = run_end;
     }
+}
+
+__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int K, int n_tiles,
+                                                                     const uint16_t *__restrict__ x, PoolView pool,
+                                                                     const int32_t *__restrict__ row_slot,
+                                                                     const float *__restrict__ row_scale,
+                                                                     uint16_t *__restrict__ V, int Rpad)
+{
+    shrink_block((int)blockIdx.x, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad);
+}
+
+// The shrink of several projections that read the same x (q / k / v, gate / up: Sec. 4.3 builds base model and adapters
+// of a batch into one graph; Sec. 5.3: the adapters target Q, K, V, Up, Down) in one launch: block `blk` of projection p
+// is workgroup ((blk / 8) * n + p) * 8 + blk % 8, so the workgroups that read the same rows of x run next to each other
+// on one XCD (workgroup b runs on XCD b % 8) and all but the first find those rows in its L2.
+constexpr int kShrinkMulti = 3;
+struct ShrinkMulti {
+    int n;
+    PoolView pool[kShrinkMulti];
+    int32_t *row_slot[kShrinkMulti];
+    float *row_scale[kShrinkMulti];
+    uint16_t *V[kShrinkMulti];
+    int Rpad[kShrinkMulti];
+};
+// route of several projections with the same routing tables (each against its own pool) in one launch
+__global__ void gemm_route_multi_kernel(int T, RouteView route, ShrinkMulti sm)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    for (int p = 0; p < sm.n; ++p) {
+        const RowRoute r = resolve_row(t, route, sm.pool[p], true);
+        sm.row_slot[p][t] = r.slot;
+        sm.row_scale[p][t] = r.scale;
+    }
+}
+__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_multi_kernel(int T, int K, int n_tiles, const uint16_t *__restrict__ x,
+                                                                           ShrinkMulti sm)
+{
+    const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
+    const int p = j % sm.n, blk = (j / sm.n) * 8 + xcd;
+    if (blk >= n_tiles + T) return;
+    shrink_block(blk, T, K, n_tiles, x, sm.pool[p], sm.row_slot[p], sm.row_scale[p], sm.V[p], sm.Rpad[p]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -671,23 +711,14 @@ size_t elora::gemm_w4_bytes(int n_tokens, int d_in, int d_out)
 
 size_t elora::gemm_v_bytes(int n_tokens, int max_rank) { return (size_t)n_tokens * round_up(max_rank, BK) * sizeof(uint16_t); }
 
-int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream)
+namespace {
+// what follows route and shrink: (the copy of a 4-bit W and) the GEMM with the expand in its K loop
+int launch_gemm_back(const LinearArgs &a, hipStream_t stream)
 {
-    (void)plan;
     int32_t *row_slot = reinterpret_cast<int32_t *>(a.ws + a.wsl.row_slot);
-    float *row_scale = reinterpret_cast<float *>(a.ws + a.wsl.row_scale);
     uint16_t *V = reinterpret_cast<uint16_t *>(a.ws + a.wsl.v);
     const int Rpad = round_up(a.pool.max_rank, BK);
     const int has_pool = a.has_pool ? 1 : 0;
-    hipLaunchKernelGGL(gemm_route_kernel, dim3((a.T + 255) / 256), dim3(256), 0, stream, a.T, a.route, a.pool, has_pool,
-                       row_slot, row_scale);
-    ELORA_HIP_TRY(hipGetLastError());
-    if (a.has_pool) {
-        const int n_tiles = (a.T + kShrinkRows - 1) / kShrinkRows;
-        hipLaunchKernelGGL(sgmv_shrink_kernel, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
-                           static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
-        ELORA_HIP_TRY(hipGetLastError());
-    }
     // 4-bit W and enough rows: the bf16 kernel on a copy made now
     const bool copy_first = a.wfmt == ELORA_W_INT4_G32 && a.wsl.wdeq_bytes != 0;
     if (copy_first) {
@@ -732,5 +763,67 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
     }
     ELORA_HIP_TRY(hipGetLastError());
     profile_mark_end(stream);
+    return ELORA_OK;
+}
+}  // namespace
+
+int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t stream)
+{
+    (void)plan;
+    int32_t *row_slot = reinterpret_cast<int32_t *>(a.ws + a.wsl.row_slot);
+    float *row_scale = reinterpret_cast<float *>(a.ws + a.wsl.row_scale);
+    uint16_t *V = reinterpret_cast<uint16_t *>(a.ws + a.wsl.v);
+    const int Rpad = round_up(a.pool.max_rank, BK);
+    const int has_pool = a.has_pool ? 1 : 0;
+    hipLaunchKernelGGL(gemm_route_kernel, dim3((a.T + 255) / 256), dim3(256), 0, stream, a.T, a.route, a.pool, has_pool,
+                       row_slot, row_scale);
+    ELORA_HIP_TRY(hipGetLastError());
+    if (a.has_pool) {
+        const int n_tiles = (a.T + kShrinkRows - 1) / kShrinkRows;
+        hipLaunchKernelGGL(sgmv_shrink_kernel, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
+                           static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
+        ELORA_HIP_TRY(hipGetLastError());
+    }
+    return launch_gemm_back(a, stream);
+}
+
+// Two or three calls of this path that read the same x with the same routing tables (each with a pool of its own):
+// one route launch, ONE shrink launch over the adapters of all of them, then each call's GEMM.
+bool elora::gemm_group_shares_shrink(const LinearArgs *a, int n)
+{
+    if (n < 2 || n > kShrinkMulti) return false;
+    for (int i = 0; i < n; ++i) {
+        if (!a[i].has_pool || a[i].x != a[0].x || a[i].T != a[0].T || a[i].K != a[0].K) return false;
+        const RouteView &r = a[i].route, &r0 = a[0].route;
+        if (r.adapter_idx != r0.adapter_idx || r.seg_offsets != r0.seg_offsets || r.seg_adapter != r0.seg_adapter ||
+            r.n_segments != r0.n_segments || r.scales != r0.scales)
+            return false;
+    }
+    return true;
+}
+
+int elora::launch_gemm_group(const LinearArgs *a, int n, hipStream_t stream)
+{
+    ShrinkMulti sm;
+    sm.n = n;
+    for (int i = 0; i < n; ++i) {
+        sm.pool[i] = a[i].pool;
+        sm.row_slot[i] = reinterpret_cast<int32_t *>(a[i].ws + a[i].wsl.row_slot);
+        sm.row_scale[i] = reinterpret_cast<float *>(a[i].ws + a[i].wsl.row_scale);
+        sm.V[i] = reinterpret_cast<uint16_t *>(a[i].ws + a[i].wsl.v);
+        sm.Rpad[i] = round_up(a[i].pool.max_rank, BK);
+    }
+    const int T = a[0].T, K = a[0].K;
+    hipLaunchKernelGGL(gemm_route_multi_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, T, a[0].route, sm);
+    ELORA_HIP_TRY(hipGetLastError());
+    const int n_tiles = (T + kShrinkRows - 1) / kShrinkRows;
+    const int per = (n_tiles + T + 7) / 8 * 8;
+    hipLaunchKernelGGL(sgmv_shrink_multi_kernel, dim3(per * n), dim3(kShrinkThreads), 0, stream, T, K, n_tiles,
+                       static_cast<const uint16_t *>(a[0].x), sm);
+    ELORA_HIP_TRY(hipGetLastError());
+    for (int i = 0; i < n; ++i) {
+        const int rc = launch_gemm_back(a[i], stream);
+        if (rc != ELORA_OK) return rc;
+    }
     return ELORA_OK;
 }

@@ -400,11 +400,50 @@ int elora_batched_lora_linear_noalloc(const elora_linear_desc_t *desc, elora_str
     return enqueue_linear(&d, wsl, stream);
 }
 
+// How a group goes out: as one decode launch, as calls of the GEMM path that share route and shrink launches, or call
+// by call.  Fills the launch arguments of the first two forms.
+enum GroupForm { kGroupSingles = 0, kGroupDecode = 1, kGroupGemmShared = 2 };
+constexpr int kMaxGroup = 3;
+
+static int group_form(const elora_linear_desc_t *descs, int n, hipStream_t stream, bool fill, LinearArgs *a, int *form)
+{
+    *form = kGroupSingles;
+    if (n < 2 || n > kMaxGroup || descs[0].n_tokens <= 0) return ELORA_OK;
+    int path0 = -1;
+    for (int i = 0; i < n; ++i) {
+        elora_plan_t plan;
+        make_plan(&descs[i], &plan);
+        if (i == 0) path0 = plan.path;
+        if (plan.path != path0 || descs[i].n_tokens != descs[0].n_tokens) return ELORA_OK;
+    }
+    if (path0 != ELORA_PATH_DECODE && path0 != ELORA_PATH_GEMM) return ELORA_OK;
+    if (path0 == ELORA_PATH_GEMM) {
+        // the same activations and routing tables, a pool each
+        for (int i = 0; i < n; ++i) {
+            const elora_linear_desc_t &d = descs[i], &d0 = descs[0];
+            if (d.pool == nullptr || d.x != d0.x || d.d_in != d0.d_in || d.adapter_idx != d0.adapter_idx ||
+                d.seg_offsets != d0.seg_offsets || d.seg_adapter != d0.seg_adapter || d.n_segments != d0.n_segments ||
+                d.scales != d0.scales)
+                return ELORA_OK;
+        }
+    }
+    if (fill) {
+        for (int i = 0; i < n; ++i) {
+            WsLayout wsl;
+            (void)validate(&descs[i], &wsl);
+            int rc = bind_workspace(&descs[i]);
+            if (rc == ELORA_OK) rc = fill_args(&descs[i], wsl, stream, a[i]);
+            if (rc != ELORA_OK) return rc;
+        }
+    }
+    *form = path0 == ELORA_PATH_DECODE ? kGroupDecode : kGroupGemmShared;
+    return ELORA_OK;
+}
+
 int elora_batched_lora_linear_group(const elora_linear_desc_t *descs, int n, elora_stream_t stream_)
 {
     if (descs == nullptr) return ELORA_E_NULL;
     if (n < 1) return ELORA_E_SHAPE;
-    constexpr int kMaxGroup = 3;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     // everything is validated before anything is enqueued
     for (int i = 0; i < n; ++i) {
@@ -413,25 +452,18 @@ int elora_batched_lora_linear_group(const elora_linear_desc_t *descs, int n, elo
         for (int j = 0; j < i; ++j)
             if (descs[i].workspace == descs[j].workspace || descs[i].y == descs[j].y) return ELORA_E_STORAGE;
     }
-    bool together = n >= 2 && n <= kMaxGroup && descs[0].n_tokens > 0;
     LinearArgs a[kMaxGroup];
-    for (int i = 0; i < n && together; ++i) {
-        elora_plan_t plan;
-        make_plan(&descs[i], &plan);
-        together = plan.path == ELORA_PATH_DECODE && descs[i].n_tokens == descs[0].n_tokens;
-        if (!together) break;
-        WsLayout wsl;
-        (void)validate(&descs[i], &wsl);
-        int rc = bind_workspace(&descs[i]);
-        if (rc == ELORA_OK) rc = fill_args(&descs[i], wsl, stream, a[i]);
-        if (rc != ELORA_OK) return rc;
-    }
-    if (together) {
-        const int rc = launch_decode_group(a, n, stream);
+    int form = kGroupSingles;
+    int rc = group_form(descs, n, stream, true, a, &form);
+    if (rc != ELORA_OK) return rc;
+    if (form == kGroupDecode) {
+        rc = launch_decode_group(a, n, stream);
         if (rc >= 0) return rc;
+    } else if (form == kGroupGemmShared) {
+        return launch_gemm_group(a, n, stream);
     }
     for (int i = 0; i < n; ++i) {
-        const int rc = elora_batched_lora_linear(&descs[i], stream_);
+        rc = elora_batched_lora_linear(&descs[i], stream_);
         if (rc != ELORA_OK) return rc;
     }
     return ELORA_OK;
@@ -442,25 +474,27 @@ int elora_linear_group_launches(const elora_linear_desc_t *descs, int n, int *n_
     if (descs == nullptr || n_launches == nullptr) return ELORA_E_NULL;
     if (n < 1) return ELORA_E_SHAPE;
     int sum = 0;
-    bool together = n >= 2 && n <= 3 && descs[0].n_tokens > 0;
     for (int i = 0; i < n; ++i) {
         const int rc = validate(&descs[i], nullptr);
         if (rc != ELORA_OK) return rc;
         elora_plan_t plan;
         make_plan(&descs[i], &plan);
         sum += descs[i].n_tokens > 0 ? plan.n_launches : 0;
-        together = together && plan.path == ELORA_PATH_DECODE && descs[i].n_tokens == descs[0].n_tokens;
     }
-    if (together) {
-        int K[3], N[3], split[3];
+    int form = kGroupSingles;
+    (void)group_form(descs, n, nullptr, false, nullptr, &form);
+    if (form == kGroupDecode) {
+        int K[kMaxGroup], N[kMaxGroup], split[kMaxGroup];
         bool wlds = true;
         for (int i = 0; i < n; ++i) {
             K[i] = descs[i].d_in;
             N[i] = descs[i].d_out;
         }
-        together = decode_group_splits(descs[0].n_tokens, n, K, N, split, &wlds);
+        if (decode_group_splits(descs[0].n_tokens, n, K, N, split, &wlds)) sum = 1;
+    } else if (form == kGroupGemmShared) {
+        sum -= 2 * (n - 1);  // one route and one shrink launch for all of them
     }
-    *n_launches = together ? 1 : sum;
+    *n_launches = sum;
     return ELORA_OK;
 }
 

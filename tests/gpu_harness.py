@@ -50,13 +50,17 @@ def rel_err(y: np.ndarray, ref: np.ndarray) -> float:
 class DeviceCase:
     """One projection of a workload resident on the GPU, with its pool loaded."""
 
-    def __init__(self, w: I.Workload, proj: I.Projection, *, load_slots=None, n_tokens_max=None):
+    def __init__(self, w: I.Workload, proj: I.Projection, *, load_slots=None, n_tokens_max=None, share=None):
+        """share: another case of the same workload and d_in whose device copies of x and of the routing tables this
+        one uses as well (projections that read the same activations: their descriptors then name the same pointers)."""
         from paper_2507_01438_amd import binding as B
         self.B = B
         self.w, self.proj = w, proj
         self.x_h = w.x(proj)
         self.W_h, self.ws_h = w.W(proj)
-        self.x = to_dev(self.x_h)
+        if share is not None:
+            assert share.w is w and share.proj.K == proj.K
+        self.x = to_dev(self.x_h) if share is None else share.x
         self.W = to_dev(self.W_h)
         self.w_scales = None if self.ws_h is None else to_dev(self.ws_h)
         self.pool = B.AdapterPool(proj.K, proj.N, w.max_rank, w.pool, w.dtype, DEV)
@@ -70,9 +74,12 @@ class DeviceCase:
         torch.cuda.synchronize()
         self.lin = B.LoraLinear(proj.K, proj.N, w.dtype, self.pool, n_tokens_max or max(w.T, 1), DEV, wfmt=w.wfmt)
         self.y = torch.zeros((max(w.T, 1), proj.N), dtype=torch.float32 if w.dtype == I.F32 else torch.int16, device=DEV)
-        self.adapter_idx = None if w.adapter_idx is None else to_dev(w.adapter_idx)
-        self.seg_offsets = None if w.seg_offsets is None else to_dev(w.seg_offsets)
-        self.seg_adapter = None if w.seg_adapter is None else to_dev(w.seg_adapter)
+        if share is not None:
+            self.adapter_idx, self.seg_offsets, self.seg_adapter = share.adapter_idx, share.seg_offsets, share.seg_adapter
+        else:
+            self.adapter_idx = None if w.adapter_idx is None else to_dev(w.adapter_idx)
+            self.seg_offsets = None if w.seg_offsets is None else to_dev(w.seg_offsets)
+            self.seg_adapter = None if w.seg_adapter is None else to_dev(w.seg_adapter)
 
     def desc(self, scales=None):
         return self.lin.desc(self.x[: self.w.T], self.W, self.y, adapter_idx=self.adapter_idx,

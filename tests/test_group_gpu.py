@@ -111,3 +111,63 @@ def test_group_with_every_wait_cut_short_still_matches_and_leaves_the_workspaces
     _run_group(B, cases, expect_launches=1)
     for c in cases:
         c.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# calls of the MFMA GEMM path that read the same activations: one route launch and one shrink launch for all
+# ---------------------------------------------------------------------------------------------
+
+def _shared_cases(w, projs):
+    cases = []
+    for p in projs:
+        cases.append(DeviceCase(w, p, load_slots=w.distinct_adapters(), share=cases[0] if cases else None))
+    return cases
+
+
+@pytest.mark.parametrize("lengths,none_segs", [([70, 1, 1, 1, 200, 30, 0, 5], (2,)), ([300, 20, 257, 15, 1, 1, 1, 90], ())])
+def test_gemm_calls_that_share_x_share_route_and_shrink(lengths, none_segs):
+    from paper_2507_01438_amd import binding as B
+    T = sum(lengths)
+    w = I.small_workload(330 + T, I.BF16, 512, 264, T, 6, (16, 8, 32, 64, 5, 24), segments=lengths, no_adapter_rows=none_segs)
+    w.projections = [I.Projection("a", 512, 264), I.Projection("b", 512, 1040), I.Projection("c", 512, 72)]
+    cases = _shared_cases(w, w.projections)
+    descs = B.desc_array([c.desc() for c in cases])
+    assert [B.elora_linear_plan(c.desc()).path for c in cases] == [2, 2, 2]
+    assert B.elora_linear_group_launches(descs) == 2 + 3           # route, shrink, three GEMMs (alone: 3 x 3)
+    for c in cases:
+        c.y.fill_(7)
+    B.elora_batched_lora_linear_group(descs)
+    torch.cuda.synchronize()
+    together = [y_to_f64(c.y[:T], I.BF16) for c in cases]
+    for c, y in zip(cases, together):
+        assert rel_err(y, c.reference()) <= 1e-2, c.proj.name
+        assert c.pool.poll_error() == (0, -1)
+    # one by one: the same bits (the shrink of a call does not depend on who shares its launch)
+    for c, y in zip(cases, together):
+        np.testing.assert_array_equal(c.run(), y)
+    # calls that name different copies of x do not share: 3 launches each
+    other = DeviceCase(w, w.projections[1], load_slots=w.distinct_adapters())
+    assert B.elora_linear_group_launches(B.desc_array([cases[0].desc(), other.desc()])) == 6
+    other.close()
+    for c in cases:
+        c.close()
+
+
+def test_config4_gate_and_up_share_their_shrink_full_shapes():
+    from paper_2507_01438_amd import binding as B
+    w = I.config4()
+    cases = _shared_cases(w, [I.LLAMA8B["gate"], I.LLAMA8B["up"]])
+    descs = B.desc_array([c.desc() for c in cases])
+    assert B.elora_linear_group_launches(descs) == 4
+    B.elora_batched_lora_linear_group(descs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    for c in cases:
+        cols = np.sort(rng.choice(c.proj.N, 48, replace=False))
+        rows = np.sort(rng.choice(w.T, 96, replace=False))
+        y = y_to_f64(c.y[: w.T], w.dtype)
+        e = rel_err(y[np.ix_(rows, cols)], c.reference(rows=rows, cols=cols))
+        print(f"config4 gate/up with a shared shrink: {c.proj.name} rel err {e:.2e}")
+        assert e <= 1e-2
+        assert c.pool.poll_error() == (0, -1)
+        c.close()
