@@ -72,7 +72,8 @@ typedef enum {
 /* Kernel family a call is dispatched to (reported by elora_linear_plan). */
 typedef enum {
     ELORA_PATH_GENERIC = 0, /* plain-ALU tiled kernels: any dtype / shape */
-    ELORA_PATH_DECODE = 1,  /* few rows: HBM-streaming split-K MFMA contraction + reduce/expand epilogue kernel */
+    ELORA_PATH_DECODE = 1,  /* few rows (up to 64 per launch, up to 256 in several launches): HBM-streaming split-K MFMA
+                               contraction with the shrink before and the expand after it in the same kernel */
     ELORA_PATH_GEMM = 2     /* many rows: LDS-tiled bf16 MFMA GEMM with the expand as a K-extension */
 } elora_path_t;
 
@@ -400,6 +401,13 @@ int elora_debug_wait_limit_us(int us);
  * XCD's L2); -1 goes back to what the device was found to do.  Errors: E_SHAPE.
  */
 int elora_debug_xcd_local(int mode);
+
+/*
+ * Test hook: calls of 65 to 256 rows (bf16, d_in a multiple of 256, d_out of 16) may run as 2 to 4 launches of the
+ * decode kernel over balanced row ranges instead of on the MFMA GEMM path.  -1 (default) and 1: they do; 0: they
+ * take the GEMM path.  Errors: E_SHAPE.
+ */
+int elora_debug_decode_passes(int mode);
 
 /*
  * Test hook: which decode calls with more than 32 rows run the kernel whose workgroups take 128 rows of W instead

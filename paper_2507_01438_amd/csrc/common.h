@@ -34,6 +34,7 @@ struct RouteView {
     const int32_t *seg_adapter;
     int n_segments;
     const float *scales;  // per row (decode form) / per segment (prefill form), or nullptr
+    int row_base;         // the tables speak of the batch's rows; row t of this launch is row t + row_base of the batch
 };
 
 struct RowRoute {
@@ -58,7 +59,8 @@ struct WsLayout {
     size_t total;
 };
 
-constexpr int kDecodeMaxTokens = 64;  // rows the streaming (decode) kernels take
+constexpr int kDecodeMaxTokens = 64;  // rows the streaming (decode) kernels take per launch
+constexpr int kDecodeMaxPasses = 4;   // a call with more rows may run as this many launches of that kernel at most
 constexpr int kDecodeMaxSplit = 8;    // K-splits of the base contraction
 constexpr int kMaxRank = 256;
 constexpr int kSyncInts = 1024;       // ints in the workspace's counter area
@@ -106,11 +108,13 @@ bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, b
 
 void decode_set_spin_limit(int limit);
 void decode_set_wait_us(int us);
+void decode_set_passes(int mode);  // -1: several launches per call where they pay, 0: never, 1: whenever the row count allows
 void decode_set_wide(int mode);    // -1: 128-row tiles where they pay, 0: never, 1: wherever the shape allows
 void decode_set_k_rotate(int on);  // 0: every workgroup walks its K-slice from the start
 void decode_set_local_override(int mode);  // 0: never assume XCD-local hand-overs, -1: as probed
 int decode_probe_device(void *scratch, size_t scratch_bytes, hipStream_t stream);  // finds out, once per device, how workgroups are placed on the XCDs
 bool decode_eligible(const elora_linear_desc_t &d, int max_rank);
+int decode_passes(const elora_linear_desc_t &d);  // launches of the decode kernel this call is cut into (1 up to 64 rows), 0: not that path
 void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
 size_t decode_mail_bytes(int d_out);  // mailboxes of the decode kernel for d_out output columns
 bool gemm_eligible(const elora_linear_desc_t &d, int max_rank);
@@ -169,6 +173,7 @@ struct RouteIndex {
 };
 __device__ __forceinline__ RouteIndex route_index(int t, const RouteView &r)
 {
+    t += r.row_base;
     RouteIndex out{-1, t};
     if (r.adapter_idx != nullptr) {
         out.idx = r.adapter_idx[t];
@@ -197,7 +202,7 @@ __device__ __forceinline__ RowRoute route_finish(int t, const RouteIndex &ri, co
     if (!ok) {
         if (record) {
             atomicAdd(&p.err[0], 1);
-            atomicMin(&p.err[1], t);
+            atomicMin(&p.err[1], t + r.row_base);
         }
         return out;
     }

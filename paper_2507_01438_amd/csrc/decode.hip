@@ -80,6 +80,7 @@ constexpr int kGaveUp = 1 << 16;  // this much for every owner on XCD x that gav
 
 int g_spin_limit = 1 << 22;
 int g_wait_us = 200;
+int g_pass_mode = -1;  // calls of 65 to 256 rows as several launches: 0 never, otherwise always
 int g_local_override = -1;
 int g_k_rotate = 1;
 constexpr int kMaxDevices = 64;
@@ -646,6 +647,7 @@ void elora::decode_set_wait_us(int us) { g_wait_us = us; }
 void elora::decode_set_local_override(int mode) { g_local_override = mode; }
 void elora::decode_set_k_rotate(int on) { g_k_rotate = on; }
 void elora::decode_set_wide(int mode) { g_wide_mode = mode; }
+void elora::decode_set_passes(int mode) { g_pass_mode = mode; }
 
 #ifdef ELORA_TRACE
 extern "C" int elora_trace_read(long long *host_out, int n_values)
@@ -659,11 +661,25 @@ extern "C" int elora_trace_clear()
 }
 #endif
 
+// Batches of 65 to 256 rows: too many for one launch of this kernel, too few to fill the device with the 256 x 256
+// tiles of the MFMA GEMM path (at 4096 output columns that path has 16 workgroups for up to 256 rows), and with a
+// different adapter in every row that path's shrink and expand work row by row.  Such a call runs as 2 to 4 launches
+// of the decode kernel over balanced row ranges, each streaming W once.  Measured with per-row adapters of mixed rank,
+// 4096 x 4096 / 4096 x 14336 / 14336 x 4096: 128 rows 47 / 91 / 90 us against 384 / 388 / 657 us on the GEMM path,
+// 256 rows 88 / 171 / 167 us against 574 / 587 / 868 us.
+int elora::decode_passes(const elora_linear_desc_t &d)
+{
+    if (!(d.dtype == ELORA_BF16 && d.wfmt == ELORA_W_SAME && d.n_tokens >= 1 && d.d_in % kChunk == 0 && d.d_out % 16 == 0)) return 0;
+    const int passes = (d.n_tokens + kDecodeMaxTokens - 1) / kDecodeMaxTokens;
+    if (passes == 1) return 1;
+    if (passes > kDecodeMaxPasses || g_pass_mode == 0) return 0;
+    return passes;
+}
+
 bool elora::decode_eligible(const elora_linear_desc_t &d, int max_rank)
 {
     (void)max_rank;
-    return d.dtype == ELORA_BF16 && d.wfmt == ELORA_W_SAME && d.n_tokens >= 1 && d.n_tokens <= kDecodeMaxTokens &&
-           d.d_in % kChunk == 0 && d.d_out % 16 == 0;
+    return decode_passes(d) >= 1;
 }
 
 // bytes of the piece mailboxes for d_out output columns: up to 8 K-slices, up to 64 rows (columns rounded up to
@@ -678,8 +694,10 @@ size_t elora::decode_mail_bytes(int d_out)
 void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 {
     Variant var{1, true, 4};
-    DecodeShape sh = make_shape(d.n_tokens, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, &var);
-    plan->n_launches = 1;
+    const int passes = decode_passes(d);
+    const int rows = (d.n_tokens + passes - 1) / passes;  // the longest row range
+    DecodeShape sh = make_shape(rows, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, &var);
+    plan->n_launches = passes;
     plan->split_k = sh.split;
     plan->tile_rows = sh.tile_rows;
     plan->tile_cols = 0;

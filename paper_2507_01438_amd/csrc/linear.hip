@@ -222,6 +222,13 @@ int elora_debug_xcd_local(int mode)
     return ELORA_OK;
 }
 
+int elora_debug_decode_passes(int mode)
+{
+    if (mode < -1 || mode > 1) return ELORA_E_SHAPE;
+    decode_set_passes(mode);
+    return ELORA_OK;
+}
+
 int elora_debug_decode_wide(int mode)
 {
     if (mode < -1 || mode > 1) return ELORA_E_SHAPE;
@@ -316,10 +323,10 @@ static int fill_args(const elora_linear_desc_t *d, const WsLayout &wsl, hipStrea
         rc = pool_ensure_cleared(const_cast<elora_pool *>(d->pool), stream);
         if (rc != ELORA_OK) return rc;
         a.pool = d->pool->view();
-        a.route = RouteView{d->adapter_idx, d->seg_offsets, d->seg_adapter, d->n_segments, d->scales};
+        a.route = RouteView{d->adapter_idx, d->seg_offsets, d->seg_adapter, d->n_segments, d->scales, 0};
     } else {
         a.pool = PoolView{nullptr, nullptr, nullptr, 0, 0, 0, 1};
-        a.route = RouteView{nullptr, nullptr, nullptr, 0, nullptr};
+        a.route = RouteView{nullptr, nullptr, nullptr, 0, nullptr, 0};
     }
     return ELORA_OK;
 }
@@ -333,7 +340,24 @@ static int enqueue_linear(const elora_linear_desc_t *d, const WsLayout &wsl, hip
     const int rc = fill_args(d, wsl, stream, a);
     if (rc != ELORA_OK) return rc;
     switch (plan.path) {
-    case ELORA_PATH_DECODE: return launch_decode(a, plan, stream);
+    case ELORA_PATH_DECODE: {
+        if (a.T <= kDecodeMaxTokens) return launch_decode(a, plan, stream);
+        // more rows than one launch takes: balanced row ranges, one launch each, on the same workspace one after the other
+        const int passes = plan.n_launches, es = 2;  // (bf16)
+        int row = 0;
+        for (int p = 0; p < passes; ++p) {
+            const int rows = a.T / passes + (p < a.T % passes ? 1 : 0);
+            LinearArgs b = a;
+            b.T = rows;
+            b.x = static_cast<const char *>(a.x) + (size_t)row * a.K * es;
+            b.y = static_cast<char *>(a.y) + (size_t)row * a.N * es;
+            b.route.row_base = row;
+            const int rc2 = launch_decode(b, plan, stream);
+            if (rc2 != ELORA_OK) return rc2;
+            row += rows;
+        }
+        return ELORA_OK;
+    }
     case ELORA_PATH_GEMM: return launch_gemm(a, plan, stream);
     default: return launch_generic(a, stream);
     }

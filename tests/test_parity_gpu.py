@@ -133,6 +133,48 @@ def test_wide_decode_kernel_small_shapes(shape, spin):
     case.close()
 
 
+@pytest.mark.parametrize("T", [65, 128, 130, 255, 256])
+@pytest.mark.parametrize("segments", [False, True])
+def test_65_to_256_rows_run_as_several_launches_of_the_decode_kernel(T, segments):
+    """Balanced row ranges, one launch each, on one workspace: per-row and per-segment routing, scale overrides that
+    are indexed by the batch's rows (or segments), and bad indices reported with the batch's row numbers."""
+    from paper_2507_01438_amd import binding as B
+    lengths = None
+    if segments:
+        lengths = [40, 0, 1, T - 40 - 1 - 17, 17]      # segments that straddle the row ranges
+    w = I.small_workload(600 + T, I.BF16, 1024, 272, T, 9, (8, 16, 32, 64, 24), segments=lengths,
+                         no_adapter_rows=(1,) if segments else (0, 64, T - 1))
+    case = DeviceCase(w, w.projections[0])
+    y = case.run()
+    assert case.last_plan.path == DECODE and case.last_plan.n_launches == (T + 63) // 64
+    ref = case.reference()
+    assert_close(y, ref, case.base_reference(), f"{T} rows")
+    assert np.array_equal(y, case.run())
+    n_sc = len(lengths) if segments else T
+    sc = np.linspace(-1.5, 2.5, n_sc).astype(np.float32)
+    row_scale = np.repeat(sc, lengths).astype(np.float32) if segments else sc
+    _check(case, case.run(scales=to_dev(sc)), case.reference(row_scale=row_scale))
+    # the MFMA GEMM path on the same call
+    B.elora_debug_decode_passes(0)
+    try:
+        yg = case.run()
+        assert case.last_plan.path == GEMM
+    finally:
+        B.elora_debug_decode_passes(-1)
+    _check(case, yg, ref)
+    assert case.pool.poll_error() == (0, -1)
+    if not segments:
+        bad = w.adapter_idx.copy()
+        first = T // 2 + 3                              # in the second row range, like the last row but one
+        bad[first], bad[T - 2] = 99, -7
+        case.adapter_idx.copy_(to_dev(bad))
+        cleaned = bad.copy()
+        cleaned[first] = cleaned[T - 2] = -1
+        _check(case, case.run(), case.reference(row_adapter=cleaned))
+        assert case.pool.poll_error() == (2, first)
+    case.close()
+
+
 def test_waits_that_run_out_of_time_fall_back_to_the_inputs():
     """With a time bound of one microsecond on every wait between workgroups (the poll bound left alone), waits that are
     not served at once give up and compute from the inputs; results stay right, and the workspace is clean afterwards."""
