@@ -69,11 +69,15 @@ def _load():
 
 @dataclass
 class Adapter:
-    """One pool entry: A [rank, K], B [N, rank], scale = alpha / rank."""
+    """One pool entry: A [rank, K], B [N, rank], scale = alpha / rank.  With A_scales / B_scales (uint16 fp16 bit
+    patterns, one per block of 32 consecutive values in row-major order) A and B are int8 codes: the 8-bit block
+    format the paper keeps its adapters in (Sec. 5 "Model"), value = scale * code."""
 
     A: np.ndarray
     B: np.ndarray
     scale: float
+    A_scales: Optional[np.ndarray] = None
+    B_scales: Optional[np.ndarray] = None
 
     @property
     def rank(self) -> int:
@@ -139,14 +143,27 @@ def _pool_args(dtype: int, adapters: Sequence[Optional[Adapter]], K: int, N: int
     scales = np.zeros(max(P, 1), dtype=np.float64)
     A_ptrs = (ctypes.c_void_p * max(P, 1))()
     B_ptrs = (ctypes.c_void_p * max(P, 1))()
+    As_ptrs = (ctypes.c_void_p * max(P, 1))()
+    Bs_ptrs = (ctypes.c_void_p * max(P, 1))()
     keep = []
     for i, ad in enumerate(adapters):
         if ad is None:
             A_ptrs[i] = None
             B_ptrs[i] = None
             continue
-        A = _check_tensor(ad.A, dtype, f"A[{i}]")
-        B = _check_tensor(ad.B, dtype, f"B[{i}]")
+        if ad.A_scales is not None or ad.B_scales is not None:
+            A, B = np.ascontiguousarray(ad.A), np.ascontiguousarray(ad.B)
+            As, Bs = np.ascontiguousarray(ad.A_scales), np.ascontiguousarray(ad.B_scales)
+            if A.dtype != np.int8 or B.dtype != np.int8 or As.dtype != np.uint16 or Bs.dtype != np.uint16:
+                raise TypeError(f"adapter {i}: 8-bit blocks are int8 codes with uint16 (fp16 bit pattern) scales")
+            if A.size % 32 or B.size % 32 or As.size != A.size // 32 or Bs.size != B.size // 32:
+                raise ValueError(f"adapter {i}: one scale per block of 32 values")
+            keep += [As, Bs]
+            As_ptrs[i] = As.ctypes.data
+            Bs_ptrs[i] = Bs.ctypes.data
+        else:
+            A = _check_tensor(ad.A, dtype, f"A[{i}]")
+            B = _check_tensor(ad.B, dtype, f"B[{i}]")
         r = A.shape[0]
         if A.shape != (r, K) or B.shape != (N, r):
             raise ValueError(f"adapter {i}: A {A.shape} / B {B.shape} do not fit K={K}, N={N}")
@@ -155,7 +172,7 @@ def _pool_args(dtype: int, adapters: Sequence[Optional[Adapter]], K: int, N: int
         scales[i] = float(ad.scale)
         A_ptrs[i] = A.ctypes.data
         B_ptrs[i] = B.ctypes.data
-    return P, ranks, scales, A_ptrs, B_ptrs, keep
+    return P, ranks, scales, (A_ptrs, As_ptrs), (B_ptrs, Bs_ptrs), keep
 
 
 def _w_args(dtype: int, wfmt: int, W: np.ndarray, w_scales: Optional[np.ndarray], K: int):
@@ -204,7 +221,7 @@ def linear(dtype: int, x: np.ndarray, W: np.ndarray, adapters: Sequence[Optional
     used = _load().elora_oracle_linear(
         ctypes.c_int(dtype), ctypes.c_int(wfmt), ctypes.c_int(T), ctypes.c_int(K), ctypes.c_int(N),
         _ptr(xc), _ptr(Wc), _ptr(ws),
-        ctypes.c_int(P), _ptr(ranks), _ptr(scales), A_ptrs, B_ptrs,
+        ctypes.c_int(P), _ptr(ranks), _ptr(scales), A_ptrs[0], B_ptrs[0], A_ptrs[1], B_ptrs[1],
         _ptr(ra), _ptr(rs),
         ctypes.c_int(nr), _ptr(rsel), ctypes.c_int(nc), _ptr(csel),
         _ptr(y), ctypes.c_int(n_threads))
@@ -233,7 +250,7 @@ def linear_grouped(dtype: int, x: np.ndarray, W: np.ndarray, adapters, row_adapt
     rc = _load().elora_oracle_linear_grouped(
         ctypes.c_int(dtype), ctypes.c_int(wfmt), ctypes.c_int(T), ctypes.c_int(K), ctypes.c_int(N),
         _ptr(xc), _ptr(Wc), _ptr(ws),
-        ctypes.c_int(P), _ptr(ranks), _ptr(scales), A_ptrs, B_ptrs, _ptr(ra), _ptr(rs), _ptr(y))
+        ctypes.c_int(P), _ptr(ranks), _ptr(scales), A_ptrs[0], B_ptrs[0], A_ptrs[1], B_ptrs[1], _ptr(ra), _ptr(rs), _ptr(y))
     del keep
     if rc < 1:
         raise ValueError(f"oracle rejected its arguments (code {rc})")

@@ -30,6 +30,12 @@
  *   W [N, K]   so that y_t[n] = sum_k W[n,k] x_t[k]
  *   A_i [r_i, K],  B_i [N, r_i]
  * dtype codes: 0 = IEEE fp32, 1 = bfloat16 stored as uint16 bit patterns.
+ * Adapters kept in 8-bit blocks (the paper stores all adapters in the format its
+ * settings call "Q8_0", Sec. 5 "Model"): A_i / B_i are then int8 codes in the same
+ * row-major shapes, cut into blocks of 32 consecutive values in that order (a
+ * block may run across rows), with one fp16 scale per block:
+ *     value = fp16_scale[flat_index / 32] * code.
+ * An adapter is in that format when a scale array is given for it.
  * wfmt codes:  0 = W has the dtype above,
  *              1 = W is 4-bit group-wise: byte b of row n holds code(k=2b) in
  *                  its low nibble and code(k=2b+1) in its high nibble,
@@ -82,6 +88,14 @@ static double widen(int dtype, const void *p, size_t idx)
     if (dtype == ORACLE_F32)
         return (double)((const float *)p)[idx];
     return widen_bf16(((const uint16_t *)p)[idx]);
+}
+
+/* entry `idx` (flat, row-major) of an adapter matrix: in the dtype above, or scale * code for 8-bit blocks */
+static double adapter_at(int dtype, const void *p, const uint16_t *block_scales, size_t idx)
+{
+    if (block_scales == NULL)
+        return widen(dtype, p, idx);
+    return widen_fp16(block_scales[idx / 32]) * (double)((const int8_t *)p)[idx];
 }
 
 static double weight_at(int dtype, int wfmt, const void *W, const uint16_t *w_scales,
@@ -164,6 +178,8 @@ int elora_oracle_ubatches(int T, int P, const int32_t *row_adapter, int32_t *per
  *
  *   ranks[i], adapter_scale[i], A[i], B[i]   describe pool entry i (A[i]/B[i]
  *       may be NULL for entries no row uses)
+ *   A_scales, B_scales   NULL, or per entry NULL (A[i]/B[i] in `dtype`) or the fp16
+ *       block scales of an entry kept as int8 codes
  *   row_adapter[t]  adapter of row t, or < 0 for "base model only"
  *   row_scale       NULL, or one factor per row that replaces adapter_scale
  *   n_threads       <= 0: library default; the value used is returned.
@@ -174,6 +190,7 @@ int elora_oracle_linear(int dtype, int wfmt, int T, int K, int N,
                         const void *x, const void *W, const uint16_t *w_scales,
                         int P, const int32_t *ranks, const double *adapter_scale,
                         const void *const *A, const void *const *B,
+                        const uint16_t *const *A_scales, const uint16_t *const *B_scales,
                         const int32_t *row_adapter, const float *row_scale,
                         int n_rows_sel, const int32_t *rows,
                         int n_cols_sel, const int32_t *cols,
@@ -212,7 +229,7 @@ int elora_oracle_linear(int dtype, int wfmt, int T, int K, int N,
         for (int j = 0; j < r; ++j) {
             double s = 0.0;
             for (int k = 0; k < K; ++k)
-                s += widen(dtype, A[i], (size_t)j * K + k) * xt[k];
+                s += adapter_at(dtype, A[i], A_scales ? A_scales[i] : NULL, (size_t)j * K + k) * xt[k];
             v[j] = s;
         }
         double scale = 0.0;
@@ -229,7 +246,7 @@ int elora_oracle_linear(int dtype, int wfmt, int T, int K, int N,
             if (i >= 0) {
                 double d = 0.0;
                 for (int j = 0; j < r; ++j)
-                    d += widen(dtype, B[i], (size_t)n * r + j) * v[j];
+                    d += adapter_at(dtype, B[i], B_scales ? B_scales[i] : NULL, (size_t)n * r + j) * v[j];
                 acc += scale * d;
             }
             y[(size_t)ri * n_cols_sel + ci] = acc;
@@ -254,6 +271,7 @@ int elora_oracle_linear_grouped(int dtype, int wfmt, int T, int K, int N,
                                 const void *x, const void *W, const uint16_t *w_scales,
                                 int P, const int32_t *ranks, const double *adapter_scale,
                                 const void *const *A, const void *const *B,
+                                const uint16_t *const *A_scales, const uint16_t *const *B_scales,
                                 const int32_t *row_adapter, const float *row_scale,
                                 double *y)
 {
@@ -290,7 +308,7 @@ int elora_oracle_linear_grouped(int dtype, int wfmt, int T, int K, int N,
             for (int j = 0; j < r; ++j) {
                 double s = 0.0;
                 for (int k = 0; k < K; ++k)
-                    s += widen(dtype, A[i], (size_t)j * K + k) * xg[(size_t)g * K + k];
+                    s += adapter_at(dtype, A[i], A_scales ? A_scales[i] : NULL, (size_t)j * K + k) * xg[(size_t)g * K + k];
                 vg[(size_t)g * r + j] = s;
             }
         /* (4) scale, combine, scatter to the original row */
@@ -300,7 +318,7 @@ int elora_oracle_linear_grouped(int dtype, int wfmt, int T, int K, int N,
             for (int n = 0; n < N; ++n) {
                 double d = 0.0;
                 for (int j = 0; j < r; ++j)
-                    d += widen(dtype, B[i], (size_t)n * r + j) * vg[(size_t)g * r + j];
+                    d += adapter_at(dtype, B[i], B_scales ? B_scales[i] : NULL, (size_t)n * r + j) * vg[(size_t)g * r + j];
                 y[(size_t)t * N + n] += scale * d;
             }
         }

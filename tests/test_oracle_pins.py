@@ -311,3 +311,84 @@ def test_bad_arguments_are_rejected():
         oracle.linear(I.F32, x, W, [None] + ads[1:], ra)
     with pytest.raises(TypeError):
         oracle.linear(I.BF16, x, W, ads, ra)
+
+
+# ---------------------------------------------------------------------------------------------
+# adapters kept in 8-bit blocks (Sec. 5 "Model": all adapters in the block format called Q8_0):
+# value = fp16 scale of the block * int8 code, blocks of 32 consecutive values in row-major order
+# ---------------------------------------------------------------------------------------------
+
+def _fp16_bits(v):
+    return np.array(v, dtype=np.float16).view(np.uint16)
+
+
+def _dequant_independent(codes, scales_bits):
+    """scale * code with numpy's own fp16 decoding, as float64 (exact)."""
+    sc = np.asarray(scales_bits, dtype=np.uint16).view(np.float16).astype(np.float64)
+    return (np.asarray(codes, dtype=np.int8).reshape(-1).astype(np.float64) * np.repeat(sc, 32)).reshape(np.shape(codes))
+
+
+def test_q8_adapters_unit_scales_integer_closed_form():
+    # unit scales, integer x, W = 0: y = s * B_codes (A_codes x) in integers, exactly
+    rng = np.random.default_rng(81)
+    K, N, T, r = 64, 12, 5, 8
+    x = rng.integers(-3, 4, size=(T, K)).astype(np.float32)
+    W = np.zeros((N, K), np.float32)
+    Ac = rng.integers(-127, 128, size=(r, K), dtype=np.int8)
+    Bc = rng.integers(-127, 128, size=(N, r), dtype=np.int8)
+    one = lambda n: np.full(n // 32, 0x3C00, dtype=np.uint16)
+    ad = oracle.Adapter(Ac, Bc, 2.0, A_scales=one(Ac.size), B_scales=one(Bc.size))
+    y = oracle.linear(I.F32, x, W, [ad], np.zeros(T, np.int32))
+    want = 2 * (Bc.astype(np.int64) @ (Ac.astype(np.int64) @ x.astype(np.int64).T)).T
+    assert np.array_equal(y, want.astype(np.float64))
+
+
+def test_q8_adapter_blocks_run_across_rows_and_carry_their_own_scales():
+    # B [8, 8]: 64 values = two blocks of four rows each.  Only B[5, 2] = 3 and A[2, 40] = 5 are non-zero, x = e_40:
+    # y[5] = s * (scale of B's second block) * 3 * (scale of A's block 2 * 2 + 1 = 5: row 2, columns 32..63) * 5.
+    K, N, r = 64, 8, 8
+    Ac = np.zeros((r, K), np.int8); Ac[2, 40] = 5
+    Bc = np.zeros((N, r), np.int8); Bc[5, 2] = 3
+    As = _fp16_bits(np.arange(1, 17, dtype=np.float32) * 0.25)      # block b of A has scale (b + 1) / 4
+    Bs = _fp16_bits([0.5, -1.5])
+    x = np.zeros((1, K), np.float32); x[0, 40] = 1
+    ad = oracle.Adapter(Ac, Bc, 1.0, A_scales=As, B_scales=Bs)
+    y = oracle.linear(I.F32, x, np.zeros((N, K), np.float32), [ad], np.zeros(1, np.int32))
+    want = np.zeros((1, N)); want[0, 5] = (-1.5 * 3) * ((6 / 4) * 5)
+    assert np.array_equal(y, want)
+
+
+def _b2d(bits):
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def test_q8_adapters_equal_the_dense_product_of_their_dequantised_values():
+    # against numpy float64 on independently dequantised matrices; mixed with an adapter in bf16, ranks 8 and 16,
+    # bf16 x and W; per-sample and grouped forms agree
+    rng = np.random.default_rng(82)
+    K, N, T = 96, 20, 7
+    x = _bf16((rng.standard_normal((T, K))).astype(np.float32))
+    W = _bf16((rng.standard_normal((N, K)) * 0.05).astype(np.float32))
+    ads, dense = [], []
+    for r in (8, 16):
+        Ac = rng.integers(-127, 128, size=(r, K), dtype=np.int8)
+        Bc = rng.integers(-127, 128, size=(N, r), dtype=np.int8)
+        As = _fp16_bits(rng.uniform(1e-3, 2e-2, Ac.size // 32).astype(np.float32))
+        Bs = _fp16_bits(rng.uniform(1e-3, 2e-2, Bc.size // 32).astype(np.float32))
+        ads.append(oracle.Adapter(Ac, Bc, 1.5, A_scales=As, B_scales=Bs))
+        dense.append((_dequant_independent(Ac, As), _dequant_independent(Bc, Bs), 1.5))
+    A2 = _bf16((rng.standard_normal((4, K)) * 0.05).astype(np.float32))
+    B2 = _bf16((rng.standard_normal((N, 4)) * 0.05).astype(np.float32))
+    ads.append(oracle.Adapter(A2, B2, 0.5))
+    dense.append((_b2d(A2), _b2d(B2), 0.5))
+    ra = np.array([0, 1, 2, -1, 1, 0, 2], dtype=np.int32)
+    y = oracle.linear(I.BF16, x, W, ads, ra)
+    xf, Wf = _b2d(x), _b2d(W)
+    want = xf @ Wf.T
+    for t, i in enumerate(ra):
+        if i >= 0:
+            A, B, s = dense[i]
+            want[t] += s * (B @ (A @ xf[t]))
+    assert np.abs(y - want).max() <= 1e-12 * np.abs(want).max()
+    yg = oracle.linear_grouped(I.BF16, x, W, ads, ra)
+    assert np.abs(yg - y).max() <= 1e-12 * np.abs(y).max()
