@@ -70,6 +70,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="distinct (W, pool, x) copies the decode steps rotate through")
     ap.add_argument("--no-groups", action="store_true",
                     help="config 3: one launch per projection instead of one for q/k/v and one for gate/up")
+    ap.add_argument("--q8-adapters", action="store_true",
+                    help="decode configurations with every adapter kept in 8-bit blocks in the pool (the paper's adapter "
+                         "storage): a line of its own, not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--cache-trace", action="store_true",
@@ -196,6 +199,8 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     from gpu_harness import DeviceCase, rel_err, to_dev, y_to_f64
 
     decode = cfg in (2, 3)
+    q8 = bool(args.q8_adapters)
+    assert decode or not q8, "--q8-adapters: decode configurations only"
     w = I.CONFIGS[cfg]()
     projs = w.projections
     distinct = w.distinct_adapters()
@@ -208,13 +213,13 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     cases = []
     for p in projs:
         first = next((c for c in cases if c.proj.K == p.K), None)
-        cases.append(DeviceCase(w, p, load_slots=None if cfg == 2 else distinct, share=first))
+        cases.append(DeviceCase(w, p, load_slots=None if cfg == 2 else distinct, share=first, q8=q8))
     layer_bytes = sum(p.N * p.K * 2 for p in projs)
     L = args.layers if args.layers is not None else (max(2, min(32, int(1.6e9 // layer_bytes))) if decode else 1)
     layers = []  # layers[l][pi] = descriptor
     keep = []
-    dev_adapters = [{i: (to_dev(A), to_dev(Bm), sc) for i, (A, Bm, sc) in case.adapters.items()} if L > 1 else {}
-                    for case in cases]
+    dev_adapters = [{i: tuple(to_dev(t) if isinstance(t, np.ndarray) else t for t in ad) for i, ad in case.adapters.items()}
+                    if L > 1 else {} for case in cases]
     for l in range(L):
         descs = []
         x_of = {}  # this layer's copy of x per d_in
@@ -225,9 +230,13 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
             if p.K not in x_of:
                 x_of[p.K] = case.x.clone()
             Wc, xc, yc = case.W.clone(), x_of[p.K], torch.zeros_like(case.y)
-            pool = B.AdapterPool(p.K, p.N, w.max_rank, w.pool, w.dtype, dev)
-            for i, (A_d, B_d, sc) in dev_adapters[pi].items():
-                pool.load(i, A_d, B_d, sc)
+            pool = B.AdapterPool(p.K, p.N, w.max_rank, w.pool, w.dtype, dev, q8=q8)
+            for i, ad in dev_adapters[pi].items():
+                if q8:
+                    Ac, Bc, sc, As, Bs = ad
+                    B.elora_pool_load_adapters_q8(pool.handle, [i], [Ac.shape[0]], [sc], [Ac], [As], [Bc], [Bs])
+                else:
+                    pool.load(i, ad[0], ad[1], ad[2])
             lin = B.LoraLinear(p.K, p.N, w.dtype, pool, w.T, dev, wfmt=w.wfmt)
             keep += [Wc, xc, yc, pool, lin]
             descs.append(lin.desc(xc, Wc, yc, adapter_idx=case.adapter_idx, seg_offsets=case.seg_offsets,
@@ -239,7 +248,8 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     n_proj = len(projs)
     # Projections that are due at the same time go out as one launch (config 3: q/k/v and gate/up).
     names = [p.name for p in projs]
-    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if not args.no_groups else []
+    # (calls with a pool of 8-bit blocks are launched one by one)
+    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if not (args.no_groups or q8) else []
     units = []  # per launch of a step: the projection indices it covers
     for pi, n in enumerate(names):
         g = next((g for g in group_names if n in g), None)
@@ -284,7 +294,7 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     region_us_per_launch = ev0.elapsed_time(ev1) * 1e3 / (steps * n_launch)
 
     flops_step = sum(w.algorithmic_flops(p) for p in projs)
-    bytes_step = sum(w.algorithmic_bytes(p) for p in projs)
+    bytes_step = sum(w.algorithmic_bytes(p, q8_adapters=q8) for p in projs)
     if decode:
         # The decode path is one kernel per call and the launches run back to back, so the device time of the
         # timed region (HIP events on the launch stream) divided by the number of launches is the kernel's average
@@ -365,7 +375,7 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
         "warmup": warmup,
         "ms_per_step": ms_per_step,
         "config": {
-            "workload": WORKLOAD[cfg],
+            "workload": WORKLOAD[cfg] + (" -- adapters kept in 8-bit blocks (int8 codes, fp16 scale per 32 values)" if q8 else ""),
             "config_number": cfg, "n_tokens": w.T, "projections": [p.name for p in projs],
             "distinct_adapters": int(len(distinct)), "rotating_layers": L,
             "path": [int(pl.path) for pl in plans], "split_k": [int(pl.split_k) for pl in plans],

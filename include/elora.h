@@ -134,9 +134,10 @@ int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const 
  * The same for adapters that are kept in 8-bit blocks, the storage format of the paper's adapters (Sec. 5 "Model"
  * names it "Q8_0"; the layout here is this library's own): A_codes[i] int8 [rank, d_in] and B_codes[i] int8
  * [d_out, rank], row-major, cut into blocks of 32 consecutive values in that order; A_scales[i] / B_scales[i] one
- * fp16 per block; value = scale * code.  The blocks are converted on the way in: the pool (dtype bf16) receives
- * bf16(scale * code), the product exact, one rounding to nearest even, so the linear calls see an ordinary bf16
- * adapter while half the bytes cross the bus.  Sources: device memory or pinned host memory, codes 8-byte aligned;
+ * fp16 per block; value = scale * code.  Into a pool created by elora_pool_create (dtype bf16) the blocks are
+ * converted on the way in: the pool receives bf16(scale * code), the product exact, one rounding to nearest even, so
+ * the linear calls see an ordinary bf16 adapter while half the bytes cross the bus.  Into a pool created by
+ * elora_pool_create_q8 they are copied as they are (ranks then multiples of 8: E_RANK otherwise).  Sources: device memory or pinned host memory, codes 8-byte aligned;
  * rank * d_in and rank * d_out multiples of 32.  One launch per 16 adapters.
  * Errors: E_NULL, E_SHAPE, E_DTYPE (pool is not bf16), E_SLOT, E_RANK, E_ALIGN (a source the device cannot read, or
  * misaligned), E_HIP.
@@ -144,6 +145,19 @@ int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const 
 int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, const int *ranks, const float *scales,
                                 const void *const *A_codes, const void *const *A_scales, const void *const *B_codes,
                                 const void *const *B_scales, elora_stream_t stream);
+
+/*
+ * A pool whose adapters STAY in 8-bit blocks (the paper's adapter storage, Sec. 5 "Model"): the blocks placed by
+ * elora_pool_load_adapters_q8 are kept as they are (int8 codes and fp16 block scales), and the linear kernels read
+ * them directly, value = scale * code formed in registers, so an adapter costs half the memory and half the traffic
+ * of its bf16 form.  x, y and W of calls that use the pool are bf16.  d_in % 32 == 0, d_out % 4 == 0, max_rank and
+ * every loaded rank multiples of 8.  Calls with such a pool take the decode path (up to 256 rows, max_rank <= 64) or
+ * else the generic kernels; elora_pool_load_adapter / _load_adapters (sources in bf16) answer E_DTYPE.
+ * Errors: as elora_pool_create, E_SHAPE / E_RANK for the divisibility rules above.
+ */
+size_t elora_pool_storage_bytes_q8(int d_in, int d_out, int max_rank, int capacity);
+int elora_pool_create_q8(int d_in, int d_out, int max_rank, int capacity, void *dev_storage, size_t storage_bytes,
+                         elora_pool_t **out);
 
 /* Mark `slot` empty (its block returns to the pool, Sec. 4.2).  Rows that still refer to it are
  * treated like rows with an invalid index.  Errors: E_NULL, E_SLOT, E_NOT_LOADED, E_HIP. */

@@ -34,7 +34,7 @@ ELORA_PATH_GENERIC, ELORA_PATH_DECODE, ELORA_PATH_GEMM = 0, 1, 2
 
 EXPORTED = [
     "elora_status_string", "elora_version", "elora_pool_storage_bytes", "elora_pool_create",
-    "elora_pool_destroy", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_load_adapters_q8", "elora_pool_evict", "elora_pool_slot_info",
+    "elora_pool_destroy", "elora_pool_storage_bytes_q8", "elora_pool_create_q8", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_load_adapters_q8", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_workspace_bytes_w", "elora_linear_plan", "elora_batched_lora_linear",
     "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_batched_lora_linear_noalloc", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
     "elora_debug_spin_limit", "elora_debug_xcd_local", "elora_debug_k_rotate", "elora_debug_decode_wide", "elora_debug_decode_passes", "elora_debug_wait_limit_us",
@@ -70,6 +70,10 @@ lib.elora_pool_storage_bytes.restype = ctypes.c_size_t
 lib.elora_pool_storage_bytes.argtypes = [ctypes.c_int] * 5
 lib.elora_pool_create.restype = ctypes.c_int
 lib.elora_pool_create.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_void_p)]
+lib.elora_pool_storage_bytes_q8.restype = ctypes.c_size_t
+lib.elora_pool_storage_bytes_q8.argtypes = [ctypes.c_int] * 4
+lib.elora_pool_create_q8.restype = ctypes.c_int
+lib.elora_pool_create_q8.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_void_p)]
 lib.elora_pool_destroy.restype = ctypes.c_int
 lib.elora_pool_destroy.argtypes = [ctypes.c_void_p]
 lib.elora_pool_load_adapter.restype = ctypes.c_int
@@ -200,6 +204,17 @@ def elora_pool_create(d_in, d_out, max_rank, capacity, dtype, dev_storage, stora
     out = ctypes.c_void_p()
     _check(lib.elora_pool_create(d_in, d_out, max_rank, capacity, dtype, _ptr(dev_storage), storage_bytes,
                                  ctypes.byref(out)), "elora_pool_create")
+    return out.value
+
+
+def elora_pool_storage_bytes_q8(d_in: int, d_out: int, max_rank: int, capacity: int) -> int:
+    return int(lib.elora_pool_storage_bytes_q8(d_in, d_out, max_rank, capacity))
+
+
+def elora_pool_create_q8(d_in, d_out, max_rank, capacity, dev_storage, storage_bytes) -> int:
+    out = ctypes.c_void_p()
+    _check(lib.elora_pool_create_q8(d_in, d_out, max_rank, capacity, _ptr(dev_storage), storage_bytes, ctypes.byref(out)),
+           "elora_pool_create_q8")
     return out.value
 
 
@@ -462,13 +477,19 @@ def elora_cache_batch_end(cache: int, slots, compute_stream=None) -> None:
 class AdapterPool:
     """Device storage (a torch byte tensor) plus the library's pool handle."""
 
-    def __init__(self, d_in, d_out, max_rank, capacity, dtype, device="cuda:0"):
-        self.d_in, self.d_out, self.max_rank, self.capacity, self.dtype = d_in, d_out, max_rank, capacity, dtype
-        self.nbytes = elora_pool_storage_bytes(d_in, d_out, max_rank, capacity, dtype)
+    def __init__(self, d_in, d_out, max_rank, capacity, dtype, device="cuda:0", q8=False):
+        """q8: the adapters stay in 8-bit blocks (elora_pool_create_q8; dtype must be bf16)."""
+        self.d_in, self.d_out, self.max_rank, self.capacity, self.dtype, self.q8 = d_in, d_out, max_rank, capacity, dtype, q8
+        self.nbytes = (elora_pool_storage_bytes_q8(d_in, d_out, max_rank, capacity) if q8 else
+                       elora_pool_storage_bytes(d_in, d_out, max_rank, capacity, dtype))
         if self.nbytes == 0:
             raise EloraError(ELORA_E_SHAPE, "elora_pool_storage_bytes")
         self.storage = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
-        self.handle = elora_pool_create(d_in, d_out, max_rank, capacity, dtype, self.storage, self.nbytes)
+        if q8:
+            assert dtype == ELORA_BF16
+            self.handle = elora_pool_create_q8(d_in, d_out, max_rank, capacity, self.storage, self.nbytes)
+        else:
+            self.handle = elora_pool_create(d_in, d_out, max_rank, capacity, dtype, self.storage, self.nbytes)
 
     def load(self, slot, A, B, scale, stream=None):
         """A [rank, d_in], B [d_out, rank]: torch tensors (device or host, contiguous) of the pool's dtype."""

@@ -26,6 +26,11 @@ struct PoolView {
     size_t b_offset;       // byte offset of the B region inside a block
     int capacity;
     int max_rank;
+    // Adapters kept in 8-bit blocks (q8 != 0): the A and B regions hold int8 codes in the same shapes, and each is
+    // followed by its fp16 scales, one per block of 32 consecutive values in row-major order (value = scale * code).
+    int q8;
+    size_t a_scale_off;    // byte offset of A's scales inside a block
+    size_t b_scale_off;    // byte offset of B's scales inside a block
 };
 
 struct RouteView {
@@ -73,6 +78,8 @@ WsLayout ws_layout(int n_tokens, int d_in, int d_out, int max_rank, int wfmt);
 
 struct elora_pool {
     int d_in, d_out, max_rank, capacity, dtype;
+    int q8;  // 1: adapters stay in 8-bit blocks (dtype is then that of x and y: bf16)
+    size_t a_scale_off, b_scale_off;
     char *storage;
     size_t storage_bytes;
     size_t meta_offset, slots_offset, slot_bytes, b_offset;
@@ -269,6 +276,70 @@ __device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, con
                 const uint32_t xw = xv[i][q], aw0 = a0[i][q], aw1 = a1[i][q];
                 s0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw0), __builtin_bit_cast(elora_bf16x2, xw), s0, false);
                 s1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(elora_bf16x2, aw1), __builtin_bit_cast(elora_bf16x2, xw), s1, false);
+            }
+        }
+    }
+    r0 = wave_sum(s0);
+    r1 = wave_sum(s1);
+}
+
+__device__ __forceinline__ const uint16_t *slot_A_scales(const PoolView &p, int slot)
+{
+    return reinterpret_cast<const uint16_t *>(p.slots + (size_t)slot * p.slot_bytes + p.a_scale_off);
+}
+__device__ __forceinline__ const uint16_t *slot_B_scales(const PoolView &p, int slot)
+{
+    return reinterpret_cast<const uint16_t *>(p.slots + (size_t)slot * p.slot_bytes + p.b_scale_off);
+}
+// entry `idx` (row-major) of a matrix kept in 8-bit blocks: the block's scale times the code (exact in fp32)
+__device__ __forceinline__ float q8_elem(const char *codes, const uint16_t *scales, size_t idx)
+{
+    return fp16_to_f32(scales[idx >> 5]) * (float)reinterpret_cast<const int8_t *>(codes)[idx];
+}
+// sum of code[j] * x[j] over 16 consecutive values: codes in c (4 per word, signed), x as 16 bf16 in xa, xb
+__device__ __forceinline__ float q8_dot16(const elora_u32x4 &c, const elora_u32x4 &xa, const elora_u32x4 &xb)
+{
+    float s = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t cw = c[q];
+        const uint32_t x01 = q < 2 ? xa[2 * q] : xb[2 * q - 4], x23 = q < 2 ? xa[2 * q + 1] : xb[2 * q - 3];
+        s = fmaf((float)(int8_t)(cw & 0xffu), __uint_as_float(x01 << 16), s);
+        s = fmaf((float)(int8_t)((cw >> 8) & 0xffu), __uint_as_float(x01 & 0xffff0000u), s);
+        s = fmaf((float)(int8_t)((cw >> 16) & 0xffu), __uint_as_float(x23 << 16), s);
+        s = fmaf((float)(int8_t)(cw >> 24), __uint_as_float(x23 & 0xffff0000u), s);
+    }
+    return s;
+}
+
+// One wave: v[t][j0], v[t][j0+1] = A_i[j0..j0+1, :] . x[t, :] over the whole of K for an adapter kept in 8-bit blocks
+// (K % 256 == 0): 16 codes per lane and load, every 16 inside one block of 32, so one scale per load.
+__device__ __forceinline__ void shrink_pair_q8(const char *__restrict__ A0, const char *__restrict__ A1,
+                                               const uint16_t *__restrict__ S0, const uint16_t *__restrict__ S1,
+                                               const uint16_t *__restrict__ xt, int K, int lane, float &r0, float &r1)
+{
+    float s0 = 0.0f, s1 = 0.0f;
+    const int pieces = K >> 4;  // 16-value pieces per row
+    for (int pb = 0; pb < pieces; pb += 64 * 4) {
+        elora_u32x4 xa[4], xb[4], c0[4], c1[4];
+        uint16_t sc0[4], sc1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int p = pb + i * 64 + lane;
+            const size_t pc = (size_t)(p < pieces ? p : 0);
+            xa[i] = *reinterpret_cast<const elora_u32x4 *>(xt + pc * 16);
+            xb[i] = *reinterpret_cast<const elora_u32x4 *>(xt + pc * 16 + 8);
+            c0[i] = __builtin_nontemporal_load(reinterpret_cast<const elora_u32x4 *>(A0 + pc * 16));
+            c1[i] = __builtin_nontemporal_load(reinterpret_cast<const elora_u32x4 *>(A1 + pc * 16));
+            sc0[i] = S0[pc >> 1];
+            sc1[i] = S1[pc >> 1];
+        }
+        __builtin_amdgcn_sched_barrier(0);  // all loads of a round in flight together
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (pb + i * 64 + lane < pieces) {
+                s0 = fmaf(fp16_to_f32(sc0[i]), q8_dot16(c0[i], xa[i], xb[i]), s0);
+                s1 = fmaf(fp16_to_f32(sc1[i]), q8_dot16(c1[i], xa[i], xb[i]), s1);
             }
         }
     }

@@ -232,14 +232,23 @@ __device__ __forceinline__ void recompute_columns(const DecodeShape &sh, const u
         if (rr.slot >= 0) {
             const uint16_t *A = reinterpret_cast<const uint16_t *>(slot_A(pool, rr.slot));
             const uint16_t *B = reinterpret_cast<const uint16_t *>(slot_B(pool, rr.slot));
+            const uint16_t *As = slot_A_scales(pool, rr.slot), *Bs = slot_B_scales(pool, rr.slot);  // (8-bit blocks)
             for (int j0 = 0; j0 < rr.rank; j0 += 2) {
                 const bool two = (j0 + 1) < rr.rank;
+                const int j1 = two ? j0 + 1 : j0;
                 float r0, r1;
-                shrink_pair(A + (size_t)j0 * K, A + (size_t)(two ? j0 + 1 : j0) * K, xt, K, lane, r0, r1);
+                if (pool.q8) {
+                    const char *Ac = reinterpret_cast<const char *>(A);
+                    shrink_pair_q8(Ac + (size_t)j0 * K, Ac + (size_t)j1 * K, As + (((size_t)j0 * K) >> 5), As + (((size_t)j1 * K) >> 5), xt,
+                                   K, lane, r0, r1);
+                } else {
+                    shrink_pair(A + (size_t)j0 * K, A + (size_t)j1 * K, xt, K, lane, r0, r1);
+                }
                 if (lane < ncols && nc0 + lane < N) {
-                    const uint16_t *Bn = B + (size_t)(nc0 + lane) * rr.rank;
-                    d = fmaf(bf16_to_f32(Bn[j0]), r0, d);
-                    if (two) d = fmaf(bf16_to_f32(Bn[j0 + 1]), r1, d);
+                    const size_t e = (size_t)(nc0 + lane) * rr.rank;
+                    const float b0 = pool.q8 ? q8_elem(reinterpret_cast<const char *>(B), Bs, e + j0) : bf16_to_f32(B[e + j0]);
+                    d = fmaf(b0, r0, d);
+                    if (two) d = fmaf(pool.q8 ? q8_elem(reinterpret_cast<const char *>(B), Bs, e + j0 + 1) : bf16_to_f32(B[e + j0 + 1]), r1, d);
                 }
             }
         }
@@ -261,7 +270,7 @@ __device__ __forceinline__ void recompute_columns(const DecodeShape &sh, const u
     }
 }
 
-template <int TT, bool kWLds, int NW>
+template <int TT, bool kWLds, int NW, bool kQ8>
 __global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
                                                                            const uint16_t *__restrict__ W, PoolView pool,
                                                                            RouteView route, int has_pool, float *__restrict__ mail,
@@ -298,6 +307,7 @@ struct DecodeGroup {
 template <int TT, bool kWLds, int NW>
 __global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_group_kernel(DecodeGroup grp_)
 {
+    constexpr bool kQ8 = false;  // (calls with a pool of 8-bit blocks are launched one by one)
     int call_i = 0;
     if (grp_.n > 1 && (int)blockIdx.x >= grp_.first[1]) call_i = 1;
     if (grp_.n > 2 && (int)blockIdx.x >= grp_.first[2]) call_i = 2;
@@ -323,14 +333,15 @@ struct Variant {
     int tt;
     bool wlds;
     int nw;
-    int index() const { return nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0); }
+    bool q8 = false;  // the pool keeps its adapters in 8-bit blocks (W through the ring always; no group launch)
+    int index() const { return (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
     int threads() const { return nw * 64; }
     int tile_rows() const { return nw * kRowsPerWave; }
     int lds() const { return ring_bytes(tt, wlds, nw); }
 };
-constexpr int kVariants = 11;
+constexpr int kVariants = 22;
 template <typename F>
-auto with_variant(const Variant &v, F &&f)
+auto with_variant_bf16(const Variant &v, F &&f)
 {
     if (v.nw > 4) return f(ic<4>{}, std::true_type{}, ic<8>{});
     switch (v.tt) {
@@ -341,6 +352,20 @@ auto with_variant(const Variant &v, F &&f)
     }
 }
 
+template <typename F>
+auto with_variant(const Variant &v, F &&f)
+{
+    if (v.q8) {
+        if (v.nw > 4) return f(ic<4>{}, std::true_type{}, ic<8>{}, std::true_type{});
+        switch (v.tt) {
+        case 1: return f(ic<1>{}, std::true_type{}, ic<4>{}, std::true_type{});
+        case 2: return f(ic<2>{}, std::true_type{}, ic<4>{}, std::true_type{});
+        case 3: return f(ic<3>{}, std::true_type{}, ic<4>{}, std::true_type{});
+        default: return f(ic<4>{}, std::true_type{}, ic<4>{}, std::true_type{});
+        }
+    }
+    return with_variant_bf16(v, [&](auto tt, auto wl, auto nw) { return f(tt, wl, nw, std::false_type{}); });
+}
 // workgroups of a kernel instance the device holds at once (registers and LDS decide; asked once per instance), and
 // its number of compute units.  group: the kernel that carries several calls; 0 if it cannot be asked (then calls
 // are launched one by one).
@@ -354,16 +379,16 @@ int resident_of(const Variant &v, bool group, int *n_cus)
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
-            e = with_variant(v, [&](auto tt, auto wl, auto nw) {
+            e = with_variant(v, [&](auto tt, auto wl, auto nw, auto q8) {
                 constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-                constexpr bool WL = decltype(wl)::value;
+                constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value;
                 // (the ring may be larger than the LDS a kernel gets without asking)
                 const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW>)
-                                       : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW>);
+                                       : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8>);
                 hipError_t e2 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW));
                 if (e2 != hipSuccess) return e2;
                 return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW>, NW * 64, ring_bytes(TT, WL, NW))
-                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW>, NW * 64, ring_bytes(TT, WL, NW));
+                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8>, NW * 64, ring_bytes(TT, WL, NW));
             });
         if (e != hipSuccess) {
             (void)hipGetLastError();
@@ -410,7 +435,7 @@ int g_wide_mode = -1;  // -1: where it pays, 0: never, 1: wherever the shape all
 
 bool wide_allowed(int T) { return g_wide_mode != 0 && T > 32; }
 
-DecodeShape make_shape(int T, int K, int N, int max_rank, Variant *var)
+DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var)
 {
     DecodeShape sh;
     sh.T = T;
@@ -422,7 +447,7 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, Variant *var)
     const int tt = (T + 15) / 16;
     int n_cus = 0;
     if (wide_allowed(T)) {
-        const Variant wide{4, true, 8};
+        const Variant wide{4, true, 8, q8};
         const int resident = resident_workgroups(wide, &n_cus);
         const int n_tiles = (N + wide.tile_rows() - 1) / wide.tile_rows();
         const int split = pick_split(K, n_tiles, resident, n_cus);
@@ -435,12 +460,12 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, Variant *var)
             return sh;
         }
     }
-    Variant v{tt, true, 4};
+    Variant v{tt, true, 4, q8};
     sh.tile_rows = v.tile_rows();
     sh.n_tiles = (N + sh.tile_rows - 1) / sh.tile_rows;
     int resident = resident_workgroups(v, &n_cus);
     sh.split = pick_split(K, sh.n_tiles, resident, n_cus);
-    if (tt > 2) {
+    if (tt > 2 && !q8) {
         const Variant r{tt, false, 4};
         const int resident_r = resident_workgroups(r, &n_cus);
         const int split_r = pick_split(K, sh.n_tiles, resident_r, n_cus);
@@ -587,6 +612,8 @@ bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *s
 int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
 {
     if (n < 2 || n > kGroupMax) return -1;
+    for (int i = 0; i < n; ++i)
+        if (a[i].has_pool && a[i].pool.q8) return -1;
     const int T = a[0].T;
     int Ks[kGroupMax], Ns[kGroupMax], split[kGroupMax];
     for (int i = 0; i < n; ++i) {
@@ -631,7 +658,7 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
     for (int i = n; i <= kGroupMax; ++i) grp.first[i] = first;
     dim3 grid(first), block(var.threads());
     profile_mark_begin(stream);
-    with_variant(var, [&](auto tt, auto wl, auto nw) {
+    with_variant_bf16(var, [&](auto tt, auto wl, auto nw) {
         constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
         constexpr bool WL = decltype(wl)::value;
         hipLaunchKernelGGL((decode_group_kernel<TT, WL, NW>), grid, block, ring_bytes(TT, WL, NW), stream, grp);
@@ -696,7 +723,7 @@ void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
     Variant var{1, true, 4};
     const int passes = decode_passes(d);
     const int rows = (d.n_tokens + passes - 1) / passes;  // the longest row range
-    DecodeShape sh = make_shape(rows, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, &var);
+    DecodeShape sh = make_shape(rows, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, d.pool && d.pool->q8, &var);
     plan->n_launches = passes;
     plan->split_k = sh.split;
     plan->tile_rows = sh.tile_rows;
@@ -708,7 +735,7 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
 {
     (void)plan;
     Variant var{1, true, 4};
-    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, &var);
+    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, a.has_pool && a.pool.q8 != 0, &var);
     float *mail = reinterpret_cast<float *>(a.ws + a.wsl.mail);
     float *vmail = reinterpret_cast<float *>(a.ws + a.wsl.vmail);
     int *sync = reinterpret_cast<int *>(a.ws + a.wsl.sync);
@@ -718,11 +745,11 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     int has_pool = a.has_pool ? 1 : 0;
     dim3 grid(sh.grid), block(var.threads());
     profile_mark_begin(stream);
-    with_variant(var, [&](auto tt, auto wl, auto nw) {
+    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8) {
         constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-        constexpr bool WL = decltype(wl)::value;
-        hipLaunchKernelGGL((decode_kernel<TT, WL, NW>), grid, block, ring_bytes(TT, WL, NW), stream, sh, x, W, a.pool, a.route, has_pool, mail,
-                           vmail, sync, y);
+        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value;
+        hipLaunchKernelGGL((decode_kernel<TT, WL, NW, Q8>), grid, block, ring_bytes(TT, WL, NW), stream, sh, x, W, a.pool, a.route, has_pool,
+                           mail, vmail, sync, y);
         return 0;
     });
     ELORA_HIP_TRY(hipGetLastError());

@@ -30,11 +30,15 @@ __global__ __launch_bounds__(256) void shrink_generic_kernel(int K, const E *__r
     if (slot < 0) return;
     int rank = pool.meta[slot].rank;
     const E *A = reinterpret_cast<const E *>(slot_A(pool, slot));
+    const uint16_t *As = slot_A_scales(pool, slot);  // (adapters kept in 8-bit blocks: value = block scale * code)
     const E *xt = x + (size_t)t * K;
     int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int j = wave; j < rank; j += 4) {
         float s = 0.0f;
-        for (int k = lane; k < K; k += 64) s += load_elem(A, (size_t)j * K + k) * load_elem(xt, (size_t)k);
+        for (int k = lane; k < K; k += 64) {
+            const float a = pool.q8 ? q8_elem(reinterpret_cast<const char *>(A), As, (size_t)j * K + k) : load_elem(A, (size_t)j * K + k);
+            s += a * load_elem(xt, (size_t)k);
+        }
         for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
         if (lane == 0) V[(size_t)t * R + j] = s;
     }
@@ -100,10 +104,12 @@ __global__ __launch_bounds__(256) void base_generic_kernel(int T, int K, int N, 
         int slot = row_slot[t];
         int rank = 0;
         const E *B = nullptr;
+        const uint16_t *Bs = nullptr;
         float scale = 0.0f;
         if (slot >= 0) {
             rank = pool.meta[slot].rank;
             B = reinterpret_cast<const E *>(slot_B(pool, slot));
+            Bs = slot_B_scales(pool, slot);
             scale = row_scale[t];
         }
 #pragma unroll
@@ -111,7 +117,10 @@ __global__ __launch_bounds__(256) void base_generic_kernel(int T, int K, int N, 
             int n = n0 + tx * 4 + j;
             if (n >= N) continue;
             float d = 0.0f;
-            for (int q = 0; q < rank; ++q) d = fmaf(V[(size_t)t * R + q], load_elem(B, (size_t)n * rank + q), d);
+            for (int q = 0; q < rank; ++q) {
+                const float b = pool.q8 ? q8_elem(reinterpret_cast<const char *>(B), Bs, (size_t)n * rank + q) : load_elem(B, (size_t)n * rank + q);
+                d = fmaf(V[(size_t)t * R + q], b, d);
+            }
             store_elem(y, (size_t)t * N + n, acc[i][j] + scale * d);
         }
     }

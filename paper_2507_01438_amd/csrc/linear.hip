@@ -116,6 +116,11 @@ static void make_plan(const elora_linear_desc_t *d, elora_plan_t *plan)
     int max_rank = d->pool ? d->pool->max_rank : 1;
     bool dec = decode_eligible(*d, max_rank);
     bool gem = gemm_eligible(*d, max_rank);
+    if (d->pool && d->pool->q8) {
+        // adapters kept in 8-bit blocks: read as they are by the decode kernel (ranks up to 64) and by the generic kernels
+        gem = false;
+        dec = dec && max_rank <= 64;
+    }
     int path = ELORA_PATH_GENERIC;
     if (g_forced_path >= 0) {
         if (g_forced_path == ELORA_PATH_DECODE && dec) path = ELORA_PATH_DECODE;
@@ -325,7 +330,7 @@ static int fill_args(const elora_linear_desc_t *d, const WsLayout &wsl, hipStrea
         a.pool = d->pool->view();
         a.route = RouteView{d->adapter_idx, d->seg_offsets, d->seg_adapter, d->n_segments, d->scales, 0};
     } else {
-        a.pool = PoolView{nullptr, nullptr, nullptr, 0, 0, 0, 1};
+        a.pool = PoolView{nullptr, nullptr, nullptr, 0, 0, 0, 1, 0, 0, 0};
         a.route = RouteView{nullptr, nullptr, nullptr, 0, nullptr, 0};
     }
     return ELORA_OK;
@@ -439,6 +444,7 @@ static int group_form(const elora_linear_desc_t *descs, int n, hipStream_t strea
         make_plan(&descs[i], &plan);
         if (i == 0) path0 = plan.path;
         if (plan.path != path0 || descs[i].n_tokens != descs[0].n_tokens) return ELORA_OK;
+        if (descs[i].pool && descs[i].pool->q8) return ELORA_OK;  // pools of 8-bit blocks: call by call
     }
     if (path0 != ELORA_PATH_DECODE && path0 != ELORA_PATH_GEMM) return ELORA_OK;
     if (path0 == ELORA_PATH_GEMM) {

@@ -110,6 +110,32 @@ __global__ __launch_bounds__(256) void pool_load_q8_batch_kernel(LoadBatchQ8 lb,
     if (blockIdx.x == 0 && threadIdx.x == 0) meta[lb.slot[e]] = SlotMeta{lb.rank[e], lb.scale[e], 1, 0};
 }
 
+// Adapters that stay in their 8-bit blocks (a pool created by elora_pool_create_q8): codes and scales are copied as
+// they are, 8 bytes of codes or 2 bytes of scales per thread and step.
+struct LoadBatchQ8Keep {
+    int n;
+    int slot[kLoadBatch], rank[kLoadBatch];
+    float scale[kLoadBatch];
+    const uint2 *A[kLoadBatch], *B[kLoadBatch];
+    const uint16_t *As[kLoadBatch], *Bs[kLoadBatch];
+    unsigned a_vals[kLoadBatch], b_vals[kLoadBatch];  // values of A and of B
+};
+__global__ __launch_bounds__(256) void pool_keep_q8_batch_kernel(LoadBatchQ8Keep lb, char *slots, size_t slot_bytes, size_t a_scale_off,
+                                                                 size_t b_offset, size_t b_scale_off, SlotMeta *meta)
+{
+    const int e = blockIdx.y;
+    char *block = slots + (size_t)lb.slot[e] * slot_bytes;
+    const unsigned na = lb.a_vals[e] / 8, nb = lb.b_vals[e] / 8, nas = lb.a_vals[e] / 32, nbs = lb.b_vals[e] / 32;
+    const unsigned total = na + nb + nas + nbs;
+    for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        if (i < na) reinterpret_cast<uint2 *>(block)[i] = lb.A[e][i];
+        else if (i < na + nb) reinterpret_cast<uint2 *>(block + b_offset)[i - na] = lb.B[e][i - na];
+        else if (i < na + nb + nas) reinterpret_cast<uint16_t *>(block + a_scale_off)[i - na - nb] = lb.As[e][i - na - nb];
+        else reinterpret_cast<uint16_t *>(block + b_scale_off)[i - na - nb - nas] = lb.Bs[e][i - na - nb - nas];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) meta[lb.slot[e]] = SlotMeta{lb.rank[e], lb.scale[e], 1, 0};
+}
+
 __global__ void pool_clear_err_kernel(int *err)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -130,6 +156,9 @@ PoolView elora_pool::view() const
     v.b_offset = b_offset;
     v.capacity = capacity;
     v.max_rank = max_rank;
+    v.q8 = q8;
+    v.a_scale_off = a_scale_off;
+    v.b_scale_off = b_scale_off;
     return v;
 }
 
@@ -185,8 +214,65 @@ int elora_pool_create(int d_in, int d_out, int max_rank, int capacity, int dtype
     p->storage_bytes = storage_bytes;
     p->meta_offset = kAlign;
     p->slots_offset = kAlign + align_up(sizeof(SlotMeta) * (size_t)capacity);
+    p->q8 = 0;
+    p->a_scale_off = p->b_scale_off = 0;
     p->b_offset = align_up((size_t)max_rank * d_in * e);
     p->slot_bytes = p->b_offset + align_up((size_t)max_rank * d_out * e);
+    p->device_cleared = false;
+    *out = p;
+    return ELORA_OK;
+}
+
+// block of a pool whose adapters stay in 8-bit blocks: A codes [max_rank, d_in], A scales, B codes [d_out, max_rank], B scales
+static void q8_block_layout(int d_in, int d_out, int max_rank, size_t *a_scale_off, size_t *b_offset, size_t *b_scale_off, size_t *slot_bytes)
+{
+    const size_t a_vals = (size_t)max_rank * d_in, b_vals = (size_t)max_rank * d_out;
+    *a_scale_off = align_up(a_vals);
+    *b_offset = *a_scale_off + align_up(a_vals / 32 * 2);
+    *b_scale_off = *b_offset + align_up(b_vals);
+    *slot_bytes = *b_scale_off + align_up((b_vals + 31) / 32 * 2);
+}
+
+static bool q8_dims_ok(int d_in, int d_out, int max_rank, int capacity)
+{
+    return pool_dims_ok(d_in, d_out, max_rank, capacity, ELORA_BF16) && d_in % 32 == 0 && d_out % 4 == 0 && max_rank % 8 == 0;
+}
+
+size_t elora_pool_storage_bytes_q8(int d_in, int d_out, int max_rank, int capacity)
+{
+    if (!q8_dims_ok(d_in, d_out, max_rank, capacity)) return 0;
+    size_t aso, bo, bso, sb;
+    q8_block_layout(d_in, d_out, max_rank, &aso, &bo, &bso, &sb);
+    return kAlign + align_up(sizeof(SlotMeta) * (size_t)capacity) + sb * (size_t)capacity;
+}
+
+int elora_pool_create_q8(int d_in, int d_out, int max_rank, int capacity, void *dev_storage, size_t storage_bytes,
+                         elora_pool_t **out)
+{
+    if (out == nullptr || dev_storage == nullptr) return ELORA_E_NULL;
+    if (d_in <= 0 || d_out <= 0 || capacity <= 0 || d_in % 32 != 0 || d_out % 4 != 0) return ELORA_E_SHAPE;
+    if (max_rank < 8 || max_rank > kMaxRank || max_rank % 8 != 0) return ELORA_E_RANK;
+    if (reinterpret_cast<uintptr_t>(dev_storage) % kAlign) return ELORA_E_ALIGN;
+    if (storage_bytes < elora_pool_storage_bytes_q8(d_in, d_out, max_rank, capacity)) return ELORA_E_STORAGE;
+    elora_pool *p = new (std::nothrow) elora_pool;
+    if (p == nullptr) return ELORA_E_STORAGE;
+    p->host_meta = new (std::nothrow) SlotMeta[capacity];
+    if (p->host_meta == nullptr) {
+        delete p;
+        return ELORA_E_STORAGE;
+    }
+    for (int i = 0; i < capacity; ++i) p->host_meta[i] = SlotMeta{0, 0.0f, 0, 0};
+    p->d_in = d_in;
+    p->d_out = d_out;
+    p->max_rank = max_rank;
+    p->capacity = capacity;
+    p->dtype = ELORA_BF16;
+    p->q8 = 1;
+    p->storage = static_cast<char *>(dev_storage);
+    p->storage_bytes = storage_bytes;
+    p->meta_offset = kAlign;
+    p->slots_offset = kAlign + align_up(sizeof(SlotMeta) * (size_t)capacity);
+    q8_block_layout(d_in, d_out, max_rank, &p->a_scale_off, &p->b_offset, &p->b_scale_off, &p->slot_bytes);
     p->device_cleared = false;
     *out = p;
     return ELORA_OK;
@@ -204,6 +290,7 @@ int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale,
                             int src_on_device, elora_stream_t stream_)
 {
     if (pool == nullptr || A == nullptr || B == nullptr) return ELORA_E_NULL;
+    if (pool->q8) return ELORA_E_DTYPE;  // this pool holds 8-bit blocks: elora_pool_load_adapters_q8
     if (slot < 0 || slot >= pool->capacity) return ELORA_E_SLOT;
     if (rank < 1 || rank > pool->max_rank) return ELORA_E_RANK;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -248,6 +335,7 @@ int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const 
 {
     if (pool == nullptr || (n > 0 && (!slots || !ranks || !scales || !A || !B))) return ELORA_E_NULL;
     if (n < 0) return ELORA_E_SHAPE;
+    if (pool->q8) return ELORA_E_DTYPE;
     for (int i = 0; i < n; ++i) {
         if (A[i] == nullptr || B[i] == nullptr) return ELORA_E_NULL;
         if (slots[i] < 0 || slots[i] >= pool->capacity) return ELORA_E_SLOT;
@@ -311,6 +399,7 @@ int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, con
         if (slots[i] < 0 || slots[i] >= pool->capacity) return ELORA_E_SLOT;
         if (ranks[i] < 1 || ranks[i] > pool->max_rank) return ELORA_E_RANK;
         if (((size_t)ranks[i] * pool->d_in) % 32 || ((size_t)ranks[i] * pool->d_out) % 32) return ELORA_E_SHAPE;
+        if (pool->q8 && ranks[i] % 8 != 0) return ELORA_E_RANK;  // resident blocks: 8 values of a row never straddle a block
         for (int j = 0; j < i; ++j)
             if (slots[j] == slots[i]) return ELORA_E_SLOT;
     }
@@ -325,6 +414,39 @@ int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, con
         if (reinterpret_cast<uintptr_t>(a) % 8 || reinterpret_cast<uintptr_t>(b) % 8 || reinterpret_cast<uintptr_t>(as) % 2 ||
             reinterpret_cast<uintptr_t>(bs) % 2)
             return ELORA_E_ALIGN;
+    }
+    if (pool->q8) {
+        // the blocks stay as they are: codes and scales are copied into the pool
+        for (int i0 = 0; i0 < n; i0 += kLoadBatch) {
+            LoadBatchQ8Keep lb;
+            lb.n = n - i0 < kLoadBatch ? n - i0 : kLoadBatch;
+            size_t most = 0;
+            for (int i = 0; i < lb.n; ++i) {
+                bool dev = false;
+                lb.slot[i] = slots[i0 + i];
+                lb.rank[i] = ranks[i0 + i];
+                lb.scale[i] = scales[i0 + i];
+                lb.A[i] = static_cast<const uint2 *>(device_readable(A_codes[i0 + i], &dev));
+                lb.B[i] = static_cast<const uint2 *>(device_readable(B_codes[i0 + i], &dev));
+                lb.As[i] = static_cast<const uint16_t *>(device_readable(A_scales[i0 + i], &dev));
+                lb.Bs[i] = static_cast<const uint16_t *>(device_readable(B_scales[i0 + i], &dev));
+                lb.a_vals[i] = (unsigned)((size_t)ranks[i0 + i] * pool->d_in);
+                lb.b_vals[i] = (unsigned)((size_t)ranks[i0 + i] * pool->d_out);
+                most = (size_t)lb.a_vals[i] + lb.b_vals[i] > most ? (size_t)lb.a_vals[i] + lb.b_vals[i] : most;
+            }
+            if (i0 == 0) {
+                const int rc = pool_ensure_cleared(pool, stream);
+                if (rc != ELORA_OK) return rc;
+            }
+            unsigned per = (unsigned)((most / 8 + 256 * 4 - 1) / (256 * 4));
+            per = per < 1 ? 1 : per > 64 ? 64 : per;
+            hipLaunchKernelGGL(pool_keep_q8_batch_kernel, dim3(per, lb.n), dim3(256), 0, stream, lb, pool->storage + pool->slots_offset,
+                               pool->slot_bytes, pool->a_scale_off, pool->b_offset, pool->b_scale_off,
+                               reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset));
+            ELORA_HIP_TRY(hipGetLastError());
+            for (int i = 0; i < lb.n; ++i) pool->host_meta[slots[i0 + i]] = SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0};
+        }
+        return ELORA_OK;
     }
     for (int i0 = 0; i0 < n; i0 += kLoadBatch) {
         LoadBatchQ8 lb;

@@ -235,15 +235,19 @@ class Workload:
         ra = self.row_adapter()
         return np.unique(ra[ra >= 0])
 
-    def algorithmic_bytes(self, proj: Projection) -> int:
+    def algorithmic_bytes(self, proj: Projection, q8_adapters: bool = False) -> int:
         """Bytes one call must move: W once, x once, y once, and the used rows
-        (r_i, not max_rank) of every DISTINCT adapter once."""
+        (r_i, not max_rank) of every DISTINCT adapter once, in the format they are stored in (q8_adapters: one byte per
+        value plus one fp16 scale per 32 values)."""
         e = 4 if self.dtype == F32 else 2
         if self.wfmt == W_SAME:
             wb = proj.N * proj.K * e
         else:
             wb = proj.N * proj.K // 2 + proj.N * (proj.K // 32) * 2
-        ab = sum((proj.K + proj.N) * int(self.ranks[i]) * e for i in self.distinct_adapters())
+        if q8_adapters:
+            ab = sum((proj.K + proj.N) * int(self.ranks[i]) * 17 // 16 for i in self.distinct_adapters())
+        else:
+            ab = sum((proj.K + proj.N) * int(self.ranks[i]) * e for i in self.distinct_adapters())
         return wb + self.T * proj.K * e + self.T * proj.N * e + ab
 
     def algorithmic_flops(self, proj: Projection) -> int:

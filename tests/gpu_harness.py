@@ -50,9 +50,11 @@ def rel_err(y: np.ndarray, ref: np.ndarray) -> float:
 class DeviceCase:
     """One projection of a workload resident on the GPU, with its pool loaded."""
 
-    def __init__(self, w: I.Workload, proj: I.Projection, *, load_slots=None, n_tokens_max=None, share=None):
+    def __init__(self, w: I.Workload, proj: I.Projection, *, load_slots=None, n_tokens_max=None, share=None, q8=False):
         """share: another case of the same workload and d_in whose device copies of x and of the routing tables this
-        one uses as well (projections that read the same activations: their descriptors then name the same pointers)."""
+        one uses as well (projections that read the same activations: their descriptors then name the same pointers).
+        q8: the workload's adapters are cut into 8-bit blocks (input preparation) and the pool keeps them that way; the
+        oracle then gets the same codes and scales."""
         from paper_2507_01438_amd import binding as B
         self.B = B
         self.w, self.proj = w, proj
@@ -63,15 +65,26 @@ class DeviceCase:
         self.x = to_dev(self.x_h) if share is None else share.x
         self.W = to_dev(self.W_h)
         self.w_scales = None if self.ws_h is None else to_dev(self.ws_h)
-        self.pool = B.AdapterPool(proj.K, proj.N, w.max_rank, w.pool, w.dtype, DEV)
+        self.q8 = q8
+        self.pool = B.AdapterPool(proj.K, proj.N, w.max_rank, w.pool, w.dtype, DEV, q8=q8)
         self.adapters = {}
         slots = range(w.pool) if load_slots is None else load_slots
+        keep = []
         for i in slots:
             A, Bm, s = w.adapter(proj, int(i))
+            if q8:
+                Ac, As = I.quantize_q8_blocks(I.bf16_bits_to_f32(A))
+                Bc, Bs = I.quantize_q8_blocks(I.bf16_bits_to_f32(Bm))
+                self.adapters[int(i)] = (Ac, Bc, s, As, Bs)
+                dev = [to_dev(Ac), to_dev(As), to_dev(Bc), to_dev(Bs)]
+                keep.append(dev)
+                B.elora_pool_load_adapters_q8(self.pool.handle, [int(i)], [Ac.shape[0]], [s], [dev[0]], [dev[1]], [dev[2]], [dev[3]])
+                continue
             self.adapters[int(i)] = (A, Bm, s)
             self.pool.load(int(i), torch.from_numpy(A.view(np.int16) if A.dtype == np.uint16 else A),
                            torch.from_numpy(Bm.view(np.int16) if Bm.dtype == np.uint16 else Bm), s)
         torch.cuda.synchronize()
+        del keep
         self.lin = B.LoraLinear(proj.K, proj.N, w.dtype, self.pool, n_tokens_max or max(w.T, 1), DEV, wfmt=w.wfmt)
         self.y = torch.zeros((max(w.T, 1), proj.N), dtype=torch.float32 if w.dtype == I.F32 else torch.int16, device=DEV)
         if share is not None:
@@ -106,6 +119,10 @@ class DeviceCase:
         ads = [None] * self.w.pool
         for i in self.w.distinct_adapters():
             if int(i) in self.adapters:
+                if self.q8:
+                    Ac, Bc, s, As, Bs = self.adapters[int(i)]
+                    ads[int(i)] = oracle.Adapter(Ac, Bc, s, A_scales=As, B_scales=Bs)
+                    continue
                 A, Bm, s = self.adapters[int(i)]
                 ads[int(i)] = oracle.Adapter(A, Bm, s)
         return ads

@@ -1,0 +1,97 @@
+"""Pools whose adapters stay in 8-bit blocks (the paper keeps all adapters in the block format its settings call "Q8_0",
+Sec. 5 "Model"): the linear kernels read codes and scales as they are.  Against the oracle on the same codes and scales
+(value = scale * code exactly, no rounding of the adapter), through the C-ABI."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_harness import DeviceCase, assert_close, rel_err, to_dev, y_to_f64
+from paper_2507_01438_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+GENERIC, DECODE, GEMM = 0, 1, 2
+
+SHAPES = [
+    # (T, K, N, pool, ranks, no_adapter_rows)
+    (1, 256, 16, 2, (8,), ()),
+    (7, 512, 48, 3, (8, 16, 24), (2,)),
+    (17, 1024, 1040, 5, (8, 16, 32, 64, 40), (0, 16)),
+    (32, 4096, 256, 8, (16,), ()),
+    (33, 2048, 272, 6, (16, 8), (5,)),
+    (64, 1792, 144, 9, (8, 16, 32, 64), (63,)),       # 7 chunks of K: uneven K-slices
+    (64, 2048, 4096, 4, (64, 8, 32), ()),             # 128-row tiles where they fill the device
+    (50, 768, 16, 2, (8,), ()),
+    (130, 1024, 272, 6, (8, 16, 32, 64, 24), (0, 64, 129)),   # several launches of the decode kernel
+]
+
+
+@pytest.mark.parametrize("path", [DECODE, GENERIC])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_q8_pool_small_shapes(shape, path):
+    T, K, N, pool, ranks, none_rows = shape
+    rk = np.resize(np.asarray(ranks, dtype=np.int32), pool)
+    w = I.small_workload(700 + T + N, I.BF16, K, N, T, pool, rk, no_adapter_rows=none_rows)
+    case = DeviceCase(w, w.projections[0], q8=True)
+    y = case.run(force_path=path)
+    assert case.last_plan.path == path
+    assert_close(y, case.reference(), case.base_reference(), f"q8 {shape}")
+    assert np.array_equal(y, case.run(force_path=path))
+    assert case.pool.poll_error() == (0, -1)
+    if path == DECODE:
+        case.B.elora_debug_spin_limit(0)        # every wait cut short: the fall-backs read the 8-bit blocks as well
+        try:
+            y0 = case.run(force_path=DECODE)
+        finally:
+            case.B.elora_debug_spin_limit(1 << 22)
+        assert rel_err(y0, case.reference()) <= 1e-2
+    case.close()
+
+
+def test_q8_pool_rules_and_the_paths_it_takes():
+    from paper_2507_01438_amd import binding as B
+    assert B.elora_pool_storage_bytes_q8(4096, 4096, 64, 8) < 0.6 * B.elora_pool_storage_bytes(4096, 4096, 64, 8, B.ELORA_BF16)
+    assert B.elora_pool_storage_bytes_q8(4096 + 16, 4096, 64, 8) == 0          # d_in a multiple of 32
+    assert B.elora_pool_storage_bytes_q8(4096, 4096, 12, 8) == 0               # max_rank a multiple of 8
+    w = I.small_workload(801, I.BF16, 512, 264, 300, 4, (8, 16), segments=[100, 200])
+    case = DeviceCase(w, w.projections[0], q8=True)
+    y = case.run()
+    assert case.last_plan.path == GENERIC      # many rows: the MFMA GEMM path does not read 8-bit blocks
+    assert rel_err(y, case.reference()) <= 1e-2
+    # adapters in bf16 are refused by such a pool, and so are ranks that are no multiple of 8
+    A = torch.zeros((8, 512), dtype=torch.int16)
+    Bm = torch.zeros((264, 8), dtype=torch.int16)
+    with pytest.raises(B.EloraError) as e:
+        case.pool.load(0, A, Bm, 1.0)
+    assert e.value.status == B.ELORA_E_DTYPE
+    c4 = to_dev(np.zeros((4, 512), np.int8)); s4 = to_dev(np.zeros(64, np.uint16))
+    b4 = to_dev(np.zeros((264, 4), np.int8)); t4 = to_dev(np.zeros(33, np.uint16))
+    with pytest.raises(B.EloraError) as e:
+        B.elora_pool_load_adapters_q8(case.pool.handle, [0], [4], [1.0], [c4], [s4], [b4], [t4])
+    assert e.value.status == B.ELORA_E_RANK
+    case.close()
+
+
+@pytest.mark.parametrize("name", ["q", "k", "gate"])
+def test_q8_pool_config3_full_shapes(name):
+    """Config 3's projections with every adapter kept in 8-bit blocks: half the adapter bytes are read."""
+    w = I.config3()
+    proj = I.LLAMA8B[name]
+    case = DeviceCase(w, proj, load_slots=w.distinct_adapters(), q8=True)
+    y = case.run()
+    assert case.last_plan.path == DECODE
+    rng = np.random.default_rng(19)
+    cols = np.unique(np.concatenate([rng.choice(proj.N, 128, replace=False), np.arange(8), np.arange(proj.N - 8, proj.N)]))
+    e = assert_close(y[:, cols], case.reference(cols=cols), case.base_reference(cols=cols), f"q8 config3 {name}")
+    print(f"config3 {name}, adapters in 8-bit blocks: rel err {e:.2e}, tile {case.last_plan.tile_rows}, split {case.last_plan.split_k}")
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
+
+
+def test_q8_pool_config2_full_shape():
+    w = I.config2()
+    case = DeviceCase(w, w.projections[0], q8=True)
+    y = case.run()
+    assert case.last_plan.path == DECODE
+    e = assert_close(y, case.reference(), case.base_reference(), "q8 config2")
+    print(f"config2, adapters in 8-bit blocks: rel err {e:.2e}")
+    case.close()
