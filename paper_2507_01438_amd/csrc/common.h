@@ -249,15 +249,17 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // One wave: v[t][j0], v[t][j0+1] = A_i[j0..j0+1, :] . x[t, :] over the whole of K (K % 256 == 0).
+// NL: 16-byte pieces per row, lane and round trip to memory (3 NL loads in flight per lane).
+template <int NL = 8>
 __device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, const uint16_t *__restrict__ A1,
                                             const uint16_t *__restrict__ xt, int K, int lane, float &r0, float &r1)
 {
     float s0 = 0.0f, s1 = 0.0f;
     const int pieces = K >> 3;  // 16-byte pieces per row
-    for (int pb = 0; pb < pieces; pb += 64 * 8) {
-        elora_u32x4 xv[8], a0[8], a1[8];
+    for (int pb = 0; pb < pieces; pb += 64 * NL) {
+        elora_u32x4 xv[NL], a0[NL], a1[NL];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < NL; ++i) {
             const int p = pb + i * 64 + lane;
             const bool in = p < pieces;
             const size_t off = (size_t)(in ? p : 0) * 8;
@@ -265,9 +267,9 @@ __device__ __forceinline__ void shrink_pair(const uint16_t *__restrict__ A0, con
             a0[i] = __builtin_nontemporal_load(reinterpret_cast<const elora_u32x4 *>(A0 + off));
             a1[i] = __builtin_nontemporal_load(reinterpret_cast<const elora_u32x4 *>(A1 + off));
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep all 24 loads in flight together: do not interleave the math
+        __builtin_amdgcn_sched_barrier(0);  // keep all loads of a round in flight together: do not interleave the math
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < NL; ++i) {
             if (pb + i * 64 + lane >= pieces) xv[i] = elora_u32x4{0, 0, 0, 0};  // past the row: contributes nothing
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
