@@ -270,6 +270,27 @@ struct Item {
 };
 constexpr int kMaxItems = kMaxRuns * (kMaxRank / BK);
 
+template <int V> using ic = std::integral_constant<int, V>;
+
+// Short runs (decode rows of a mixed batch, short prompts).  As columns of an expand block a run costs its rank's
+// share of a whole 256 x 256 x 64 block whatever its length; a run of at most 32 rows is instead added after the K
+// loop, to the one or two 32-row accumulator blocks it lies in: per block and 16 rank entries one fragment of V and
+// four of B_i straight from memory and four matrix instructions in each of the two waves that own the rows.
+constexpr int kEpiRows = 32;
+__device__ __forceinline__ bool run_is_short(int start, int end, int rank, int N)
+{
+    return end - start <= kEpiRows && (rank & 7) == 0 && N < (1 << 22);  // (a lane's offset into B_i fits 32 bits)
+}
+constexpr int kEpiAhead = 8;  // (run, block, 16 rank entries) steps whose loads are in flight per wave
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(ic<I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 
@@ -292,6 +313,9 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     __shared__ Item s_items[kMaxItems];
     __shared__ uint16_t s_blk_first[kMaxItems + 1];  // expand block b holds items [s_blk_first[b], s_blk_first[b + 1])
     __shared__ int s_nblk;
+    __shared__ uint8_t s_pairs[BM / 32][32];  // short runs that have rows in 32-row block g of the tile
+    __shared__ int s_npairs[BM / 32], s_nsteps[BM / 32];
+    __shared__ int s_nlong, s_nshort, s_short_cols, s_use_ring;  // runs that go into expand blocks / that may be added afterwards
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = ga.T, K = ga.K, N = ga.N;
@@ -320,6 +344,14 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     if (tid == 0) {
         s_nruns = 0;
         s_nblk = 0;
+        s_nlong = 0;
+        s_nshort = 0;
+        s_short_cols = 0;
+        s_use_ring = 0;
+    }
+    if (tid < BM / 32) {
+        s_npairs[tid] = 0;
+        s_nsteps[tid] = 0;
     }
     {
         int slot = -1;
@@ -344,14 +376,27 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
             }
         }
         const int k = atomicAdd(&s_nruns, 1);
-        s_runs[k] = Run{tid, end, s_slot[tid], pool.meta[s_slot[tid]].rank};
+        const int rank = pool.meta[s_slot[tid]].rank;
+        s_runs[k] = Run{tid, end, s_slot[tid], rank};
+        if (rank > 0 && run_is_short(tid, end, rank, N)) {
+            atomicAdd(&s_nshort, 1);
+            atomicAdd(&s_short_cols, (rank + 7) & ~7);
+            for (int g = tid >> 5; g <= (end - 1) >> 5; ++g) {  // a 32-row block has rows of at most 32 runs
+                s_pairs[g][atomicAdd(&s_npairs[g], 1)] = (uint8_t)k;
+                atomicAdd(&s_nsteps[g], (rank + 15) >> 4);
+            }
+        } else if (rank > 0) {
+            atomicAdd(&s_nlong, 1);
+        }
     }
     __syncthreads();
     const int nruns = s_nruns;
-    // pack the runs' rank columns into expand blocks of 64 K columns
+    // Pack the rank columns of the long runs into expand blocks of 64 K columns.  Short runs whose columns all fit
+    // into what the last of these blocks has left travel with them for nothing (the tail of a prompt next to the
+    // head of the next one); otherwise they are added after the K loop.
     if (tid == 0 && nruns > 0) {
         int nitems = 0, nblk = 0, used = BK;
-        for (int ri = 0; ri < nruns; ++ri) {
+        auto pack = [&](int ri) {
             const int rank = s_runs[ri].rank;
             for (int j0 = 0; j0 < rank; j0 += BK) {
                 const int w = (min(BK, rank - j0) + 7) & ~7;
@@ -362,6 +407,16 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
                 s_items[nitems++] = Item{(uint16_t)ri, (uint16_t)j0, (uint8_t)used, (uint8_t)w, 0};
                 used += w;
             }
+        };
+        const int nshort = s_nshort;
+        if (s_nlong > 0)
+            for (int ri = 0; ri < nruns; ++ri)
+                if (!run_is_short(s_runs[ri].start, s_runs[ri].end, s_runs[ri].rank, N)) pack(ri);
+        if (nshort > 0 && nblk > 0 && s_short_cols <= BK - used) {
+            for (int ri = 0; ri < nruns; ++ri)
+                if (run_is_short(s_runs[ri].start, s_runs[ri].end, s_runs[ri].rank, N)) pack(ri);
+        } else if (nshort > 0) {
+            s_use_ring = 1;
         }
         s_blk_first[nblk] = (uint16_t)nitems;
         s_nblk = nblk;
@@ -625,6 +680,127 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(fr[1]);
         __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- short runs: v B_i^T added block by block ----------------------------------------------------------
+    // A step is (32-row block, run, 16 rank entries): the A-operand is the block's rows of V with every row outside
+    // the run zero (lane -> row lane % 32, entries 8 (lane / 32) .. + 7 of the 16), the B-operands are the same
+    // entries of B_i for the wave's 4 x 32 columns.  The steps of a (block, run) pair follow each other in rank
+    // order and no two pairs of a block share a row, so the sums do not depend on the order the pairs were listed in.
+    // The steps of the upper and of the lower four blocks are first written out as a table each (one thread per
+    // block, into the stages, which are free now), every block filled up to a multiple of the ring's length with
+    // empty steps, so that ring slot and accumulator block of every multiplication are compile-time constants and
+    // the loop that walks the table has no branch in it: with one wave per SIMD, what bounds this part is the
+    // number of instructions per step (a cursor kept in scalar registers took 2.5 times as long as the table).
+    // The loads of kEpiAhead steps are in flight while one is multiplied; a step issues its five loads whatever
+    // the lane's row and whether it is empty (addresses inside some run's own data, the fragment of V masked when it
+    // is used), and every multiplication waits for exactly the loads issued after its own (the loads are written as
+    // instructions and counted by hand: left to the compiler, the loop waits for all loads once per turn).
+    // Entries at and beyond the rank are zero in V, so B_i's fragment there only has to be finite: it re-reads
+    // entry 0; an empty step re-reads the step before it.
+    {
+        constexpr int kTabBlock = kEpiRows * (kMaxRank / 16);             // steps of a block: 32 runs of 16 steps
+        constexpr int kTabHalf = 4 * kTabBlock + kEpiAhead + 1;           // + the steps issued past the end
+        static_assert(2 * kTabHalf * 16 <= 2 * kStageElems * 2, "the tables fit into the stages");
+        static_assert(kTabBlock % kEpiAhead == 0 && (kEpiAhead & (kEpiAhead - 1)) == 0 && 5 * (kEpiAhead - 1) < 64, "a power of two; the load counter has six bits");
+        auto up = [](int n) { return (n + kEpiAhead - 1) & ~(kEpiAhead - 1); };
+        int nst[BM / 32];
+        int any = 0;
+#pragma unroll
+        for (int g = 0; g < BM / 32; ++g) {
+            nst[g] = __builtin_amdgcn_readfirstlane(s_nsteps[g]);
+            any += nst[g];
+        }
+        if (!s_use_ring) any = 0;
+        if (any > 0) {
+            u32x4 *tab = reinterpret_cast<u32x4 *>(smem_raw);
+            // step record: x = first row | (end row << 9) | (block << 18) (rows counted in the tile), y = first entry |
+            // (rank << 16), z / w = byte offset of B_i from the pool's first slot
+            auto record = [&](const Run &run, int g, int j0) {
+                const unsigned long long off = (unsigned long long)run.slot * pool.slot_bytes + pool.b_offset;
+                return u32x4{(uint32_t)(run.start | (run.end << 9) | (g << 18)), (uint32_t)(j0 | (run.rank << 16)), (uint32_t)off, (uint32_t)(off >> 32)};
+            };
+            __syncthreads();  // every wave is done with the stages
+            if (tid < BM / 32) {
+                const int g = tid;
+                int off = 0;
+                for (int h = g & ~3; h < g; ++h) off += up(s_nsteps[h]);
+                u32x4 *out = tab + (g >> 2) * kTabHalf + off;
+                int n = 0;
+                for (int i = 0; i < s_npairs[g]; ++i) {
+                    const Run run = s_runs[s_pairs[g][i]];
+                    for (int j0 = 0; j0 < run.rank; j0 += 16) out[n++] = record(run, g, j0);
+                }
+                for (; (n & (kEpiAhead - 1)) != 0; ++n) out[n] = u32x4{0, out[n - 1][1], out[n - 1][2], out[n - 1][3]};
+            } else if (tid < BM / 32 + 2) {
+                // past the end of a half's table: empty steps that re-read the half's first run
+                const int half = tid - BM / 32;
+                int total = 0, first = -1;
+                for (int h = 4 * half; h < 4 * half + 4; ++h) {
+                    if (first < 0 && s_npairs[h] > 0) first = h;
+                    total += up(s_nsteps[h]);
+                }
+                if (first >= 0) {
+                    u32x4 r = record(s_runs[s_pairs[first][0]], first, 0);
+                    r[0] = 0;
+                    for (int i = 0; i <= kEpiAhead; ++i) tab[half * kTabHalf + total + i] = r;
+                }
+            }
+            __syncthreads();
+            const int g0 = wm * 4;
+            if (nst[g0] + nst[g0 + 1] + nst[g0 + 2] + nst[g0 + 3] > 0) {
+                u32x4 va[kEpiAhead], vb[kEpiAhead][4];
+                bool in_run[kEpiAhead];
+                const u32x4 *next = tab + wm * kTabHalf;
+                u32x4 rec = *next;
+                auto load16 = [](const void *p) {
+                    u32x4 v;
+                    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+                    return v;
+                };
+                uint32_t ncol[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) ncol[b] = (uint32_t)min(n0 + wn * 128 + b * 32 + (lane & 31), N - 1);
+                auto issue = [&](auto dc) {
+                    constexpr int d = decltype(dc)::value;
+                    const u32x4 r = rec;
+                    rec = *++next;  // (read now, used by the next step)
+                    const int row = (int)(r[0] >> 18) * 32 + (lane & 31);
+                    in_run[d] = row >= (int)(r[0] & 511u) && row < (int)((r[0] >> 9) & 511u);
+                    const uint32_t rank = r[1] >> 16, j = (r[1] & 0xffffu) + (lane >> 5) * 8;
+                    va[d] = load16(ga.V + (size_t)min(m0 + row, T - 1) * ga.Rpad + j);
+                    const uint32_t jb = j < rank ? j : 0;
+                    const char *Bb = pool.slots + (((unsigned long long)r[3] << 32) | r[2]);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) vb[d][b] = load16(Bb + (size_t)((ncol[b] * rank + jb) * 2u));
+                };
+                static_for<0, kEpiAhead>(issue);
+                auto block_steps = [&](auto ac) {
+                    constexpr int a = decltype(ac)::value;
+                    const int n_up = up(nst[g0 + a]);
+                    auto consume = [&](auto dc) {
+                        constexpr int d = decltype(dc)::value;
+                        // five loads per step, kEpiAhead - 1 younger steps in flight; the operands tie what follows to the wait
+                        asm volatile("s_waitcnt vmcnt(%5)" : "+v"(va[d]), "+v"(vb[d][0]), "+v"(vb[d][1]), "+v"(vb[d][2]), "+v"(vb[d][3]) : "n"(5 * (kEpiAhead - 1)) : "memory");
+                        const bf16x8 fa = __builtin_bit_cast(bf16x8, in_run[d] ? va[d] : u32x4{0, 0, 0, 0});
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, __builtin_bit_cast(bf16x8, vb[d][b]), acc[a][b], 0, 0, 0);
+                    };
+                    for (int i = 0; i < n_up; i += kEpiAhead)
+                        static_for<0, kEpiAhead>([&](auto dc) {
+                            consume(dc);
+                            issue(dc);
+                        });
+                };
+                block_steps(ic<0>{});
+                block_steps(ic<1>{});
+                block_steps(ic<2>{});
+                block_steps(ic<3>{});
+                // the empty steps issued last are still on their way into registers the compiler takes to be free
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+        }
     }
 
     // ---- epilogue -------------------------------------------------------------------------------------

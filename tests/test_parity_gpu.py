@@ -492,6 +492,8 @@ GEMM_SMALL = [
     (256, 2048 + 40, 6, (16,), [1] * 70 + [130] + [1] * 60, (5, 100)),    # decode-like rows around a prompt
     (192, 72, 3, (8, 16), [70, 10, 300], ()),                             # three K blocks: one straight-line iteration
     (128, 264, 2, (16,), [260], ()),                                      # two K blocks: the general loop only
+    # runs of at most 32 rows (added after the K loop) across 32-, 128- and 256-row boundaries, ranks up to 256
+    (256, 264, 5, (64, 8, 256, 32, 48), [30, 3, 31, 1, 40, 23, 2, 20, 31, 32, 33, 8, 1, 1, 28, 5], (3,)),
 ]
 
 
