@@ -848,10 +848,9 @@ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // ------------------------------------------------------------------------------------------------
 constexpr int kDequantFirstRows = 768;
 
-__global__ __launch_bounds__(256) void w4_dequant_kernel(size_t n_pieces, const uint32_t *__restrict__ codes,
-                                                         const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
+__device__ __forceinline__ void w4_dequant_piece(size_t i, size_t n_pieces, const uint32_t *__restrict__ codes,
+                                                 const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
 {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n_pieces) return;
     const uint32_t q = codes[i];
     const float sc = fp16_to_f32(scales[i >> 2]), c8 = -8.0f * sc;
@@ -861,6 +860,37 @@ __global__ __launch_bounds__(256) void w4_dequant_kernel(size_t n_pieces, const 
     for (int b = 0; b < 4; ++b)
         o[b] = pack_bf16x2(fmaf((float)((lo >> (8 * b)) & 0xffu), sc, c8), fmaf((float)((hi >> (8 * b)) & 0xffu), sc, c8));
     out[i] = o;
+}
+
+__global__ __launch_bounds__(256) void w4_dequant_kernel(size_t n_pieces, const uint32_t *__restrict__ codes,
+                                                         const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
+{
+    w4_dequant_piece((size_t)blockIdx.x * 256 + threadIdx.x, n_pieces, codes, scales, out);
+}
+
+// The shrink and the copy of W do not depend on each other, and the shrink of a few hundred rows is a few dozen
+// workgroups that wait for memory most of the time: in one launch (the shrink's workgroups first, so that they start
+// at once) the copy fills the rest of the device meanwhile and the call is one launch and one kernel's time shorter.
+static_assert(kShrinkThreads == 256, "one block shape for both halves");
+constexpr int kCopyPerThread = 8;
+__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_w4_dequant_kernel(int n_shrink, int T, int K, int n_tiles,
+                                                                                const uint16_t *__restrict__ x, PoolView pool,
+                                                                                const int32_t *__restrict__ row_slot,
+                                                                                const float *__restrict__ row_scale,
+                                                                                uint16_t *__restrict__ V, int Rpad, size_t n_pieces,
+                                                                                const uint32_t *__restrict__ codes,
+                                                                                const uint16_t *__restrict__ scales,
+                                                                                u32x4 *__restrict__ out)
+{
+    if ((int)blockIdx.x < n_shrink) {
+        shrink_block((int)blockIdx.x, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad);
+        return;
+    }
+    // (the shrink's LDS counts for these workgroups too and halves how many of them a compute unit holds: each takes
+    // kCopyPerThread pieces per thread, their loads under way together)
+    const size_t base = (size_t)(blockIdx.x - n_shrink) * (256 * kCopyPerThread) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < kCopyPerThread; ++u) w4_dequant_piece(base + (size_t)u * 256, n_pieces, codes, scales, out);
 }
 
 }  // namespace
@@ -874,7 +904,7 @@ bool elora::gemm_eligible(const elora_linear_desc_t &d, int max_rank)
 void elora::gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 {
     const bool copy_first = d.wfmt == ELORA_W_INT4_G32 && gemm_w4_bytes(d.n_tokens, d.d_in, d.d_out) != 0;
-    plan->n_launches = (d.pool ? 3 : 2) + (copy_first ? 1 : 0);
+    plan->n_launches = (d.pool ? 3 : 2) + (copy_first && !d.pool ? 1 : 0);  // (with a pool the copy shares the shrink's launch)
     plan->tile_rows = BM;
     plan->tile_cols = BN;
     plan->grid = gemm_grid((d.n_tokens + BM - 1) / BM, (d.d_out + BN - 1) / BN);
@@ -889,7 +919,7 @@ size_t elora::gemm_v_bytes(int n_tokens, int max_rank) { return (size_t)n_tokens
 
 namespace {
 // what follows route and shrink: (the copy of a 4-bit W and) the GEMM with the expand in its K loop
-int launch_gemm_back(const LinearArgs &a, hipStream_t stream)
+int launch_gemm_back(const LinearArgs &a, hipStream_t stream, bool copy_done = false)
 {
     int32_t *row_slot = reinterpret_cast<int32_t *>(a.ws + a.wsl.row_slot);
     uint16_t *V = reinterpret_cast<uint16_t *>(a.ws + a.wsl.v);
@@ -897,7 +927,7 @@ int launch_gemm_back(const LinearArgs &a, hipStream_t stream)
     const int has_pool = a.has_pool ? 1 : 0;
     // 4-bit W and enough rows: the bf16 kernel on a copy made now
     const bool copy_first = a.wfmt == ELORA_W_INT4_G32 && a.wsl.wdeq_bytes != 0;
-    if (copy_first) {
+    if (copy_first && !copy_done) {
         const size_t n_pieces = (size_t)a.N * (size_t)(a.K / 8);
         hipLaunchKernelGGL(w4_dequant_kernel, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces,
                            static_cast<const uint32_t *>(a.W), static_cast<const uint16_t *>(a.w_scales),
@@ -954,13 +984,23 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
     hipLaunchKernelGGL(gemm_route_kernel, dim3((a.T + 255) / 256), dim3(256), 0, stream, a.T, a.route, a.pool, has_pool,
                        row_slot, row_scale);
     ELORA_HIP_TRY(hipGetLastError());
+    bool copy_done = false;
     if (a.has_pool) {
         const int n_tiles = (a.T + kShrinkRows - 1) / kShrinkRows;
-        hipLaunchKernelGGL(sgmv_shrink_kernel, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
-                           static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
+        const size_t n_pieces = (size_t)a.N * (size_t)(a.K / 8), n_copy = (n_pieces + 256 * kCopyPerThread - 1) / (256 * kCopyPerThread);
+        if (a.wfmt == ELORA_W_INT4_G32 && a.wsl.wdeq_bytes != 0 && n_copy + (size_t)(n_tiles + a.T) < (size_t)1 << 31) {
+            hipLaunchKernelGGL(sgmv_shrink_w4_dequant_kernel, dim3((unsigned)(n_tiles + a.T + n_copy)), dim3(kShrinkThreads), 0,
+                               stream, n_tiles + a.T, a.T, a.K, n_tiles, static_cast<const uint16_t *>(a.x), a.pool, row_slot,
+                               row_scale, V, Rpad, n_pieces, static_cast<const uint32_t *>(a.W),
+                               static_cast<const uint16_t *>(a.w_scales), reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
+            copy_done = true;
+        } else {
+            hipLaunchKernelGGL(sgmv_shrink_kernel, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
+                               static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
+        }
         ELORA_HIP_TRY(hipGetLastError());
     }
-    return launch_gemm_back(a, stream);
+    return launch_gemm_back(a, stream, copy_done);
 }
 
 // Two or three calls of this path that read the same x with the same routing tables (each with a pool of its own):
