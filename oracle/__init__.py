@@ -31,6 +31,7 @@ F32 = 0
 BF16 = 1
 W_SAME = 0
 W_INT4_G32 = 1
+W_INT8_G32 = 2
 
 
 def build(force: bool = False) -> str:
@@ -182,9 +183,14 @@ def _w_args(dtype: int, wfmt: int, W: np.ndarray, w_scales: Optional[np.ndarray]
             raise ValueError("W must be [N, K]")
         return Wc, None, int(Wc.shape[0])
     if K % 32:
-        raise ValueError("4-bit W needs K % 32 == 0")
+        raise ValueError("group-wise W needs K % 32 == 0")
     Wc = np.ascontiguousarray(W)
-    if Wc.dtype != np.uint8 or Wc.ndim != 2 or Wc.shape[1] != K // 2:
+    if wfmt == W_INT8_G32:
+        if Wc.dtype != np.int8 or Wc.ndim != 2 or Wc.shape[1] != K:
+            raise ValueError("8-bit W must be int8 [N, K]")
+    elif wfmt != W_INT4_G32:
+        raise ValueError("unknown weight format")
+    elif Wc.dtype != np.uint8 or Wc.ndim != 2 or Wc.shape[1] != K // 2:
         raise ValueError("4-bit W must be uint8 [N, K/2]")
     ws = np.ascontiguousarray(w_scales)
     if ws.dtype != np.uint16 or ws.shape != (Wc.shape[0], K // 32):

@@ -42,6 +42,9 @@
  *                  w[n,k] = fp16_scale[n, k/32] * (code - 8)
  *                  (symmetric "Q4_0"-style block of 32 named in Sec. 5's
  *                  settings; the byte order is this build's own).
+ *              2 = W is 8-bit group-wise (the "Q8_0" base of Sec. 5's setting
+ *                  S1): int8 code per weight, row-major [N, K],
+ *                  w[n,k] = fp16_scale[n, k/32] * code.
  */
 #include <math.h>
 #include <stdint.h>
@@ -55,6 +58,7 @@
 #define ORACLE_BF16 1
 #define ORACLE_W_SAME 0
 #define ORACLE_W_INT4_G32 1
+#define ORACLE_W_INT8_G32 2
 
 /* ---------- exact widening of stored values to double ---------- */
 
@@ -103,6 +107,8 @@ static double weight_at(int dtype, int wfmt, const void *W, const uint16_t *w_sc
 {
     if (wfmt == ORACLE_W_SAME)
         return widen(dtype, W, (size_t)n * K + k);
+    if (wfmt == ORACLE_W_INT8_G32)
+        return widen_fp16(w_scales[(size_t)n * (K / 32) + k / 32]) * (double)((const int8_t *)W)[(size_t)n * K + k];
     const uint8_t *row = (const uint8_t *)W + (size_t)n * (K / 2);
     uint8_t byte = row[k / 2];
     int code = (k & 1) ? (byte >> 4) : (byte & 0x0f);

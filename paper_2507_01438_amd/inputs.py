@@ -30,6 +30,7 @@ F32 = 0
 BF16 = 1
 W_SAME = 0
 W_INT4_G32 = 1
+W_INT8_G32 = 2
 
 
 # ----------------------------------------------------------------------------
@@ -80,6 +81,23 @@ def quantize_int4_g32(w: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     q = np.clip(np.rint(g / sf_safe[:, :, None]) + 8, 0, 15).astype(np.uint8).reshape(N, K)
     packed = (q[:, 0::2] | (q[:, 1::2] << 4)).astype(np.uint8)
     return np.ascontiguousarray(packed), np.ascontiguousarray(scale.view(np.uint16))
+
+
+def quantize_int8_g32(w: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Symmetric 8-bit group-wise storage of W [N, K] (the "Q8_0" base of Sec. 5's
+    setting S1): groups of 32 along K, scale = absmax / 127 rounded to fp16,
+    code = clamp(rne(w / scale), -127, 127).  Returns (int8 [N, K], fp16 scale bit
+    patterns uint16 [N, K/32]).  The layer consumes (code, scale) as they are."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    N, K = w.shape
+    if K % 32:
+        raise ValueError("K must be a multiple of 32")
+    g = w.reshape(N, K // 32, 32)
+    scale = (np.abs(g).max(axis=2) / np.float32(127.0)).astype(np.float16)
+    sf = scale.astype(np.float32)
+    sf_safe = np.where(sf == 0, np.float32(1.0), sf)
+    q = np.clip(np.rint(g / sf_safe[:, :, None]), -127, 127).astype(np.int8).reshape(N, K)
+    return np.ascontiguousarray(q), np.ascontiguousarray(scale.view(np.uint16))
 
 
 # ----------------------------------------------------------------------------
@@ -213,12 +231,14 @@ class Workload:
         return self._rng(2, self.proj_id(proj)).standard_normal((proj.N, proj.K), dtype=np.float32) * np.float32(self.w_std)
 
     def W(self, proj: Projection):
-        """Base weight [N, K] in storage form: (W, None) or (packed int4, fp16 scale bits)."""
+        """Base weight [N, K] in storage form: (W, None), (packed int4, fp16 scale bits) or (int8, fp16 scale bits)."""
         key = ("W", proj.name)
         if key not in self._cache:
             wf = self.W_float(proj)
             if self.wfmt == W_SAME:
                 self._cache[key] = (store(wf, self.dtype), None)
+            elif self.wfmt == W_INT8_G32:
+                self._cache[key] = quantize_int8_g32(wf)
             else:
                 self._cache[key] = quantize_int4_g32(wf)
         return self._cache[key]
@@ -242,6 +262,8 @@ class Workload:
         e = 4 if self.dtype == F32 else 2
         if self.wfmt == W_SAME:
             wb = proj.N * proj.K * e
+        elif self.wfmt == W_INT8_G32:
+            wb = proj.N * proj.K + proj.N * (proj.K // 32) * 2
         else:
             wb = proj.N * proj.K // 2 + proj.N * (proj.K // 32) * 2
         if q8_adapters:

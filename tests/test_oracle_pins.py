@@ -142,6 +142,63 @@ def test_int4_unit_scale_integer_closed_form():
     assert np.array_equal(y, xi.astype(np.int64) @ (code.astype(np.int64) - 8).T)
 
 
+def test_int8_base_sign_group_and_row_order():
+    # int8 code per weight, row-major; one fp16 scale per 32 consecutive k of a row; w = scale * code
+    K, N = 64, 2
+    codes = np.zeros((N, K), dtype=np.int8)
+    codes[0, 0], codes[0, 31], codes[0, 32], codes[1, 5], codes[1, 63] = -128, 127, -3, 9, -77
+    scales = np.array([[np.float16(0.5), np.float16(2.0)], [np.float16(1.0), np.float16(-3.0)]]).view(np.uint16)
+    at = lambda n, k: oracle.weight_at(I.BF16, I.W_INT8_G32, codes, scales, K, n, k)
+    assert at(0, 0) == 0.5 * -128       # signed, not a byte 0..255
+    assert at(0, 31) == 0.5 * 127       # last element of group 0
+    assert at(0, 32) == 2.0 * -3        # first element of group 1
+    assert at(1, 5) == 1.0 * 9          # row 1 starts K codes and K/32 scales later
+    assert at(1, 63) == -3.0 * -77
+    assert at(1, 6) == 0.0
+
+
+def test_int8_base_unit_scale_integer_closed_form():
+    g = json.load(open(os.path.join(GOLDEN, "closed_forms.json")))["int8_unit_scale"]
+    K, N = g["K"], g["N"]
+    code = (((np.arange(N)[:, None] + 3 * np.arange(K)[None, :]) % 255) - 127).astype(np.int8)
+    scales = np.full((N, K // 32), np.float16(1.0)).view(np.uint16)
+    y = oracle.linear(I.BF16, _bf16(np.ones((2, K))), code, [], [-1, -1], wfmt=I.W_INT8_G32, w_scales=scales)
+    assert np.all(y == g["y0_all_ones"] + g["slope"] * np.arange(N)[None, :])
+    # integer x, unit scales -> exact integer result sum_k x_k code[n, k]
+    rng = np.random.default_rng(6)
+    xi = rng.integers(-4, 5, size=(3, K)).astype(np.float32)
+    y = oracle.linear(I.BF16, _bf16(xi), code, [], [-1] * 3, wfmt=I.W_INT8_G32, w_scales=scales)
+    assert np.array_equal(y, xi.astype(np.int64) @ code.astype(np.int64).T)
+
+
+def test_int8_base_matches_dequantised_dense():
+    # the 8-bit base must equal the dense path run on the matrix dequantised by numpy, adapters on top as before
+    rng = np.random.default_rng(12)
+    K, N, T = 96, 10, 4
+    codes, sb = I.quantize_int8_g32(rng.standard_normal((N, K)).astype(np.float32))
+    wd = codes.astype(np.float64) * np.repeat(sb.view(np.float16).astype(np.float64), 32, axis=1)
+    x = I.normal(rng, (T, K), 1.0, I.BF16)
+    ad = Adapter(I.normal(rng, (3, K), 1.0, I.BF16), I.normal(rng, (N, 3), 1.0, I.BF16), 0.5)
+    y = oracle.linear(I.BF16, x, codes, [ad], [0, -1, 0, 0], wfmt=I.W_INT8_G32, w_scales=sb)
+    xd = I.as_f64(x, I.BF16)
+    ref = xd @ wd.T
+    for t in (0, 2, 3):
+        ref[t] += 0.5 * (I.as_f64(ad.B, I.BF16) @ (I.as_f64(ad.A, I.BF16) @ xd[t]))
+    np.testing.assert_allclose(y, ref, rtol=1e-13, atol=1e-13)
+    yg = oracle.linear_grouped(I.BF16, x, codes, [ad], [0, -1, 0, 0], wfmt=I.W_INT8_G32, w_scales=sb)
+    np.testing.assert_allclose(yg, y, rtol=1e-13, atol=1e-13)
+
+
+def test_int8_quantiser_round_trip_bound():
+    # the generator's codes reproduce w within half a step of its group's scale (what the test inputs rely on)
+    rng = np.random.default_rng(13)
+    w = rng.standard_normal((6, 128)).astype(np.float32)
+    codes, sb = I.quantize_int8_g32(w)
+    s = np.repeat(sb.view(np.float16).astype(np.float64), 32, axis=1)
+    assert np.all(np.abs(codes.astype(np.float64) * s - w) <= 0.5 * s + 1e-12)
+    assert codes.min() >= -127 and codes.max() <= 127
+
+
 def test_int4_matches_dequantised_dense():
     # the 4-bit path must equal the dense path run on the dequantised matrix (library decode via numpy)
     rng = np.random.default_rng(11)
