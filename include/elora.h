@@ -62,11 +62,14 @@ typedef enum { ELORA_F32 = 0, ELORA_BF16 = 1 } elora_dtype_t; /* element type of
 
 typedef enum {
     ELORA_W_SAME = 0,    /* W [d_out, d_in] has the dtype of x */
-    ELORA_W_INT4_G32 = 1 /* W is 4-bit, symmetric, groups of 32 along d_in (the block format the paper's
+    ELORA_W_INT4_G32 = 1, /* W is 4-bit, symmetric, groups of 32 along d_in (the block format the paper's
                             settings name "Q4_0", Sec. 5 "Model"; byte order is this library's own):
                             uint8 [d_out, d_in/2], byte b of a row = code(k=2b) | code(k=2b+1) << 4,
                             w = scale * (code - 8), scales fp16 [d_out, d_in/32].  Needs dtype bf16,
                             d_in % 32 == 0. */
+    ELORA_W_INT8_G32 = 2  /* W is 8-bit, symmetric, groups of 32 along d_in (the "Q8_0" base model of the
+                            paper's setting S1, Sec. 5 "Model"): int8 [d_out, d_in], w = scale * code,
+                            scales fp16 [d_out, d_in/32].  Needs dtype bf16, d_in % 32 == 0. */
 } elora_wfmt_t;
 
 /* Kernel family a call is dispatched to (reported by elora_linear_plan). */
@@ -278,8 +281,8 @@ typedef struct {
     int wfmt;              /* elora_wfmt_t */
     /* tensors (device) */
     const void *x;         /* [n_tokens, d_in] */
-    const void *W;         /* [d_out, d_in] (or packed 4-bit [d_out, d_in/2]) */
-    const void *w_scales;  /* fp16 [d_out, d_in/32] for ELORA_W_INT4_G32, else NULL */
+    const void *W;         /* [d_out, d_in] (packed 4-bit: [d_out, d_in/2] bytes; 8-bit: [d_out, d_in] bytes) */
+    const void *w_scales;  /* fp16 [d_out, d_in/32] for ELORA_W_INT4_G32 and ELORA_W_INT8_G32, else NULL */
     void *y;               /* [n_tokens, d_out], overwritten */
     /* adapters */
     const elora_pool_t *pool;   /* NULL: base model only (y = W x), routing tables are ignored */
@@ -298,8 +301,8 @@ typedef struct {
 /* Device scratch one call may use, for up to n_tokens_max rows, with W in the dtype of x (ELORA_W_SAME).
  * 0 if an argument is invalid. */
 size_t elora_workspace_bytes(int n_tokens_max, int d_in, int d_out, int max_rank);
-/* The same for a given weight format (elora_wfmt_t): with a 4-bit W and 768 rows or more the workspace also holds the
- * call's bf16 copy of W (d_out x d_in x 2 bytes). */
+/* The same for a given weight format (elora_wfmt_t): with a 4-bit W and 768 rows or more, or an 8-bit W and more than
+ * 256 rows, the workspace also holds the call's bf16 copy of W (d_out x d_in x 2 bytes). */
 size_t elora_workspace_bytes_w(int n_tokens_max, int d_in, int d_out, int max_rank, int wfmt);
 
 /*

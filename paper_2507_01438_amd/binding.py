@@ -29,7 +29,7 @@ ELORA_OK = 0
 (ELORA_E_NULL, ELORA_E_ALIGN, ELORA_E_DTYPE, ELORA_E_SHAPE, ELORA_E_RANK, ELORA_E_SLOT,
  ELORA_E_NOT_LOADED, ELORA_E_STORAGE, ELORA_E_SEGMENTS, ELORA_E_HIP) = range(1, 11)
 ELORA_F32, ELORA_BF16 = 0, 1
-ELORA_W_SAME, ELORA_W_INT4_G32 = 0, 1
+ELORA_W_SAME, ELORA_W_INT4_G32, ELORA_W_INT8_G32 = 0, 1, 2
 ELORA_PATH_GENERIC, ELORA_PATH_DECODE, ELORA_PATH_GEMM = 0, 1, 2
 
 EXPORTED = [

@@ -59,7 +59,7 @@ struct WsLayout {
     size_t row_scale;  // float [T]
     size_t row_rank;   // int32 [T]
     size_t v;          // float/bf16 shrink results of the generic and gemm kernels
-    size_t wdeq;       // bf16 [d_out][d_in]: a call's dequantised copy of a 4-bit W (gemm_w4_bytes(); 0 bytes below
+    size_t wdeq;       // bf16 [d_out][d_in]: a call's dequantised copy of a 4-bit or 8-bit W (gemm_wcopy_bytes(); 0 bytes below
     size_t wdeq_bytes; //   the row count from which converting W once pays)
     size_t total;
 };
@@ -126,6 +126,7 @@ void decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
 size_t decode_mail_bytes(int d_out);  // mailboxes of the decode kernel for d_out output columns
 bool gemm_eligible(const elora_linear_desc_t &d, int max_rank);
 void gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan);
+size_t gemm_wcopy_bytes(int wfmt, int n_tokens, int d_in, int d_out);  // (see below)
 size_t gemm_w4_bytes(int n_tokens, int d_in, int d_out);  // room for the bf16 copy of a 4-bit W; 0: converted tile by tile
 size_t gemm_v_bytes(int n_tokens, int max_rank);  // bf16 shrink results, rank padded to the GEMM's K block
 

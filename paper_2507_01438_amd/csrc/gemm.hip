@@ -848,6 +848,23 @@ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // ------------------------------------------------------------------------------------------------
 constexpr int kDequantFirstRows = 768;
 
+// 8-bit W (groups of 32 along d_in, w = scale * code: exact in fp32, rounded once to bf16): the same copy, one thread
+// per 8 weights (8 bytes of codes in, 16 bytes out).
+__device__ __forceinline__ void w8_dequant_piece(size_t i, size_t n_pieces, const uint32_t *__restrict__ codes,
+                                                 const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
+{
+    if (i >= n_pieces) return;
+    const u32x2 q = reinterpret_cast<const u32x2 *>(codes)[i];
+    const float sc = fp16_to_f32(scales[i >> 2]);
+    u32x4 o;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const uint32_t w = q[b >> 1] >> (16 * (b & 1));
+        o[b] = pack_bf16x2(sc * (float)(int8_t)(w & 0xffu), sc * (float)(int8_t)((w >> 8) & 0xffu));
+    }
+    out[i] = o;
+}
+
 __device__ __forceinline__ void w4_dequant_piece(size_t i, size_t n_pieces, const uint32_t *__restrict__ codes,
                                                  const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
 {
@@ -862,10 +879,19 @@ __device__ __forceinline__ void w4_dequant_piece(size_t i, size_t n_pieces, cons
     out[i] = o;
 }
 
-__global__ __launch_bounds__(256) void w4_dequant_kernel(size_t n_pieces, const uint32_t *__restrict__ codes,
-                                                         const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
+template <int WFMT>
+__device__ __forceinline__ void w_dequant_piece(size_t i, size_t n_pieces, const uint32_t *__restrict__ codes,
+                                                const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
 {
-    w4_dequant_piece((size_t)blockIdx.x * 256 + threadIdx.x, n_pieces, codes, scales, out);
+    if (WFMT == ELORA_W_INT8_G32) w8_dequant_piece(i, n_pieces, codes, scales, out);
+    else w4_dequant_piece(i, n_pieces, codes, scales, out);
+}
+
+template <int WFMT>
+__global__ __launch_bounds__(256) void w_dequant_kernel(size_t n_pieces, const uint32_t *__restrict__ codes,
+                                                        const uint16_t *__restrict__ scales, u32x4 *__restrict__ out)
+{
+    w_dequant_piece<WFMT>((size_t)blockIdx.x * 256 + threadIdx.x, n_pieces, codes, scales, out);
 }
 
 // The shrink and the copy of W do not depend on each other, and the shrink of a few hundred rows is a few dozen
@@ -873,7 +899,8 @@ __global__ __launch_bounds__(256) void w4_dequant_kernel(size_t n_pieces, const 
 // at once) the copy fills the rest of the device meanwhile and the call is one launch and one kernel's time shorter.
 static_assert(kShrinkThreads == 256, "one block shape for both halves");
 constexpr int kCopyPerThread = 8;
-__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_w4_dequant_kernel(int n_shrink, int T, int K, int n_tiles,
+template <int WFMT>
+__global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_w_dequant_kernel(int n_shrink, int T, int K, int n_tiles,
                                                                                 const uint16_t *__restrict__ x, PoolView pool,
                                                                                 const int32_t *__restrict__ row_slot,
                                                                                 const float *__restrict__ row_scale,
@@ -890,7 +917,7 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_w4_dequant_kernel(
     // kCopyPerThread pieces per thread, their loads under way together)
     const size_t base = (size_t)(blockIdx.x - n_shrink) * (256 * kCopyPerThread) + threadIdx.x;
 #pragma unroll
-    for (int u = 0; u < kCopyPerThread; ++u) w4_dequant_piece(base + (size_t)u * 256, n_pieces, codes, scales, out);
+    for (int u = 0; u < kCopyPerThread; ++u) w_dequant_piece<WFMT>(base + (size_t)u * 256, n_pieces, codes, scales, out);
 }
 
 }  // namespace
@@ -898,12 +925,14 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_w4_dequant_kernel(
 bool elora::gemm_eligible(const elora_linear_desc_t &d, int max_rank)
 {
     (void)max_rank;
-    return d.dtype == ELORA_BF16 && d.n_tokens >= 1 && d.d_in % BK == 0 && d.d_out % 8 == 0;
+    if (!(d.dtype == ELORA_BF16 && d.n_tokens >= 1 && d.d_in % BK == 0 && d.d_out % 8 == 0)) return false;
+    // an 8-bit W is always multiplied from its bf16 copy here (batches too small for one belong to the decode kernel)
+    return d.wfmt != ELORA_W_INT8_G32 || gemm_wcopy_bytes(d.wfmt, d.n_tokens, d.d_in, d.d_out) != 0;
 }
 
 void elora::gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 {
-    const bool copy_first = d.wfmt == ELORA_W_INT4_G32 && gemm_w4_bytes(d.n_tokens, d.d_in, d.d_out) != 0;
+    const bool copy_first = gemm_wcopy_bytes(d.wfmt, d.n_tokens, d.d_in, d.d_out) != 0;
     plan->n_launches = (d.pool ? 3 : 2) + (copy_first && !d.pool ? 1 : 0);  // (with a pool the copy shares the shrink's launch)
     plan->tile_rows = BM;
     plan->tile_cols = BN;
@@ -913,6 +942,15 @@ void elora::gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
 size_t elora::gemm_w4_bytes(int n_tokens, int d_in, int d_out)
 {
     return n_tokens >= kDequantFirstRows ? (size_t)d_in * (size_t)d_out * sizeof(uint16_t) : 0;
+}
+
+// room for the call's bf16 copy of a group-wise W: 4-bit from 768 rows on (below that it is converted tile by tile),
+// 8-bit for every batch that has more rows than the decode kernel takes
+size_t elora::gemm_wcopy_bytes(int wfmt, int n_tokens, int d_in, int d_out)
+{
+    if (wfmt == ELORA_W_INT4_G32) return gemm_w4_bytes(n_tokens, d_in, d_out);
+    if (wfmt == ELORA_W_INT8_G32) return n_tokens > kDecodeMaxTokens * kDecodeMaxPasses ? (size_t)d_in * (size_t)d_out * sizeof(uint16_t) : 0;
+    return 0;
 }
 
 size_t elora::gemm_v_bytes(int n_tokens, int max_rank) { return (size_t)n_tokens * round_up(max_rank, BK) * sizeof(uint16_t); }
@@ -926,14 +964,19 @@ int launch_gemm_back(const LinearArgs &a, hipStream_t stream, bool copy_done = f
     const int Rpad = round_up(a.pool.max_rank, BK);
     const int has_pool = a.has_pool ? 1 : 0;
     // 4-bit W and enough rows: the bf16 kernel on a copy made now
-    const bool copy_first = a.wfmt == ELORA_W_INT4_G32 && a.wsl.wdeq_bytes != 0;
+    const bool copy_first = a.wfmt != ELORA_W_SAME && a.wsl.wdeq_bytes != 0;
     if (copy_first && !copy_done) {
         const size_t n_pieces = (size_t)a.N * (size_t)(a.K / 8);
-        hipLaunchKernelGGL(w4_dequant_kernel, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces,
-                           static_cast<const uint32_t *>(a.W), static_cast<const uint16_t *>(a.w_scales),
-                           reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
+        const dim3 cgrid((unsigned)((n_pieces + 255) / 256));
+        if (a.wfmt == ELORA_W_INT8_G32)
+            hipLaunchKernelGGL(w_dequant_kernel<ELORA_W_INT8_G32>, cgrid, dim3(256), 0, stream, n_pieces, static_cast<const uint32_t *>(a.W),
+                               static_cast<const uint16_t *>(a.w_scales), reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
+        else
+            hipLaunchKernelGGL(w_dequant_kernel<ELORA_W_INT4_G32>, cgrid, dim3(256), 0, stream, n_pieces, static_cast<const uint32_t *>(a.W),
+                               static_cast<const uint16_t *>(a.w_scales), reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
         ELORA_HIP_TRY(hipGetLastError());
     }
+    if (a.wfmt == ELORA_W_INT8_G32 && !copy_first) return ELORA_E_DTYPE;  // (no tile-by-tile conversion for 8-bit W)
     GemmArgs ga;
     ga.T = a.T;
     ga.K = a.K;
@@ -988,11 +1031,18 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
     if (a.has_pool) {
         const int n_tiles = (a.T + kShrinkRows - 1) / kShrinkRows;
         const size_t n_pieces = (size_t)a.N * (size_t)(a.K / 8), n_copy = (n_pieces + 256 * kCopyPerThread - 1) / (256 * kCopyPerThread);
-        if (a.wfmt == ELORA_W_INT4_G32 && a.wsl.wdeq_bytes != 0 && n_copy + (size_t)(n_tiles + a.T) < (size_t)1 << 31) {
-            hipLaunchKernelGGL(sgmv_shrink_w4_dequant_kernel, dim3((unsigned)(n_tiles + a.T + n_copy)), dim3(kShrinkThreads), 0,
-                               stream, n_tiles + a.T, a.T, a.K, n_tiles, static_cast<const uint16_t *>(a.x), a.pool, row_slot,
-                               row_scale, V, Rpad, n_pieces, static_cast<const uint32_t *>(a.W),
-                               static_cast<const uint16_t *>(a.w_scales), reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
+        if (a.wfmt != ELORA_W_SAME && a.wsl.wdeq_bytes != 0 && n_copy + (size_t)(n_tiles + a.T) < (size_t)1 << 31) {
+            const dim3 mgrid((unsigned)(n_tiles + a.T + n_copy));
+            if (a.wfmt == ELORA_W_INT8_G32)
+                hipLaunchKernelGGL(sgmv_shrink_w_dequant_kernel<ELORA_W_INT8_G32>, mgrid, dim3(kShrinkThreads), 0, stream, n_tiles + a.T,
+                                   a.T, a.K, n_tiles, static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad, n_pieces,
+                                   static_cast<const uint32_t *>(a.W), static_cast<const uint16_t *>(a.w_scales),
+                                   reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
+            else
+                hipLaunchKernelGGL(sgmv_shrink_w_dequant_kernel<ELORA_W_INT4_G32>, mgrid, dim3(kShrinkThreads), 0, stream, n_tiles + a.T,
+                                   a.T, a.K, n_tiles, static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad, n_pieces,
+                                   static_cast<const uint32_t *>(a.W), static_cast<const uint16_t *>(a.w_scales),
+                                   reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
             copy_done = true;
         } else {
             hipLaunchKernelGGL(sgmv_shrink_kernel, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,

@@ -49,6 +49,8 @@ __device__ __forceinline__ float weight_elem(const void *W, const uint16_t *w_sc
 {
     if (WFMT == ELORA_W_SAME) {
         return load_elem(static_cast<const E *>(W), (size_t)n * K + k);
+    } else if (WFMT == ELORA_W_INT8_G32) {
+        return fp16_to_f32(w_scales[(size_t)n * (K >> 5) + (k >> 5)]) * (float)static_cast<const int8_t *>(W)[(size_t)n * K + k];
     } else {
         uint8_t byte = static_cast<const uint8_t *>(W)[(size_t)n * (K >> 1) + (k >> 1)];
         int code = (k & 1) ? (byte >> 4) : (byte & 15);
@@ -157,5 +159,6 @@ int elora::launch_generic(const LinearArgs &a, hipStream_t stream)
 {
     if (a.dtype == ELORA_F32) return launch_typed<ELORA_W_SAME, float>(a, stream);
     if (a.wfmt == ELORA_W_SAME) return launch_typed<ELORA_W_SAME, uint16_t>(a, stream);
+    if (a.wfmt == ELORA_W_INT8_G32) return launch_typed<ELORA_W_INT8_G32, uint16_t>(a, stream);
     return launch_typed<ELORA_W_INT4_G32, uint16_t>(a, stream);
 }

@@ -72,7 +72,7 @@ WsLayout elora::ws_layout(int T, int K, int N, int R, int wfmt)
     off += align_up(v_full > v_gemm ? v_full : v_gemm);
     // last, and zero bytes for small row counts: a workspace sized for more rows holds every smaller layout
     l.wdeq = off;
-    l.wdeq_bytes = wfmt == ELORA_W_INT4_G32 ? gemm_w4_bytes(T, K, N) : 0;
+    l.wdeq_bytes = gemm_wcopy_bytes(wfmt, T, K, N);
     off += align_up(l.wdeq_bytes);
     l.total = off;
     return l;
@@ -82,12 +82,13 @@ static int validate(const elora_linear_desc_t *d, WsLayout *wsl_out)
 {
     if (d == nullptr) return ELORA_E_NULL;
     if (d->dtype != ELORA_F32 && d->dtype != ELORA_BF16) return ELORA_E_DTYPE;
-    if (d->wfmt != ELORA_W_SAME && d->wfmt != ELORA_W_INT4_G32) return ELORA_E_DTYPE;
-    if (d->wfmt == ELORA_W_INT4_G32 && d->dtype != ELORA_BF16) return ELORA_E_DTYPE;
+    const bool grouped = d->wfmt == ELORA_W_INT4_G32 || d->wfmt == ELORA_W_INT8_G32;
+    if (d->wfmt != ELORA_W_SAME && !grouped) return ELORA_E_DTYPE;
+    if (grouped && d->dtype != ELORA_BF16) return ELORA_E_DTYPE;
     if (d->n_tokens < 0 || d->d_in <= 0 || d->d_out <= 0) return ELORA_E_SHAPE;
-    if (d->wfmt == ELORA_W_INT4_G32 && (d->d_in % 32) != 0) return ELORA_E_SHAPE;
+    if (grouped && (d->d_in % 32) != 0) return ELORA_E_SHAPE;
     if (d->x == nullptr || d->W == nullptr || d->y == nullptr || d->workspace == nullptr) return ELORA_E_NULL;
-    if (d->wfmt == ELORA_W_INT4_G32 && d->w_scales == nullptr) return ELORA_E_NULL;
+    if (grouped && d->w_scales == nullptr) return ELORA_E_NULL;
     int max_rank = 1;
     if (d->pool != nullptr) {
         const elora_pool *p = d->pool;
@@ -179,7 +180,7 @@ int elora_version(void) { return 1; }
 size_t elora_workspace_bytes_w(int n_tokens_max, int d_in, int d_out, int max_rank, int wfmt)
 {
     if (n_tokens_max < 0 || d_in <= 0 || d_out <= 0 || max_rank < 1 || max_rank > kMaxRank) return 0;
-    if (wfmt != ELORA_W_SAME && wfmt != ELORA_W_INT4_G32) return 0;
+    if (wfmt != ELORA_W_SAME && wfmt != ELORA_W_INT4_G32 && wfmt != ELORA_W_INT8_G32) return 0;
     return ws_layout(n_tokens_max, d_in, d_out, max_rank, wfmt).total;
 }
 

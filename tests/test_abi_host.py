@@ -96,7 +96,7 @@ def test_linear_descriptor_validation(B):
     assert _plan_status(B, _desc(B, h, workspace=None)) == B.ELORA_E_NULL
     assert _plan_status(B, _desc(B, h, dtype=3)) == B.ELORA_E_DTYPE
     assert _plan_status(B, _desc(B, h, dtype=B.ELORA_F32)) == B.ELORA_E_DTYPE          # pool is bf16
-    assert _plan_status(B, _desc(B, h, wfmt=2)) == B.ELORA_E_DTYPE
+    assert _plan_status(B, _desc(B, h, wfmt=3)) == B.ELORA_E_DTYPE
     assert _plan_status(B, _desc(B, None, wfmt=B.ELORA_W_INT4_G32, dtype=B.ELORA_F32, w_scales=FAKE)) == B.ELORA_E_DTYPE
     assert _plan_status(B, _desc(B, h, wfmt=B.ELORA_W_INT4_G32)) == B.ELORA_E_NULL      # scales missing
     assert _plan_status(B, _desc(B, h, d_in=2048)) == B.ELORA_E_SHAPE                   # pool says 4096
@@ -168,3 +168,15 @@ def test_workspace_grows_with_rows_and_holds_the_copy_of_a_4bit_w(B):
     assert _plan_status(B, d) == B.ELORA_E_STORAGE
     d = _desc(B, None, n_tokens=768, d_in=K, d_out=N, wfmt=B.ELORA_W_INT4_G32, w_scales=FAKE, workspace_bytes=sizes[4])
     assert _plan_status(B, d) == B.ELORA_OK
+    # an 8-bit W: the copy from 257 rows on (what the decode kernel does not take), none below
+    s8 = [B.elora_workspace_bytes_w(t, K, N, R, B.ELORA_W_INT8_G32) for t in (1, 64, 256, 257, 4096)]
+    assert all(a <= b for a, b in zip(s8, s8[1:]))
+    assert s8[3] - s8[2] >= K * N * 2 and s8[:3] == [B.elora_workspace_bytes(t, K, N, R) for t in (1, 64, 256)]
+    d = _desc(B, None, n_tokens=257, d_in=K, d_out=N, wfmt=B.ELORA_W_INT8_G32, w_scales=FAKE, workspace_bytes=s8[2])
+    assert _plan_status(B, d) == B.ELORA_E_STORAGE
+    d = _desc(B, None, n_tokens=257, d_in=K, d_out=N, wfmt=B.ELORA_W_INT8_G32, w_scales=FAKE, workspace_bytes=s8[3])
+    assert _plan_status(B, d) == B.ELORA_OK
+    # group-wise formats need bf16, d_in % 32 == 0 and their scales
+    assert _plan_status(B, _desc(B, None, n_tokens=4, d_in=K, d_out=N, wfmt=B.ELORA_W_INT8_G32, w_scales=None)) == B.ELORA_E_NULL
+    assert _plan_status(B, _desc(B, None, n_tokens=4, d_in=48, d_out=N, wfmt=B.ELORA_W_INT8_G32, w_scales=FAKE)) == B.ELORA_E_SHAPE
+    assert _plan_status(B, _desc(B, None, n_tokens=4, d_in=K, d_out=N, dtype=B.ELORA_F32, wfmt=B.ELORA_W_INT8_G32, w_scales=FAKE)) == B.ELORA_E_DTYPE
