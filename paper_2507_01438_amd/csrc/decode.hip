@@ -64,14 +64,27 @@ constexpr int kChunk = 256;               // K elements per register set of W (8
 // where W travels through the ring as well (see the kernel), the tile's 64 rows of W.
 constexpr int kSubSpan = 128;
 // (nw = waves per workgroup: 4, or 8 for the wide kernel whose tile is 128 rows of W: 3 slots of 48 KiB)
-__host__ __device__ constexpr int ring_slots(int tt, int nw) { return nw > 4 ? 3 : tt <= 2 ? 5 : 4; }
+// (the wide kernel without W in the ring, which is the one for an 8-bit W: 5 slots of 16 KiB; it is given the LDS of
+// the other wide kernel all the same, because what follows the contraction stages as much there)
+__host__ __device__ constexpr int ring_slots(int tt, bool wlds, int nw) { return nw > 4 ? (wlds ? 3 : 5) : tt <= 2 ? 5 : 4; }
 __host__ __device__ constexpr int slot_rows(int tt, bool wlds, int nw) { return tt * 16 + (wlds ? nw * kRowsPerWave : 0); }
-__host__ __device__ constexpr int ring_bytes(int tt, bool wlds, int nw) { return ring_slots(tt, nw) * slot_rows(tt, wlds, nw) * kSubSpan * 2; }
+__host__ __device__ constexpr int ring_bytes(int tt, bool wlds, int nw)
+{
+    return nw > 4 && !wlds ? ring_bytes(tt, true, nw) : ring_slots(tt, wlds, nw) * slot_rows(tt, wlds, nw) * kSubSpan * 2;
+}
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kMetaLds = 512;  // slot tables up to this many entries are copied to LDS whole
 
 constexpr int kXcds = 8;                  // workgroup b runs on XCD b % 8
 template <int V> using ic = std::integral_constant<int, V>;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16_pair_t __attribute__((ext_vector_type(2)));
+typedef float float_pair_t __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair (low half first), round-to-nearest-even
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(float_pair_t{lo, hi}, bf16_pair_t));
+}
 
 // sync area (ints) at the start of the workspace
 constexpr int kCntAll = 0;        // XCDs all of whose workgroups have finished
@@ -132,6 +145,7 @@ struct DecodeShape {
     int wait_ticks; // a wait for another workgroup gives up after this many ticks of the 100 MHz clock
     int tile_rows;  // rows of W per tile: 64 (four waves) or 128 (the wide kernel, eight waves)
     int rot_mask;   // a workgroup starts its K-slice (tile number on its XCD & rot_mask) sub-spans in: 2^n - 1, below every slice's length
+    const uint16_t *w_scales;  // 8-bit W: fp16 [d_out][d_in / 32] group scales; else nullptr
 };
 
 // ---- mailbox accesses (agent scope: past the per-XCD L2) -----------------------------------------
@@ -255,6 +269,23 @@ __device__ __forceinline__ void recompute_columns(const DecodeShape &sh, const u
         for (int c = 0; c < ncols && nc0 + c < N; ++c) {
             const uint16_t *wn = W + (size_t)(nc0 + c) * K;
             float s = 0.0f;
+            if (sh.w_scales != nullptr) {
+                // 8-bit W: w = bf16(scale * code), the value the main path multiplies
+                const int8_t *wc = reinterpret_cast<const int8_t *>(W) + (size_t)(nc0 + c) * K;
+                const uint16_t *ws = sh.w_scales + (size_t)(nc0 + c) * (K >> 5);
+                for (int k = lane * 8; k < K; k += 64 * 8) {
+                    const u32x2 cv = *reinterpret_cast<const u32x2 *>(wc + k);
+                    const u32x4 xv = *reinterpret_cast<const u32x4 *>(xt + k);
+                    const float sc = fp16_to_f32(ws[k >> 5]);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t cw = cv[q >> 1] >> (16 * (q & 1));
+                        const uint32_t wp = pack_bf16_pair(sc * (float)(int8_t)(cw & 0xffu), sc * (float)(int8_t)((cw >> 8) & 0xffu));
+                        s = fmaf(__uint_as_float(wp << 16), __uint_as_float(xv[q] << 16), s);
+                        s = fmaf(__uint_as_float(wp & 0xffff0000u), __uint_as_float(xv[q] & 0xffff0000u), s);
+                    }
+                }
+            } else
             for (int k = lane * 8; k < K; k += 64 * 8) {
                 const u32x4 wv = *reinterpret_cast<const u32x4 *>(wn + k), xv = *reinterpret_cast<const u32x4 *>(xt + k);
 #pragma unroll
@@ -270,7 +301,7 @@ __device__ __forceinline__ void recompute_columns(const DecodeShape &sh, const u
     }
 }
 
-template <int TT, bool kWLds, int NW, bool kQ8>
+template <int TT, bool kWLds, int NW, bool kQ8, bool kW8>
 __global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
                                                                            const uint16_t *__restrict__ W, PoolView pool,
                                                                            RouteView route, int has_pool, float *__restrict__ mail,
@@ -307,7 +338,7 @@ struct DecodeGroup {
 template <int TT, bool kWLds, int NW>
 __global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_group_kernel(DecodeGroup grp_)
 {
-    constexpr bool kQ8 = false;  // (calls with a pool of 8-bit blocks are launched one by one)
+    constexpr bool kQ8 = false, kW8 = false;  // (calls with a pool of 8-bit blocks or an 8-bit W are launched one by one)
     int call_i = 0;
     if (grp_.n > 1 && (int)blockIdx.x >= grp_.first[1]) call_i = 1;
     if (grp_.n > 2 && (int)blockIdx.x >= grp_.first[2]) call_i = 2;
@@ -334,12 +365,13 @@ struct Variant {
     bool wlds;
     int nw;
     bool q8 = false;  // the pool keeps its adapters in 8-bit blocks (W through the ring always; no group launch)
-    int index() const { return (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
+    bool w8 = false;  // W is 8-bit (into registers, four waves, bf16 adapters; no group launch)
+    int index() const { return w8 ? (nw > 4 ? 26 : 21 + tt) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
     int threads() const { return nw * 64; }
     int tile_rows() const { return nw * kRowsPerWave; }
     int lds() const { return ring_bytes(tt, wlds, nw); }
 };
-constexpr int kVariants = 22;
+constexpr int kVariants = 27;
 template <typename F>
 auto with_variant_bf16(const Variant &v, F &&f)
 {
@@ -355,16 +387,27 @@ auto with_variant_bf16(const Variant &v, F &&f)
 template <typename F>
 auto with_variant(const Variant &v, F &&f)
 {
-    if (v.q8) {
-        if (v.nw > 4) return f(ic<4>{}, std::true_type{}, ic<8>{}, std::true_type{});
+    const std::true_type yes{};
+    const std::false_type no{};
+    if (v.w8) {
+        if (v.nw > 4) return f(ic<4>{}, no, ic<8>{}, no, yes);
         switch (v.tt) {
-        case 1: return f(ic<1>{}, std::true_type{}, ic<4>{}, std::true_type{});
-        case 2: return f(ic<2>{}, std::true_type{}, ic<4>{}, std::true_type{});
-        case 3: return f(ic<3>{}, std::true_type{}, ic<4>{}, std::true_type{});
-        default: return f(ic<4>{}, std::true_type{}, ic<4>{}, std::true_type{});
+        case 1: return f(ic<1>{}, no, ic<4>{}, no, yes);
+        case 2: return f(ic<2>{}, no, ic<4>{}, no, yes);
+        case 3: return f(ic<3>{}, no, ic<4>{}, no, yes);
+        default: return f(ic<4>{}, no, ic<4>{}, no, yes);
         }
     }
-    return with_variant_bf16(v, [&](auto tt, auto wl, auto nw) { return f(tt, wl, nw, std::false_type{}); });
+    if (v.q8) {
+        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, yes, no);
+        switch (v.tt) {
+        case 1: return f(ic<1>{}, yes, ic<4>{}, yes, no);
+        case 2: return f(ic<2>{}, yes, ic<4>{}, yes, no);
+        case 3: return f(ic<3>{}, yes, ic<4>{}, yes, no);
+        default: return f(ic<4>{}, yes, ic<4>{}, yes, no);
+        }
+    }
+    return with_variant_bf16(v, [&](auto tt, auto wl, auto nw) { return f(tt, wl, nw, no, no); });
 }
 // workgroups of a kernel instance the device holds at once (registers and LDS decide; asked once per instance), and
 // its number of compute units.  group: the kernel that carries several calls; 0 if it cannot be asked (then calls
@@ -379,16 +422,24 @@ int resident_of(const Variant &v, bool group, int *n_cus)
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
-            e = with_variant(v, [&](auto tt, auto wl, auto nw, auto q8) {
+            e = with_variant(v, [&](auto tt, auto wl, auto nw, auto q8, auto w8) {
                 constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-                constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value;
+                constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value;
                 // (the ring may be larger than the LDS a kernel gets without asking)
+                if constexpr (W8) {  // (never launched in a group)
+                    const void *fn8 = reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, true>);
+                    hipError_t e8 = hipFuncSetAttribute(fn8, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW));
+                    if (e8 != hipSuccess) return e8;
+                    if (group) return hipErrorInvalidValue;
+                    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, true>, NW * 64, ring_bytes(TT, WL, NW));
+                } else {
                 const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW>)
-                                       : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8>);
+                                       : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, false>);
                 hipError_t e2 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW));
                 if (e2 != hipSuccess) return e2;
                 return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW>, NW * 64, ring_bytes(TT, WL, NW))
-                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8>, NW * 64, ring_bytes(TT, WL, NW));
+                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, false>, NW * 64, ring_bytes(TT, WL, NW));
+                }
             });
         if (e != hipSuccess) {
             (void)hipGetLastError();
@@ -435,9 +486,10 @@ int g_wide_mode = -1;  // -1: where it pays, 0: never, 1: wherever the shape all
 
 bool wide_allowed(int T) { return g_wide_mode != 0 && T > 32; }
 
-DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var)
+DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var, const uint16_t *w_scales = nullptr)
 {
     DecodeShape sh;
+    sh.w_scales = w_scales;
     sh.T = T;
     sh.K = K;
     sh.N = N;
@@ -446,6 +498,31 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var)
     sh.jg_inv = (unsigned)((1ull << 32) / (unsigned)sh.jgroups) + 1u;
     const int tt = (T + 15) / 16;
     int n_cus = 0;
+    if (w_scales != nullptr) {
+        // 8-bit W: always into registers; more than 32 rows: 128 rows of W per workgroup where that grid covers the device
+        if (wide_allowed(T)) {
+            const Variant wide{4, false, 8, false, true};
+            const int resident = resident_workgroups(wide, &n_cus);
+            const int n_tiles = (N + wide.tile_rows() - 1) / wide.tile_rows();
+            const int split = pick_split(K, n_tiles, resident, n_cus);
+            if (n_tiles * split <= resident && (g_wide_mode == 1 || n_tiles * split * 8 >= n_cus * 7)) {
+                sh.tile_rows = wide.tile_rows();
+                sh.n_tiles = n_tiles;
+                sh.split = split;
+                *var = wide;
+                finish_shape(sh, max_rank, resident, n_cus, true);
+                return sh;
+            }
+        }
+        Variant v8{tt, false, 4, false, true};
+        sh.tile_rows = v8.tile_rows();
+        sh.n_tiles = (N + sh.tile_rows - 1) / sh.tile_rows;
+        const int resident = resident_workgroups(v8, &n_cus);
+        sh.split = pick_split(K, sh.n_tiles, resident, n_cus);
+        *var = v8;
+        finish_shape(sh, max_rank, resident, n_cus, true);
+        return sh;
+    }
     if (wide_allowed(T)) {
         const Variant wide{4, true, 8, q8};
         const int resident = resident_workgroups(wide, &n_cus);
@@ -613,7 +690,7 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
 {
     if (n < 2 || n > kGroupMax) return -1;
     for (int i = 0; i < n; ++i)
-        if (a[i].has_pool && a[i].pool.q8) return -1;
+        if ((a[i].has_pool && a[i].pool.q8) || a[i].wfmt != ELORA_W_SAME) return -1;
     const int T = a[0].T;
     int Ks[kGroupMax], Ns[kGroupMax], split[kGroupMax];
     for (int i = 0; i < n; ++i) {
@@ -632,6 +709,7 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
     for (int i = 0; i < n; ++i) {
         DecodeCall &c = grp.call[i];
         const int max_rank = a[i].has_pool ? a[i].pool.max_rank : 1;
+        c.sh.w_scales = nullptr;
         c.sh.T = T;
         c.sh.K = a[i].K;
         c.sh.N = a[i].N;
@@ -696,7 +774,9 @@ extern "C" int elora_trace_clear()
 // 256 rows 88 / 171 / 167 us against 574 / 587 / 868 us.
 int elora::decode_passes(const elora_linear_desc_t &d)
 {
-    if (!(d.dtype == ELORA_BF16 && d.wfmt == ELORA_W_SAME && d.n_tokens >= 1 && d.d_in % kChunk == 0 && d.d_out % 16 == 0)) return 0;
+    // (an 8-bit W with bf16 adapters; a pool of 8-bit blocks only with a bf16 W)
+    const bool w_ok = d.wfmt == ELORA_W_SAME || (d.wfmt == ELORA_W_INT8_G32 && !(d.pool && d.pool->q8));
+    if (!(d.dtype == ELORA_BF16 && w_ok && d.n_tokens >= 1 && d.d_in % kChunk == 0 && d.d_out % 16 == 0)) return 0;
     const int passes = (d.n_tokens + kDecodeMaxTokens - 1) / kDecodeMaxTokens;
     if (passes == 1) return 1;
     if (passes > kDecodeMaxPasses || g_pass_mode == 0) return 0;
@@ -723,7 +803,8 @@ void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
     Variant var{1, true, 4};
     const int passes = decode_passes(d);
     const int rows = (d.n_tokens + passes - 1) / passes;  // the longest row range
-    DecodeShape sh = make_shape(rows, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, d.pool && d.pool->q8, &var);
+    DecodeShape sh = make_shape(rows, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, d.pool && d.pool->q8, &var,
+                                d.wfmt == ELORA_W_INT8_G32 ? static_cast<const uint16_t *>(d.w_scales) : nullptr);
     plan->n_launches = passes;
     plan->split_k = sh.split;
     plan->tile_rows = sh.tile_rows;
@@ -735,7 +816,8 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
 {
     (void)plan;
     Variant var{1, true, 4};
-    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, a.has_pool && a.pool.q8 != 0, &var);
+    DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, a.has_pool && a.pool.q8 != 0, &var,
+                                a.wfmt == ELORA_W_INT8_G32 ? static_cast<const uint16_t *>(a.w_scales) : nullptr);
     float *mail = reinterpret_cast<float *>(a.ws + a.wsl.mail);
     float *vmail = reinterpret_cast<float *>(a.ws + a.wsl.vmail);
     int *sync = reinterpret_cast<int *>(a.ws + a.wsl.sync);
@@ -745,10 +827,10 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     int has_pool = a.has_pool ? 1 : 0;
     dim3 grid(sh.grid), block(var.threads());
     profile_mark_begin(stream);
-    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8) {
+    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8, auto w8) {
         constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value;
-        hipLaunchKernelGGL((decode_kernel<TT, WL, NW, Q8>), grid, block, ring_bytes(TT, WL, NW), stream, sh, x, W, a.pool, a.route, has_pool,
+        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value;
+        hipLaunchKernelGGL((decode_kernel<TT, WL, NW, Q8, W8>), grid, block, ring_bytes(TT, WL, NW), stream, sh, x, W, a.pool, a.route, has_pool,
                            mail, vmail, sync, y);
         return 0;
     });

@@ -64,3 +64,117 @@ def test_gemm_path_without_pool():
     y = y_to_f64(case.y[: w.T], w.dtype)
     assert rel_err(y, case.base_reference()) <= TOL
     case.close()
+
+
+# (K, N, T, pool, ranks): the decode kernel with W read as 8-bit codes: 1 to 4 blocks of 16 rows of x, one to eight
+# K-slices per tile, a ragged last tile, rows without adapter
+W8_DECODE = [
+    (256, 16, 1, 2, (8,)),
+    (512, 80, 5, 3, (16, 8, 24)),
+    (1024, 64, 16, 4, (8, 16)),
+    (2048, 208, 20, 4, (16, 64, 8, 32)),
+    (1024, 144, 33, 5, (8, 16, 32)),
+    (4096, 256, 48, 4, (16,)),
+    (2048, 528, 64, 6, (8, 16, 32, 64)),
+    (4096, 4096, 32, 8, (16,)),
+    (14336, 512, 64, 4, (8, 64)),
+]
+
+
+@pytest.mark.parametrize("shape", W8_DECODE)
+def test_decode_kernel_reads_the_8bit_base(shape):
+    K, N, T, pool, ranks = shape
+    case = _case(910 + K + T, K, N, T, pool, ranks, no_adapter_rows=(0,) if T > 1 else ())
+    y = case.run()
+    assert case.last_plan.path == DECODE and case.last_plan.n_launches == 1
+    ref = case.reference()
+    assert rel_err(y, ref) <= TOL
+    # row by row, and the adapter term on its own
+    base = case.base_reference()
+    assert np.max(np.max(np.abs(y - ref), axis=1) / np.max(np.abs(ref), axis=1)) <= 2e-2
+    if np.max(np.abs(ref - base)) > 0:
+        assert np.max(np.abs((y - base) - (ref - base))) / np.max(np.abs(ref - base)) <= 6e-2
+    y2 = case.run()
+    assert np.array_equal(y, y2)
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
+
+
+def test_decode_kernel_8bit_base_against_generic_kernels():
+    # two independent readers of the same codes and scales on the device
+    case = _case(930, 1024, 272, 40, 4, (8, 32))
+    y_dec = case.run(force_path=DECODE)
+    assert case.last_plan.path == DECODE
+    y_gen = case.run(force_path=GENERIC)
+    assert case.last_plan.path == GENERIC
+    assert rel_err(y_dec, y_gen) <= TOL
+    case.close()
+
+
+@pytest.mark.parametrize("T", [65, 130, 256])
+def test_8bit_base_65_to_256_rows_in_passes(T):
+    case = _case(940 + T, 1024, 320, T, 6, (8, 16, 32))
+    y = case.run()
+    assert case.last_plan.path == DECODE and case.last_plan.n_launches == (T + 63) // 64
+    assert rel_err(y, case.reference()) <= TOL
+    case.close()
+
+
+def test_8bit_base_when_waits_run_out():
+    # a workgroup that gives up on the others recomputes its columns from the inputs: the 8-bit W has to be read there too
+    from paper_2507_01438_amd import binding as B
+    case = _case(950, 2048, 192, 24, 4, (16, 8))
+    ref = case.reference()
+    B.elora_debug_spin_limit(0)
+    try:
+        y = case.run()
+    finally:
+        B.elora_debug_spin_limit(1 << 22)
+    assert case.last_plan.path == DECODE
+    assert rel_err(y, ref) <= TOL
+    y = case.run()
+    assert rel_err(y, ref) <= TOL
+    case.close()
+
+
+W8_WIDE = [
+    # (T, K, N, pool, ranks, no_adapter_rows): more than 32 rows, the kernel with 128-row tiles forced
+    (33, 256, 128, 3, (8, 16), (1, 32)),       # one tile, one K-slice: sums stored straight from the accumulators
+    (64, 512, 192, 4, (8, 16, 32, 64), ()),    # last tile half there, two K-slices: adapter term on the matrix cores
+    (48, 1024, 1040, 5, (16,), (0,)),          # four K-slices
+    (64, 4096, 400, 6, (8, 24, 64), (63,)),    # eight K-slices, last tile an eighth there
+    (37, 768, 2048, 4, (8, 24, 40), ()),       # uneven K-slices
+    (40, 512, 272, 4, (8, 20, 16, 3), (2,)),   # ranks that are no multiples of 8: the general tail
+]
+
+
+@pytest.mark.parametrize("spin", [None, 0])
+@pytest.mark.parametrize("shape", W8_WIDE)
+def test_wide_decode_kernel_reads_the_8bit_base(shape, spin):
+    from paper_2507_01438_amd import binding as B
+    T, K, N, pool, ranks, none_rows = shape
+    rk = np.resize(np.asarray(ranks, dtype=np.int32), pool)
+    case = _case(960 + T + N, K, N, T, pool, rk, no_adapter_rows=none_rows)
+    ref = case.reference()
+    B.elora_debug_decode_wide(1)
+    if spin is not None:
+        B.elora_debug_spin_limit(spin)
+    try:
+        y = case.run(force_path=DECODE)
+        assert case.last_plan.path == DECODE and case.last_plan.tile_rows == 128
+        y2 = case.run(force_path=DECODE)
+    finally:
+        B.elora_debug_decode_wide(-1)
+        B.elora_debug_spin_limit(1 << 22)
+    assert rel_err(y, ref) <= TOL
+    base = case.base_reference()
+    if np.max(np.abs(ref - base)) > 0:
+        assert np.max(np.abs((y - base) - (ref - base))) / np.max(np.abs(ref - base)) <= 6e-2
+    if spin is None:
+        assert np.array_equal(y, y2)
+    else:
+        assert rel_err(y2, ref) <= TOL
+    y64 = case.run(force_path=DECODE)      # the same workspace serves the 64-row kernel right after
+    assert rel_err(y64, ref) <= TOL
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
