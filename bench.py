@@ -49,7 +49,7 @@ TRAFFIC = {
     2: (46.1e6, "profiles/decode_kernel_config2.md"),
     3: (213.8e6, "profiles/decode_kernels_config3.md"),
     4: (1.86e9, "profiles/lora_gemm_kernel_config4.md"),
-    5: (0.74e9, "profiles/lora_gemm_kernel_config5.md"),
+    5: (0.69e9, "profiles/lora_gemm_kernel_config5.md"),
 }
 WORKLOAD = {
     2: "Llama3.1-8B q_proj decode: W 4096x4096 bf16, 32 tokens, pool 64 adapters rank 16, adapter_idx power-law(1.1), scale 2.0",
