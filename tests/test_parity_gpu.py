@@ -494,6 +494,11 @@ GEMM_SMALL = [
     (128, 264, 2, (16,), [260], ()),                                      # two K blocks: the general loop only
     # runs of at most 32 rows (added after the K loop) across 32-, 128- and 256-row boundaries, ranks up to 256
     (256, 264, 5, (64, 8, 256, 32, 48), [30, 3, 31, 1, 40, 23, 2, 20, 31, 32, 33, 8, 1, 1, 28, 5], (3,)),
+    (64, 264, 300, (256,), [1] * 300, ()),          # a run per row, every rank 256: the step table of a 32-row block is full
+    (128, 72, 7, (16, 8), [1] * 45, (4, 44)),       # short runs only, one partial tile in both directions
+    (192, 776, 6, (8, 24, 40), [5, 1, 1, 32, 2, 31, 9, 1] * 9, ()),   # short runs only, four column tiles, 2.5 row tiles
+    (128, 264, 3, (32,), [250, 6], ()),             # a prompt's expand block has room for the short run behind it
+    (128, 264, 3, (64, 32), [250, 6], ()),          # ... and here it has not (rank 64 fills the block): added after the loop
 ]
 
 
