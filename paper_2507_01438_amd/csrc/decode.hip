@@ -64,14 +64,19 @@ constexpr int kChunk = 256;               // K elements per register set of W (8
 // where W travels through the ring as well (see the kernel), the tile's 64 rows of W.
 constexpr int kSubSpan = 128;
 // (nw = waves per workgroup: 4, or 8 for the wide kernel whose tile is 128 rows of W: 3 slots of 48 KiB)
-// (the wide kernel without W in the ring, which is the one for an 8-bit W: 5 slots of 16 KiB; it is given the LDS of
-// the other wide kernel all the same, because what follows the contraction stages as much there)
-__host__ __device__ constexpr int ring_slots(int tt, bool wlds, int nw) { return nw > 4 ? (wlds ? 3 : 5) : tt <= 2 ? 5 : 4; }
-__host__ __device__ constexpr int slot_rows(int tt, bool wlds, int nw) { return tt * 16 + (wlds ? nw * kRowsPerWave : 0); }
-__host__ __device__ constexpr int ring_bytes(int tt, bool wlds, int nw)
+// (rows of 256 bytes: a row of x, a row of a bf16 W, or two rows of an 8-bit W; the wide kernel for an 8-bit W has 4
+// slots of 32 KiB, and every wide kernel gets the LDS of the bf16 one, because what follows the contraction stages as
+// much there)
+__host__ __device__ constexpr int ring_slots(int tt, bool wlds, int nw, bool w8 = false) { return nw > 4 ? (w8 ? 4 : 3) : tt <= 2 ? 5 : 4; }
+__host__ __device__ constexpr int slot_rows(int tt, bool wlds, int nw, bool w8 = false)
 {
-    return nw > 4 && !wlds ? ring_bytes(tt, true, nw) : ring_slots(tt, wlds, nw) * slot_rows(tt, wlds, nw) * kSubSpan * 2;
+    return tt * 16 + (wlds ? nw * kRowsPerWave / (w8 ? 2 : 1) : 0);
 }
+__host__ __device__ constexpr int ring_bytes(int tt, bool wlds, int nw, bool w8 = false)
+{
+    return nw > 4 ? 3 * (tt * 16 + nw * kRowsPerWave) * kSubSpan * 2 : ring_slots(tt, wlds, nw, w8) * slot_rows(tt, wlds, nw, w8) * kSubSpan * 2;
+}
+static_assert(ring_slots(4, true, 8, true) * slot_rows(4, true, 8, true) <= 3 * (64 + 128), "the 8-bit wide ring fits");
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 constexpr int kMetaLds = 512;  // slot tables up to this many entries are copied to LDS whole
 
@@ -369,7 +374,7 @@ struct Variant {
     int index() const { return w8 ? (nw > 4 ? 26 : 21 + tt) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
     int threads() const { return nw * 64; }
     int tile_rows() const { return nw * kRowsPerWave; }
-    int lds() const { return ring_bytes(tt, wlds, nw); }
+    int lds() const { return ring_bytes(tt, wlds, nw, w8); }
 };
 constexpr int kVariants = 27;
 template <typename F>
@@ -390,7 +395,7 @@ auto with_variant(const Variant &v, F &&f)
     const std::true_type yes{};
     const std::false_type no{};
     if (v.w8) {
-        if (v.nw > 4) return f(ic<4>{}, no, ic<8>{}, no, yes);
+        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, no, yes);
         switch (v.tt) {
         case 1: return f(ic<1>{}, no, ic<4>{}, no, yes);
         case 2: return f(ic<2>{}, no, ic<4>{}, no, yes);
@@ -428,10 +433,10 @@ int resident_of(const Variant &v, bool group, int *n_cus)
                 // (the ring may be larger than the LDS a kernel gets without asking)
                 if constexpr (W8) {  // (never launched in a group)
                     const void *fn8 = reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, true>);
-                    hipError_t e8 = hipFuncSetAttribute(fn8, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW));
+                    hipError_t e8 = hipFuncSetAttribute(fn8, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW, true));
                     if (e8 != hipSuccess) return e8;
                     if (group) return hipErrorInvalidValue;
-                    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, true>, NW * 64, ring_bytes(TT, WL, NW));
+                    return hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, true>, NW * 64, ring_bytes(TT, WL, NW, true));
                 } else {
                 const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW>)
                                        : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, false>);
@@ -499,9 +504,10 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var,
     const int tt = (T + 15) / 16;
     int n_cus = 0;
     if (w_scales != nullptr) {
-        // 8-bit W: always into registers; more than 32 rows: 128 rows of W per workgroup where that grid covers the device
+        // 8-bit W: into registers on four waves; more than 32 rows: 128 rows of W per workgroup, through the ring, where
+        // that grid covers the device
         if (wide_allowed(T)) {
-            const Variant wide{4, false, 8, false, true};
+            const Variant wide{4, true, 8, false, true};
             const int resident = resident_workgroups(wide, &n_cus);
             const int n_tiles = (N + wide.tile_rows() - 1) / wide.tile_rows();
             const int split = pick_split(K, n_tiles, resident, n_cus);
@@ -830,7 +836,7 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     with_variant(var, [&](auto tt, auto wl, auto nw, auto q8, auto w8) {
         constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
         constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value;
-        hipLaunchKernelGGL((decode_kernel<TT, WL, NW, Q8, W8>), grid, block, ring_bytes(TT, WL, NW), stream, sh, x, W, a.pool, a.route, has_pool,
+        hipLaunchKernelGGL((decode_kernel<TT, WL, NW, Q8, W8>), grid, block, ring_bytes(TT, WL, NW, W8), stream, sh, x, W, a.pool, a.route, has_pool,
                            mail, vmail, sync, y);
         return 0;
     });
