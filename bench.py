@@ -70,8 +70,10 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="distinct (W, pool, x) copies the decode steps rotate through")
     ap.add_argument("--no-groups", action="store_true",
                     help="config 3: one launch per projection instead of one for q/k/v and one for gate/up")
+    ap.add_argument("--w8-base", action="store_true",
+                    help="keep the base weight in 8-bit groups of 32 (int8 codes, fp16 scales) instead of bf16 (configs 2, 3, 4)")
     ap.add_argument("--q8-adapters", action="store_true",
-                    help="decode configurations with every adapter kept in 8-bit blocks in the pool (the paper's adapter "
+                    help="every adapter kept in 8-bit blocks in the pool (the paper's adapter "
                          "storage): a line of its own, not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -200,8 +202,10 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
 
     decode = cfg in (2, 3)
     q8 = bool(args.q8_adapters)
-    assert decode or not q8, "--q8-adapters: decode configurations only"
     w = I.CONFIGS[cfg]()
+    if args.w8_base:
+        assert w.wfmt == I.W_SAME and w.dtype == I.BF16, "--w8-base: configurations with a bf16 base (2, 3, 4)"
+        w.wfmt = I.W_INT8_G32
     projs = w.projections
     distinct = w.distinct_adapters()
 
@@ -249,7 +253,7 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     # Projections that are due at the same time go out as one launch (config 3: q/k/v and gate/up).
     names = [p.name for p in projs]
     # (calls with a pool of 8-bit blocks are launched one by one)
-    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if not (args.no_groups or q8) else []
+    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if not (args.no_groups or (q8 and decode) or (args.w8_base and decode)) else []
     units = []  # per launch of a step: the projection indices it covers
     for pi, n in enumerate(names):
         g = next((g for g in group_names if n in g), None)
@@ -375,7 +379,8 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
         "warmup": warmup,
         "ms_per_step": ms_per_step,
         "config": {
-            "workload": WORKLOAD[cfg] + (" -- adapters kept in 8-bit blocks (int8 codes, fp16 scale per 32 values)" if q8 else ""),
+            "workload": WORKLOAD[cfg] + (" -- adapters kept in 8-bit blocks (int8 codes, fp16 scale per 32 values)" if q8 else "")
+                        + (" -- base weight kept in 8-bit groups of 32 (int8 codes, fp16 scales)" if args.w8_base else ""),
             "config_number": cfg, "n_tokens": w.T, "projections": [p.name for p in projs],
             "distinct_adapters": int(len(distinct)), "rotating_layers": L,
             "path": [int(pl.path) for pl in plans], "split_k": [int(pl.split_k) for pl in plans],

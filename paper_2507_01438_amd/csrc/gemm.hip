@@ -28,6 +28,30 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    bf16x2_t v = __builtin_convertvector(float2_t{lo, hi}, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Eight consecutive values of an adapter kept in 8-bit blocks (they lie in one block: ranks and d_in are multiples of
+// 8 there) as matrix-core operands: scale * code, exact in fp32, rounded once to bf16.  (The decode and generic
+// kernels multiply the exact products; here the adapter passes through the matrix cores like every other operand.)
+__device__ __forceinline__ u32x4 q8_to_bf16x8(u32x2 codes, float sc)
+{
+    u32x4 o;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const uint32_t w = codes[b >> 1] >> (16 * (b & 1));
+        o[b] = pack_bf16x2(sc * (float)(int8_t)(w & 0xffu), sc * (float)(int8_t)((w >> 8) & 0xffu));
+    }
+    return o;
+}
+
 // ------------------------------------------------------------------------------------------------
 // route
 // ------------------------------------------------------------------------------------------------
@@ -57,12 +81,12 @@ constexpr int kShrinkUnroll = 4;        // K steps of 32 whose loads are issued 
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 
-__device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tiles, const uint16_t *__restrict__ x,
+template <bool kQ8>
+__device__ __forceinline__ void shrink_block_t(int block, int T, int K, int n_tiles, const uint16_t *__restrict__ x,
                                              const PoolView &pool, const int32_t *__restrict__ row_slot,
-                                             const float *__restrict__ row_scale, uint16_t *__restrict__ V, int Rpad)
+                                             const float *__restrict__ row_scale, uint16_t *__restrict__ V, int Rpad,
+                                             int (&s_slot)[kShrinkRows], float (&s_red)[4][kShrinkRows][kShrinkColsPerPass + 1])
 {
-    __shared__ int s_slot[kShrinkRows];
-    __shared__ float s_red[4][kShrinkRows][kShrinkColsPerPass + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     if (block >= n_tiles) {
@@ -81,8 +105,15 @@ __device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tile
             const uint16_t *A = reinterpret_cast<const uint16_t *>(slot_A(pool, slot));
             for (int j0 = 2 * wave; j0 < rank; j0 += 2 * 4) {
                 const bool two = (j0 + 1) < rank;
+                const int j1 = two ? j0 + 1 : j0;
                 float a0, a1;
-                shrink_pair(A + (size_t)j0 * K, two ? A + (size_t)(j0 + 1) * K : A + (size_t)j0 * K, x + (size_t)t * K, K, lane, a0, a1);
+                if constexpr (kQ8) {
+                    const char *Ac = reinterpret_cast<const char *>(A);
+                    const uint16_t *As = slot_A_scales(pool, slot);
+                    shrink_pair_q8(Ac + (size_t)j0 * K, Ac + (size_t)j1 * K, As + (((size_t)j0 * K) >> 5), As + (((size_t)j1 * K) >> 5),
+                                   x + (size_t)t * K, K, lane, a0, a1);
+                } else
+                shrink_pair(A + (size_t)j0 * K, A + (size_t)j1 * K, x + (size_t)t * K, K, lane, a0, a1);
                 if (lane == 0) {
                     vrow[j0] = a0;
                     if (two) vrow[j0 + 1] = a1;
@@ -125,6 +156,8 @@ __device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tile
         if (slot >= 0 && run_end - run_start >= kShortRun) {
             const int rank = pool.meta[slot].rank;
             const uint16_t *A = reinterpret_cast<const uint16_t *>(slot_A(pool, slot));
+            const char *Ac = reinterpret_cast<const char *>(A);       // (8-bit blocks: codes, and their scales)
+            const uint16_t *As = kQ8 ? slot_A_scales(pool, slot) : nullptr;
             for (int j0 = 0; j0 < rank; j0 += kShrinkColsPerPass) {
                 floatx4 acc[2][4];
 #pragma unroll
@@ -149,7 +182,14 @@ __device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tile
                         for (int b = 0; b < 4; ++b) {
                             const int j = j0 + b * 16 + m;
                             u32x4 v{0, 0, 0, 0};
-                            if (b < ncb) v = *reinterpret_cast<const u32x4 *>(A + (size_t)min(j, rank - 1) * K + (kin ? kk : kbeg));
+                            if constexpr (kQ8) {
+                                if (b < ncb) {
+                                    const size_t e = (size_t)min(j, rank - 1) * K + (kin ? kk : kbeg);
+                                    v = q8_to_bf16x8(*reinterpret_cast<const u32x2 *>(Ac + e), fp16_to_f32(As[e >> 5]));
+                                }
+                            } else {
+                                if (b < ncb) v = *reinterpret_cast<const u32x4 *>(A + (size_t)min(j, rank - 1) * K + (kin ? kk : kbeg));
+                            }
                             if (j >= rank) v = u32x4{0, 0, 0, 0};
                             ab[u][b] = __builtin_bit_cast(bf16x8, v);
                         }
@@ -184,6 +224,16 @@ __device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tile
         }
         run_start = run_end;
     }
+}
+
+__device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tiles, const uint16_t *__restrict__ x,
+                                             const PoolView &pool, const int32_t *__restrict__ row_slot,
+                                             const float *__restrict__ row_scale, uint16_t *__restrict__ V, int Rpad)
+{
+    __shared__ int s_slot[kShrinkRows];
+    __shared__ float s_red[4][kShrinkRows][kShrinkColsPerPass + 1];
+    if (pool.q8) shrink_block_t<true>(block, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad, s_slot, s_red);
+    else shrink_block_t<false>(block, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad, s_slot, s_red);
 }
 
 __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int K, int n_tiles,
@@ -277,9 +327,10 @@ template <int V> using ic = std::integral_constant<int, V>;
 // loop, to the one or two 32-row accumulator blocks it lies in: per block and 16 rank entries one fragment of V and
 // four of B_i straight from memory and four matrix instructions in each of the two waves that own the rows.
 constexpr int kEpiRows = 32;
-__device__ __forceinline__ bool run_is_short(int start, int end, int rank, int N)
+__device__ __forceinline__ bool run_is_short(int start, int end, int rank, int N, int q8)
 {
-    return end - start <= kEpiRows && (rank & 7) == 0 && N < (1 << 22);  // (a lane's offset into B_i fits 32 bits)
+    // (a lane's offset into B_i fits 32 bits; adapters kept in 8-bit blocks always travel as expand blocks)
+    return end - start <= kEpiRows && (rank & 7) == 0 && N < (1 << 22) && !q8;
 }
 constexpr int kEpiAhead = 8;  // (run, block, 16 rank entries) steps whose loads are in flight per wave
 template <int I, int N, typename F>
@@ -291,15 +342,6 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float float2_t __attribute__((ext_vector_type(2)));
-
-// two floats -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32 on gfx950)
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    bf16x2_t v = __builtin_convertvector(float2_t{lo, hi}, bf16x2_t);
-    return __builtin_bit_cast(uint32_t, v);
-}
 
 template <int WFMT>
 __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, PoolView pool, int has_pool)
@@ -378,7 +420,7 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
         const int k = atomicAdd(&s_nruns, 1);
         const int rank = pool.meta[s_slot[tid]].rank;
         s_runs[k] = Run{tid, end, s_slot[tid], rank};
-        if (rank > 0 && run_is_short(tid, end, rank, N)) {
+        if (rank > 0 && run_is_short(tid, end, rank, N, pool.q8)) {
             atomicAdd(&s_nshort, 1);
             atomicAdd(&s_short_cols, (rank + 7) & ~7);
             for (int g = tid >> 5; g <= (end - 1) >> 5; ++g) {  // a 32-row block has rows of at most 32 runs
@@ -411,10 +453,10 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
         const int nshort = s_nshort;
         if (s_nlong > 0)
             for (int ri = 0; ri < nruns; ++ri)
-                if (!run_is_short(s_runs[ri].start, s_runs[ri].end, s_runs[ri].rank, N)) pack(ri);
+                if (!run_is_short(s_runs[ri].start, s_runs[ri].end, s_runs[ri].rank, N, pool.q8)) pack(ri);
         if (nshort > 0 && nblk > 0 && s_short_cols <= BK - used) {
             for (int ri = 0; ri < nruns; ++ri)
-                if (run_is_short(s_runs[ri].start, s_runs[ri].end, s_runs[ri].rank, N)) pack(ri);
+                if (run_is_short(s_runs[ri].start, s_runs[ri].end, s_runs[ri].rank, N, pool.q8)) pack(ri);
         } else if (nshort > 0) {
             s_use_ring = 1;
         }
@@ -513,7 +555,7 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
         const int e = blk - base_blocks;
         const int kc = pchunk * 8;
         int run_start = 0, run_end = 0, run_rank = 0, j = 0;
-        const uint16_t *Bm = nullptr;
+        const uint16_t *Bm = nullptr, *Bs = nullptr;  // (Bs: block scales of an adapter kept in 8-bit blocks)
         for (int it = s_blk_first[e]; it < s_blk_first[e + 1]; ++it) {
             const Item item = s_items[it];
             if (kc >= item.kcol && kc < item.kcol + item.width) {
@@ -523,6 +565,7 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
                 run_rank = run.rank;
                 j = item.j0 + (kc - item.kcol);
                 Bm = reinterpret_cast<const uint16_t *>(slot_B(pool, run.slot));
+                if (pool.q8) Bs = slot_B_scales(pool, run.slot);
             }
         }
         // A-operand: the run's rows of V (zero beyond the rank up to Rpad); every other row contributes nothing
@@ -540,7 +583,11 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
         for (int i = 0; i < kPieces; ++i) {
             const int n = n0 + prow + 32 * i;
             u32x4 v{0, 0, 0, 0};
-            if (Bm != nullptr && n < N) {
+            if (Bs != nullptr && n < N) {
+                // (8-bit blocks: ranks are multiples of 8, the eight values lie in one block)
+                const size_t e = (size_t)n * run_rank + j;
+                if (j < run_rank) v = q8_to_bf16x8(*reinterpret_cast<const u32x2 *>(reinterpret_cast<const char *>(Bm) + e), fp16_to_f32(Bs[e >> 5]));
+            } else if (Bm != nullptr && n < N) {
                 const uint16_t *src = Bm + (size_t)n * run_rank + j;
                 if (vec) {
                     if (j < run_rank) v = *reinterpret_cast<const u32x4 *>(src);

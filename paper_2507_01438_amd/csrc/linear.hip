@@ -118,8 +118,8 @@ static void make_plan(const elora_linear_desc_t *d, elora_plan_t *plan)
     bool dec = decode_eligible(*d, max_rank);
     bool gem = gemm_eligible(*d, max_rank);
     if (d->pool && d->pool->q8) {
-        // adapters kept in 8-bit blocks: read as they are by the decode kernel (ranks up to 64) and by the generic kernels
-        gem = false;
+        // adapters kept in 8-bit blocks: read as they are by the decode kernel (ranks up to 64, W in the dtype of x), by
+        // the MFMA GEMM path's shrink and expand blocks, and by the generic kernels
         dec = dec && max_rank <= 64;
     }
     int path = ELORA_PATH_GENERIC;
@@ -445,7 +445,8 @@ static int group_form(const elora_linear_desc_t *descs, int n, hipStream_t strea
         make_plan(&descs[i], &plan);
         if (i == 0) path0 = plan.path;
         if (plan.path != path0 || descs[i].n_tokens != descs[0].n_tokens) return ELORA_OK;
-        if (descs[i].pool && descs[i].pool->q8) return ELORA_OK;  // pools of 8-bit blocks: call by call
+        // (the decode kernel that carries several calls reads bf16 pools only)
+        if (plan.path == ELORA_PATH_DECODE && descs[i].pool && descs[i].pool->q8) return ELORA_OK;
     }
     if (path0 != ELORA_PATH_DECODE && path0 != ELORA_PATH_GEMM) return ELORA_OK;
     if (path0 == ELORA_PATH_GEMM) {

@@ -55,7 +55,7 @@ def test_q8_pool_rules_and_the_paths_it_takes():
     w = I.small_workload(801, I.BF16, 512, 264, 300, 4, (8, 16), segments=[100, 200])
     case = DeviceCase(w, w.projections[0], q8=True)
     y = case.run()
-    assert case.last_plan.path == GENERIC      # many rows: the MFMA GEMM path does not read 8-bit blocks
+    assert case.last_plan.path == GEMM         # many rows: the MFMA GEMM path turns the blocks into matrix-core operands
     assert rel_err(y, case.reference()) <= 1e-2
     # adapters in bf16 are refused by such a pool, and so are ranks that are no multiple of 8
     A = torch.zeros((8, 512), dtype=torch.int16)
@@ -95,3 +95,46 @@ def test_q8_pool_config2_full_shape():
     e = assert_close(y, case.reference(), case.base_reference(), "q8 config2")
     print(f"config2, adapters in 8-bit blocks: rel err {e:.2e}")
     case.close()
+
+
+GEMM_Q8 = [
+    # (K, N, pool, ranks, segment lengths, adapter-less segments): prefill / mixed batches on a pool of 8-bit blocks
+    (320, 136, 3, (16, 8, 24), [40, 3, 17, 1, 1, 90, 150], (2,)),
+    (1024, 264, 4, (32, 16, 64, 8), [300, 20, 0, 257, 15], ()),        # runs crossing 256-row tiles
+    (256, 520, 6, (16,), [1] * 70 + [130] + [1] * 60, (5, 100)),       # decode-like rows around a prompt: expand blocks
+    (192, 72, 3, (8, 128), [70, 10, 300], ()),                         # rank 128: two expand items per run
+]
+
+
+@pytest.mark.parametrize("shape", GEMM_Q8)
+def test_q8_pool_on_the_gemm_path(shape):
+    K, N, pool, ranks, lengths, none_segs = shape
+    w = I.small_workload(820 + K, I.BF16, K, N, sum(lengths), pool, ranks, segments=lengths, no_adapter_rows=none_segs)
+    case = DeviceCase(w, w.projections[0], q8=True)
+    y = case.run(force_path=GEMM)
+    assert case.last_plan.path == GEMM
+    assert_close(y, case.reference(), case.base_reference(), f"q8 gemm {shape}")
+    assert np.array_equal(y, case.run(force_path=GEMM))
+    # the generic kernels read the same blocks element by element
+    y_gen = case.run(force_path=GENERIC)
+    assert rel_err(y, y_gen) <= 1e-2
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
+
+
+def test_q8_pools_share_route_and_shrink_on_the_gemm_path():
+    # gate and up of a prefill batch, each with its own pool of 8-bit blocks: one route and one shrink launch for both
+    from paper_2507_01438_amd import binding as B
+    lengths = [280, 40, 1, 1, 300]
+    w = I.small_workload(830, I.BF16, 256, 264, sum(lengths), 4, (16, 8), segments=lengths)
+    a = DeviceCase(w, w.projections[0], q8=True)
+    b = DeviceCase(w, w.projections[0], q8=True, share=a)
+    arr = B.desc_array([a.desc(), b.desc()])
+    assert B.elora_linear_group_launches(arr) == 4          # route, shrink, two GEMMs
+    B.elora_batched_lora_linear_group(arr)
+    torch.cuda.synchronize()
+    from gpu_harness import y_to_f64
+    for c in (a, b):
+        y = y_to_f64(c.y[: w.T], w.dtype)
+        assert rel_err(y, c.reference()) <= 1e-2
+    a.close(); b.close()
