@@ -178,3 +178,45 @@ def test_wide_decode_kernel_reads_the_8bit_base(shape, spin):
     assert rel_err(y64, ref) <= TOL
     assert case.pool.poll_error() == (0, -1)
     case.close()
+
+
+@pytest.mark.parametrize("T,K,Ns", [(40, 1024, (272, 64, 128)), (20, 512, (4096, 1024)), (64, 2048, (144, 144, 1040)),
+                                    (1, 256, (16, 32)), (64, 4096, (4096, 1024, 1024))])
+def test_groups_of_calls_on_8bit_bases_run_as_one_launch(T, K, Ns):
+    import torch
+    from paper_2507_01438_amd import binding as B
+    from gpu_harness import y_to_f64
+    ranks_of = [(16, 8, 32), (8,), (5, 64, 16)][: len(Ns)]
+    cases = []
+    for N, ranks in zip(Ns, ranks_of):
+        w = I.small_workload(970 + T, I.BF16, K, N, T, 6, ranks, wfmt=I.W_INT8_G32, no_adapter_rows=(T // 2,) if T > 1 else ())
+        cases.append(DeviceCase(w, w.projections[0]))
+    for rep in range(2):
+        for c in cases:
+            c.y.fill_(7)
+        descs = B.desc_array([c.desc() for c in cases])
+        assert B.elora_linear_group_launches(descs) == 1
+        B.elora_batched_lora_linear_group(descs)
+        torch.cuda.synchronize()
+        for c in cases:
+            assert rel_err(y_to_f64(c.y[: c.w.T], c.w.dtype), c.reference()) <= TOL, (c.proj.N, rep)
+            assert c.pool.poll_error() == (0, -1)
+    for c in cases:     # one by one on the same workspaces: the mailboxes were left idle
+        assert rel_err(c.run(), c.reference()) <= TOL
+        c.close()
+
+
+def test_group_of_mixed_weight_formats_goes_call_by_call():
+    import torch
+    from paper_2507_01438_amd import binding as B
+    from gpu_harness import y_to_f64
+    w8 = I.small_workload(980, I.BF16, 512, 144, 24, 4, (8, 16), wfmt=I.W_INT8_G32)
+    wb = I.small_workload(980, I.BF16, 512, 80, 24, 4, (8, 16))
+    cases = [DeviceCase(w8, w8.projections[0]), DeviceCase(wb, wb.projections[0])]
+    descs = B.desc_array([c.desc() for c in cases])
+    assert B.elora_linear_group_launches(descs) == 2
+    B.elora_batched_lora_linear_group(descs)
+    torch.cuda.synchronize()
+    for c in cases:
+        assert rel_err(y_to_f64(c.y[: c.w.T], c.w.dtype), c.reference()) <= TOL
+        c.close()
