@@ -413,6 +413,13 @@ int elora_debug_spin_limit(int limit);
 int elora_debug_wait_limit_us(int us);
 
 /*
+ * Test and measurement hook: the row count from which a call with a 4-bit W converts W once into its workspace
+ * instead of tile by tile inside the GEMM kernel (default 768; workspaces are sized with the value in force, so set it
+ * before elora_workspace_bytes_w).  Errors: E_SHAPE (rows < 1).
+ */
+int elora_debug_w4_copy_rows(int rows);
+
+/*
  * Test hook: 0 makes the decode kernel run as if the device gave no guarantee that the workgroups
  * which exchange partial sums share an XCD (every hand-over then goes through memory instead of that
  * XCD's L2); -1 goes back to what the device was found to do.  Errors: E_SHAPE.

@@ -37,7 +37,7 @@ EXPORTED = [
     "elora_pool_destroy", "elora_pool_storage_bytes_q8", "elora_pool_create_q8", "elora_pool_load_adapter", "elora_pool_load_adapters", "elora_pool_load_adapters_q8", "elora_pool_evict", "elora_pool_slot_info",
     "elora_pool_poll_error", "elora_workspace_bytes", "elora_workspace_bytes_w", "elora_linear_plan", "elora_batched_lora_linear",
     "elora_batched_lora_linear_group", "elora_linear_group_launches", "elora_batched_lora_linear_noalloc", "elora_force_path", "elora_profile_arm", "elora_profile_read", "elora_workspace_init",
-    "elora_debug_spin_limit", "elora_debug_xcd_local", "elora_debug_k_rotate", "elora_debug_decode_wide", "elora_debug_decode_passes", "elora_debug_wait_limit_us",
+    "elora_debug_spin_limit", "elora_debug_xcd_local", "elora_debug_k_rotate", "elora_debug_decode_wide", "elora_debug_decode_passes", "elora_debug_wait_limit_us", "elora_debug_w4_copy_rows",
     "elora_cache_create", "elora_cache_destroy", "elora_cache_acquire", "elora_cache_release", "elora_cache_lookup",
     "elora_cache_acquire_batch", "elora_cache_release_batch", "elora_cache_select",
     "elora_cache_drop", "elora_cache_stats", "elora_cache_reset_stats", "elora_cache_load_begin",
@@ -117,6 +117,8 @@ lib.elora_debug_xcd_local.restype = ctypes.c_int
 lib.elora_debug_xcd_local.argtypes = [ctypes.c_int]
 lib.elora_debug_wait_limit_us.restype = ctypes.c_int
 lib.elora_debug_wait_limit_us.argtypes = [ctypes.c_int]
+lib.elora_debug_w4_copy_rows.restype = ctypes.c_int
+lib.elora_debug_w4_copy_rows.argtypes = [ctypes.c_int]
 lib.elora_debug_decode_passes.restype = ctypes.c_int
 lib.elora_debug_decode_passes.argtypes = [ctypes.c_int]
 lib.elora_debug_decode_wide.restype = ctypes.c_int
@@ -336,6 +338,10 @@ def elora_debug_spin_limit(limit: int) -> None:
 
 def elora_debug_xcd_local(mode: int) -> None:
     _check(lib.elora_debug_xcd_local(int(mode)), "elora_debug_xcd_local")
+
+
+def elora_debug_w4_copy_rows(rows: int) -> None:
+    _check(lib.elora_debug_w4_copy_rows(int(rows)), "elora_debug_w4_copy_rows")
 
 
 def elora_debug_wait_limit_us(us: int) -> None:

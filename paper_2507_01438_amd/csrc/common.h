@@ -115,6 +115,7 @@ bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, b
 
 void decode_set_spin_limit(int limit);
 void decode_set_wait_us(int us);
+void gemm_set_w4_copy_rows(int rows);
 void decode_set_passes(int mode);  // -1: several launches per call where they pay, 0: never, 1: whenever the row count allows
 void decode_set_wide(int mode);    // -1: 128-row tiles where they pay, 0: never, 1: wherever the shape allows
 void decode_set_k_rotate(int on);  // 0: every workgroup walks its K-slice from the start

@@ -893,7 +893,7 @@ int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // One thread per 8 weights (4 bytes of codes in, 16 bytes out; four threads share a group's fp16 scale): a wave
 // reads 256 and writes 1024 consecutive bytes.
 // ------------------------------------------------------------------------------------------------
-constexpr int kDequantFirstRows = 768;
+int g_dequant_first_rows = 768;  // (elora_debug_w4_copy_rows)
 
 // 8-bit W (groups of 32 along d_in, w = scale * code: exact in fp32, rounded once to bf16): the same copy, one thread
 // per 8 weights (8 bytes of codes in, 16 bytes out).
@@ -986,9 +986,11 @@ void elora::gemm_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
     plan->grid = gemm_grid((d.n_tokens + BM - 1) / BM, (d.d_out + BN - 1) / BN);
 }
 
+void elora::gemm_set_w4_copy_rows(int rows) { g_dequant_first_rows = rows; }
+
 size_t elora::gemm_w4_bytes(int n_tokens, int d_in, int d_out)
 {
-    return n_tokens >= kDequantFirstRows ? (size_t)d_in * (size_t)d_out * sizeof(uint16_t) : 0;
+    return n_tokens >= g_dequant_first_rows ? (size_t)d_in * (size_t)d_out * sizeof(uint16_t) : 0;
 }
 
 // room for the call's bf16 copy of a group-wise W: 4-bit from 768 rows on (below that it is converted tile by tile),

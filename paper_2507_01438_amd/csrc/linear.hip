@@ -221,6 +221,13 @@ int elora_debug_wait_limit_us(int us)
     return ELORA_OK;
 }
 
+int elora_debug_w4_copy_rows(int rows)
+{
+    if (rows < 1) return ELORA_E_SHAPE;
+    gemm_set_w4_copy_rows(rows);
+    return ELORA_OK;
+}
+
 int elora_debug_xcd_local(int mode)
 {
     if (mode != 0 && mode != -1) return ELORA_E_SHAPE;
