@@ -226,23 +226,26 @@ __device__ __forceinline__ void shrink_block_t(int block, int T, int K, int n_ti
     }
 }
 
+// (the pool's storage format is a property of the launch: decided at run time inside the kernel, the bf16 shrink of two
+// projections in one launch took 114 instead of 83 us)
+template <bool kQ8>
 __device__ __forceinline__ void shrink_block(int block, int T, int K, int n_tiles, const uint16_t *__restrict__ x,
                                              const PoolView &pool, const int32_t *__restrict__ row_slot,
                                              const float *__restrict__ row_scale, uint16_t *__restrict__ V, int Rpad)
 {
     __shared__ int s_slot[kShrinkRows];
     __shared__ float s_red[4][kShrinkRows][kShrinkColsPerPass + 1];
-    if (pool.q8) shrink_block_t<true>(block, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad, s_slot, s_red);
-    else shrink_block_t<false>(block, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad, s_slot, s_red);
+    shrink_block_t<kQ8>(block, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad, s_slot, s_red);
 }
 
+template <bool kQ8>
 __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_kernel(int T, int K, int n_tiles,
                                                                      const uint16_t *__restrict__ x, PoolView pool,
                                                                      const int32_t *__restrict__ row_slot,
                                                                      const float *__restrict__ row_scale,
                                                                      uint16_t *__restrict__ V, int Rpad)
 {
-    shrink_block((int)blockIdx.x, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad);
+    shrink_block<kQ8>((int)blockIdx.x, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad);
 }
 
 // The shrink of several projections that read the same x (q / k / v, gate / up: Sec. 4.3 builds base model and adapters
@@ -269,13 +272,14 @@ __global__ void gemm_route_multi_kernel(int T, RouteView route, ShrinkMulti sm)
         sm.row_scale[p][t] = r.scale;
     }
 }
+template <bool kQ8>
 __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_multi_kernel(int T, int K, int n_tiles, const uint16_t *__restrict__ x,
                                                                            ShrinkMulti sm)
 {
     const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
     const int p = j % sm.n, blk = (j / sm.n) * 8 + xcd;
     if (blk >= n_tiles + T) return;
-    shrink_block(blk, T, K, n_tiles, x, sm.pool[p], sm.row_slot[p], sm.row_scale[p], sm.V[p], sm.Rpad[p]);
+    shrink_block<kQ8>(blk, T, K, n_tiles, x, sm.pool[p], sm.row_slot[p], sm.row_scale[p], sm.V[p], sm.Rpad[p]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -946,7 +950,7 @@ __global__ __launch_bounds__(256) void w_dequant_kernel(size_t n_pieces, const u
 // at once) the copy fills the rest of the device meanwhile and the call is one launch and one kernel's time shorter.
 static_assert(kShrinkThreads == 256, "one block shape for both halves");
 constexpr int kCopyPerThread = 8;
-template <int WFMT>
+template <int WFMT, bool kQ8>
 __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_w_dequant_kernel(int n_shrink, int T, int K, int n_tiles,
                                                                                 const uint16_t *__restrict__ x, PoolView pool,
                                                                                 const int32_t *__restrict__ row_slot,
@@ -957,7 +961,7 @@ __global__ __launch_bounds__(kShrinkThreads) void sgmv_shrink_w_dequant_kernel(i
                                                                                 u32x4 *__restrict__ out)
 {
     if ((int)blockIdx.x < n_shrink) {
-        shrink_block((int)blockIdx.x, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad);
+        shrink_block<kQ8>((int)blockIdx.x, T, K, n_tiles, x, pool, row_slot, row_scale, V, Rpad);
         return;
     }
     // (the shrink's LDS counts for these workgroups too and halves how many of them a compute unit holds: each takes
@@ -1082,19 +1086,25 @@ int elora::launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_
         const size_t n_pieces = (size_t)a.N * (size_t)(a.K / 8), n_copy = (n_pieces + 256 * kCopyPerThread - 1) / (256 * kCopyPerThread);
         if (a.wfmt != ELORA_W_SAME && a.wsl.wdeq_bytes != 0 && n_copy + (size_t)(n_tiles + a.T) < (size_t)1 << 31) {
             const dim3 mgrid((unsigned)(n_tiles + a.T + n_copy));
-            if (a.wfmt == ELORA_W_INT8_G32)
-                hipLaunchKernelGGL(sgmv_shrink_w_dequant_kernel<ELORA_W_INT8_G32>, mgrid, dim3(kShrinkThreads), 0, stream, n_tiles + a.T,
-                                   a.T, a.K, n_tiles, static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad, n_pieces,
+            auto go = [&](auto kern) {
+                hipLaunchKernelGGL(kern, mgrid, dim3(kShrinkThreads), 0, stream, n_tiles + a.T, a.T, a.K, n_tiles,
+                                   static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad, n_pieces,
                                    static_cast<const uint32_t *>(a.W), static_cast<const uint16_t *>(a.w_scales),
                                    reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
-            else
-                hipLaunchKernelGGL(sgmv_shrink_w_dequant_kernel<ELORA_W_INT4_G32>, mgrid, dim3(kShrinkThreads), 0, stream, n_tiles + a.T,
-                                   a.T, a.K, n_tiles, static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad, n_pieces,
-                                   static_cast<const uint32_t *>(a.W), static_cast<const uint16_t *>(a.w_scales),
-                                   reinterpret_cast<u32x4 *>(a.ws + a.wsl.wdeq));
+            };
+            if (a.wfmt == ELORA_W_INT8_G32) {
+                if (a.pool.q8) go(sgmv_shrink_w_dequant_kernel<ELORA_W_INT8_G32, true>);
+                else go(sgmv_shrink_w_dequant_kernel<ELORA_W_INT8_G32, false>);
+            } else {
+                if (a.pool.q8) go(sgmv_shrink_w_dequant_kernel<ELORA_W_INT4_G32, true>);
+                else go(sgmv_shrink_w_dequant_kernel<ELORA_W_INT4_G32, false>);
+            }
             copy_done = true;
+        } else if (a.pool.q8) {
+            hipLaunchKernelGGL(sgmv_shrink_kernel<true>, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
+                               static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
         } else {
-            hipLaunchKernelGGL(sgmv_shrink_kernel, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
+            hipLaunchKernelGGL(sgmv_shrink_kernel<false>, dim3(n_tiles + a.T), dim3(kShrinkThreads), 0, stream, a.T, a.K, n_tiles,
                                static_cast<const uint16_t *>(a.x), a.pool, row_slot, row_scale, V, Rpad);
         }
         ELORA_HIP_TRY(hipGetLastError());
@@ -1109,6 +1119,7 @@ bool elora::gemm_group_shares_shrink(const LinearArgs *a, int n)
     if (n < 2 || n > kShrinkMulti) return false;
     for (int i = 0; i < n; ++i) {
         if (!a[i].has_pool || a[i].x != a[0].x || a[i].T != a[0].T || a[i].K != a[0].K) return false;
+        if ((a[i].pool.q8 != 0) != (a[0].pool.q8 != 0)) return false;  // (one storage format of the pools per shrink launch)
         const RouteView &r = a[i].route, &r0 = a[0].route;
         if (r.adapter_idx != r0.adapter_idx || r.seg_offsets != r0.seg_offsets || r.seg_adapter != r0.seg_adapter ||
             r.n_segments != r0.n_segments || r.scales != r0.scales)
@@ -1133,8 +1144,12 @@ int elora::launch_gemm_group(const LinearArgs *a, int n, hipStream_t stream)
     ELORA_HIP_TRY(hipGetLastError());
     const int n_tiles = (T + kShrinkRows - 1) / kShrinkRows;
     const int per = (n_tiles + T + 7) / 8 * 8;
-    hipLaunchKernelGGL(sgmv_shrink_multi_kernel, dim3(per * n), dim3(kShrinkThreads), 0, stream, T, K, n_tiles,
-                       static_cast<const uint16_t *>(a[0].x), sm);
+    if (a[0].pool.q8)
+        hipLaunchKernelGGL(sgmv_shrink_multi_kernel<true>, dim3(per * n), dim3(kShrinkThreads), 0, stream, T, K, n_tiles,
+                           static_cast<const uint16_t *>(a[0].x), sm);
+    else
+        hipLaunchKernelGGL(sgmv_shrink_multi_kernel<false>, dim3(per * n), dim3(kShrinkThreads), 0, stream, T, K, n_tiles,
+                           static_cast<const uint16_t *>(a[0].x), sm);
     ELORA_HIP_TRY(hipGetLastError());
     for (int i = 0; i < n; ++i) {
         const int rc = launch_gemm_back(a[i], stream);

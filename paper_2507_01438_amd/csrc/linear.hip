@@ -457,10 +457,11 @@ static int group_form(const elora_linear_desc_t *descs, int n, hipStream_t strea
     }
     if (path0 != ELORA_PATH_DECODE && path0 != ELORA_PATH_GEMM) return ELORA_OK;
     if (path0 == ELORA_PATH_GEMM) {
-        // the same activations and routing tables, a pool each
+        // the same activations and routing tables, a pool each (all in the dtype of x, or all in 8-bit blocks)
         for (int i = 0; i < n; ++i) {
             const elora_linear_desc_t &d = descs[i], &d0 = descs[0];
-            if (d.pool == nullptr || d.x != d0.x || d.d_in != d0.d_in || d.adapter_idx != d0.adapter_idx ||
+            if (d.pool == nullptr || d0.pool == nullptr || (d.pool->q8 != 0) != (d0.pool->q8 != 0)) return ELORA_OK;
+            if (d.x != d0.x || d.d_in != d0.d_in || d.adapter_idx != d0.adapter_idx ||
                 d.seg_offsets != d0.seg_offsets || d.seg_adapter != d0.seg_adapter || d.n_segments != d0.n_segments ||
                 d.scales != d0.scales)
                 return ELORA_OK;
