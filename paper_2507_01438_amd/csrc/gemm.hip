@@ -645,55 +645,81 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
     int blk0 = 0;
     if (WFMT == ELORA_W_SAME && base_blocks > 2) {
         // While the two blocks after this one are base blocks, nothing in an iteration is conditional: straight-line
-        // code.  The direct loads of block b + 2 go out as soon as the barrier of iteration b has shown that everybody
-        // is done reading the stage they fill (the one block b sat in), a block and a quarter before they are waited
-        // for, and they and the address arithmetic of each are spread over the sixteen matrix instructions of the
-        // last K step (a matrix instruction keeps its pipe busy for 32 cycles, during which the wave can issue a
-        // handful of other instructions; issued ahead of them, at the top of an iteration, as the general loop below
-        // does, they cost a fifth of the iteration and have three quarters of a block to land).
-        // (the LDS reads come first in program order: the compiler keeps direct loads, which write LDS, and LDS reads in
-        // the order they are written in)
-        auto issue_base = [&](int blk, int buf) {
-            uint16_t *sa = stage0 + buf * kStageElems;
-            uint16_t *sb = sa + BM * BK;
-            const int k0 = blk * BK;
-            const uint16_t *W = static_cast<const uint16_t *>(ga.W);
+        // code in which every matrix instruction has its slot, and what else the wave has to issue is dealt out over
+        // the slots by hand (a matrix instruction keeps its pipe busy for 32 cycles, during which the wave can issue
+        // a handful of other instructions: two or three per slot go unnoticed).
+        //  - LDS reads: the eight fragments of the next K step, one behind each of the first eight matrix
+        //    instructions of this one.  (Left alone, the compiler moves them to the end of the step, to save
+        //    registers, and the wave then waits for them.)
+        //  - Direct loads: the sixteen of a block in two halves of eight, one load per slot: the first half behind the
+        //    last K step of iteration b (block b + 2; the barrier just before has shown that everybody is done reading
+        //    the stage it fills, the one block b sat in), the second half behind the first K step of iteration b + 1;
+        //    they are waited for at that iteration's barrier.  Sixteen loads in eight consecutive slots were 5 % slower
+        //    (4 waves x 16 KiB at once are more than the CU's path to the L2 takes in that time, and a load that is
+        //    not accepted holds up the matrix instruction behind it); thinner spreads, over three or four K steps,
+        //    were slower as well: their last loads have too little time to land.
+        // Addresses: one base per matrix that is the same for the whole wave (the tile's first row at the block's first
+        // column; it lives in scalar registers) plus a 32-bit byte offset per lane and load that never changes (row
+        // inside the tile, clamped to the matrix, and 16-byte chunk), and wave-uniform LDS destinations: a load costs
+        // two scalar instructions besides itself.  (Written as instructions: the compiler's own form of the load takes
+        // a 64-bit address per lane, i.e. a 64-bit vector addition per load, and reads the LDS address out of a vector
+        // register; M0 holds the LDS address of the wave's 1 KiB and needs a cycle to settle.  No other code of this
+        // kernel keeps a value in M0 across statements.)
+        const int swave = __builtin_amdgcn_readfirstlane(wave);
+        uint32_t xoff[8], woff[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int q = wave * 8 + i, row = 8 * q + (lane >> 3);
-                const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-                __builtin_amdgcn_global_load_lds((gptr_t)(ga.x + (size_t)min(m0 + row, T - 1) * K + k0 + chunk * 8), (lptr_t)(sa + q * 512), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((gptr_t)(W + (size_t)min(n0 + row, N - 1) * K + k0 + chunk * 8), (lptr_t)(sb + q * 512), 16, 0, 0);
+        for (int i = 0; i < 8; ++i) {
+            const int row = 8 * (swave * 8 + i) + (lane >> 3);
+            const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+            xoff[i] = (uint32_t)(((size_t)(min(m0 + row, T - 1) - m0) * K + chunk * 8) * 2);
+            woff[i] = (uint32_t)(((size_t)(min(n0 + row, N - 1) - n0) * K + chunk * 8) * 2);
+        }
+        const char *const xbase = reinterpret_cast<const char *>(ga.x + (size_t)m0 * K);
+        const char *const wbase = reinterpret_cast<const char *>(static_cast<const uint16_t *>(ga.W) + (size_t)n0 * K);
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)(stage0 + swave * 8 * 512);
+        // load k of a block's sixteen: rows 8 (k / 2) .. + 7 of the wave's 64, of X (k even) or of W (k odd)
+        auto issue_one = [&](int blk, int buf, int k) __attribute__((always_inline)) {
+            const int i = k >> 1;
+            const uint32_t off = (k & 1) ? woff[i] : xoff[i];
+            const char *base = ((k & 1) ? wbase : xbase) + (size_t)blk * BK * 2;
+            const uint32_t lds = lds0 + (uint32_t)(buf * kStageElems + ((k & 1) ? BM * BK : 0) + i * 512) * 2;
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds) : "memory");
+        };
+        auto read_frag = [&](bf16x8 *dst, int buf, int ks, int f) __attribute__((always_inline)) {
+            const int slot = ((ks * 2 + fhalf) ^ fsw) << 3;
+            const uint16_t *src = stage0 + buf * kStageElems + (f < 4 ? 0 : BM * BK) + ((f < 4 ? wm : wn) * 128 + (lane & 31) + (f & 3) * 32) * BK + slot;
+            dst[f] = *reinterpret_cast<const bf16x8 *>(src);
+        };
+        // One K step: sixteen matrix instructions on the fragments `cur`; behind each of the first eight a fragment
+        // of the step after it is read into `nxt`, behind each of the last eight (kLoads) load kFirst + 0 .. 7 of block
+        // lblk.  Nothing may move across the slots: the order below is the order of the instructions.
+        auto k_step = [&](auto first_c, auto loads_c, const bf16x8 *cur, bf16x8 *nxt, int rbuf, int rks, int lblk, int lbuf) __attribute__((always_inline)) {
+            constexpr int kFirst = decltype(first_c)::value;
+            constexpr bool kLoads = decltype(loads_c)::value;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                acc[e >> 2][e & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[e >> 2], cur[4 + (e & 3)], acc[e >> 2][e & 3], 0, 0, 0);
+                if (e < 8) read_frag(nxt, rbuf, rks, e);
+                else if (kLoads) issue_one(lblk, lbuf, kFirst + e - 8);
+                __builtin_amdgcn_sched_barrier(0);
             }
         };
-        issue_base(1, 1);
+        using std::integral_constant;
+        const integral_constant<bool, true> with_loads;
+        const integral_constant<bool, false> no_loads;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) issue_one(1, 1, k);  // (the loop's first turn asks for the second half of block 1)
         for (; blk0 + 2 < base_blocks; ++blk0) {
             const int buf = blk0 & 1;
-            read_frags(fr[1], buf, 1);
-            mfma_step(fr[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(fr[0], buf, 2);
-            mfma_step(fr[1]);
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(fr[1], buf, 3);
-            mfma_step(fr[0]);
-            __builtin_amdgcn_sched_barrier(0);
+            k_step(integral_constant<int, 8>{}, with_loads, fr[0], fr[1], buf, 1, blk0 + 1, buf ^ 1);
+            k_step(integral_constant<int, 0>{}, no_loads, fr[1], fr[0], buf, 2, 0, 0);
+            k_step(integral_constant<int, 0>{}, no_loads, fr[0], fr[1], buf, 3, 0, 0);
             __builtin_amdgcn_s_waitcnt(0x0F70);  // block blk0 + 1 has landed
             __syncthreads();
-            read_frags(fr[0], buf ^ 1, 0);
-            issue_base(blk0 + 2, buf);
-            mfma_step(fr[1]);
-#define ELORA_SLOT_R __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-#define ELORA_SLOT   __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x006, 6, 0); \
-                     __builtin_amdgcn_sched_group_barrier(0x010, 1, 0); __builtin_amdgcn_sched_group_barrier(0x006, 6, 0); \
-                     __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-            ELORA_SLOT_R ELORA_SLOT_R ELORA_SLOT_R ELORA_SLOT_R ELORA_SLOT_R ELORA_SLOT_R ELORA_SLOT_R ELORA_SLOT_R
-            ELORA_SLOT ELORA_SLOT ELORA_SLOT ELORA_SLOT ELORA_SLOT ELORA_SLOT ELORA_SLOT ELORA_SLOT
-#undef ELORA_SLOT_R
-#undef ELORA_SLOT
-            __builtin_amdgcn_sched_barrier(0);
+            k_step(integral_constant<int, 0>{}, with_loads, fr[1], fr[0], buf ^ 1, 0, blk0 + 2, buf);
         }
-        // (block blk0 + 1 is on its way; the loop below asks for it once more, which is harmless: same bytes, same place)
+        // (the first half of block blk0 + 1 is on its way; the loop below asks for the whole block, which is harmless:
+        // same bytes, same place)
     }
     for (int blk = blk0; blk < total_blocks; ++blk) {
         const int buf = blk & 1;
@@ -977,6 +1003,7 @@ bool elora::gemm_eligible(const elora_linear_desc_t &d, int max_rank)
 {
     (void)max_rank;
     if (!(d.dtype == ELORA_BF16 && d.n_tokens >= 1 && d.d_in % BK == 0 && d.d_out % 8 == 0)) return false;
+    if (d.d_in > (1 << 22)) return false;  // a lane's byte offset inside a tile (up to 255 rows of d_in bf16) is kept in 32 bits
     // an 8-bit W is always multiplied from its bf16 copy here (batches too small for one belong to the decode kernel)
     return d.wfmt != ELORA_W_INT8_G32 || gemm_wcopy_bytes(d.wfmt, d.n_tokens, d.d_in, d.d_out) != 0;
 }
