@@ -53,9 +53,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 4;         // waves per workgroup
 constexpr int kRowsPerWave = 16;  // W rows per wave (one MFMA row block)
-constexpr int kTileRows = kWaves * kRowsPerWave;
 constexpr int kChunk = 256;               // K elements per register set of W (8 MFMA K steps)
 // The ring of sub-spans in LDS (dynamic LDS: the only such array of the kernel; the staging after the contraction reuses
 // it).  A sub-span is 128 elements of K.  Up to 32 rows of x: 5 slots, more rows: 4.  A slot holds the rows of x and,
