@@ -91,12 +91,18 @@ __device__ __forceinline__ void shrink_block_t(int block, int T, int K, int n_ti
 
     if (block >= n_tiles) {
         // ---- one row of a short run ---------------------------------------------------------------
+        // (most rows of a batch of prompts sit in long runs and their workgroups end here: one load of the tile's slots
+        // and a vote, not a walk along the rows with a dependent load per step)
         const int t = block - n_tiles;
         const int r0 = t / kShrinkRows * kShrinkRows, r1 = min(r0 + kShrinkRows, T);
-        const int slot = row_slot[t];
-        int lo = t, hi = t + 1;  // the run's piece inside this tile
-        while (lo > r0 && row_slot[lo - 1] == slot) --lo;
-        while (hi < r1 && row_slot[hi] == slot) ++hi;
+        static_assert(kShrinkRows == 32, "one lane of a half-wave per row of the tile");
+        const int l = lane & 31;
+        const int mine = r0 + l < r1 ? row_slot[r0 + l] : INT32_MIN;
+        const int slot = __builtin_amdgcn_readlane(mine, t - r0);
+        const uint32_t same = (uint32_t)__ballot(mine == slot);       // (both halves of the wave vote alike)
+        const int p = t - r0;
+        const uint32_t below = ~same & ((1u << p) - 1u), above = ~same & ~((2u << p) - 1u);  // (2u << 31 == 0: nothing above)
+        const int lo = below ? 32 - __builtin_clz(below) : 0, hi = above ? __builtin_ctz(above) : 32;  // the run's piece inside this tile
         if (hi - lo >= kShortRun) return;
         float *vrow = &s_red[0][0][0];  // Rpad <= 256 floats
         int rank = 0;
