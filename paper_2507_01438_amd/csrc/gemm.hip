@@ -888,10 +888,14 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
 
     // ---- epilogue -------------------------------------------------------------------------------------
     // C layout of the 32x32 MFMA: lane holds column (lane % 32); value i sits in row (i / 4) * 8 + (lane / 32) * 4 + i % 4.
-    // Neighbouring lanes swap one value per row pair (one cross-lane move inside the quad, no LDS) so that every lane
-    // stores two adjacent columns (4 bytes).  A tile that lies wholly inside y, the usual case, stores without any
-    // test: 128 stores per lane, each of which would otherwise sit in a branch of its own.
+    // A lane rounds its two values of a row pair into one register (low half: row i0, high half: row i1), neighbouring
+    // lanes exchange that register (one cross-lane move inside the quad, no LDS), and a byte permute picks the two
+    // halves that belong to the lane's row: the even lane stores row i0, the odd lane row i1, two adjacent columns
+    // (4 bytes) each.  A tile that lies wholly inside y, the usual case, stores without any test: 128 stores per lane,
+    // each of which would otherwise sit in a branch of its own.
     const bool odd = lane & 1;
+    const uint32_t pick = odd ? 0x03020706u : 0x05040100u;  // bytes of {neighbour's register : own register}
+    char *const ycorner = reinterpret_cast<char *>(ga.y + (size_t)m0 * N + n0 + wn * 128);
     auto store_tile = [&](auto checked) {
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
@@ -900,16 +904,15 @@ __global__ __launch_bounds__(kGemmThreads) void lora_gemm_kernel(GemmArgs ga, Po
                 const int i_mine = 2 * ip + (odd ? 1 : 0);
                 const int rl = wm * 128 + a * 32 + (i_mine >> 2) * 8 + (lane >> 5) * 4 + (i_mine & 3);
                 const int row = m0 + rl;
-                uint16_t *yrow = ga.y + (size_t)row * N + n0 + wn * 128 + (lane & 30);  // even column of the pair
+                // (the wave's corner of y is the same for all lanes; a lane's place relative to it fits 32 bits)
+                char *yrow = ycorner + (uint32_t)(((uint32_t)rl * (uint32_t)N + (uint32_t)(lane & 30)) * 2u);  // even column of the pair
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    // even lane keeps row i0 and gets the neighbour's i0 value; odd lane keeps row i1 and gets the neighbour's i1
-                    const float lo = acc[a][b][2 * ip], hi = acc[a][b][2 * ip + 1];
-                    const float send = odd ? lo : hi, mine = odd ? hi : lo;
-                    const float recv = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, false));  // quad_perm [1, 0, 3, 2]
-                    const uint32_t packed = odd ? pack_bf16x2(recv, mine) : pack_bf16x2(mine, recv);
+                    const uint32_t own = pack_bf16x2(acc[a][b][2 * ip], acc[a][b][2 * ip + 1]);
+                    const uint32_t other = (uint32_t)__builtin_amdgcn_mov_dpp((int)own, 0xB1, 0xF, 0xF, true);  // quad_perm [1, 0, 3, 2]
+                    const uint32_t packed = __builtin_amdgcn_perm(other, own, pick);
                     if (!decltype(checked)::value || (row < T && n0 + wn * 128 + b * 32 + (lane & 30) < N))
-                        *reinterpret_cast<uint32_t *>(yrow + b * 32) = packed;
+                        *reinterpret_cast<uint32_t *>(yrow + b * 64) = packed;
                 }
             }
         }
@@ -1009,7 +1012,8 @@ bool elora::gemm_eligible(const elora_linear_desc_t &d, int max_rank)
 {
     (void)max_rank;
     if (!(d.dtype == ELORA_BF16 && d.n_tokens >= 1 && d.d_in % BK == 0 && d.d_out % 8 == 0)) return false;
-    if (d.d_in > (1 << 22)) return false;  // a lane's byte offset inside a tile (up to 255 rows of d_in bf16) is kept in 32 bits
+    // a lane's byte offset inside a tile (up to 255 rows of d_in or d_out bf16) is kept in 32 bits
+    if (d.d_in > (1 << 22) || d.d_out > (1 << 22)) return false;
     // an 8-bit W is always multiplied from its bf16 copy here (batches too small for one belong to the decode kernel)
     return d.wfmt != ELORA_W_INT8_G32 || gemm_wcopy_bytes(d.wfmt, d.n_tokens, d.d_in, d.d_out) != 0;
 }
