@@ -1,7 +1,8 @@
-// Prefill / mixed path (many rows, MFMA-bound): bf16 activations, bf16 or 4-bit base weights.
+// Prefill / mixed path (many rows, MFMA-bound): bf16 activations; bf16, 4-bit or 8-bit base weights.
 //
-// Three launches per call (four with a 4-bit W and 768 rows or more: W is then converted to bf16 once, into the
-// workspace, and the bf16 kernel runs on the copy; below that the 4-bit W is converted tile by tile inside the gemm):
+// Three launches per call (a 4-bit W with 768 rows or more and an 8-bit W are converted to bf16 once per call, into
+// the workspace, in the shrink's launch, and the bf16 kernel runs on the copy; below that the 4-bit W is converted
+// tile by tile inside the gemm):
 //   route   per row: validated pool slot and scale (Sec. 3.4: each request names its adapter)
 //   shrink  V[t, :] = bf16(s_t * A_i x_t) for every row, with the rows grouped by adapter inside each
 //           32-row tile ("u-batches", Sec. 3.4 / 4.3: rows that share an adapter are computed together):
@@ -11,10 +12,10 @@
 //           the K loop as extra K blocks: a run of rows that share an adapter takes rank (rounded up to
 //           8) of a block's 64 K columns, with the run's rows of V as A-operand (zero in all other rows)
 //           and B_i as B-operand in the same columns, so one block serves several short runs at once
-//           (decode rows of a mixed batch included).  While the next two blocks are base blocks the loop is
-//           straight-line code in which the direct loads of block b + 2 are spread over the matrix instructions
-//           of the last K step of block b.  The epilogue rounds once to bf16 and stores each row at its own
-//           position.
+//           (runs of at most 32 rows, such as the decode rows of a mixed batch, are added after the K loop
+//           instead).  While the next two blocks are base blocks the loop is straight-line code in which the
+//           LDS reads and the direct loads are dealt out by hand over the matrix instructions' slots.  The
+//           epilogue rounds once to bf16 and stores each row at its own position.
 #include <type_traits>
 
 #include "common.h"
