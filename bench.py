@@ -252,8 +252,7 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
     n_proj = len(projs)
     # Projections that are due at the same time go out as one launch (config 3: q/k/v and gate/up).
     names = [p.name for p in projs]
-    # (calls with a pool of 8-bit blocks are launched one by one)
-    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if not (args.no_groups or (q8 and decode)) else []
+    group_names = [g for g in (("q", "k", "v"), ("gate", "up")) if all(n in names for n in g)] if not args.no_groups else []
     units = []  # per launch of a step: the projection indices it covers
     for pi, n in enumerate(names):
         g = next((g for g in group_names if n in g), None)

@@ -111,7 +111,7 @@ int launch_gemm(const LinearArgs &a, const elora_plan_t &plan, hipStream_t strea
 bool gemm_group_shares_shrink(const LinearArgs *a, int n);  // same x and routing tables, a pool each: one shrink launch serves all
 int launch_gemm_group(const LinearArgs *a, int n, hipStream_t stream);
 int launch_decode_group(const LinearArgs *a, int n, hipStream_t stream);  // -1: the calls do not fit into one launch
-bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds, bool w8 = false);  // K-slices per call if they fit
+bool decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds, bool w8 = false, bool q8 = false);  // K-slices per call if they fit
 
 void decode_set_spin_limit(int limit);
 void decode_set_wait_us(int us);

@@ -336,10 +336,9 @@ struct DecodeGroup {
     DecodeCall call[kGroupMax];
 };
 
-template <int TT, bool kWLds, int NW, bool kW8>
+template <int TT, bool kWLds, int NW, bool kQ8, bool kW8>
 __global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_group_kernel(DecodeGroup grp_)
 {
-    constexpr bool kQ8 = false;  // (calls with a pool of 8-bit blocks are launched one by one)
     int call_i = 0;
     if (grp_.n > 1 && (int)blockIdx.x >= grp_.first[1]) call_i = 1;
     if (grp_.n > 2 && (int)blockIdx.x >= grp_.first[2]) call_i = 2;
@@ -365,8 +364,8 @@ struct Variant {
     int tt;
     bool wlds;
     int nw;
-    bool q8 = false;  // the pool keeps its adapters in 8-bit blocks (W through the ring always; no group launch)
-    bool w8 = false;  // W is 8-bit (into registers, four waves, bf16 adapters; no group launch)
+    bool q8 = false;  // the pool keeps its adapters in 8-bit blocks (W through the ring always)
+    bool w8 = false;  // W is 8-bit (into registers on four waves, through the ring on eight; bf16 adapters)
     int index() const { return w8 ? (nw > 4 ? 26 : 21 + tt) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
     int threads() const { return nw * 64; }
     int tile_rows() const { return nw * kRowsPerWave; }
@@ -428,18 +427,18 @@ int resident_of(const Variant &v, bool group, int *n_cus)
                 constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value;
                 // (the ring may be larger than the LDS a kernel gets without asking)
                 if constexpr (W8) {
-                    const void *fn8 = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, true>)
+                    const void *fn8 = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, Q8, true>)
                                             : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, true>);
                     hipError_t e8 = hipFuncSetAttribute(fn8, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW, true));
                     if (e8 != hipSuccess) return e8;
-                    return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, true>, NW * 64, ring_bytes(TT, WL, NW, true))
+                    return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, Q8, true>, NW * 64, ring_bytes(TT, WL, NW, true))
                                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, true>, NW * 64, ring_bytes(TT, WL, NW, true));
                 } else {
-                const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, false>)
+                const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, Q8, false>)
                                        : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, false>);
                 hipError_t e2 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW));
                 if (e2 != hipSuccess) return e2;
-                return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, false>, NW * 64, ring_bytes(TT, WL, NW))
+                return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, Q8, false>, NW * 64, ring_bytes(TT, WL, NW))
                              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, false>, NW * 64, ring_bytes(TT, WL, NW));
                 }
             });
@@ -636,7 +635,7 @@ int elora::decode_probe_device(void *scratch, size_t scratch_bytes, hipStream_t 
 // tried first if its workgroups then cover at least seven eighths of the compute units; then W through LDS (one
 // workgroup per compute unit); then W into registers, which leaves room for two per unit.
 namespace {
-bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant *var, bool w8 = false)
+bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant *var, bool w8 = false, bool q8 = false)
 {
     if (n < 2 || n > kGroupMax || T < 1 || T > kDecodeMaxTokens) return false;
     const int tt = (T + 15) / 16;
@@ -645,6 +644,9 @@ bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant 
     if (w8) {  // (an 8-bit W: through the ring on eight waves, into registers on four)
         if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8, false, true};
         cand[n_cand++] = Variant{tt, false, 4, false, true};
+    } else if (q8) {  // (adapters in 8-bit blocks: W through the ring always)
+        if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8, true, false};
+        cand[n_cand++] = Variant{tt, true, 4, true, false};
     } else {
         if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8};
         cand[n_cand++] = Variant{tt, true, 4};
@@ -685,10 +687,10 @@ bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant 
 }
 }  // namespace
 
-bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds, bool w8)
+bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *split, bool *w_lds, bool w8, bool q8)
 {
     Variant v{1, true, 4};
-    const bool ok = group_splits(T, n, K, N, split, &v, w8);
+    const bool ok = group_splits(T, n, K, N, split, &v, w8, q8);
     if (ok) *w_lds = v.wlds;
     return ok;
 }
@@ -697,10 +699,13 @@ bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *s
 int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
 {
     if (n < 2 || n > kGroupMax) return -1;
-    // bf16 pools; W in the dtype of x in every call, or 8-bit in every call
+    // W in the dtype of x in every call, or 8-bit in every call; the pools all bf16, or all in 8-bit blocks (then with a W
+    // in the dtype of x: the kernel has no instance for an 8-bit W next to 8-bit adapters)
     const bool w8 = a[0].wfmt == ELORA_W_INT8_G32;
+    bool q8 = false;
+    for (int i = 0; i < n; ++i) q8 = q8 || (a[i].has_pool && a[i].pool.q8);
     for (int i = 0; i < n; ++i)
-        if ((a[i].has_pool && a[i].pool.q8) || a[i].wfmt != a[0].wfmt || (a[i].wfmt != ELORA_W_SAME && !w8)) return -1;
+        if ((a[i].has_pool && (a[i].pool.q8 != 0) != q8) || a[i].wfmt != a[0].wfmt || (a[i].wfmt != ELORA_W_SAME && !w8) || (q8 && w8)) return -1;
     const int T = a[0].T;
     int Ks[kGroupMax], Ns[kGroupMax], split[kGroupMax];
     for (int i = 0; i < n; ++i) {
@@ -709,7 +714,7 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
         Ns[i] = a[i].N;
     }
     Variant var{1, true, 4};
-    if (!group_splits(T, n, Ks, Ns, split, &var, w8)) return -1;
+    if (!group_splits(T, n, Ks, Ns, split, &var, w8, q8)) return -1;
     int n_cus = 0;
     (void)resident_workgroups(var, &n_cus);
     const int resident = resident_group_workgroups(var);
@@ -746,12 +751,10 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
     for (int i = n; i <= kGroupMax; ++i) grp.first[i] = first;
     dim3 grid(first), block(var.threads());
     profile_mark_begin(stream);
-    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8, auto w8c) {
+    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8c, auto w8c) {
         constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-        constexpr bool WL = decltype(wl)::value, W8 = decltype(w8c)::value;
-        static_assert(!decltype(q8)::value || true, "");
-        if constexpr (!decltype(q8)::value)
-            hipLaunchKernelGGL((decode_group_kernel<TT, WL, NW, W8>), grid, block, ring_bytes(TT, WL, NW, W8), stream, grp);
+        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8c)::value, W8 = decltype(w8c)::value;
+        hipLaunchKernelGGL((decode_group_kernel<TT, WL, NW, Q8, W8>), grid, block, ring_bytes(TT, WL, NW, W8), stream, grp);
         return 0;
     });
     ELORA_HIP_TRY(hipGetLastError());

@@ -452,8 +452,14 @@ static int group_form(const elora_linear_desc_t *descs, int n, hipStream_t strea
         make_plan(&descs[i], &plan);
         if (i == 0) path0 = plan.path;
         if (plan.path != path0 || descs[i].n_tokens != descs[0].n_tokens) return ELORA_OK;
-        // (the decode kernel that carries several calls reads bf16 pools only, and one weight format per launch)
-        if (plan.path == ELORA_PATH_DECODE && ((descs[i].pool && descs[i].pool->q8) || descs[i].wfmt != descs[0].wfmt)) return ELORA_OK;
+        // (the decode kernel that carries several calls has one weight format and one storage format of the pools per launch)
+        if (plan.path == ELORA_PATH_DECODE && descs[i].wfmt != descs[0].wfmt) return ELORA_OK;
+    }
+    if (path0 == ELORA_PATH_DECODE) {
+        bool q8 = false;
+        for (int i = 0; i < n; ++i) q8 = q8 || (descs[i].pool && descs[i].pool->q8);
+        for (int i = 0; i < n; ++i)
+            if (descs[i].pool && (descs[i].pool->q8 != 0) != q8) return ELORA_OK;
     }
     if (path0 != ELORA_PATH_DECODE && path0 != ELORA_PATH_GEMM) return ELORA_OK;
     if (path0 == ELORA_PATH_GEMM) {
@@ -530,7 +536,9 @@ int elora_linear_group_launches(const elora_linear_desc_t *descs, int n, int *n_
             K[i] = descs[i].d_in;
             N[i] = descs[i].d_out;
         }
-        if (decode_group_splits(descs[0].n_tokens, n, K, N, split, &wlds, descs[0].wfmt == ELORA_W_INT8_G32)) sum = 1;
+        bool q8 = false;
+        for (int i = 0; i < n; ++i) q8 = q8 || (descs[i].pool && descs[i].pool->q8);
+        if (decode_group_splits(descs[0].n_tokens, n, K, N, split, &wlds, descs[0].wfmt == ELORA_W_INT8_G32, q8)) sum = 1;
     } else if (form == kGroupGemmShared) {
         sum -= 2 * (n - 1);  // one route and one shrink launch for all of them
     }

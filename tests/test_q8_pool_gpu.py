@@ -138,3 +138,71 @@ def test_q8_pools_share_route_and_shrink_on_the_gemm_path():
         y = y_to_f64(c.y[: w.T], w.dtype)
         assert rel_err(y, c.reference()) <= 1e-2
     a.close(); b.close()
+
+
+def _q8_decode_cases(T, K, Ns, ranks_of, seed, q8=(True, True, True)):
+    cases = []
+    for N, ranks, q in zip(Ns, ranks_of, q8):
+        w = I.small_workload(seed, I.BF16, K, N, T, 6, ranks, no_adapter_rows=(T // 2,) if T > 1 else ())
+        cases.append(DeviceCase(w, w.projections[0], q8=q))
+    return cases
+
+
+def _run_decode_group(B, cases, expect_launches):
+    for c in cases:
+        c.y.fill_(7)
+    descs = B.desc_array([c.desc() for c in cases])
+    assert B.elora_linear_group_launches(descs) == expect_launches
+    B.elora_batched_lora_linear_group(descs)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for c in cases:
+        e = rel_err(y_to_f64(c.y[: c.w.T], c.w.dtype), c.reference())
+        assert e <= 1e-2, (c.proj.N, e)
+        assert c.pool.poll_error() == (0, -1)
+        worst = max(worst, e)
+    return worst
+
+
+@pytest.mark.parametrize("T,K,Ns", [(40, 1024, (272, 64, 128)), (20, 512, (4096, 1024)), (64, 2048, (144, 144, 1040)),
+                                    (1, 256, (16, 32)), (33, 768, (80, 4096 + 64, 48))])
+def test_q8_pools_in_one_decode_launch(T, K, Ns):
+    # calls that are due together (Sec. 3.4: the layer's projections of one batch), each with a pool of 8-bit blocks
+    from paper_2507_01438_amd import binding as B
+    ranks_of = [(16, 8, 32), (8,), (8, 64, 16)][: len(Ns)]
+    cases = _q8_decode_cases(T, K, Ns, ranks_of, seed=840 + T)
+    e = _run_decode_group(B, cases, expect_launches=1)
+    e2 = _run_decode_group(B, cases, expect_launches=1)       # mailboxes were left idle
+    for c in cases:
+        assert rel_err(c.run(), c.reference()) <= 1e-2        # and one by one on the same workspaces
+    print(f"q8 group T={T} K={K} N={Ns}: rel err {e:.2e} / {e2:.2e}")
+    for c in cases:
+        c.close()
+
+
+def test_pools_of_both_formats_do_not_share_a_decode_launch():
+    from paper_2507_01438_amd import binding as B
+    cases = _q8_decode_cases(24, 512, (96, 160), [(8, 16), (16,)], seed=850, q8=(True, False))
+    _run_decode_group(B, cases, expect_launches=2)
+    for c in cases:
+        c.close()
+
+
+@pytest.mark.parametrize("names", [("q", "k", "v"), ("gate", "up")])
+def test_q8_pool_config3_groups_full_shapes(names):
+    from paper_2507_01438_amd import binding as B
+    w = I.config3()
+    cases = [DeviceCase(w, I.LLAMA8B[n], load_slots=w.distinct_adapters(), q8=True) for n in names]
+    descs = B.desc_array([c.desc() for c in cases])
+    assert B.elora_linear_group_launches(descs) == 1
+    B.elora_batched_lora_linear_group(descs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(19)
+    for c, n in zip(cases, names):
+        cols = np.sort(rng.choice(c.proj.N, 48, replace=False))
+        y = y_to_f64(c.y[: w.T], w.dtype)
+        e = rel_err(y[:, cols], c.reference(cols=cols))
+        print(f"config3 q8 group {names}: {n} rel err {e:.2e}")
+        assert e <= 1e-2
+        assert c.pool.poll_error() == (0, -1)
+        c.close()
