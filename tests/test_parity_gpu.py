@@ -70,6 +70,7 @@ SMALL = [
     (48, 512, 64, 3, (64, 8, 8), tuple(range(1, 48))),   # more than 32 rows, one of them with an adapter: 32 shrink units in all
     (48, 512, 64, 3, (64, 8, 8), tuple(range(48))),      # a pool, and no row uses it: no shrink unit at all
     (64, 1024, 128, 4, (1, 64, 3, 8), (10, 11)),         # ranks 1 to 64 side by side (one pair of rank rows to 32 per row)
+    (64, 512, 32768, 3, (8, 16), (3,)),                  # 256 tiles of 128 rows: one K-slice per tile, sums straight to y
 ]
 
 

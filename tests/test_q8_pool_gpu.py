@@ -22,6 +22,8 @@ SHAPES = [
     (64, 2048, 4096, 4, (64, 8, 32), ()),             # 128-row tiles where they fill the device
     (50, 768, 16, 2, (8,), ()),
     (130, 1024, 272, 6, (8, 16, 32, 64, 24), (0, 64, 129)),   # several launches of the decode kernel
+    (64, 512, 32768, 3, (8, 16), (3,)),               # 256 tiles of 128 rows, one K-slice per tile: the sums still go through the mailboxes
+    (40, 256, 28672, 2, (16,), ()),                   # 224 such tiles
 ]
 
 
