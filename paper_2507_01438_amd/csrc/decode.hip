@@ -394,7 +394,6 @@ auto with_variant(const Variant &v, F &&f)
         switch (v.tt) {
         case 1: return f(ic<1>{}, no, ic<4>{}, no, yes);
         case 2: return f(ic<2>{}, no, ic<4>{}, no, yes);
-        case 3: return f(ic<3>{}, no, ic<4>{}, no, yes);
         default: return f(ic<4>{}, no, ic<4>{}, no, yes);
         }
     }
@@ -516,7 +515,9 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var,
                 return sh;
             }
         }
-        Variant v8{tt, false, 4, false, true};
+        // (33 to 48 rows take the instance for four blocks of x: the one for three needs more registers than a wave has,
+        // and what the compiler would move to scratch memory there may be the target of a load still on its way)
+        Variant v8{tt == 3 ? 4 : tt, false, 4, false, true};
         sh.tile_rows = v8.tile_rows();
         sh.n_tiles = (N + sh.tile_rows - 1) / sh.tile_rows;
         const int resident = resident_workgroups(v8, &n_cus);
@@ -643,7 +644,7 @@ bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant 
     int n_cand = 0;
     if (w8) {  // (an 8-bit W: through the ring on eight waves, into registers on four)
         if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8, false, true};
-        cand[n_cand++] = Variant{tt, false, 4, false, true};
+        cand[n_cand++] = Variant{tt == 3 ? 4 : tt, false, 4, false, true};
     } else if (q8) {  // (adapters in 8-bit blocks: W through the ring always)
         if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8, true, false};
         cand[n_cand++] = Variant{tt, true, 4, true, false};
