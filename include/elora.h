@@ -153,9 +153,11 @@ int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, con
  * A pool whose adapters STAY in 8-bit blocks (the paper's adapter storage, Sec. 5 "Model"): the blocks placed by
  * elora_pool_load_adapters_q8 are kept as they are (int8 codes and fp16 block scales), and the linear kernels read
  * them directly, value = scale * code formed in registers, so an adapter costs half the memory and half the traffic
- * of its bf16 form.  x, y and W of calls that use the pool are bf16.  d_in % 32 == 0, d_out % 4 == 0, max_rank and
- * every loaded rank multiples of 8.  Calls with such a pool take the decode path (up to 256 rows, max_rank <= 64) or
- * else the generic kernels; elora_pool_load_adapter / _load_adapters (sources in bf16) answer E_DTYPE.
+ * of its bf16 form.  x and y of calls that use the pool are bf16, W is bf16 or in one of the grouped formats (with
+ * ELORA_W_INT8_G32 base and adapters are both stored as in the paper's setting S1).  d_in % 32 == 0, d_out % 4 == 0,
+ * max_rank and every loaded rank multiples of 8.  Calls with such a pool take the decode path (up to 256 rows,
+ * max_rank <= 64), the GEMM path, or else the generic kernels; elora_pool_load_adapter / _load_adapters (sources in
+ * bf16) answer E_DTYPE.
  * Errors: as elora_pool_create, E_SHAPE / E_RANK for the divisibility rules above.
  */
 size_t elora_pool_storage_bytes_q8(int d_in, int d_out, int max_rank, int capacity);

@@ -365,13 +365,13 @@ struct Variant {
     bool wlds;
     int nw;
     bool q8 = false;  // the pool keeps its adapters in 8-bit blocks (W through the ring always)
-    bool w8 = false;  // W is 8-bit (into registers on four waves, through the ring on eight; bf16 adapters)
-    int index() const { return w8 ? (nw > 4 ? 26 : 21 + tt) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
+    bool w8 = false;  // W is 8-bit (into registers on four waves, through the ring on eight)
+    int index() const { return w8 ? (nw > 4 ? 26 : 21 + tt) + (q8 ? 6 : 0) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
     int threads() const { return nw * 64; }
     int tile_rows() const { return nw * kRowsPerWave; }
     int lds() const { return ring_bytes(tt, wlds, nw, w8); }
 };
-constexpr int kVariants = 27;
+constexpr int kVariants = 33;
 template <typename F>
 auto with_variant_bf16(const Variant &v, F &&f)
 {
@@ -389,6 +389,14 @@ auto with_variant(const Variant &v, F &&f)
 {
     const std::true_type yes{};
     const std::false_type no{};
+    if (v.w8 && v.q8) {
+        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, yes, yes);
+        switch (v.tt) {
+        case 1: return f(ic<1>{}, no, ic<4>{}, yes, yes);
+        case 2: return f(ic<2>{}, no, ic<4>{}, yes, yes);
+        default: return f(ic<4>{}, no, ic<4>{}, yes, yes);
+        }
+    }
     if (v.w8) {
         if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, no, yes);
         switch (v.tt) {
@@ -502,7 +510,7 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var,
         // 8-bit W: into registers on four waves; more than 32 rows: 128 rows of W per workgroup, through the ring, where
         // that grid covers the device
         if (wide_allowed(T)) {
-            const Variant wide{4, true, 8, false, true};
+            const Variant wide{4, true, 8, q8, true};
             const int resident = resident_workgroups(wide, &n_cus);
             const int n_tiles = (N + wide.tile_rows() - 1) / wide.tile_rows();
             const int split = pick_split(K, n_tiles, resident, n_cus);
@@ -517,7 +525,7 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var,
         }
         // (33 to 48 rows take the instance for four blocks of x: the one for three needs more registers than a wave has,
         // and what the compiler would move to scratch memory there may be the target of a load still on its way)
-        Variant v8{tt == 3 ? 4 : tt, false, 4, false, true};
+        Variant v8{tt == 3 ? 4 : tt, false, 4, q8, true};
         sh.tile_rows = v8.tile_rows();
         sh.n_tiles = (N + sh.tile_rows - 1) / sh.tile_rows;
         const int resident = resident_workgroups(v8, &n_cus);
@@ -643,8 +651,8 @@ bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant 
     Variant cand[3];
     int n_cand = 0;
     if (w8) {  // (an 8-bit W: through the ring on eight waves, into registers on four)
-        if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8, false, true};
-        cand[n_cand++] = Variant{tt == 3 ? 4 : tt, false, 4, false, true};
+        if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8, q8, true};
+        cand[n_cand++] = Variant{tt == 3 ? 4 : tt, false, 4, q8, true};
     } else if (q8) {  // (adapters in 8-bit blocks: W through the ring always)
         if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8, true, false};
         cand[n_cand++] = Variant{tt, true, 4, true, false};
@@ -700,13 +708,12 @@ bool elora::decode_group_splits(int T, int n, const int *K, const int *N, int *s
 int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
 {
     if (n < 2 || n > kGroupMax) return -1;
-    // W in the dtype of x in every call, or 8-bit in every call; the pools all bf16, or all in 8-bit blocks (then with a W
-    // in the dtype of x: the kernel has no instance for an 8-bit W next to 8-bit adapters)
+    // W in the dtype of x in every call, or 8-bit in every call; the pools all bf16, or all in 8-bit blocks
     const bool w8 = a[0].wfmt == ELORA_W_INT8_G32;
     bool q8 = false;
     for (int i = 0; i < n; ++i) q8 = q8 || (a[i].has_pool && a[i].pool.q8);
     for (int i = 0; i < n; ++i)
-        if ((a[i].has_pool && (a[i].pool.q8 != 0) != q8) || a[i].wfmt != a[0].wfmt || (a[i].wfmt != ELORA_W_SAME && !w8) || (q8 && w8)) return -1;
+        if ((a[i].has_pool && (a[i].pool.q8 != 0) != q8) || a[i].wfmt != a[0].wfmt || (a[i].wfmt != ELORA_W_SAME && !w8)) return -1;
     const int T = a[0].T;
     int Ks[kGroupMax], Ns[kGroupMax], split[kGroupMax];
     for (int i = 0; i < n; ++i) {
@@ -790,8 +797,7 @@ extern "C" int elora_trace_clear()
 // 256 rows 88 / 171 / 167 us against 574 / 587 / 868 us.
 int elora::decode_passes(const elora_linear_desc_t &d)
 {
-    // (an 8-bit W with bf16 adapters; a pool of 8-bit blocks only with a bf16 W)
-    const bool w_ok = d.wfmt == ELORA_W_SAME || (d.wfmt == ELORA_W_INT8_G32 && !(d.pool && d.pool->q8));
+    const bool w_ok = d.wfmt == ELORA_W_SAME || d.wfmt == ELORA_W_INT8_G32;
     if (!(d.dtype == ELORA_BF16 && w_ok && d.n_tokens >= 1 && d.d_in % kChunk == 0 && d.d_out % 16 == 0)) return 0;
     const int passes = (d.n_tokens + kDecodeMaxTokens - 1) / kDecodeMaxTokens;
     if (passes == 1) return 1;

@@ -118,7 +118,7 @@ static void make_plan(const elora_linear_desc_t *d, elora_plan_t *plan)
     bool dec = decode_eligible(*d, max_rank);
     bool gem = gemm_eligible(*d, max_rank);
     if (d->pool && d->pool->q8) {
-        // adapters kept in 8-bit blocks: read as they are by the decode kernel (ranks up to 64, W in the dtype of x), by
+        // adapters kept in 8-bit blocks: read as they are by the decode kernel (ranks up to 64), by
         // the MFMA GEMM path's shrink and expand blocks, and by the generic kernels
         dec = dec && max_rank <= 64;
     }
