@@ -46,8 +46,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the same counter reads for a 1 GiB device copy on the same box (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Figures
 # and commands: the files named here.  None = not measured for that configuration.
 TRAFFIC = {
-    2: (46.1e6, "profiles/decode_kernel_config2.md"),
-    3: (213.8e6, "profiles/decode_kernels_config3.md"),
+    2: (46.0e6, "profiles/decode_kernel_config2.md"),
+    3: (209.9e6, "profiles/decode_kernels_config3.md"),
     4: (1.86e9, "profiles/lora_gemm_kernel_config4.md"),
     5: (0.69e9, "profiles/lora_gemm_kernel_config5.md"),
 }
