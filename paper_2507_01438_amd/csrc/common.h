@@ -31,6 +31,9 @@ struct PoolView {
     int q8;
     size_t a_scale_off;    // byte offset of A's scales inside a block
     size_t b_scale_off;    // byte offset of B's scales inside a block
+    // (host knowledge, for the choice of a kernel instance) loaded adapters whose rank is no multiple of 8: the decode
+    // kernel's short tail only serves ranks that are, and instances without the general tail exist for pools without others
+    int n_odd_ranks;
 };
 
 struct RouteView {
@@ -84,7 +87,13 @@ struct elora_pool {
     size_t storage_bytes;
     size_t meta_offset, slots_offset, slot_bytes, b_offset;
     bool device_cleared;
-    elora::SlotMeta *host_meta;  // mirror of the device slot table
+    elora::SlotMeta *host_meta;  // mirror of the device slot table (written through set_host_meta)
+    int n_odd_ranks;             // loaded slots whose rank is no multiple of 8
+    void set_host_meta(int slot, const elora::SlotMeta &m)
+    {
+        n_odd_ranks += (int)(m.loaded && (m.rank & 7) != 0) - (int)(host_meta[slot].loaded && (host_meta[slot].rank & 7) != 0);
+        host_meta[slot] = m;
+    }
     elora::PoolView view() const;
 };
 

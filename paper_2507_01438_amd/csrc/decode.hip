@@ -302,7 +302,7 @@ __device__ __forceinline__ void recompute_columns(const DecodeShape &sh, const u
     }
 }
 
-template <int TT, bool kWLds, int NW, bool kQ8, bool kW8>
+template <int TT, bool kWLds, int NW, bool kQ8, bool kW8, bool kLeanOnly>
 __global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_kernel(DecodeShape sh, const uint16_t *__restrict__ x,
                                                                            const uint16_t *__restrict__ W, PoolView pool,
                                                                            RouteView route, int has_pool, float *__restrict__ mail,
@@ -336,7 +336,7 @@ struct DecodeGroup {
     DecodeCall call[kGroupMax];
 };
 
-template <int TT, bool kWLds, int NW, bool kQ8, bool kW8>
+template <int TT, bool kWLds, int NW, bool kQ8, bool kW8, bool kLeanOnly>
 __global__ __launch_bounds__(NW * 64, NW > 4 ? 1 : 2) void decode_group_kernel(DecodeGroup grp_)
 {
     int call_i = 0;
@@ -366,12 +366,22 @@ struct Variant {
     int nw;
     bool q8 = false;  // the pool keeps its adapters in 8-bit blocks (W through the ring always)
     bool w8 = false;  // W is 8-bit (into registers on four waves, through the ring on eight)
-    int index() const { return w8 ? (nw > 4 ? 26 : 21 + tt) + (q8 ? 6 : 0) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0); }
+    // the instance without the general tail (eight waves, bf16 W, bf16 pool or none): for calls whose pool, as the host
+    // knows it, holds only ranks that are multiples of 8, up to 64.  24 KB less code; config 3: 178.6 -> 175.9 us per
+    // step.  (The same for the four-wave instances made config 2 slower, 15.45 -> 15.94 us, although a build in which
+    // every instance lacked that tail ran it in 14.8: where the code lies matters as much as how much there is.)
+    bool lean = false;
+    int index() const
+    {
+        if (lean) return 33;
+        return w8 ? (nw > 4 ? 26 : 21 + tt) + (q8 ? 6 : 0) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0);
+    }
+    void allow_lean(bool ok) { lean = ok && !q8 && !w8 && wlds && nw > 4; }
     int threads() const { return nw * 64; }
     int tile_rows() const { return nw * kRowsPerWave; }
     int lds() const { return ring_bytes(tt, wlds, nw, w8); }
 };
-constexpr int kVariants = 33;
+constexpr int kVariants = 34;
 template <typename F>
 auto with_variant_bf16(const Variant &v, F &&f)
 {
@@ -385,36 +395,37 @@ auto with_variant_bf16(const Variant &v, F &&f)
 }
 
 template <typename F>
-auto with_variant(const Variant &v, F &&f)
+auto with_variant(const Variant &v, F &&f)  // f(blocks of x, W through the ring, waves, 8-bit pool, 8-bit W, no general tail)
 {
     const std::true_type yes{};
     const std::false_type no{};
+    if (v.lean) return f(ic<4>{}, yes, ic<8>{}, no, no, yes);
     if (v.w8 && v.q8) {
-        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, yes, yes);
+        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, yes, yes, no);
         switch (v.tt) {
-        case 1: return f(ic<1>{}, no, ic<4>{}, yes, yes);
-        case 2: return f(ic<2>{}, no, ic<4>{}, yes, yes);
-        default: return f(ic<4>{}, no, ic<4>{}, yes, yes);
+        case 1: return f(ic<1>{}, no, ic<4>{}, yes, yes, no);
+        case 2: return f(ic<2>{}, no, ic<4>{}, yes, yes, no);
+        default: return f(ic<4>{}, no, ic<4>{}, yes, yes, no);
         }
     }
     if (v.w8) {
-        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, no, yes);
+        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, no, yes, no);
         switch (v.tt) {
-        case 1: return f(ic<1>{}, no, ic<4>{}, no, yes);
-        case 2: return f(ic<2>{}, no, ic<4>{}, no, yes);
-        default: return f(ic<4>{}, no, ic<4>{}, no, yes);
+        case 1: return f(ic<1>{}, no, ic<4>{}, no, yes, no);
+        case 2: return f(ic<2>{}, no, ic<4>{}, no, yes, no);
+        default: return f(ic<4>{}, no, ic<4>{}, no, yes, no);
         }
     }
     if (v.q8) {
-        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, yes, no);
+        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, yes, no, no);
         switch (v.tt) {
-        case 1: return f(ic<1>{}, yes, ic<4>{}, yes, no);
-        case 2: return f(ic<2>{}, yes, ic<4>{}, yes, no);
-        case 3: return f(ic<3>{}, yes, ic<4>{}, yes, no);
-        default: return f(ic<4>{}, yes, ic<4>{}, yes, no);
+        case 1: return f(ic<1>{}, yes, ic<4>{}, yes, no, no);
+        case 2: return f(ic<2>{}, yes, ic<4>{}, yes, no, no);
+        case 3: return f(ic<3>{}, yes, ic<4>{}, yes, no, no);
+        default: return f(ic<4>{}, yes, ic<4>{}, yes, no, no);
         }
     }
-    return with_variant_bf16(v, [&](auto tt, auto wl, auto nw) { return f(tt, wl, nw, no, no); });
+    return with_variant_bf16(v, [&](auto tt, auto wl, auto nw) { return f(tt, wl, nw, no, no, no); });
 }
 // workgroups of a kernel instance the device holds at once (registers and LDS decide; asked once per instance), and
 // its number of compute units.  group: the kernel that carries several calls; 0 if it cannot be asked (then calls
@@ -429,24 +440,24 @@ int resident_of(const Variant &v, bool group, int *n_cus)
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
-            e = with_variant(v, [&](auto tt, auto wl, auto nw, auto q8, auto w8) {
+            e = with_variant(v, [&](auto tt, auto wl, auto nw, auto q8, auto w8, auto ln) {
                 constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-                constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value;
+                constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value, LN = decltype(ln)::value;
                 // (the ring may be larger than the LDS a kernel gets without asking)
                 if constexpr (W8) {
-                    const void *fn8 = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, Q8, true>)
-                                            : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, true>);
+                    const void *fn8 = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, Q8, true, LN>)
+                                            : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, true, LN>);
                     hipError_t e8 = hipFuncSetAttribute(fn8, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW, true));
                     if (e8 != hipSuccess) return e8;
-                    return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, Q8, true>, NW * 64, ring_bytes(TT, WL, NW, true))
-                                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, true>, NW * 64, ring_bytes(TT, WL, NW, true));
+                    return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, Q8, true, LN>, NW * 64, ring_bytes(TT, WL, NW, true))
+                                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, true, LN>, NW * 64, ring_bytes(TT, WL, NW, true));
                 } else {
-                const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, Q8, false>)
-                                       : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, false>);
+                const void *fn = group ? reinterpret_cast<const void *>(&decode_group_kernel<TT, WL, NW, Q8, false, LN>)
+                                       : reinterpret_cast<const void *>(&decode_kernel<TT, WL, NW, Q8, false, LN>);
                 hipError_t e2 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, ring_bytes(TT, WL, NW));
                 if (e2 != hipSuccess) return e2;
-                return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, Q8, false>, NW * 64, ring_bytes(TT, WL, NW))
-                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, false>, NW * 64, ring_bytes(TT, WL, NW));
+                return group ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_group_kernel<TT, WL, NW, Q8, false, LN>, NW * 64, ring_bytes(TT, WL, NW))
+                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<TT, WL, NW, Q8, false, LN>, NW * 64, ring_bytes(TT, WL, NW));
                 }
             });
         if (e != hipSuccess) {
@@ -494,7 +505,11 @@ int g_wide_mode = -1;  // -1: where it pays, 0: never, 1: wherever the shape all
 
 bool wide_allowed(int T) { return g_wide_mode != 0 && T > 32; }
 
-DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var, const uint16_t *w_scales = nullptr)
+// what the kernel's short tail serves (its `lean`), as far as the host can tell: every loaded rank a multiple of 8, and
+// max_rank from 5 to 64
+bool ranks_fit_short_tail(int n_odd_ranks, int max_rank) { return n_odd_ranks == 0 && max_rank <= 64 && max_rank > 4; }
+
+DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var, const uint16_t *w_scales = nullptr, bool lean_ok = false)
 {
     DecodeShape sh;
     sh.w_scales = w_scales;
@@ -535,7 +550,8 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var,
         return sh;
     }
     if (wide_allowed(T)) {
-        const Variant wide{4, true, 8, q8};
+        Variant wide{4, true, 8, q8};
+        wide.allow_lean(lean_ok);
         const int resident = resident_workgroups(wide, &n_cus);
         const int n_tiles = (N + wide.tile_rows() - 1) / wide.tile_rows();
         const int split = pick_split(K, n_tiles, resident, n_cus);
@@ -549,6 +565,7 @@ DecodeShape make_shape(int T, int K, int N, int max_rank, bool q8, Variant *var,
         }
     }
     Variant v{tt, true, 4, q8};
+    v.allow_lean(lean_ok);
     sh.tile_rows = v.tile_rows();
     sh.n_tiles = (N + sh.tile_rows - 1) / sh.tile_rows;
     int resident = resident_workgroups(v, &n_cus);
@@ -644,7 +661,7 @@ int elora::decode_probe_device(void *scratch, size_t scratch_bytes, hipStream_t 
 // tried first if its workgroups then cover at least seven eighths of the compute units; then W through LDS (one
 // workgroup per compute unit); then W into registers, which leaves room for two per unit.
 namespace {
-bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant *var, bool w8 = false, bool q8 = false)
+bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant *var, bool w8 = false, bool q8 = false, bool lean_ok = false)
 {
     if (n < 2 || n > kGroupMax || T < 1 || T > kDecodeMaxTokens) return false;
     const int tt = (T + 15) / 16;
@@ -660,6 +677,7 @@ bool group_splits(int T, int n, const int *K, const int *N, int *split, Variant 
         if (wide_allowed(T)) cand[n_cand++] = Variant{4, true, 8};
         cand[n_cand++] = Variant{tt, true, 4};
         if (tt > 2) cand[n_cand++] = Variant{tt, false, 4};
+        for (int i = 0; i < n_cand; ++i) cand[i].allow_lean(lean_ok);
     }
     for (int attempt = 0; attempt < n_cand; ++attempt) {
         const Variant v = cand[attempt];
@@ -722,7 +740,9 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
         Ns[i] = a[i].N;
     }
     Variant var{1, true, 4};
-    if (!group_splits(T, n, Ks, Ns, split, &var, w8, q8)) return -1;
+    bool lean_ok = true;
+    for (int i = 0; i < n; ++i) lean_ok = lean_ok && (!a[i].has_pool || ranks_fit_short_tail(a[i].pool.n_odd_ranks, a[i].pool.max_rank));
+    if (!group_splits(T, n, Ks, Ns, split, &var, w8, q8, lean_ok)) return -1;
     int n_cus = 0;
     (void)resident_workgroups(var, &n_cus);
     const int resident = resident_group_workgroups(var);
@@ -759,10 +779,10 @@ int elora::launch_decode_group(const LinearArgs *a, int n, hipStream_t stream)
     for (int i = n; i <= kGroupMax; ++i) grp.first[i] = first;
     dim3 grid(first), block(var.threads());
     profile_mark_begin(stream);
-    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8c, auto w8c) {
+    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8c, auto w8c, auto ln) {
         constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8c)::value, W8 = decltype(w8c)::value;
-        hipLaunchKernelGGL((decode_group_kernel<TT, WL, NW, Q8, W8>), grid, block, ring_bytes(TT, WL, NW, W8), stream, grp);
+        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8c)::value, W8 = decltype(w8c)::value, LN = decltype(ln)::value;
+        hipLaunchKernelGGL((decode_group_kernel<TT, WL, NW, Q8, W8, LN>), grid, block, ring_bytes(TT, WL, NW, W8), stream, grp);
         return 0;
     });
     ELORA_HIP_TRY(hipGetLastError());
@@ -826,7 +846,8 @@ void elora::decode_plan(const elora_linear_desc_t &d, elora_plan_t *plan)
     const int passes = decode_passes(d);
     const int rows = (d.n_tokens + passes - 1) / passes;  // the longest row range
     DecodeShape sh = make_shape(rows, d.d_in, d.d_out, d.pool ? d.pool->max_rank : 1, d.pool && d.pool->q8, &var,
-                                d.wfmt == ELORA_W_INT8_G32 ? static_cast<const uint16_t *>(d.w_scales) : nullptr);
+                                d.wfmt == ELORA_W_INT8_G32 ? static_cast<const uint16_t *>(d.w_scales) : nullptr,
+                                !d.pool || ranks_fit_short_tail(d.pool->n_odd_ranks, d.pool->max_rank));
     plan->n_launches = passes;
     plan->split_k = sh.split;
     plan->tile_rows = sh.tile_rows;
@@ -839,7 +860,8 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     (void)plan;
     Variant var{1, true, 4};
     DecodeShape sh = make_shape(a.T, a.K, a.N, a.has_pool ? a.pool.max_rank : 1, a.has_pool && a.pool.q8 != 0, &var,
-                                a.wfmt == ELORA_W_INT8_G32 ? static_cast<const uint16_t *>(a.w_scales) : nullptr);
+                                a.wfmt == ELORA_W_INT8_G32 ? static_cast<const uint16_t *>(a.w_scales) : nullptr,
+                                !a.has_pool || ranks_fit_short_tail(a.pool.n_odd_ranks, a.pool.max_rank));
     float *mail = reinterpret_cast<float *>(a.ws + a.wsl.mail);
     float *vmail = reinterpret_cast<float *>(a.ws + a.wsl.vmail);
     int *sync = reinterpret_cast<int *>(a.ws + a.wsl.sync);
@@ -849,10 +871,10 @@ int elora::launch_decode(const LinearArgs &a, const elora_plan_t &plan, hipStrea
     int has_pool = a.has_pool ? 1 : 0;
     dim3 grid(sh.grid), block(var.threads());
     profile_mark_begin(stream);
-    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8, auto w8) {
+    with_variant(var, [&](auto tt, auto wl, auto nw, auto q8, auto w8, auto ln) {
         constexpr int TT = decltype(tt)::value, NW = decltype(nw)::value;
-        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value;
-        hipLaunchKernelGGL((decode_kernel<TT, WL, NW, Q8, W8>), grid, block, ring_bytes(TT, WL, NW, W8), stream, sh, x, W, a.pool, a.route, has_pool,
+        constexpr bool WL = decltype(wl)::value, Q8 = decltype(q8)::value, W8 = decltype(w8)::value, LN = decltype(ln)::value;
+        hipLaunchKernelGGL((decode_kernel<TT, WL, NW, Q8, W8, LN>), grid, block, ring_bytes(TT, WL, NW, W8), stream, sh, x, W, a.pool, a.route, has_pool,
                            mail, vmail, sync, y);
         return 0;
     });

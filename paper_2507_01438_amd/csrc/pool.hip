@@ -159,6 +159,7 @@ PoolView elora_pool::view() const
     v.q8 = q8;
     v.a_scale_off = a_scale_off;
     v.b_scale_off = b_scale_off;
+    v.n_odd_ranks = n_odd_ranks;
     return v;
 }
 
@@ -204,6 +205,7 @@ int elora_pool_create(int d_in, int d_out, int max_rank, int capacity, int dtype
         return ELORA_E_STORAGE;
     }
     for (int i = 0; i < capacity; ++i) p->host_meta[i] = SlotMeta{0, 0.0f, 0, 0};
+    p->n_odd_ranks = 0;
     size_t e = elem_bytes(dtype);
     p->d_in = d_in;
     p->d_out = d_out;
@@ -262,6 +264,7 @@ int elora_pool_create_q8(int d_in, int d_out, int max_rank, int capacity, void *
         return ELORA_E_STORAGE;
     }
     for (int i = 0; i < capacity; ++i) p->host_meta[i] = SlotMeta{0, 0.0f, 0, 0};
+    p->n_odd_ranks = 0;
     p->d_in = d_in;
     p->d_out = d_out;
     p->max_rank = max_rank;
@@ -303,12 +306,12 @@ int elora_pool_load_adapter(elora_pool_t *pool, int slot, int rank, float scale,
     // the slot reads as empty while its content is being replaced
     hipLaunchKernelGGL(pool_set_meta_kernel, dim3(1), dim3(64), 0, stream, dmeta, slot, 0, 0.0f, 0);
     ELORA_HIP_TRY(hipGetLastError());
-    pool->host_meta[slot] = SlotMeta{0, 0.0f, 0, 0};
+    pool->set_host_meta(slot, SlotMeta{0, 0.0f, 0, 0});
     ELORA_HIP_TRY(hipMemcpyAsync(block, A, (size_t)rank * pool->d_in * e, kind, stream));
     ELORA_HIP_TRY(hipMemcpyAsync(block + pool->b_offset, B, (size_t)rank * pool->d_out * e, kind, stream));
     hipLaunchKernelGGL(pool_set_meta_kernel, dim3(1), dim3(64), 0, stream, dmeta, slot, rank, scale, 1);
     ELORA_HIP_TRY(hipGetLastError());
-    pool->host_meta[slot] = SlotMeta{rank, scale, 1, 0};
+    pool->set_host_meta(slot, SlotMeta{rank, scale, 1, 0});
     return ELORA_OK;
 }
 
@@ -382,7 +385,7 @@ int elora_pool_load_adapters(elora_pool_t *pool, int n, const int *slots, const 
         hipLaunchKernelGGL(pool_load_batch_kernel, dim3(per, lb.n), dim3(256), 0, stream, lb, pool->storage + pool->slots_offset,
                            pool->slot_bytes, pool->b_offset, dmeta);
         ELORA_HIP_TRY(hipGetLastError());
-        for (int i = 0; i < lb.n; ++i) pool->host_meta[slots[i0 + i]] = SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0};
+        for (int i = 0; i < lb.n; ++i) pool->set_host_meta(slots[i0 + i], SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0});
     }
     return ELORA_OK;
 }
@@ -444,7 +447,7 @@ int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, con
                                pool->slot_bytes, pool->a_scale_off, pool->b_offset, pool->b_scale_off,
                                reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset));
             ELORA_HIP_TRY(hipGetLastError());
-            for (int i = 0; i < lb.n; ++i) pool->host_meta[slots[i0 + i]] = SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0};
+            for (int i = 0; i < lb.n; ++i) pool->set_host_meta(slots[i0 + i], SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0});
         }
         return ELORA_OK;
     }
@@ -481,7 +484,7 @@ int elora_pool_load_adapters_q8(elora_pool_t *pool, int n, const int *slots, con
         hipLaunchKernelGGL(pool_load_q8_batch_kernel, dim3(per, lb.n), dim3(256), 0, stream, lb, pool->storage + pool->slots_offset,
                            pool->slot_bytes, pool->b_offset, reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset));
         ELORA_HIP_TRY(hipGetLastError());
-        for (int i = 0; i < lb.n; ++i) pool->host_meta[slots[i0 + i]] = SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0};
+        for (int i = 0; i < lb.n; ++i) pool->set_host_meta(slots[i0 + i], SlotMeta{ranks[i0 + i], scales[i0 + i], 1, 0});
     }
     return ELORA_OK;
 }
@@ -497,7 +500,7 @@ int elora_pool_evict(elora_pool_t *pool, int slot, elora_stream_t stream_)
     hipLaunchKernelGGL(pool_set_meta_kernel, dim3(1), dim3(64), 0, stream,
                        reinterpret_cast<SlotMeta *>(pool->storage + pool->meta_offset), slot, 0, 0.0f, 0);
     ELORA_HIP_TRY(hipGetLastError());
-    pool->host_meta[slot] = SlotMeta{0, 0.0f, 0, 0};
+    pool->set_host_meta(slot, SlotMeta{0, 0.0f, 0, 0});
     return ELORA_OK;
 }
 

@@ -616,3 +616,33 @@ def test_config5_mixed_int4_full_shape():
     print(f"config5: T={w.T} rel err {e:.2e}")
     assert e <= 1e-2
     case.close()
+
+
+@pytest.mark.parametrize("T,K,N", [(24, 512, 96), (64, 1024, 1040)])
+def test_decode_follows_the_ranks_the_pool_holds(T, K, N):
+    """The decode path has instances without the tail for ranks that are no multiples of 8; which one a call takes
+    follows what the pool holds when the call is made (Sec. 3.3 / 4.2: adapters come and go between batches)."""
+    w = I.small_workload(1300 + T, I.BF16, K, N, T, 4, (8, 16, 32, 5))
+    idx_even = (np.arange(T) % 3).astype(np.int32)          # rows use slots 0..2: ranks 8, 16, 32
+    idx_all = (np.arange(T) % 4).astype(np.int32)           # ... and slot 3: rank 5
+    w.adapter_idx = idx_even
+    case = DeviceCase(w, w.projections[0], load_slots=[0, 1, 2])
+    assert rel_err(case.run(), case.reference()) <= TOL[w.dtype]
+    # the adapter of rank 5 arrives: rows that use it, and rows that do not
+    A, Bm, s = w.adapter(w.projections[0], 3)
+    case.adapters[3] = (A, Bm, s)
+    case.pool.load(3, torch.from_numpy(A.view(np.int16)), torch.from_numpy(Bm.view(np.int16)), s)
+    w.adapter_idx = idx_all
+    case.adapter_idx.copy_(torch.from_numpy(idx_all))
+    y = case.run()
+    assert case.last_plan.path == DECODE
+    assert rel_err(y, case.reference()) <= TOL[w.dtype]
+    w.adapter_idx = idx_even
+    case.adapter_idx.copy_(torch.from_numpy(idx_even))
+    assert rel_err(case.run(), case.reference()) <= TOL[w.dtype]
+    # and leaves again
+    case.pool.evict(3)
+    del case.adapters[3]
+    assert rel_err(case.run(), case.reference()) <= TOL[w.dtype]
+    assert case.pool.poll_error() == (0, -1)
+    case.close()
