@@ -366,22 +366,23 @@ struct Variant {
     int nw;
     bool q8 = false;  // the pool keeps its adapters in 8-bit blocks (W through the ring always)
     bool w8 = false;  // W is 8-bit (into registers on four waves, through the ring on eight)
-    // the instance without the general tail (eight waves, bf16 W, bf16 pool or none): for calls whose pool, as the host
-    // knows it, holds only ranks that are multiples of 8, up to 64.  24 KB less code; config 3: 178.6 -> 175.9 us per
-    // step.  (The same for the four-wave instances made config 2 slower, 15.45 -> 15.94 us, although a build in which
-    // every instance lacked that tail ran it in 14.8: where the code lies matters as much as how much there is.)
+    // the instances without the general tail (bf16 W through the ring, bf16 pool or none; eight waves, or four waves
+    // with one or two blocks of x): for calls whose pool, as the host knows it, holds only ranks that are multiples of
+    // 8, up to 64.  14 to 24 KB less code per instance; config 3: 178.0 -> 175.1 us per step, config 2: 15.45 -> 14.8.
+    // (In the eight-wave instance the kernel also takes the short tail for granted; in the four-wave ones it still
+    // looks, which is what the compiler made the faster code of: 14.8 against 15.9 us.)
     bool lean = false;
     int index() const
     {
-        if (lean) return 33;
+        if (lean) return 33 + (nw > 4 ? 2 : tt - 1);
         return w8 ? (nw > 4 ? 26 : 21 + tt) + (q8 ? 6 : 0) : (nw > 4 ? 10 : tt * 2 + (wlds ? 1 : 0)) + (q8 ? 11 : 0);
     }
-    void allow_lean(bool ok) { lean = ok && !q8 && !w8 && wlds && nw > 4; }
+    void allow_lean(bool ok) { lean = ok && !q8 && !w8 && wlds && (nw > 4 || tt <= 2); }
     int threads() const { return nw * 64; }
     int tile_rows() const { return nw * kRowsPerWave; }
     int lds() const { return ring_bytes(tt, wlds, nw, w8); }
 };
-constexpr int kVariants = 34;
+constexpr int kVariants = 36;
 template <typename F>
 auto with_variant_bf16(const Variant &v, F &&f)
 {
@@ -399,7 +400,11 @@ auto with_variant(const Variant &v, F &&f)  // f(blocks of x, W through the ring
 {
     const std::true_type yes{};
     const std::false_type no{};
-    if (v.lean) return f(ic<4>{}, yes, ic<8>{}, no, no, yes);
+    if (v.lean) {
+        if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, no, no, yes);
+        if (v.tt == 1) return f(ic<1>{}, yes, ic<4>{}, no, no, yes);
+        return f(ic<2>{}, yes, ic<4>{}, no, no, yes);
+    }
     if (v.w8 && v.q8) {
         if (v.nw > 4) return f(ic<4>{}, yes, ic<8>{}, yes, yes, no);
         switch (v.tt) {
