@@ -20,7 +20,10 @@ ms_per_step, parity figure and cpu_baseline.  --config N runs configuration N al
 Inputs are resident in HBM before the timed region.  For the decode configs
 consecutive steps rotate through several distinct copies of the weights and
 pools (like the layers of a model do) so that the 256 MB last-level cache
-cannot serve them.
+cannot serve them.  Set-up runs the step on every copy once and keeps the
+device busy for 30 ms, so that short runs (--steps 20 --warmup 5 is under
+5 ms of device time) measure the device at its working clocks rather than on
+its way out of idle; then come the W warm-up steps and the K timed steps.
 
 Prints ONE JSON line: throughput of the whole job plus
   roofline     the dominant kernel's algorithmic bytes (decode) or flops
@@ -277,9 +280,16 @@ def run_config(cfg, steps, warmup, args, B, I, dev, cpu_seconds):
             else:
                 B.lib.elora_batched_lora_linear_group(arr, n, stream)
 
-    # set-up: every rotating copy is touched once (first use of its pages), whatever the number of warm-up steps
-    for i in range(L):
+    # set-up: every rotating copy is touched once (first use of its pages), whatever the number of warm-up steps, and the
+    # device is kept busy for 30 ms, so that it has left its idle clocks before the warm-up steps start (five warm-up
+    # steps of the layer are under a millisecond)
+    t_setup = time.perf_counter()
+    i = 0
+    while i < L or time.perf_counter() - t_setup < 0.03:
         step(i)
+        i += 1
+        if i % 8 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     for i in range(warmup):
         step(i)
